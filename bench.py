@@ -1,0 +1,323 @@
+#!/usr/bin/env python3
+"""Benchmark of the HAGO quantized-operator hot path on one MI355X.
+
+Headline (the JSON line's `value`): int8 TOP/s of the BERT-base dense stack
+(BASELINE config 5: M = 32 x 128 = 4096 rows through 768->2304, 768->768,
+768->3072, 3072->768), each layer one `hago_qdense` launch with int32
+accumulation, zero-point correction and the fused per-channel requantize.
+One step = the four launches; inputs are resident in HBM before timing.
+
+The same line carries
+  roofline     -- the int8-MFMA GEMM kernel: algorithmic ops / average launch
+                  time (HIP events on the launch stream) against 5.0 POP/s;
+  cpu_baseline -- the CPU oracle timed on a bounded sample of the same stack;
+  ops          -- the other operators of the path (simquant, depthwise,
+                  pointwise, standalone requantize, the conv configs and
+                  batch-scaled variants), each with its own bound.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_INT8_TOPS = 5000.0   # dense int8 MFMA, MI355X published (5.0 POP/s)
+PEAK_HBM_GBS = 8000.0     # HBM3E, MI355X published
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra-ops", action="store_true")
+    ap.add_argument("--only", default="", help="comma list of extra-op names to time (default all)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); "
+                 "use --gpus 1")
+
+    import torch
+    import paper_2103_14949_amd as hago
+    from paper_2103_14949_amd import datagen
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    hago.lib()  # fails loudly if the HIP library is missing
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    def to_dev(x):
+        return torch.from_numpy(np.ascontiguousarray(x)).to(dev)
+
+    def rq_of(mult, shift, out_u8=False, z_out=0, clip=None):
+        q = hago.QType(hago.U8 if out_u8 else hago.I8, 8, not out_u8, z_out)
+        lo, hi = clip if clip else (None, None)
+        return hago.Requant(to_dev(mult), to_dev(shift), q, lo, hi)
+
+    def event_time_ms(fn, iters, warmup):
+        """Average milliseconds per call of fn over `iters` back-to-back calls (HIP events on
+        the launch stream, so launch latency is amortised as in steady-state inference)."""
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters
+
+    # ------------------------------------------------------------------ headline: config 5
+    M = 4096
+    layers = []
+    for idx, (K, N) in enumerate(datagen.BERT_LAYERS):
+        c = datagen.config5_layer(idx, M)
+        layers.append(dict(
+            K=K, N=N, host=c, a=to_dev(c["a"]), w=to_dev(c["w"]), bias=to_dev(c["bias"]),
+            a_t=hago.QType(hago.U8, 8, False, c["z_a"]), w_t=hago.QType(hago.I8),
+            rq=rq_of(c["mult"], c["shift"]),
+            out=torch.empty((M, N), dtype=torch.int8, device=dev), ops=2.0 * M * N * K))
+    total_ops = sum(l["ops"] for l in layers)
+
+    def run_layer(l):
+        hago.qdense(l["a"], l["a_t"], l["w"], l["w_t"], l["bias"], hago.I32, l["rq"], out=l["out"])
+
+    def step():
+        for l in layers:
+            run_layer(l)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    ev_ms = e0.elapsed_time(e1)
+    ms_per_step = wall_ms / args.steps
+    value_tops = total_ops * args.steps / (wall_ms * 1e-3) / 1e12
+    # dominant kernel: the int8 MFMA GEMM; four launches per step
+    avg_launch_ms = ev_ms / (args.steps * len(layers))
+    achieved = total_ops * args.steps / (ev_ms * 1e-3) / 1e12
+    per_layer = []
+    for l in layers:
+        ms = event_time_ms(lambda: run_layer(l), args.steps, 5)
+        per_layer.append({"K": l["K"], "N": l["N"], "us": round(ms * 1e3, 3),
+                          "tops": round(l["ops"] / (ms * 1e-3) / 1e12, 1),
+                          "frac": round(l["ops"] / (ms * 1e-3) / 1e12 / PEAK_INT8_TOPS, 4)})
+    log("config 5 layers:", per_layer)
+
+    roofline = {"bound": "mfma", "kernel": "qgemm_kernel (int8 MFMA 32x32x32, fused requantize)",
+                "achieved": round(achieved, 2), "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
+                "frac": round(achieved / PEAK_INT8_TOPS, 4), "traffic": None,
+                "avg_launch_us": round(avg_launch_ms * 1e3, 3), "launches_per_step": len(layers),
+                "ops_per_step": total_ops, "per_layer": per_layer}
+
+    # ------------------------------------------------------------------ other operators
+    ops = {}
+    if not args.no_extra_ops:
+        only = set(filter(None, args.only.split(",")))
+        ops = extra_ops(torch, hago, datagen, to_dev, rq_of, event_time_ms, only)
+
+    # ------------------------------------------------------------------ CPU oracle baseline
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(datagen, layers)
+
+    out = {
+        "metric": "int8 TOPS (qdense + fused requantize, BERT-base dense stack)",
+        "value": round(value_tops, 2), "unit": "TOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+        "config": {"workload": "config5: BERT-base dense stack, M=4096 (batch 32 x seq 128), "
+                               "u8 x i8 -> i32, per-channel requantize to i8; 4 launches/step",
+                   "M": M, "layers_KN": [list(x) for x in datagen.BERT_LAYERS]},
+        "roofline": roofline, "cpu_baseline": cpu, "ops": ops,
+    }
+    print(json.dumps(out), flush=True)
+
+
+def cpu_baseline(datagen, layers):
+    """The oracle as it stands on a bounded sample: the first rows of every layer."""
+    from oracle import hago_ref as ref
+    ref.build()
+    threads = int(os.environ.get("OMP_NUM_THREADS", "0")) or (os.cpu_count() or 1)
+    threads = max(1, min(threads, os.cpu_count() or 1))
+    rows = 1024
+    ops = 0.0
+    t0 = time.perf_counter()
+    for l in layers:
+        c = l["host"]
+        rq = ref.Requant(c["mult"], c["shift"], out_dtype=ref.I8)
+        ref.qdense_threaded(c["a"][:rows], c["z_a"], c["w"], c["bias"], ref.I32, rq, threads=threads)
+        ops += 2.0 * rows * l["N"] * l["K"]
+    dt = time.perf_counter() - t0
+    log(f"cpu oracle: {ops / 1e9:.2f} GOP in {dt:.2f} s on {threads} threads")
+    return {"value": round(ops / dt / 1e12, 5), "unit": "TOP/s", "cores": threads, "kind": "oracle",
+            "sample": f"first {rows} of 4096 rows of each of the 4 layers ({ops / 1e9:.1f} GOP), "
+                      f"row slices on {threads} threads, {dt:.2f} s wall"}
+
+
+def extra_ops(torch, hago, datagen, to_dev, rq_of, event_time_ms, only):
+    """Timings of the remaining operators.  HBM-bound operators rotate over buffer sets that
+    together exceed the 256 MB last-level cache, so the figure is an HBM rate."""
+    dev = "cuda:0"
+    res = {}
+
+    def want(name):
+        return not only or name in only
+
+    def record(name, ms, ops=None, bytes_=None, bound=None, note=None):
+        r = {"us": round(ms * 1e3, 3)}
+        if ops is not None:
+            r["tops"] = round(ops / (ms * 1e-3) / 1e12, 3)
+            r["frac_mfma"] = round(r["tops"] / PEAK_INT8_TOPS, 4)
+        if bytes_ is not None:
+            r["gbs"] = round(bytes_ / (ms * 1e-3) / 1e9, 1)
+            r["frac_hbm"] = round(r["gbs"] / PEAK_HBM_GBS, 4)
+        r["bound"] = bound
+        if note:
+            r["note"] = note
+        res[name] = r
+        log(name, r)
+
+    def rotating(make_set, nbytes_per_set, min_total=640e6):
+        n = max(2, int(np.ceil(min_total / nbytes_per_set)))
+        sets = [make_set(i) for i in range(n)]
+        state = {"i": 0}
+
+        def nxt():
+            s = sets[state["i"] % n]
+            state["i"] += 1
+            return s
+        return nxt
+
+    # ---- simquant, config 4 tensor
+    if want("simquant_c4"):
+        c = datagen.config4_simquant()
+        x0 = to_dev(c["x"].reshape(32, 144, -1))
+        scale, zp = to_dev(c["scale"]), to_dev(c["zp"])
+        q = hago.QType(hago.I8)
+        nb = x0.numel() * 8
+        nxt = rotating(lambda i: (x0.clone(), torch.empty_like(x0)), nb)
+
+        def f():
+            x, y = nxt()
+            hago.simquant(x, scale, zp, q, out=y)
+        record("simquant_c4", event_time_ms(f, 60, 6), bytes_=nb, bound="hbm",
+               note="fp32 [32,144,56,56], per-channel, 8 B/elem")
+        del nxt
+
+    # ---- depthwise + pointwise, config 4
+    c4 = datagen.config4()
+    a_t, w_t = hago.QType(hago.I8, 8, True, 0), hago.QType(hago.I8)
+    if want("depthwise_c4"):
+        a0 = to_dev(c4["a"])
+        w, rq = to_dev(c4["w_dw"]), rq_of(c4["mult_dw"], c4["shift_dw"])
+        nb = a0.numel() * 2
+        nxt = rotating(lambda i: (a0.clone(), torch.empty_like(a0)), nb)
+
+        def f():
+            a, o = nxt()
+            hago.qconv2d(a, a_t, w, w_t, None, hago.NCHW, (1, 1), (1, 1), 144, hago.I32, rq, out=o)
+        record("depthwise_c4", event_time_ms(f, 100, 10), ops=2.0 * a0.numel() * 9, bytes_=nb,
+               bound="hbm", note="i8 [32,144,56,56] 3x3, 2 B/output")
+        del nxt
+    if want("pointwise_c4"):
+        a0 = to_dev(c4["a"])  # same distribution as the depthwise output
+        w, rq = to_dev(c4["w_pw"]), rq_of(c4["mult_pw"], c4["shift_pw"])
+        o_shape = (32, 24, 56, 56)
+        nb = a0.numel() + 32 * 24 * 56 * 56
+        nxt = rotating(lambda i: (a0.clone(), torch.empty(o_shape, dtype=torch.int8, device=dev)), nb)
+
+        def f():
+            a, o = nxt()
+            hago.qconv2d(a, a_t, w, w_t, None, hago.NCHW, (1, 1), (0, 0), 1, hago.I32, rq, out=o)
+        record("pointwise_c4", event_time_ms(f, 100, 10), ops=2.0 * 32 * 56 * 56 * 24 * 144,
+               bytes_=nb, bound="hbm", note="1x1 conv 144->24 on MFMA, 168 B/pixel")
+        del nxt
+
+    # ---- standalone requantize
+    if want("requantize_i32"):
+        acc0 = torch.randint(-2 ** 20, 2 ** 20, (32, 144, 3136), dtype=torch.int32, device=dev)
+        rq = rq_of(c4["mult_dw"], c4["shift_dw"])
+        nb = acc0.numel() * 5
+        nxt = rotating(lambda i: (acc0.clone(), torch.empty(acc0.shape, dtype=torch.int8, device=dev)), nb)
+
+        def f():
+            a, o = nxt()
+            hago.requantize(a, rq, out=o)
+        record("requantize_i32", event_time_ms(f, 60, 6), bytes_=nb, bound="hbm",
+               note="i32 [32,144,3136] -> i8, 5 B/elem")
+        del nxt
+
+    # ---- config 1 (as specified and scaled)
+    for name, Mrows in (("dense_c1", 64), ("dense_c1_M8192", 8192)):
+        if not want(name):
+            continue
+        c = datagen.config1(M=Mrows)
+        a, w = to_dev(c["a"]), to_dev(c["w"])
+        rq = rq_of(c["mult"], c["shift"])
+        out = torch.empty((Mrows, 128), dtype=torch.int8, device=dev)
+        at = hago.QType(hago.U8, 8, False, 128)
+
+        def f():
+            hago.qdense(a, at, w, w_t, None, hago.I32, rq, out=out)
+        record(name, event_time_ms(f, 200, 20), ops=2.0 * Mrows * 128 * 256,
+               bound="latency" if Mrows == 64 else "hbm",
+               note="u8 [M,256] x i8 [128,256]" + (" (scaled batch)" if Mrows != 64 else ""))
+
+    # ---- config 2 (as specified and scaled)
+    for name, B in (("conv_c2", 1), ("conv_c2_B64", 64)):
+        if not want(name):
+            continue
+        c = datagen.config2(B=B)
+        a, w = to_dev(c["a"]), to_dev(c["w"])
+        rq = rq_of(c["mult"], c["shift"], True, 0, (0, 255))
+        out = torch.empty((B, 64, 56, 56), dtype=torch.uint8, device=dev)
+        at = hago.QType(hago.U8, 8, False, 0)
+
+        def f():
+            hago.qconv2d(a, at, w, w_t, None, hago.NCHW, (1, 1), (1, 1), 1, hago.I32, rq, out=out)
+        record(name, event_time_ms(f, 100, 10), ops=2.0 * B * 3136 * 64 * 576,
+               bound="latency" if B == 1 else "mfma",
+               note="3x3 conv 64->64 @56x56 NCHW" + (" (scaled batch)" if B != 1 else ""))
+
+    # ---- config 3 (int16 accumulation; as specified and scaled)
+    for name, B in (("conv_c3_acc16", 8), ("conv_c3_acc16_B64", 64)):
+        if not want(name):
+            continue
+        c = datagen.config3(B=B)
+        a, w = to_dev(c["a"]), to_dev(c["w"])
+        out = torch.empty((B, 128, 28, 28), dtype=torch.int16, device=dev)
+        at, wt = hago.QType(hago.I8, 4, False, 0), hago.QType(hago.I8, 4, True, 0)
+
+        def f():
+            hago.qconv2d(a, at, w, wt, None, hago.NCHW, (1, 1), (1, 1), 1, hago.I16, None, out=out)
+        record(name, event_time_ms(f, 100, 10), ops=2.0 * B * 784 * 128 * 1152, bound="mfma",
+               note="3x3 conv 128->128 @28x28, raw int16 out" + (" (scaled batch)" if B != 8 else ""))
+    return res
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,177 @@
+/*
+ * hago.h -- C ABI of libhago: the quantized-operator hot path of HAGO
+ * (arXiv 2103.14949, "Automated Backend-Aware Post-Training Quantization")
+ * as hand-written HIP kernels for AMD MI355X (gfx950).
+ *
+ * The library exports the operators the paper's realization pass produces and
+ * its search loop executes:
+ *   hago_simquant   -- simulated_quantize (Sec. 4.2; Eq. 3; Sec. 5.2)
+ *   hago_qdense     -- integer dense, integer accumulate, fused requantize
+ *   hago_qconv2d    -- integer conv2d (groups == 1 or depthwise), same epilogue
+ *   hago_requantize -- the standalone requantize operator (Sec. 6.1, 6.2)
+ *
+ * Conventions common to every call
+ *   - Pointers marked "device" are GPU addresses valid on the current HIP
+ *     device; "host" are ordinary pointers.  The caller owns every buffer: the
+ *     library never allocates, frees or keeps a pointer after returning.
+ *   - Tensors are dense and contiguous in the stated order.  `out` must not
+ *     overlap any input.
+ *   - `stream` is the caller's hipStream_t (NULL = the default stream).  Calls
+ *     enqueue work on it and return without synchronizing.
+ *   - Every argument error is detected on the host BEFORE anything is
+ *     launched and reported as a status code; nothing is written in that
+ *     case.  The CONTENTS of device arrays (multiplier, shift, scale) cannot
+ *     be inspected without a synchronizing copy and are the caller's
+ *     contract: multiplier in [0, 2^31), shift in [0, 31], scale finite and
+ *     non-zero.
+ *   - Quantization parameters that the search varies (scales, zero points,
+ *     multipliers, shifts, clip limits, effective bits) are runtime arguments,
+ *     never compile-time constants (Sec. 6.3, batched search).
+ */
+#ifndef HAGO_H_
+#define HAGO_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  HAGO_OK = 0,
+  HAGO_ERR_NULL = 1,      /* a required pointer is NULL                          */
+  HAGO_ERR_SHAPE = 2,     /* negative/zero/inconsistent dimension, bad groups,
+                             bad layout, a size beyond the 32-bit index range   */
+  HAGO_ERR_DTYPE = 3,     /* operand / accumulator / output dtype combination
+                             that the operator does not define                  */
+  HAGO_ERR_BITS = 4,      /* effective bits < 1 or > container width, zero point
+                             or clip range outside the container / bit range    */
+  HAGO_ERR_PARAM = 5,     /* other invalid scalar parameter (flags, per_channel) */
+  HAGO_ERR_ACC_BOUND = 6, /* HAGO_STRICT_ACC16 set and K*Amax*Wmax > 32767       */
+  HAGO_ERR_DEVICE = 7     /* the HIP runtime refused the launch                  */
+} hago_status;
+
+/* Container data types.  "Effective bits" (Sec. 2, Sec. 5.3) may be fewer
+ * than the container's width: a 6-bit value is still stored in an int8. */
+typedef enum {
+  HAGO_U8 = 0,
+  HAGO_I8 = 1,
+  HAGO_I16 = 2,
+  HAGO_I32 = 3,
+  HAGO_F32 = 4
+} hago_dtype;
+
+typedef enum {
+  HAGO_NCHW = 0, /* activations [B,C,H,W], weights [O,C/g,KH,KW], out [B,O,OH,OW] */
+  HAGO_NHWC = 1  /* activations [B,H,W,C], weights [O,KH,KW,C/g], out [B,OH,OW,O] */
+} hago_layout;
+
+/* flags */
+#define HAGO_STRICT_ACC16 1u /* refuse int16 accumulation unless the declared
+                                operand ranges prove it cannot overflow */
+
+/* A quantized tensor type: container, effective bit count, signedness of the
+ * effective range, zero point.  `bits` is a CONTRACT on the value range
+ * (signed b bits: [-2^(b-1), 2^(b-1)-1]; unsigned: [0, 2^b-1]); kernels never
+ * mask operands to it.  It bounds the zero point and clip limits and feeds the
+ * int16-accumulation overflow check. */
+typedef struct {
+  hago_dtype dtype;
+  int32_t bits;
+  int32_t is_signed;
+  int32_t zero_point;
+} hago_qtype;
+
+/* Requantize epilogue (Sec. 6.1 realization; Sec. 6.2 "integer-only
+ * computations"): for an accumulator acc of output channel c
+ *     r   = floor(acc * multiplier[c] / 2^(31 + shift[c]) + 1/2)
+ *     out = clip(r + out.zero_point, clip_lo, clip_hi)  cast to out.dtype
+ * evaluated exactly in 64-bit integers (single rounding, ties toward
+ * +infinity).  ReLU / ReLU6 are expressed through clip_lo / clip_hi in the
+ * output's quantized domain (Sec. 6.1). */
+typedef struct {
+  const int32_t* multiplier; /* device, [channels] or [1]; Q31                  */
+  const int32_t* shift;      /* device, [channels] or [1]; 0..31                */
+  int32_t per_channel;       /* 0: entry 0 serves every channel; 1: one each    */
+  hago_qtype out;            /* dtype HAGO_I8 or HAGO_U8; bits; zero_point      */
+  int32_t clip_lo, clip_hi;  /* inclusive; within out's effective-bit range     */
+} hago_requant;
+
+/*
+ * simulated_quantize (Sec. 4.2 "Simulated Quantize Operator"; Eq. 3;
+ * rounding and saturation errors of Sec. 5.2).  Elementwise over
+ * x[outer, channels, inner] (device, fp32):
+ *     y = (clip(rint(x / s) + z, clip_lo, clip_hi) - z) * s
+ * in IEEE binary32 with true division, round-half-to-even and a
+ * compare-select clip (NaN stays NaN, +-inf saturates, no -0 results).
+ * s = scale[c], z = zero_point[c] (device, [channels]) when per_channel != 0,
+ * else entry 0.  q names the simulated container / effective bits and bounds
+ * clip_lo/clip_hi and nothing else.  y (device) may equal x (in place).
+ * Errors: NULL, SHAPE (negative dim), DTYPE (q.dtype not U8/I8/I16/I32),
+ * BITS (clip range outside q), DEVICE.  Empty tensors are a no-op.
+ */
+hago_status hago_simquant(const float* x, float* y, int64_t outer,
+                          int64_t channels, int64_t inner, const float* scale,
+                          const int32_t* zero_point, int32_t per_channel,
+                          hago_qtype q, int32_t clip_lo, int32_t clip_hi,
+                          void* stream);
+
+/*
+ * Quantized dense (Introduction: u8 x i8 -> i32 and i8 x i8 -> i16 operand
+ * triples; Sec. 6.2: dense on the fast integer instruction):
+ *     acc[m,n] = bias[n] + sum_k (a[m,k] - a_t.zero_point) * w[n,k]
+ * reduced modulo 2^32 (acc_dtype HAGO_I32) or modulo 2^16 and sign-extended
+ * (HAGO_I16, the int16-accumulation mode of Sec. 8.4).  With rq != NULL (host
+ * pointer to the struct) each accumulator is requantized with channel = n and
+ * out is [M,N] of rq->out.dtype; with rq == NULL the raw accumulators are
+ * stored as [M,N] int32 / int16.
+ * a: device [M,K], HAGO_U8 or HAGO_I8.  w: device [N,K] HAGO_I8, symmetric
+ * (w_t.zero_point must be 0).  bias: device [N] int32 or NULL.
+ * Errors: NULL, SHAPE (negative dims, > 2^31-1), DTYPE, BITS, PARAM,
+ * ACC_BOUND (flags & HAGO_STRICT_ACC16 and acc_dtype I16 and
+ * K * max|a - z_a| * max|w| over the declared bit ranges > 32767), DEVICE.
+ * M == 0 or N == 0 is a no-op; K == 0 yields the bias.
+ */
+hago_status hago_qdense(const void* a, hago_qtype a_t, const void* w,
+                        hago_qtype w_t, const int32_t* bias, int64_t M,
+                        int64_t N, int64_t K, hago_dtype acc_dtype,
+                        const hago_requant* rq, void* out, uint32_t flags,
+                        void* stream);
+
+/*
+ * Quantized conv2d (same operand triples; Sec. 6.2 conv2d; depthwise is the
+ * memory-bound MobileNet case of Sec. 8.3).  Cross-correlation, dilation 1:
+ *     acc[b,o,y,x] = bias[o] + sum_{c,ky,kx} (a[b,c,y*sh+ky-ph,x*sw+kx-pw] - z_a)
+ *                                            * w[o,c,ky,kx]
+ * where taps outside the image contribute exactly 0 (the input is padded with
+ * its zero point).  OH = (H + 2*pad_h - KH) / stride_h + 1 (floor), same for
+ * OW.  groups must be 1, or equal C and O (depthwise).  Accumulator width,
+ * requantize (channel = o) and raw output as for hago_qdense.
+ * Errors as for hago_qdense; additionally SHAPE for any other `groups`, a
+ * kernel larger than the padded image, stride < 1, pad < 0.
+ */
+hago_status hago_qconv2d(const void* a, hago_qtype a_t, const void* w,
+                         hago_qtype w_t, const int32_t* bias,
+                         hago_layout layout, int64_t B, int64_t C, int64_t H,
+                         int64_t W, int64_t O, int32_t KH, int32_t KW,
+                         int32_t stride_h, int32_t stride_w, int32_t pad_h,
+                         int32_t pad_w, int32_t groups, hago_dtype acc_dtype,
+                         const hago_requant* rq, void* out, uint32_t flags,
+                         void* stream);
+
+/*
+ * Standalone requantize (Sec. 6.1, 6.2): acc[outer, channels, inner] (device,
+ * HAGO_I32 or HAGO_I16; int16 is sign-extended) -> out of rq->out.dtype with
+ * the same shape, channel = axis 1.  rq must be non-NULL.
+ */
+hago_status hago_requantize(const void* acc, hago_dtype acc_dtype,
+                            int64_t outer, int64_t channels, int64_t inner,
+                            const hago_requant* rq, void* out, void* stream);
+
+/* Static, NUL-terminated description of a status code. */
+const char* hago_status_string(hago_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HAGO_H_ */

@@ -1,0 +1,12 @@
+"""MI355X-native quantized operators of HAGO (arXiv 2103.14949).
+
+The package is a thin ctypes binding over ``libhago.so`` (hand-written HIP
+kernels behind a C ABI, see ``include/hago.h``).  Every operator runs in those
+kernels; Python only marshals arguments.  PyTorch supplies device memory and
+streams.
+"""
+from .binding import (  # noqa: F401
+    HagoError, QType, Requant, lib, library_path,
+    simquant, requantize, qdense, qconv2d,
+    U8, I8, I16, I32, F32, NCHW, NHWC, STRICT_ACC16,
+)

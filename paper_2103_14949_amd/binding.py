@@ -1,0 +1,193 @@
+"""ctypes binding of libhago.so: same names as the C ABI, argument marshalling only.
+
+Tensors are torch tensors on the GPU; the binding passes their device pointers
+and the current torch stream to the library and allocates the output tensor.
+There is no CPU fallback: if the library is missing, loading fails.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+U8, I8, I16, I32, F32 = 0, 1, 2, 3, 4
+NCHW, NHWC = 0, 1
+STRICT_ACC16 = 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libhago.so")
+
+EXPORTS = ("hago_simquant", "hago_qdense", "hago_qconv2d", "hago_requantize", "hago_status_string")
+
+
+class _QType(C.Structure):
+    _fields_ = [("dtype", C.c_int32), ("bits", C.c_int32), ("is_signed", C.c_int32),
+                ("zero_point", C.c_int32)]
+
+
+class _Requant(C.Structure):
+    _fields_ = [("multiplier", C.c_void_p), ("shift", C.c_void_p), ("per_channel", C.c_int32),
+                ("out", _QType), ("clip_lo", C.c_int32), ("clip_hi", C.c_int32)]
+
+
+class HagoError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"libhago: {msg} (status {code})")
+        self.code = code
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+_lib = None
+
+
+def lib():
+    """Load libhago.so (built by paper_2103_14949_amd/build.py); raises if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise FileNotFoundError(
+                f"{_LIB_PATH} is missing: build it with `python -m paper_2103_14949_amd.build` "
+                "(there is no fallback path)")
+        L = C.CDLL(_LIB_PATH)
+        i32, i64, u32, vp = C.c_int32, C.c_int64, C.c_uint32, C.c_void_p
+        L.hago_status_string.restype = C.c_char_p
+        L.hago_status_string.argtypes = [i32]
+        L.hago_simquant.restype = i32
+        L.hago_simquant.argtypes = [vp, vp, i64, i64, i64, vp, vp, i32, _QType, i32, i32, vp]
+        L.hago_requantize.restype = i32
+        L.hago_requantize.argtypes = [vp, i32, i64, i64, i64, C.POINTER(_Requant), vp, vp]
+        L.hago_qdense.restype = i32
+        L.hago_qdense.argtypes = [vp, _QType, vp, _QType, vp, i64, i64, i64, i32,
+                                  C.POINTER(_Requant), vp, u32, vp]
+        L.hago_qconv2d.restype = i32
+        L.hago_qconv2d.argtypes = [vp, _QType, vp, _QType, vp, i32, i64, i64, i64, i64, i64,
+                                   i32, i32, i32, i32, i32, i32, i32, i32,
+                                   C.POINTER(_Requant), vp, u32, vp]
+        _lib = L
+    return _lib
+
+
+def _check(code):
+    if code != 0:
+        raise HagoError(code, lib().hago_status_string(code).decode())
+
+
+class QType:
+    """Container dtype, effective bits, signedness of the effective range, zero point."""
+
+    def __init__(self, dtype, bits=None, is_signed=None, zero_point=0):
+        self.dtype = dtype
+        self.bits = {U8: 8, I8: 8, I16: 16, I32: 32}.get(dtype, 0) if bits is None else bits
+        self.is_signed = (dtype != U8) if is_signed is None else bool(is_signed)
+        self.zero_point = int(zero_point)
+
+    def c(self):
+        return _QType(self.dtype, self.bits, int(self.is_signed), self.zero_point)
+
+
+class Requant:
+    """Requantize parameters; multiplier/shift are int32 device tensors."""
+
+    def __init__(self, multiplier, shift, out: QType, clip_lo=None, clip_hi=None, per_channel=None):
+        self.multiplier = multiplier
+        self.shift = shift
+        self.out = out
+        lo, hi = ((-(1 << (out.bits - 1)), (1 << (out.bits - 1)) - 1) if out.is_signed
+                  else (0, (1 << out.bits) - 1))
+        self.clip_lo = lo if clip_lo is None else int(clip_lo)
+        self.clip_hi = hi if clip_hi is None else int(clip_hi)
+        self.per_channel = int(multiplier.numel() > 1) if per_channel is None else int(per_channel)
+
+    def c(self):
+        return _Requant(self.multiplier.data_ptr(), self.shift.data_ptr(), self.per_channel,
+                        self.out.c(), self.clip_lo, self.clip_hi)
+
+
+def _torch():
+    import torch
+    return torch
+
+
+def _stream():
+    return _torch().cuda.current_stream().cuda_stream
+
+
+def _tdtype(code):
+    t = _torch()
+    return {U8: t.uint8, I8: t.int8, I16: t.int16, I32: t.int32, F32: t.float32}[code]
+
+
+def _code(tensor):
+    t = _torch()
+    return {t.uint8: U8, t.int8: I8, t.int16: I16, t.int32: I32, t.float32: F32}[tensor.dtype]
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+def simquant(x, scale, zero_point, q: QType, clip_lo=None, clip_hi=None, per_channel=None, out=None):
+    """hago_simquant over x[outer, channels, inner] (fp32, contiguous)."""
+    assert x.dim() == 3 and x.is_contiguous()
+    outer, channels, inner = x.shape
+    lo, hi = ((-(1 << (q.bits - 1)), (1 << (q.bits - 1)) - 1) if q.is_signed else (0, (1 << q.bits) - 1))
+    clip_lo = lo if clip_lo is None else clip_lo
+    clip_hi = hi if clip_hi is None else clip_hi
+    pc = int(scale.numel() > 1) if per_channel is None else int(per_channel)
+    y = _torch().empty_like(x) if out is None else out
+    _check(lib().hago_simquant(_ptr(x), _ptr(y), outer, channels, inner, _ptr(scale),
+                               _ptr(zero_point), pc, q.c(), int(clip_lo), int(clip_hi), _stream()))
+    return y
+
+
+def requantize(acc, rq: Requant, out=None):
+    """hago_requantize over acc[outer, channels, inner] (int32 / int16)."""
+    assert acc.dim() == 3 and acc.is_contiguous()
+    outer, channels, inner = acc.shape
+    if out is None:
+        out = _torch().empty(acc.shape, dtype=_tdtype(rq.out.dtype), device=acc.device)
+    st = rq.c()
+    _check(lib().hago_requantize(_ptr(acc), _code(acc), outer, channels, inner, C.byref(st),
+                                 _ptr(out), _stream()))
+    return out
+
+
+def qdense(a, a_t: QType, w, w_t: QType, bias=None, acc_dtype=I32, rq: Requant | None = None,
+           flags=0, out=None):
+    """hago_qdense: a [M,K] (uint8/int8), w [N,K] int8 -> [M,N]."""
+    assert a.dim() == 2 and w.dim() == 2 and a.is_contiguous() and w.is_contiguous()
+    M, K = a.shape
+    N = w.shape[0]
+    assert w.shape[1] == K
+    if out is None:
+        dt = _tdtype(rq.out.dtype) if rq is not None else _tdtype(acc_dtype)
+        out = _torch().empty((M, N), dtype=dt, device=a.device)
+    st = rq.c() if rq is not None else None
+    _check(lib().hago_qdense(_ptr(a), a_t.c(), _ptr(w), w_t.c(), _ptr(bias), M, N, K, acc_dtype,
+                             C.byref(st) if st is not None else None, _ptr(out), flags, _stream()))
+    return out
+
+
+def qconv2d(a, a_t: QType, w, w_t: QType, bias=None, layout=NCHW, stride=(1, 1), pad=(0, 0),
+            groups=1, acc_dtype=I32, rq: Requant | None = None, flags=0, out=None):
+    """hago_qconv2d: NCHW a [B,C,H,W], w [O,C/g,KH,KW]; NHWC a [B,H,W,C], w [O,KH,KW,C/g]."""
+    assert a.dim() == 4 and w.dim() == 4 and a.is_contiguous() and w.is_contiguous()
+    if layout == NCHW:
+        B, Cc, H, W = a.shape
+        O, _, KH, KW = w.shape
+    else:
+        B, H, W, Cc = a.shape
+        O, KH, KW, _ = w.shape
+    OH = (H + 2 * pad[0] - KH) // stride[0] + 1
+    OW = (W + 2 * pad[1] - KW) // stride[1] + 1
+    if out is None:
+        dt = _tdtype(rq.out.dtype) if rq is not None else _tdtype(acc_dtype)
+        shape = (B, O, max(OH, 0), max(OW, 0)) if layout == NCHW else (B, max(OH, 0), max(OW, 0), O)
+        out = _torch().empty(shape, dtype=dt, device=a.device)
+    st = rq.c() if rq is not None else None
+    _check(lib().hago_qconv2d(_ptr(a), a_t.c(), _ptr(w), w_t.c(), _ptr(bias), layout, B, Cc, H, W, O,
+                              KH, KW, stride[0], stride[1], pad[0], pad[1], groups, acc_dtype,
+                              C.byref(st) if st is not None else None, _ptr(out), flags, _stream()))
+    return out

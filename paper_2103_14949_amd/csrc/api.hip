@@ -1,0 +1,236 @@
+// C ABI of libhago: argument validation (host only, before any launch) and
+// dispatch to the kernel families.  See include/hago.h for the contract.
+#include "../../include/hago.h"
+
+#include "launch.h"
+
+namespace {
+
+using hago::ConvGeom;
+using hago::GemmArgs;
+using hago::RequantArgs;
+
+constexpr int64_t kI32Max = 2147483647ll;
+
+int container_bits(hago_dtype d) {
+  switch (d) {
+    case HAGO_U8: case HAGO_I8: return 8;
+    case HAGO_I16: return 16;
+    case HAGO_I32: return 32;
+    default: return 0;
+  }
+}
+
+// Inclusive value range of `bits` effective bits (Sec. 2: 2^bit bins).
+void bit_range(int bits, int is_signed, int64_t* lo, int64_t* hi) {
+  if (is_signed) {
+    *lo = -((int64_t)1 << (bits - 1));
+    *hi = ((int64_t)1 << (bits - 1)) - 1;
+  } else {
+    *lo = 0;
+    *hi = ((int64_t)1 << bits) - 1;
+  }
+}
+
+void container_range(hago_dtype d, int64_t* lo, int64_t* hi) {
+  switch (d) {
+    case HAGO_U8: *lo = 0; *hi = 255; break;
+    case HAGO_I8: *lo = -128; *hi = 127; break;
+    case HAGO_I16: *lo = -32768; *hi = 32767; break;
+    default: *lo = -2147483648ll; *hi = 2147483647ll; break;
+  }
+}
+
+// bits within the container, effective range inside the container's range.
+hago_status check_qtype(const hago_qtype& q, bool zero_point_in_container) {
+  const int cb = container_bits(q.dtype);
+  if (cb == 0) return HAGO_ERR_DTYPE;
+  if (q.bits < 1 || q.bits > cb) return HAGO_ERR_BITS;
+  int64_t blo, bhi, clo, chi;
+  bit_range(q.bits, q.is_signed != 0, &blo, &bhi);
+  container_range(q.dtype, &clo, &chi);
+  if (blo < clo || bhi > chi) return HAGO_ERR_BITS;  // e.g. 8 unsigned bits in an int8
+  if (zero_point_in_container && (q.zero_point < clo || q.zero_point > chi)) return HAGO_ERR_BITS;
+  return HAGO_OK;
+}
+
+hago_status check_requant(const hago_requant* rq, RequantArgs* out) {
+  if (!rq->multiplier || !rq->shift) return HAGO_ERR_NULL;
+  if (rq->out.dtype != HAGO_I8 && rq->out.dtype != HAGO_U8) return HAGO_ERR_DTYPE;
+  if (rq->per_channel != 0 && rq->per_channel != 1) return HAGO_ERR_PARAM;
+  hago_status s = check_qtype(rq->out, true);
+  if (s != HAGO_OK) return s;
+  int64_t blo, bhi;
+  bit_range(rq->out.bits, rq->out.is_signed != 0, &blo, &bhi);
+  if (rq->clip_lo > rq->clip_hi || rq->clip_lo < blo || rq->clip_hi > bhi) return HAGO_ERR_BITS;
+  out->multiplier = rq->multiplier;
+  out->shift = rq->shift;
+  out->per_channel = rq->per_channel;
+  out->out_unsigned = rq->out.dtype == HAGO_U8;
+  out->z_out = rq->out.zero_point;
+  out->clip_lo = rq->clip_lo;
+  out->clip_hi = rq->clip_hi;
+  return HAGO_OK;
+}
+
+// Shared operand checks of qdense / qconv2d.
+hago_status check_operands(const void* a, const hago_qtype& a_t, const void* w,
+                           const hago_qtype& w_t, hago_dtype acc_dtype, const hago_requant* rq,
+                           const void* out, uint32_t flags, int64_t K, GemmArgs* g) {
+  if (!a || !w || !out) return HAGO_ERR_NULL;
+  if (a_t.dtype != HAGO_U8 && a_t.dtype != HAGO_I8) return HAGO_ERR_DTYPE;
+  if (w_t.dtype != HAGO_I8) return HAGO_ERR_DTYPE;
+  if (w_t.zero_point != 0) return HAGO_ERR_DTYPE;  // weights are symmetric
+  if (acc_dtype != HAGO_I32 && acc_dtype != HAGO_I16) return HAGO_ERR_DTYPE;
+  if (flags & ~HAGO_STRICT_ACC16) return HAGO_ERR_PARAM;
+  hago_status s = check_qtype(a_t, true);
+  if (s != HAGO_OK) return s;
+  s = check_qtype(w_t, false);
+  if (s != HAGO_OK) return s;
+  g->has_rq = 0;
+  g->rq = RequantArgs{};
+  if (rq) {
+    s = check_requant(rq, &g->rq);
+    if (s != HAGO_OK) return s;
+    g->has_rq = 1;
+  }
+  if ((flags & HAGO_STRICT_ACC16) && acc_dtype == HAGO_I16) {
+    // Worst case of |sum_k (a - z_a) w| over the declared ranges (Sec. 5.3:
+    // effective bits are what keeps a 16-bit accumulator from overflowing).
+    int64_t alo, ahi, wlo, whi;
+    bit_range(a_t.bits, a_t.is_signed != 0, &alo, &ahi);
+    bit_range(w_t.bits, w_t.is_signed != 0, &wlo, &whi);
+    const int64_t amax = (ahi - a_t.zero_point > a_t.zero_point - alo) ? ahi - a_t.zero_point
+                                                                       : a_t.zero_point - alo;
+    const int64_t wmax = (whi > -wlo) ? whi : -wlo;
+    if (amax > 0 && wmax > 0 && K > 0) {
+      if (amax > 32767 || wmax > 32767 || K > 32767 || K * amax * wmax > 32767)
+        return HAGO_ERR_ACC_BOUND;
+    }
+  }
+  g->act = a;
+  g->wgt = static_cast<const int8_t*>(w);
+  g->out = const_cast<void*>(out);
+  g->act_unsigned = a_t.dtype == HAGO_U8;
+  g->act_zero_point = a_t.zero_point;
+  g->acc16 = acc_dtype == HAGO_I16;
+  return HAGO_OK;
+}
+
+hago_status from_hip(hipError_t e) { return e == hipSuccess ? HAGO_OK : HAGO_ERR_DEVICE; }
+
+}  // namespace
+
+extern "C" {
+
+const char* hago_status_string(hago_status s) {
+  switch (s) {
+    case HAGO_OK: return "ok";
+    case HAGO_ERR_NULL: return "a required pointer is NULL";
+    case HAGO_ERR_SHAPE: return "invalid or unsupported shape";
+    case HAGO_ERR_DTYPE: return "unsupported dtype combination";
+    case HAGO_ERR_BITS: return "effective bits, zero point or clip range outside the container";
+    case HAGO_ERR_PARAM: return "invalid parameter";
+    case HAGO_ERR_ACC_BOUND: return "int16 accumulation may overflow for the declared bit widths";
+    case HAGO_ERR_DEVICE: return "HIP runtime error";
+  }
+  return "unknown status";
+}
+
+hago_status hago_simquant(const float* x, float* y, int64_t outer, int64_t channels, int64_t inner,
+                          const float* scale, const int32_t* zero_point, int32_t per_channel,
+                          hago_qtype q, int32_t clip_lo, int32_t clip_hi, void* stream) {
+  if (!x || !y || !scale || !zero_point) return HAGO_ERR_NULL;
+  if (outer < 0 || channels < 0 || inner < 0) return HAGO_ERR_SHAPE;
+  if (per_channel != 0 && per_channel != 1) return HAGO_ERR_PARAM;
+  if (q.dtype == HAGO_F32) return HAGO_ERR_DTYPE;
+  hago_status s = check_qtype(q, false);
+  if (s != HAGO_OK) return s;
+  int64_t blo, bhi;
+  bit_range(q.bits, q.is_signed != 0, &blo, &bhi);
+  if (clip_lo > clip_hi || clip_lo < blo || clip_hi > bhi) return HAGO_ERR_BITS;
+  // codes must be exactly representable in binary32
+  if (clip_lo < -(1 << 24) || clip_hi > (1 << 24)) return HAGO_ERR_BITS;
+  if (outer && channels && inner) {
+    if (outer > INT64_MAX / channels || outer * channels > INT64_MAX / inner) return HAGO_ERR_SHAPE;
+  }
+  return from_hip(hago::launch_simquant(x, y, outer, channels, inner, scale, zero_point,
+                                        per_channel, clip_lo, clip_hi,
+                                        static_cast<hipStream_t>(stream)));
+}
+
+hago_status hago_requantize(const void* acc, hago_dtype acc_dtype, int64_t outer, int64_t channels,
+                            int64_t inner, const hago_requant* rq, void* out, void* stream) {
+  if (!acc || !rq || !out) return HAGO_ERR_NULL;
+  if (outer < 0 || channels < 0 || inner < 0) return HAGO_ERR_SHAPE;
+  if (acc_dtype != HAGO_I32 && acc_dtype != HAGO_I16) return HAGO_ERR_DTYPE;
+  RequantArgs ra{};
+  hago_status s = check_requant(rq, &ra);
+  if (s != HAGO_OK) return s;
+  if (outer && channels && inner) {
+    if (outer > INT64_MAX / channels || outer * channels > INT64_MAX / inner) return HAGO_ERR_SHAPE;
+  }
+  return from_hip(hago::launch_requantize(acc, acc_dtype == HAGO_I16, outer, channels, inner, ra,
+                                          out, static_cast<hipStream_t>(stream)));
+}
+
+hago_status hago_qdense(const void* a, hago_qtype a_t, const void* w, hago_qtype w_t,
+                        const int32_t* bias, int64_t M, int64_t N, int64_t K, hago_dtype acc_dtype,
+                        const hago_requant* rq, void* out, uint32_t flags, void* stream) {
+  GemmArgs g{};
+  if (M < 0 || N < 0 || K < 0) return HAGO_ERR_SHAPE;
+  hago_status s = check_operands(a, a_t, w, w_t, acc_dtype, rq, out, flags, K, &g);
+  if (s != HAGO_OK) return s;
+  // tile counts, row offsets inside a tile and K + 64 use 32-bit arithmetic
+  if (M > kI32Max - 512 || N > kI32Max - 512 || K > kI32Max - 512) return HAGO_ERR_SHAPE;
+  g.bias = bias;
+  g.M = (int32_t)M;
+  g.N = (int32_t)N;
+  g.K = (int32_t)K;
+  return from_hip(hago::launch_qdense(g, static_cast<hipStream_t>(stream)));
+}
+
+hago_status hago_qconv2d(const void* a, hago_qtype a_t, const void* w, hago_qtype w_t,
+                         const int32_t* bias, hago_layout layout, int64_t B, int64_t C, int64_t H,
+                         int64_t W, int64_t O, int32_t KH, int32_t KW, int32_t stride_h,
+                         int32_t stride_w, int32_t pad_h, int32_t pad_w, int32_t groups,
+                         hago_dtype acc_dtype, const hago_requant* rq, void* out, uint32_t flags,
+                         void* stream) {
+  GemmArgs g{};
+  if (B < 0 || C < 1 || H < 1 || W < 1 || O < 1 || KH < 1 || KW < 1 || stride_h < 1 ||
+      stride_w < 1 || pad_h < 0 || pad_w < 0)
+    return HAGO_ERR_SHAPE;
+  if (layout != HAGO_NCHW && layout != HAGO_NHWC) return HAGO_ERR_SHAPE;
+  const bool depthwise = (groups != 1) && (groups == C) && (groups == O);
+  if (groups != 1 && !depthwise) return HAGO_ERR_SHAPE;
+  if (H + 2 * (int64_t)pad_h < KH || W + 2 * (int64_t)pad_w < KW) return HAGO_ERR_SHAPE;
+  const int64_t OH = (H + 2 * (int64_t)pad_h - KH) / stride_h + 1;
+  const int64_t OW = (W + 2 * (int64_t)pad_w - KW) / stride_w + 1;
+  const int64_t Kred = depthwise ? (int64_t)KH * KW : C * (int64_t)KH * KW;
+  hago_status s = check_operands(a, a_t, w, w_t, acc_dtype, rq, out, flags, Kred, &g);
+  if (s != HAGO_OK) return s;
+  // every flat offset into the input, weights and (per image) output fits 31 bits
+  const int64_t lim = kI32Max - 512;
+  if (KH > 4096 || KW > 4096 || pad_h > 4096 || pad_w > 4096 || stride_h > 4096 ||
+      stride_w > 4096)
+    return HAGO_ERR_SHAPE;
+  if (C > lim || H > lim || W > lim || O > lim || B > lim) return HAGO_ERR_SHAPE;
+  if ((B ? B : 1) * C > lim / H / W) return HAGO_ERR_SHAPE;         // input elements
+  if ((B ? B : 1) * OH * OW > lim) return HAGO_ERR_SHAPE;            // GEMM rows
+  if ((B ? B : 1) * O > lim / OH / OW) return HAGO_ERR_SHAPE;        // output elements
+  if (O * Kred > lim) return HAGO_ERR_SHAPE;                          // weight elements
+  ConvGeom cg{};
+  cg.B = (int32_t)B; cg.C = (int32_t)C; cg.H = (int32_t)H; cg.W = (int32_t)W; cg.O = (int32_t)O;
+  cg.OH = (int32_t)OH; cg.OW = (int32_t)OW; cg.KH = KH; cg.KW = KW;
+  cg.stride_h = stride_h; cg.stride_w = stride_w; cg.pad_h = pad_h; cg.pad_w = pad_w;
+  cg.nhwc = layout == HAGO_NHWC;
+  g.bias = bias;
+  g.M = (int32_t)(B * OH * OW);
+  g.N = (int32_t)O;
+  g.K = (int32_t)Kred;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (depthwise) return from_hip(hago::launch_qconv_depthwise(g, cg, st));
+  return from_hip(hago::launch_qconv_gemm(g, cg, st));
+}
+
+}  // extern "C"

@@ -1,0 +1,238 @@
+// Depthwise quantized convolution (groups == C == O) with the fused requantize
+// epilogue.  Bandwidth-bound: each output byte needs one input byte from HBM,
+// so there is no MFMA here; the work is 9 multiply-adds per output on the
+// vector ALUs (4 at a time with v_dot4) out of an LDS copy of the input plane.
+//
+//   plane3x3 : NCHW, 3x3, stride 1, pad 1.  One workgroup per (image, channel,
+//              band of rows).  The band plus a one-pixel halo (filled with the
+//              zero point, so padded taps contribute 0) is staged in LDS with
+//              the image column x at LDS column x + 4; four adjacent outputs
+//              share three aligned dword reads per input row.
+//   direct   : every other geometry / layout: one output per lane straight
+//              from global memory (cache-served), same arithmetic.
+#include "hago_device.h"
+#include "launch.h"
+
+namespace hago {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kBandRows = 64;          // output rows per workgroup (plane3x3)
+constexpr int kMaxLdsBytes = 60 * 1024;
+
+struct DwArgs {
+  const uint8_t* act;
+  const int8_t* wgt;
+  const int32_t* bias;
+  void* out;
+  ConvGeom g;
+  uint32_t act_xor;    // 0x80 for a uint8 container (maps it to int8 = a - 128)
+  int32_t act_off;     // 128 for uint8, 0 for int8
+  int32_t z_a;
+  int32_t acc16;
+  int32_t has_rq;
+  int32_t out_mode;    // 0: requantized 8-bit, 1: raw int32, 2: raw int16
+  const int32_t* mult;
+  const int32_t* shift;
+  int32_t per_channel;
+  RequantScalars rs;
+};
+
+__device__ __forceinline__ int32_t wrap_acc(int32_t acc, int acc16) {
+  return acc16 ? (int32_t)(int16_t)acc : acc;
+}
+
+__device__ __forceinline__ void store_one(const DwArgs& p, int64_t idx, int32_t acc, int32_t m,
+                                          int32_t sh) {
+  if (p.out_mode == 0)
+    static_cast<uint8_t*>(p.out)[idx] = (uint8_t)requant_one(acc, m, sh, p.rs);
+  else if (p.out_mode == 1)
+    static_cast<int32_t*>(p.out)[idx] = acc;
+  else
+    static_cast<int16_t*>(p.out)[idx] = (int16_t)acc;
+}
+
+__global__ __launch_bounds__(kThreads) void dw_direct_kernel(DwArgs p) {
+  const ConvGeom& g = p.g;
+  const int64_t total = (int64_t)g.B * g.O * g.OH * g.OW;
+  const int64_t stride = (int64_t)gridDim.x * kThreads;
+  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += stride) {
+    int32_t b, c, oy, ox;
+    int64_t r = i;
+    if (g.nhwc) {
+      c = (int32_t)(r % g.O); r /= g.O;
+      ox = (int32_t)(r % g.OW); r /= g.OW;
+      oy = (int32_t)(r % g.OH); b = (int32_t)(r / g.OH);
+    } else {
+      ox = (int32_t)(r % g.OW); r /= g.OW;
+      oy = (int32_t)(r % g.OH); r /= g.OH;
+      c = (int32_t)(r % g.O); b = (int32_t)(r / g.O);
+    }
+    int32_t acc = p.bias ? p.bias[c] : 0;
+    for (int ky = 0; ky < g.KH; ++ky) {
+      const int iy = oy * g.stride_h + ky - g.pad_h;
+      if (iy < 0 || iy >= g.H) continue;
+      for (int kx = 0; kx < g.KW; ++kx) {
+        const int ix = ox * g.stride_w + kx - g.pad_w;
+        if (ix < 0 || ix >= g.W) continue;
+        const int64_t ai = g.nhwc ? (((int64_t)b * g.H + iy) * g.W + ix) * g.C + c
+                                  : (((int64_t)b * g.C + c) * g.H + iy) * g.W + ix;
+        const int64_t wi = g.nhwc ? ((int64_t)c * g.KH + ky) * g.KW + kx
+                                  : ((int64_t)c * g.KH + ky) * g.KW + kx;
+        const int32_t av = (int32_t)(int8_t)(p.act[ai] ^ p.act_xor) + p.act_off - p.z_a;
+        acc += av * (int32_t)p.wgt[wi];
+      }
+    }
+    acc = wrap_acc(acc, p.acc16);
+    const int pc = p.per_channel ? c : 0;
+    store_one(p, i, acc, p.has_rq ? p.mult[pc] : 0, p.has_rq ? p.shift[pc] : 0);
+  }
+}
+
+// NCHW 3x3 stride 1 pad 1.  Dynamic LDS: (band_rows + 2) * rs bytes where
+// rs = row stride (multiple of 4, >= W + 12).
+__global__ __launch_bounds__(kThreads) void dw_plane3x3_kernel(DwArgs p, int32_t rs, int32_t nband,
+                                                              int32_t vec_io) {
+  extern __shared__ uint32_t lds[];
+  const ConvGeom& g = p.g;
+  const int H = g.H, W = g.W;
+  const int64_t plane = blockIdx.x / nband;  // b * C + c
+  const int band = (int)(blockIdx.x - plane * nband);
+  const int c = (int)(plane % g.C);
+  const int y0 = band * kBandRows;
+  const int rows = (H - y0 < kBandRows) ? H - y0 : kBandRows;  // output rows in this band
+  const int lrows = rows + 2;
+  const int rs4 = rs >> 2;
+
+  const uint32_t padb = ((uint32_t)p.z_a ^ p.act_xor) & 0xffu;
+  const uint32_t pad4 = padb * 0x01010101u;
+  for (int i = threadIdx.x; i < lrows * rs4; i += kThreads) lds[i] = pad4;
+  __syncthreads();
+
+  // stage input rows y0-1 .. y0+rows (clipped to the image); image column x
+  // goes to LDS column x + 4 so that aligned dwords stay aligned.
+  const uint8_t* src = p.act + plane * (int64_t)H * W;
+  const int ya = (y0 - 1 < 0) ? 0 : y0 - 1;
+  const int yb = (y0 + rows + 1 > H) ? H : y0 + rows + 1;
+  if (vec_io) {
+    const int w4 = W >> 2;
+    const uint32_t x4 = p.act_xor * 0x01010101u;
+    const uint32_t* src4 = reinterpret_cast<const uint32_t*>(src);
+    for (int i = threadIdx.x; i < (yb - ya) * w4; i += kThreads) {
+      const int r = i / w4, q = i - r * w4;
+      lds[(ya + r - (y0 - 1)) * rs4 + 1 + q] = src4[(ya + r) * w4 + q] ^ x4;
+    }
+  } else {
+    uint8_t* l8 = reinterpret_cast<uint8_t*>(lds);
+    for (int i = threadIdx.x; i < (yb - ya) * W; i += kThreads) {
+      const int r = i / W, x = i - r * W;
+      l8[(ya + r - (y0 - 1)) * rs + 4 + x] = (uint8_t)(src[(int64_t)(ya + r) * W + x] ^ p.act_xor);
+    }
+  }
+
+  // per-channel constants
+  const int8_t* wc = p.wgt + (int64_t)c * 9;
+  uint32_t wrow[3];
+  int32_t wsum = 0;
+#pragma unroll
+  for (int ky = 0; ky < 3; ++ky) {
+    const int32_t w0 = wc[ky * 3 + 0], w1 = wc[ky * 3 + 1], w2 = wc[ky * 3 + 2];
+    wsum += w0 + w1 + w2;
+    wrow[ky] = (uint32_t)(w0 & 0xff) | ((uint32_t)(w1 & 0xff) << 8) | ((uint32_t)(w2 & 0xff) << 16);
+  }
+  // sum (a - z) w = sum (a' + off - z) w = sum a' w + (off - z) * sum w, a' = staged byte
+  const int32_t corr = (p.bias ? p.bias[c] : 0) + (p.act_off - p.z_a) * wsum;
+  const int pc = p.per_channel ? c : 0;
+  const int32_t m = p.has_rq ? p.mult[pc] : 0;
+  const int32_t sh = p.has_rq ? p.shift[pc] : 0;
+  __syncthreads();
+
+  const int gx = (W + 3) >> 2;  // groups of 4 outputs per row
+  const int64_t obase = plane * (int64_t)H * W;
+  for (int it = threadIdx.x; it < rows * gx; it += kThreads) {
+    const int ry = it / gx, q = it - ry * gx;
+    int32_t acc[4] = {corr, corr, corr, corr};
+#pragma unroll
+    for (int ky = 0; ky < 3; ++ky) {
+      const uint32_t* row = lds + (ry + ky) * rs4 + q;  // LDS columns 4q .. 4q+11
+      const uint32_t d0 = row[0], d1 = row[1], d2 = row[2];
+      // output x = 4q + i reads LDS columns x + 3 .. x + 5
+      const uint32_t w0 = __builtin_amdgcn_alignbyte(d1, d0, 3);
+      const uint32_t w1 = d1;
+      const uint32_t w2 = __builtin_amdgcn_alignbyte(d2, d1, 1);
+      const uint32_t w3 = __builtin_amdgcn_alignbyte(d2, d1, 2);
+      acc[0] = __builtin_amdgcn_sdot4((int)w0, (int)wrow[ky], acc[0], false);
+      acc[1] = __builtin_amdgcn_sdot4((int)w1, (int)wrow[ky], acc[1], false);
+      acc[2] = __builtin_amdgcn_sdot4((int)w2, (int)wrow[ky], acc[2], false);
+      acc[3] = __builtin_amdgcn_sdot4((int)w3, (int)wrow[ky], acc[3], false);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc[i] = wrap_acc(acc[i], p.acc16);
+    const int x0 = q << 2;
+    const int64_t o = obase + (int64_t)(y0 + ry) * W + x0;
+    if (vec_io) {
+      if (p.out_mode == 0) {
+        reinterpret_cast<uint32_t*>(p.out)[o >> 2] =
+            pack4(requant_one(acc[0], m, sh, p.rs), requant_one(acc[1], m, sh, p.rs),
+                  requant_one(acc[2], m, sh, p.rs), requant_one(acc[3], m, sh, p.rs));
+      } else if (p.out_mode == 1) {
+        reinterpret_cast<int4*>(p.out)[o >> 2] = make_int4(acc[0], acc[1], acc[2], acc[3]);
+      } else {
+        reinterpret_cast<short4*>(p.out)[o >> 2] =
+            make_short4((short)acc[0], (short)acc[1], (short)acc[2], (short)acc[3]);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if (x0 + i < W) store_one(p, o + i, acc[i], m, sh);
+    }
+  }
+}
+
+}  // namespace
+
+hipError_t launch_qconv_depthwise(const GemmArgs& a, const ConvGeom& cg, hipStream_t st) {
+  DwArgs p{};
+  p.act = static_cast<const uint8_t*>(a.act);
+  p.wgt = a.wgt;
+  p.bias = a.bias;
+  p.out = a.out;
+  p.g = cg;
+  p.act_xor = a.act_unsigned ? 0x80u : 0u;
+  p.act_off = a.act_unsigned ? 128 : 0;
+  p.z_a = a.act_zero_point;
+  p.acc16 = a.acc16;
+  p.has_rq = a.has_rq;
+  p.out_mode = a.has_rq ? 0 : (a.acc16 ? 2 : 1);
+  p.mult = a.rq.multiplier;
+  p.shift = a.rq.shift;
+  p.per_channel = a.rq.per_channel;
+  p.rs = RequantScalars{a.rq.z_out, a.rq.clip_lo - a.rq.z_out, a.rq.clip_hi - a.rq.z_out};
+
+  const int64_t total = (int64_t)cg.B * cg.O * cg.OH * cg.OW;
+  if (total == 0) return hipSuccess;
+
+  const bool plane_ok = !cg.nhwc && cg.KH == 3 && cg.KW == 3 && cg.stride_h == 1 &&
+                        cg.stride_w == 1 && cg.pad_h == 1 && cg.pad_w == 1;
+  const int rs = ((cg.W + 12 + 3) / 4) * 4;
+  const int band_rows = cg.H < kBandRows ? cg.H : kBandRows;
+  const size_t lds_bytes = (size_t)(band_rows + 2) * rs;
+  const int64_t planes = (int64_t)cg.B * cg.C;
+  const int nband = (cg.H + kBandRows - 1) / kBandRows;
+  if (plane_ok && lds_bytes <= (size_t)kMaxLdsBytes && planes * nband < (1ll << 31)) {
+    const size_t esz = a.has_rq ? 1 : (a.acc16 ? 2 : 4);
+    const bool vec_io = (cg.W % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.act) & 3u) == 0) &&
+                        ((reinterpret_cast<uintptr_t>(a.out) & (4 * esz - 1)) == 0);
+    hipLaunchKernelGGL(dw_plane3x3_kernel, dim3((unsigned)(planes * nband)), dim3(kThreads),
+                       lds_bytes, st, p, rs, nband, vec_io ? 1 : 0);
+  } else {
+    const int64_t blocks = (total + kThreads - 1) / kThreads;
+    const int64_t cap = 256 * 64;
+    hipLaunchKernelGGL(dw_direct_kernel, dim3((unsigned)(blocks < cap ? blocks : cap)),
+                       dim3(kThreads), 0, st, p);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace hago

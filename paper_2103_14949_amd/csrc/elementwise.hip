@@ -1,0 +1,214 @@
+// Bandwidth-bound elementwise kernels: fp32 simulated_quantize and the
+// standalone integer requantize.  Both stream [outer, channels, inner] tensors
+// once (read) and once (write); the only reuse is the per-channel parameter,
+// which is block-uniform in the row kernels and so lives in scalar registers.
+//
+// Two launch shapes per operator:
+//   rows : one workgroup per (row = outer*channels index, segment of inner);
+//          128-bit loads/stores; parameters fetched once per workgroup.
+//   flat : one element per lane with the channel recovered by division; used
+//          for short or unaligned rows (e.g. channel-last tensors).
+#include "hago_device.h"
+#include "launch.h"
+
+namespace hago {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kSegVec = 1024;  // 128-bit vectors per row segment (4 per lane)
+
+// Eq. 3 with zero point and saturation, in binary32.  The clip is written as
+// compare-select so that NaN propagates and the comparison structure is the
+// same as the scalar definition.
+__device__ __forceinline__ float simquant_one(float x, float s, float zf, float lo, float hi) {
+  const float t = x / s;  // IEEE division (correctly rounded)
+  const float u = rintf(t);
+  float v = u + zf;
+  v = (v < lo) ? lo : ((v > hi) ? hi : v);
+  return (v - zf) * s;
+}
+
+__global__ __launch_bounds__(kThreads) void simquant_rows_kernel(
+    const float4* __restrict__ x, float4* __restrict__ y, int64_t rows, int32_t channels,
+    int64_t inner_vec, int32_t nseg, const float* __restrict__ scale,
+    const int32_t* __restrict__ zp, int per_channel, float lo, float hi) {
+  for (int64_t job = blockIdx.x; job < rows * nseg; job += gridDim.x) {
+    const int64_t row = job / nseg;
+    const int32_t seg = (int32_t)(job - row * nseg);
+    const int32_t c = per_channel ? (int32_t)(row % channels) : 0;
+    const float s = scale[c];
+    const float zf = (float)zp[c];
+    const int64_t v0 = (int64_t)seg * kSegVec;
+    const int64_t v1 = (v0 + kSegVec < inner_vec) ? v0 + kSegVec : inner_vec;
+    const float4* xr = x + row * inner_vec;
+    float4* yr = y + row * inner_vec;
+    for (int64_t v = v0 + threadIdx.x; v < v1; v += kThreads) {
+      float4 a = xr[v];
+      float4 r;
+      r.x = simquant_one(a.x, s, zf, lo, hi);
+      r.y = simquant_one(a.y, s, zf, lo, hi);
+      r.z = simquant_one(a.z, s, zf, lo, hi);
+      r.w = simquant_one(a.w, s, zf, lo, hi);
+      yr[v] = r;
+    }
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void simquant_flat_kernel(
+    const float* __restrict__ x, float* __restrict__ y, int64_t total, int64_t inner,
+    int64_t channels, const float* __restrict__ scale, const int32_t* __restrict__ zp,
+    int per_channel, float lo, float hi) {
+  const int64_t stride = (int64_t)gridDim.x * kThreads;
+  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += stride) {
+    const int64_t c = per_channel ? (i / inner) % channels : 0;
+    y[i] = simquant_one(x[i], scale[c], (float)zp[c], lo, hi);
+  }
+}
+
+template <typename AccT>
+__device__ __forceinline__ int32_t load_acc(const AccT* p, int64_t i) {
+  return (int32_t)p[i];
+}
+
+// rows: 4 accumulators -> 4 output bytes per step, 128-bit loads for int32.
+template <typename AccT>
+__global__ __launch_bounds__(kThreads) void requant_rows_kernel(
+    const AccT* __restrict__ acc, uint32_t* __restrict__ out, int64_t rows, int32_t channels,
+    int64_t inner_vec, int32_t nseg, const int32_t* __restrict__ mult,
+    const int32_t* __restrict__ shift, int per_channel, RequantScalars rs) {
+  for (int64_t job = blockIdx.x; job < rows * nseg; job += gridDim.x) {
+    const int64_t row = job / nseg;
+    const int32_t seg = (int32_t)(job - row * nseg);
+    const int32_t c = per_channel ? (int32_t)(row % channels) : 0;
+    const int32_t m = mult[c];
+    const int32_t sh = shift[c];
+    const int64_t v0 = (int64_t)seg * kSegVec;
+    const int64_t v1 = (v0 + kSegVec < inner_vec) ? v0 + kSegVec : inner_vec;
+    const AccT* ar = acc + row * inner_vec * 4;
+    uint32_t* orow = out + row * inner_vec;
+    for (int64_t v = v0 + threadIdx.x; v < v1; v += kThreads) {
+      int32_t a0, a1, a2, a3;
+      if constexpr (sizeof(AccT) == 4) {
+        const int4 q = reinterpret_cast<const int4*>(ar)[v];
+        a0 = q.x; a1 = q.y; a2 = q.z; a3 = q.w;
+      } else {
+        const short4 q = reinterpret_cast<const short4*>(ar)[v];
+        a0 = q.x; a1 = q.y; a2 = q.z; a3 = q.w;
+      }
+      orow[v] = pack4(requant_one(a0, m, sh, rs), requant_one(a1, m, sh, rs),
+                      requant_one(a2, m, sh, rs), requant_one(a3, m, sh, rs));
+    }
+  }
+}
+
+// channel-last (inner == 1) with channels % 4 == 0: 4 consecutive channels.
+template <typename AccT>
+__global__ __launch_bounds__(kThreads) void requant_lastaxis_kernel(
+    const AccT* __restrict__ acc, uint32_t* __restrict__ out, int64_t total_vec,
+    int32_t channels_vec, const int4* __restrict__ mult, const int4* __restrict__ shift,
+    RequantScalars rs) {
+  const int64_t stride = (int64_t)gridDim.x * kThreads;
+  for (int64_t v = (int64_t)blockIdx.x * kThreads + threadIdx.x; v < total_vec; v += stride) {
+    const int32_t cv = (int32_t)(v % channels_vec);
+    const int4 m = mult[cv];
+    const int4 sh = shift[cv];
+    int32_t a0, a1, a2, a3;
+    if constexpr (sizeof(AccT) == 4) {
+      const int4 q = reinterpret_cast<const int4*>(acc)[v];
+      a0 = q.x; a1 = q.y; a2 = q.z; a3 = q.w;
+    } else {
+      const short4 q = reinterpret_cast<const short4*>(acc)[v];
+      a0 = q.x; a1 = q.y; a2 = q.z; a3 = q.w;
+    }
+    out[v] = pack4(requant_one(a0, m.x, sh.x, rs), requant_one(a1, m.y, sh.y, rs),
+                   requant_one(a2, m.z, sh.z, rs), requant_one(a3, m.w, sh.w, rs));
+  }
+}
+
+template <typename AccT>
+__global__ __launch_bounds__(kThreads) void requant_flat_kernel(
+    const AccT* __restrict__ acc, uint8_t* __restrict__ out, int64_t total, int64_t inner,
+    int64_t channels, const int32_t* __restrict__ mult, const int32_t* __restrict__ shift,
+    int per_channel, RequantScalars rs) {
+  const int64_t stride = (int64_t)gridDim.x * kThreads;
+  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += stride) {
+    const int64_t c = per_channel ? (i / inner) % channels : 0;
+    out[i] = (uint8_t)requant_one(load_acc(acc, i), mult[c], shift[c], rs);
+  }
+}
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+inline int grid_for(int64_t jobs) {
+  const int64_t cap = 256 * 64;  // 64 workgroups per CU is plenty for a streaming kernel
+  return (int)(jobs < cap ? (jobs > 0 ? jobs : 1) : cap);
+}
+
+}  // namespace
+
+hipError_t launch_simquant(const float* x, float* y, int64_t outer, int64_t channels, int64_t inner,
+                           const float* scale, const int32_t* zp, int per_channel, int32_t clip_lo,
+                           int32_t clip_hi, hipStream_t st) {
+  const int64_t total = outer * channels * inner;
+  if (total == 0) return hipSuccess;
+  const float lo = (float)clip_lo, hi = (float)clip_hi;
+  // Per-tensor parameters: the whole tensor is one row.
+  int64_t rows = per_channel ? outer * channels : 1;
+  int64_t row_len = per_channel ? inner : total;
+  if (row_len % 4 == 0 && row_len >= 512 && aligned16(x) && aligned16(y)) {
+    const int64_t inner_vec = row_len / 4;
+    const int32_t nseg = (int32_t)((inner_vec + kSegVec - 1) / kSegVec);
+    hipLaunchKernelGGL(simquant_rows_kernel, dim3(grid_for(rows * nseg)), dim3(kThreads), 0, st,
+                       reinterpret_cast<const float4*>(x), reinterpret_cast<float4*>(y), rows,
+                       (int32_t)(per_channel ? channels : 1), inner_vec, nseg, scale, zp,
+                       per_channel, lo, hi);
+  } else {
+    hipLaunchKernelGGL(simquant_flat_kernel, dim3(grid_for((total + kThreads - 1) / kThreads)),
+                       dim3(kThreads), 0, st, x, y, total, inner, channels, scale, zp, per_channel,
+                       lo, hi);
+  }
+  return hipGetLastError();
+}
+
+template <typename AccT>
+static hipError_t launch_requantize_t(const AccT* acc, int64_t outer, int64_t channels,
+                                      int64_t inner, const RequantArgs& rq, void* out,
+                                      hipStream_t st) {
+  const int64_t total = outer * channels * inner;
+  if (total == 0) return hipSuccess;
+  const RequantScalars rs{rq.z_out, rq.clip_lo - rq.z_out, rq.clip_hi - rq.z_out};
+  const int pc = rq.per_channel;
+  int64_t rows = pc ? outer * channels : 1;
+  int64_t row_len = pc ? inner : total;
+  const bool io_aligned = aligned16(acc) && aligned16(out);
+  if (row_len % 4 == 0 && row_len >= 512 && io_aligned) {
+    const int64_t inner_vec = row_len / 4;
+    const int32_t nseg = (int32_t)((inner_vec + kSegVec - 1) / kSegVec);
+    hipLaunchKernelGGL(requant_rows_kernel<AccT>, dim3(grid_for(rows * nseg)), dim3(kThreads), 0, st,
+                       acc, reinterpret_cast<uint32_t*>(out), rows, (int32_t)(pc ? channels : 1),
+                       inner_vec, nseg, rq.multiplier, rq.shift, pc, rs);
+  } else if (pc && inner == 1 && channels % 4 == 0 && io_aligned && aligned16(rq.multiplier) &&
+             aligned16(rq.shift)) {
+    const int64_t total_vec = total / 4;
+    hipLaunchKernelGGL(requant_lastaxis_kernel<AccT>,
+                       dim3(grid_for((total_vec + kThreads - 1) / kThreads)), dim3(kThreads), 0, st,
+                       acc, reinterpret_cast<uint32_t*>(out), total_vec, (int32_t)(channels / 4),
+                       reinterpret_cast<const int4*>(rq.multiplier),
+                       reinterpret_cast<const int4*>(rq.shift), rs);
+  } else {
+    hipLaunchKernelGGL(requant_flat_kernel<AccT>, dim3(grid_for((total + kThreads - 1) / kThreads)),
+                       dim3(kThreads), 0, st, acc, reinterpret_cast<uint8_t*>(out), total, inner,
+                       channels, rq.multiplier, rq.shift, pc, rs);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_requantize(const void* acc, int acc16, int64_t outer, int64_t channels,
+                             int64_t inner, const RequantArgs& rq, void* out, hipStream_t st) {
+  if (acc16)
+    return launch_requantize_t(static_cast<const int16_t*>(acc), outer, channels, inner, rq, out, st);
+  return launch_requantize_t(static_cast<const int32_t*>(acc), outer, channels, inner, rq, out, st);
+}
+
+}  // namespace hago

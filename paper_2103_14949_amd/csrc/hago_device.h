@@ -1,0 +1,39 @@
+// Device-side helpers shared by the libhago kernels (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace hago {
+
+// Requantize epilogue parameters that are uniform over a launch.  The clip
+// limits are stored relative to the output zero point:
+//   clip(r + z, lo, hi) == clip(r, lo - z, hi - z) + z
+// so the sum r + z is only formed once r is already small.
+struct RequantScalars {
+  int32_t z_out;
+  int32_t lo_rel;  // clip_lo - z_out
+  int32_t hi_rel;  // clip_hi - z_out
+};
+
+// r = floor(acc * mult / 2^(31 + sh) + 1/2), exact in 64-bit integers
+// (|acc * mult| < 2^62, rounding term <= 2^61).  The result always fits in
+// int32 for mult < 2^31.
+__device__ __forceinline__ int32_t rounding_mul_shift(int32_t acc, int32_t mult, int32_t sh) {
+  const int64_t p = (int64_t)acc * (int64_t)mult + ((int64_t)1 << (30 + sh));
+  return (int32_t)(p >> (31 + sh));
+}
+
+__device__ __forceinline__ int32_t requant_one(int32_t acc, int32_t mult, int32_t sh,
+                                               const RequantScalars& rs) {
+  int32_t r = rounding_mul_shift(acc, mult, sh);
+  r = r < rs.lo_rel ? rs.lo_rel : (r > rs.hi_rel ? rs.hi_rel : r);
+  return r + rs.z_out;
+}
+
+__device__ __forceinline__ uint32_t pack4(int32_t b0, int32_t b1, int32_t b2, int32_t b3) {
+  return (uint32_t)(b0 & 0xff) | ((uint32_t)(b1 & 0xff) << 8) | ((uint32_t)(b2 & 0xff) << 16) |
+         ((uint32_t)b3 << 24);
+}
+
+}  // namespace hago

@@ -1,0 +1,52 @@
+// Host-side launch entry points of the kernel families; called only from the
+// C ABI layer after all arguments have been validated.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace hago {
+
+struct RequantArgs {
+  const int32_t* multiplier;  // device
+  const int32_t* shift;       // device
+  int32_t per_channel;
+  int32_t out_unsigned;  // 1: uint8 container, 0: int8
+  int32_t z_out, clip_lo, clip_hi;
+};
+
+// fp32 simulated quantize over [outer, channels, inner].
+hipError_t launch_simquant(const float* x, float* y, int64_t outer, int64_t channels, int64_t inner,
+                           const float* scale, const int32_t* zp, int per_channel, int32_t clip_lo,
+                           int32_t clip_hi, hipStream_t st);
+
+// standalone requantize over [outer, channels, inner]; acc16 != 0: int16 input.
+hipError_t launch_requantize(const void* acc, int acc16, int64_t outer, int64_t channels,
+                             int64_t inner, const RequantArgs& rq, void* out, hipStream_t st);
+
+struct ConvGeom {
+  int32_t B, C, H, W, O, OH, OW, KH, KW, stride_h, stride_w, pad_h, pad_w;
+  int32_t nhwc;
+};
+
+struct GemmArgs {
+  const void* act;    // activations, uint8 or int8 container
+  const int8_t* wgt;  // weights [N, K] (conv: [O, C*KH*KW] in the layout's own order)
+  const int32_t* bias;
+  void* out;
+  int32_t M, N, K;
+  int32_t act_unsigned;  // 1: uint8 container
+  int32_t act_zero_point;
+  int32_t acc16;           // reduce accumulator modulo 2^16
+  int32_t has_rq;          // 0: store raw accumulators
+  RequantArgs rq;
+};
+
+// C[M,N] = act[M,K] x wgt[N,K]^T on int8 MFMA; out row-major [M,N].
+hipError_t launch_qdense(const GemmArgs& g, hipStream_t st);
+// implicit-GEMM convolution, groups == 1.
+hipError_t launch_qconv_gemm(const GemmArgs& g, const ConvGeom& cg, hipStream_t st);
+// depthwise convolution (groups == C == O), no MFMA.
+hipError_t launch_qconv_depthwise(const GemmArgs& g, const ConvGeom& cg, hipStream_t st);
+
+}  // namespace hago
