@@ -15,7 +15,7 @@
  *     device; "host" are ordinary pointers.  The caller owns every buffer: the
  *     library never allocates, frees or keeps a pointer after returning.
  *   - Tensors are dense and contiguous in the stated order.  `out` must not
- *     overlap any input.
+ *     overlap any input.  A tensor with zero elements may be passed as NULL.
  *   - `stream` is the caller's hipStream_t (NULL = the default stream).  Calls
  *     enqueue work on it and return without synchronizing.
  *   - Every argument error is detected on the host BEFORE anything is

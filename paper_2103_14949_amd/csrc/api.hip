@@ -76,8 +76,10 @@ hago_status check_requant(const hago_requant* rq, RequantArgs* out) {
 // Shared operand checks of qdense / qconv2d.
 hago_status check_operands(const void* a, const hago_qtype& a_t, const void* w,
                            const hago_qtype& w_t, hago_dtype acc_dtype, const hago_requant* rq,
-                           const void* out, uint32_t flags, int64_t K, GemmArgs* g) {
-  if (!a || !w || !out) return HAGO_ERR_NULL;
+                           const void* out, uint32_t flags, int64_t K, bool a_empty,
+                           bool w_empty, bool out_empty, GemmArgs* g) {
+  // an empty tensor may come with a NULL pointer
+  if ((!a && !a_empty) || (!w && !w_empty) || (!out && !out_empty)) return HAGO_ERR_NULL;
   if (a_t.dtype != HAGO_U8 && a_t.dtype != HAGO_I8) return HAGO_ERR_DTYPE;
   if (w_t.dtype != HAGO_I8) return HAGO_ERR_DTYPE;
   if (w_t.zero_point != 0) return HAGO_ERR_DTYPE;  // weights are symmetric
@@ -140,8 +142,9 @@ const char* hago_status_string(hago_status s) {
 hago_status hago_simquant(const float* x, float* y, int64_t outer, int64_t channels, int64_t inner,
                           const float* scale, const int32_t* zero_point, int32_t per_channel,
                           hago_qtype q, int32_t clip_lo, int32_t clip_hi, void* stream) {
-  if (!x || !y || !scale || !zero_point) return HAGO_ERR_NULL;
   if (outer < 0 || channels < 0 || inner < 0) return HAGO_ERR_SHAPE;
+  const bool sq_empty = outer == 0 || channels == 0 || inner == 0;
+  if (((!x || !y) && !sq_empty) || !scale || !zero_point) return HAGO_ERR_NULL;
   if (per_channel != 0 && per_channel != 1) return HAGO_ERR_PARAM;
   if (q.dtype == HAGO_F32) return HAGO_ERR_DTYPE;
   hago_status s = check_qtype(q, false);
@@ -161,8 +164,9 @@ hago_status hago_simquant(const float* x, float* y, int64_t outer, int64_t chann
 
 hago_status hago_requantize(const void* acc, hago_dtype acc_dtype, int64_t outer, int64_t channels,
                             int64_t inner, const hago_requant* rq, void* out, void* stream) {
-  if (!acc || !rq || !out) return HAGO_ERR_NULL;
   if (outer < 0 || channels < 0 || inner < 0) return HAGO_ERR_SHAPE;
+  const bool rq_empty = outer == 0 || channels == 0 || inner == 0;
+  if (((!acc || !out) && !rq_empty) || !rq) return HAGO_ERR_NULL;
   if (acc_dtype != HAGO_I32 && acc_dtype != HAGO_I16) return HAGO_ERR_DTYPE;
   RequantArgs ra{};
   hago_status s = check_requant(rq, &ra);
@@ -179,7 +183,8 @@ hago_status hago_qdense(const void* a, hago_qtype a_t, const void* w, hago_qtype
                         const hago_requant* rq, void* out, uint32_t flags, void* stream) {
   GemmArgs g{};
   if (M < 0 || N < 0 || K < 0) return HAGO_ERR_SHAPE;
-  hago_status s = check_operands(a, a_t, w, w_t, acc_dtype, rq, out, flags, K, &g);
+  hago_status s = check_operands(a, a_t, w, w_t, acc_dtype, rq, out, flags, K, M == 0 || K == 0,
+                                 N == 0 || K == 0, M == 0 || N == 0, &g);
   if (s != HAGO_OK) return s;
   // tile counts, row offsets inside a tile and K + 64 use 32-bit arithmetic
   if (M > kI32Max - 512 || N > kI32Max - 512 || K > kI32Max - 512) return HAGO_ERR_SHAPE;
@@ -207,7 +212,8 @@ hago_status hago_qconv2d(const void* a, hago_qtype a_t, const void* w, hago_qtyp
   const int64_t OH = (H + 2 * (int64_t)pad_h - KH) / stride_h + 1;
   const int64_t OW = (W + 2 * (int64_t)pad_w - KW) / stride_w + 1;
   const int64_t Kred = depthwise ? (int64_t)KH * KW : C * (int64_t)KH * KW;
-  hago_status s = check_operands(a, a_t, w, w_t, acc_dtype, rq, out, flags, Kred, &g);
+  hago_status s = check_operands(a, a_t, w, w_t, acc_dtype, rq, out, flags, Kred, B == 0, false,
+                                 B == 0, &g);
   if (s != HAGO_OK) return s;
   // every flat offset into the input, weights and (per image) output fits 31 bits
   const int64_t lim = kI32Max - 512;
