@@ -24,11 +24,24 @@ __device__ __forceinline__ int32_t rounding_mul_shift(int32_t acc, int32_t mult,
   return (int32_t)(p >> (31 + sh));
 }
 
+// median of three = clamp when lo <= hi; one instruction instead of two compare/select pairs
+__device__ __forceinline__ int32_t med3(int32_t x, int32_t lo, int32_t hi) {
+  int32_t r;
+  asm("v_med3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(x), "v"(lo), "v"(hi));
+  return r;
+}
+
 __device__ __forceinline__ int32_t requant_one(int32_t acc, int32_t mult, int32_t sh,
                                                const RequantScalars& rs) {
-  int32_t r = rounding_mul_shift(acc, mult, sh);
-  r = r < rs.lo_rel ? rs.lo_rel : (r > rs.hi_rel ? rs.hi_rel : r);
-  return r + rs.z_out;
+  const int32_t r = rounding_mul_shift(acc, mult, sh);
+  return med3(r, rs.lo_rel, rs.hi_rel) + rs.z_out;
+}
+
+// Four results -> one little-endian dword of their low bytes.
+__device__ __forceinline__ uint32_t pack4_perm(int32_t b0, int32_t b1, int32_t b2, int32_t b3) {
+  const uint32_t lo = __builtin_amdgcn_perm((uint32_t)b1, (uint32_t)b0, 0x0c0c0400u);
+  const uint32_t hi = __builtin_amdgcn_perm((uint32_t)b3, (uint32_t)b2, 0x04000c0cu);
+  return lo | hi;
 }
 
 __device__ __forceinline__ uint32_t pack4(int32_t b0, int32_t b1, int32_t b2, int32_t b3) {

@@ -2,7 +2,7 @@
 // dense layers and non-depthwise convolutions (implicit GEMM), int32
 // accumulation (optionally reduced modulo 2^16), fused requantize epilogue.
 //
-// One workgroup = 256 lanes = 4 wavefronts computes a BP x BQ tile of
+// A workgroup of WP x WQ wavefronts computes a BP x BQ tile of
 // D[i][j] = sum_k P[i][k] * Q[j][k].  Both operands are byte matrices that are
 // contiguous along k, which is what the MFMA wants: lane l feeds 16
 // consecutive k-bytes of row (l % 32), the upper 32 lanes the next 16 bytes.
@@ -13,6 +13,15 @@
 //   dense, NHWC conv : P = weights (i = output channel),  Q = activations
 //   NCHW conv        : P = activations (i = output pixel), Q = weights
 //
+// What bounds the kernel.  A CU multiplies 4096 byte pairs per clock but its
+// vector memory path delivers about 64 bytes per clock and its LDS about
+// 128-140, so a tile must reuse every staged byte many times: the L1 traffic of
+// a tile is (BP + BQ) * K bytes for BP * BQ * K products, and each wavefront
+// re-reads its fragments from LDS once per 32 k.  Hence the large tiles
+// (up to 256 x 256 per workgroup, 64 x 128 per wavefront) and eight wavefronts
+// per workgroup, two per SIMD, so that one can issue MFMAs while the other
+// waits on LDS.
+//
 // Zero points and unsigned activations.  The MFMA multiplies signed bytes.
 // A uint8 activation a is fed as a' = a XOR 0x80 = a - 128, an int8 one as is
 // (off = 128 or 0).  Then
@@ -22,49 +31,27 @@
 // convolution taps are staged as the zero point itself, which makes them
 // contribute exactly 0 under the same identity.
 //
-// K is processed in stages of 64 bytes, double-buffered in LDS through
-// registers (global -> VGPR -> LDS), one barrier per stage.  LDS rows are 64
-// bytes; the four 16-byte chunks of a row are XOR-swizzled with the row index
-// so that the 128-bit fragment reads and the staging writes spread over banks.
-#include "hago_device.h"
-#include "launch.h"
+// K is processed in stages of 128 bytes (one cache line per row), double
+// buffered in LDS through registers (global -> VGPR -> LDS), one barrier per
+// stage; the loads of stage s+1 are in flight while stage s is multiplied.
+// The eight 16-byte chunks of an LDS row are XOR-swizzled with the row index
+// so that fragment reads and staging writes spread over all banks.
+#include "qgemm_common.h"
+
+#include <cstdlib>
 
 namespace hago {
 
 namespace {
 
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef int v16i __attribute__((ext_vector_type(16)));
-
-constexpr int kThreads = 256;
-constexpr int kBK = 64;  // k-bytes per LDS stage
+constexpr int kBK = 128;           // k-bytes per LDS stage
+constexpr int kChunks = kBK / 16;  // 16-byte chunks per LDS row
 
 enum { MODE_DENSE = 0, MODE_CONV_NCHW = 1, MODE_CONV_NHWC = 2 };
 
-struct QgemmParams {
-  const uint8_t* act;
-  const int8_t* wgt;
-  const int32_t* bias;
-  void* out;
-  const int32_t* mult;
-  const int32_t* shift;
-  int32_t M, N, K;
-  int32_t per_channel, has_rq, acc16;
-  int32_t out_mode;    // 0: requantized 8-bit, 1: raw int32, 2: raw int16
-  uint32_t act_xor4;   // 0x80808080 for uint8 activations, else 0
-  int32_t corr_coef;   // off - z_a
-  uint32_t pad_byte;   // staged value of a padded tap: (z_a XOR act_xor) & 0xff
-  int32_t vec_k;       // rows of both operands can be read as aligned 16-byte chunks
-  int32_t vec_out;     // four consecutive results along the packed axis form one aligned store
-  RequantScalars rs;
-  ConvGeom g;
-};
-
-__device__ __forceinline__ int swz(int row, int chunk) {
-  return chunk ^ (((row >> 1) ^ (row >> 3)) & 3);
+__device__ __forceinline__ int lds_off(int row, int chunk) {
+  return row * kBK + ((chunk ^ row ^ (row >> 3)) & (kChunks - 1)) * 16;
 }
-
-__device__ __forceinline__ int lds_off(int row, int chunk) { return row * kBK + swz(row, chunk) * 16; }
 
 // 16 bytes of row `row` of a row-major [ext, K] byte matrix starting at k,
 // zero beyond the matrix.
@@ -122,12 +109,14 @@ __device__ __forceinline__ PixelPos pixel_pos(const ConvGeom& g, int m, int M, b
 __device__ __forceinline__ v4i load_im2col_nchw(const QgemmParams& p, const PixelPos& pp, int k0) {
   const ConvGeom& g = p.g;
   uint32_t d[4] = {0u, 0u, 0u, 0u};
+  if (k0 >= p.K) return v4i{0, 0, 0, 0};
   const int khw = g.KH * g.KW;
   int c = k0 / khw;
   int t = k0 - c * khw;
   int ky = t / g.KW;
   int kx = t - ky * g.KW;
   int koff = (c * g.H + ky) * g.W + kx;
+  const uint32_t xor1 = p.act_xor4 & 0xffu;
 #pragma unroll
   for (int j = 0; j < 16; ++j) {
     uint32_t b = 0;
@@ -135,7 +124,7 @@ __device__ __forceinline__ v4i load_im2col_nchw(const QgemmParams& p, const Pixe
       const int iy = pp.iy0 + ky, ix = pp.ix0 + kx;
       const bool ok = pp.valid && (unsigned)iy < (unsigned)g.H && (unsigned)ix < (unsigned)g.W;
       b = p.pad_byte;
-      if (ok) b = (uint32_t)p.act[pp.base + koff] ^ (p.act_xor4 & 0xffu);
+      if (ok) b = (uint32_t)p.act[pp.base + koff] ^ xor1;
     }
     d[j >> 2] |= b << (8 * (j & 3));
     // advance (c, ky, kx) by one tap
@@ -189,24 +178,32 @@ __device__ __forceinline__ v4i load_im2col_nhwc(const QgemmParams& p, const Pixe
   return v4i{(int)d[0], (int)d[1], (int)d[2], (int)d[3]};
 }
 
-template <int WP, int WQ, int TP, int TQ, int MODE>
-__global__ __launch_bounds__(kThreads) void qgemm_kernel(QgemmParams p) {
-  static_assert(WP * WQ == 4, "four wavefronts per workgroup");
+// VEC: every operand row can be read as aligned 16-byte chunks (dense: K % 16 == 0; NHWC: C % 16
+// == 0).  Then staging loads are unconditional (addresses clamped into the tensor, the value
+// replaced afterwards where it lies outside), so that a whole stage of loads is in flight while
+// the previous stage is multiplied.  Without VEC the loads are assembled bytewise (any shape).
+template <int WP, int WQ, int TP, int TQ, int MODE, bool VEC>
+__global__ __launch_bounds__(64 * WP * WQ) void qgemm_kernel(QgemmParams p) {
+  constexpr int NT = 64 * WP * WQ;
   constexpr int BP = WP * TP * 32;
   constexpr int BQ = WQ * TQ * 32;
-  constexpr int NP = (BP * 4 + kThreads - 1) / kThreads;  // 16-byte chunks per lane per stage
-  constexpr int NQ = (BQ * 4 + kThreads - 1) / kThreads;
+  constexpr int NP = (BP * kChunks + NT - 1) / NT;  // 16-byte chunks per lane per stage
+  constexpr int NQ = (BQ * kChunks + NT - 1) / NT;
   constexpr bool ACT_ON_P = (MODE == MODE_CONV_NCHW);
   constexpr int CH = ACT_ON_P ? BQ : BP;  // output channels covered by the tile
   constexpr int RA = ACT_ON_P ? BP : BQ;  // rows of the activation tile
   constexpr int NA = ACT_ON_P ? NP : NQ;
   constexpr int NW = ACT_ON_P ? NQ : NP;
   constexpr int RW = ACT_ON_P ? BQ : BP;  // rows of the weight tile
+  constexpr int STAGE = (BP + BQ) * kBK;  // bytes of one LDS stage
+  static_assert(MODE == MODE_DENSE || (RA % 64 == 0 && (NT % RA == 0 || RA % NT == 0)),
+                "im2col staging needs a fixed tile row per lane and a uniform chunk per wavefront");
 
-  __shared__ __attribute__((aligned(16))) uint8_t s_tile[2][(BP + BQ) * kBK];
-  __shared__ int32_t s_corr[CH];
-  __shared__ int32_t s_mult[CH];
-  __shared__ int32_t s_shift[CH];
+  extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+  uint8_t* s_tile = smem;  // 2 stages
+  int32_t* s_corr = reinterpret_cast<int32_t*>(smem + 2 * STAGE);
+  int32_t* s_mult = s_corr + CH;
+  int32_t* s_shift = s_mult + CH;
 
   const int t = threadIdx.x;
   const int lane = t & 63;
@@ -217,8 +214,9 @@ __global__ __launch_bounds__(kThreads) void qgemm_kernel(QgemmParams p) {
   const int P_ext = ACT_ON_P ? p.M : p.N;
   const int Q_ext = ACT_ON_P ? p.N : p.M;
   const int tiles_p = (P_ext + BP - 1) / BP;
-  const int tile_p = blockIdx.x % tiles_p;
-  const int tile_q = blockIdx.x / tiles_p;
+  const int tile = xcd_remap(blockIdx.x, gridDim.x);
+  const int tile_p = tile % tiles_p;
+  const int tile_q = tile / tiles_p;
   const int p0 = tile_p * BP;
   const int q0 = tile_q * BQ;
   const int a0 = ACT_ON_P ? p0 : q0;  // first activation row (m) of the tile
@@ -235,52 +233,103 @@ __global__ __launch_bounds__(kThreads) void qgemm_kernel(QgemmParams p) {
 #pragma unroll
   for (int s = 0; s < NW; ++s) wsum[s] = 0;
 
-  auto fetch = [&](int k0) {
+  // fast path: clamped row pointers, computed once
+  const uint8_t* wrow[NW];
+  const uint8_t* arow[NA];
+  bool wrow_ok[NW], arow_ok[NA];
+  if constexpr (VEC) {
 #pragma unroll
     for (int s = 0; s < NW; ++s) {
-      const int q = t + kThreads * s;
-      st_w[s] = v4i{0, 0, 0, 0};
-      if (q < RW * 4) {
-        st_w[s] = load_rowmajor(reinterpret_cast<const uint8_t*>(p.wgt), w0 + (q >> 2), p.N, p.K,
-                                k0 + (q & 3) * 16, p.vec_k);
-        wsum[s] += bytesum(st_w[s]);
+      const int q = t + NT * s;
+      const int row = w0 + q / kChunks;
+      wrow_ok[s] = (q < RW * kChunks) && row < p.N;
+      wrow[s] = reinterpret_cast<const uint8_t*>(p.wgt) + (size_t)(wrow_ok[s] ? row : 0) * p.K +
+                (q % kChunks) * 16;
+    }
+    if constexpr (MODE == MODE_DENSE) {
+#pragma unroll
+      for (int s = 0; s < NA; ++s) {
+        const int q = t + NT * s;
+        const int row = a0 + q / kChunks;
+        arow_ok[s] = (q < RA * kChunks) && row < p.M;
+        arow[s] = p.act + (size_t)(arow_ok[s] ? row : 0) * p.K + (q % kChunks) * 16;
+      }
+    }
+  }
+  const int kmax = p.K - 16;  // last chunk start that is inside a row (VEC: K % 16 == 0, K >= 16)
+
+  auto fetch = [&](int k0) {
+    if constexpr (VEC) {
+#pragma unroll
+      for (int s = 0; s < NW; ++s) {
+        const int kc = k0 + ((t + NT * s) % kChunks) * 16;
+        const int back = kc > kmax ? kc - kmax : 0;  // pull a chunk beyond K back inside the row
+        st_w[s] = *reinterpret_cast<const v4i*>(wrow[s] + k0 - back);
+      }
+    } else {
+#pragma unroll
+      for (int s = 0; s < NW; ++s) {
+        const int q = t + NT * s;
+        st_w[s] = v4i{0, 0, 0, 0};
+        if (q < RW * kChunks)
+          st_w[s] = load_rowmajor(reinterpret_cast<const uint8_t*>(p.wgt), w0 + q / kChunks, p.N,
+                                  p.K, k0 + (q % kChunks) * 16, p.vec_k);
       }
     }
 #pragma unroll
     for (int s = 0; s < NA; ++s) {
-      const int q = t + kThreads * s;
-      st_a[s] = v4i{0, 0, 0, 0};
-      if (q < RA * 4) {
-        if constexpr (MODE == MODE_DENSE) {
-          v4i v = load_rowmajor(p.act, a0 + (q >> 2), p.M, p.K, k0 + (q & 3) * 16, p.vec_k);
-          const int x4 = (int)p.act_xor4;
-          st_a[s] = v4i{v.x ^ x4, v.y ^ x4, v.z ^ x4, v.w ^ x4};
-        } else {
-          // chunk index is uniform over a wavefront (RA is a multiple of 64 or divides it evenly)
-          const int ch = __builtin_amdgcn_readfirstlane(q / RA);
-          if constexpr (MODE == MODE_CONV_NCHW)
-            st_a[s] = load_im2col_nchw(p, pp, k0 + ch * 16);
-          else
-            st_a[s] = load_im2col_nhwc(p, pp, k0 + ch * 16);
+      const int q = t + NT * s;
+      if constexpr (MODE == MODE_DENSE && VEC) {
+        const int kc = k0 + (q % kChunks) * 16;
+        const int back = kc > kmax ? kc - kmax : 0;
+        st_a[s] = *reinterpret_cast<const v4i*>(arow[s] + k0 - back);
+      } else {
+        st_a[s] = v4i{0, 0, 0, 0};
+        if (q < RA * kChunks) {
+          if constexpr (MODE == MODE_DENSE) {
+            st_a[s] = load_rowmajor(p.act, a0 + q / kChunks, p.M, p.K, k0 + (q % kChunks) * 16, p.vec_k);
+          } else {
+            const int ch = __builtin_amdgcn_readfirstlane(q / RA);
+            if constexpr (MODE == MODE_CONV_NCHW)
+              st_a[s] = load_im2col_nchw(p, pp, k0 + ch * 16);
+            else
+              st_a[s] = load_im2col_nhwc(p, pp, k0 + ch * 16);
+          }
         }
       }
     }
   };
 
-  auto stash = [&](int buf) {
-    uint8_t* base = s_tile[buf];
+  // registers -> LDS; the weight row sums and the uint8 -> int8 flip happen here, once per byte
+  auto stash = [&](int buf, int k0) {
+    uint8_t* base = s_tile + buf * STAGE;
 #pragma unroll
     for (int s = 0; s < NW; ++s) {
-      const int q = t + kThreads * s;
-      if (q < RW * 4) *reinterpret_cast<v4i*>(base + w_lds + lds_off(q >> 2, q & 3)) = st_w[s];
+      const int q = t + NT * s;
+      if (q < RW * kChunks) {
+        v4i v = st_w[s];
+        if constexpr (VEC) {
+          if (!(wrow_ok[s] && k0 + (q % kChunks) * 16 < p.K)) v = v4i{0, 0, 0, 0};
+        }
+        wsum[s] += bytesum(v);
+        *reinterpret_cast<v4i*>(base + w_lds + lds_off(q / kChunks, q % kChunks)) = v;
+      }
     }
 #pragma unroll
     for (int s = 0; s < NA; ++s) {
-      const int q = t + kThreads * s;
-      if (q < RA * 4) {
-        const int row = (MODE == MODE_DENSE) ? (q >> 2) : (q % RA);
-        const int ch = (MODE == MODE_DENSE) ? (q & 3) : (q / RA);
-        *reinterpret_cast<v4i*>(base + a_lds + lds_off(row, ch)) = st_a[s];
+      const int q = t + NT * s;
+      if (q < RA * kChunks) {
+        if constexpr (MODE == MODE_DENSE) {
+          const int x4 = (int)p.act_xor4;
+          v4i v = st_a[s];
+          if constexpr (VEC) {
+            if (!(arow_ok[s] && k0 + (q % kChunks) * 16 < p.K)) v = v4i{0, 0, 0, 0};
+          }
+          *reinterpret_cast<v4i*>(base + a_lds + lds_off(q / kChunks, q % kChunks)) =
+              v4i{v.x ^ x4, v.y ^ x4, v.z ^ x4, v.w ^ x4};
+        } else {
+          *reinterpret_cast<v4i*>(base + a_lds + lds_off(q % RA, q / RA)) = st_a[s];
+        }
       }
     }
   };
@@ -296,7 +345,7 @@ __global__ __launch_bounds__(kThreads) void qgemm_kernel(QgemmParams p) {
   const int KT = (p.K + kBK - 1) / kBK;
   if (KT > 0) {
     fetch(0);
-    stash(0);
+    stash(0, 0);
   }
   __syncthreads();
 
@@ -305,9 +354,9 @@ __global__ __launch_bounds__(kThreads) void qgemm_kernel(QgemmParams p) {
   for (int kt = 0; kt < KT; ++kt) {
     const int buf = kt & 1;
     if (kt + 1 < KT) fetch((kt + 1) * kBK);
-    const uint8_t* base = s_tile[buf];
+    const uint8_t* base = s_tile + buf * STAGE;
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
+    for (int ks = 0; ks < kBK / 32; ++ks) {
       v4i pf[TP], qf[TQ];
 #pragma unroll
       for (int i = 0; i < TP; ++i) {
@@ -325,7 +374,7 @@ __global__ __launch_bounds__(kThreads) void qgemm_kernel(QgemmParams p) {
         for (int j = 0; j < TQ; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(pf[i], qf[j], acc[i][j], 0, 0, 0);
     }
-    if (kt + 1 < KT) stash(buf ^ 1);
+    if (kt + 1 < KT) stash(buf ^ 1, (kt + 1) * kBK);
     __syncthreads();
   }
 
@@ -335,154 +384,141 @@ __global__ __launch_bounds__(kThreads) void qgemm_kernel(QgemmParams p) {
     int32_t v = wsum[s];
     v += __shfl_xor(v, 1);
     v += __shfl_xor(v, 2);
-    const int q = t + kThreads * s;
-    if (q < RW * 4 && (q & 3) == 0) s_corr[q >> 2] = v;
+    v += __shfl_xor(v, 4);
+    const int q = t + NT * s;
+    if (q < RW * kChunks && (q % kChunks) == 0) s_corr[q / kChunks] = v;
   }
   __syncthreads();
-  for (int ci = t; ci < CH; ci += kThreads) {
-    const int n = w0 + ci;
-    int32_t corr = 0, mu = 0, sh = 0;
-    if (n < p.N) {
-      corr = (p.bias ? p.bias[n] : 0) + p.corr_coef * s_corr[ci];
-      if (p.has_rq) {
-        mu = p.mult[p.per_channel ? n : 0];
-        sh = p.shift[p.per_channel ? n : 0];
-      }
-    }
-    s_corr[ci] = corr;
-    s_mult[ci] = mu;
-    s_shift[ci] = sh;
-  }
-  __syncthreads();
-
-  // ---- epilogue: requantize and store.  Per lane: column j, rows i0 .. i0+3 per register group.
-  const int ohw = p.g.OH * p.g.OW;
-#pragma unroll
-  for (int tj = 0; tj < TQ; ++tj) {
-    const int j_loc = (wq * TQ + tj) * 32 + frow;
-    const int j = q0 + j_loc;
-#pragma unroll
-    for (int ti = 0; ti < TP; ++ti) {
-#pragma unroll
-      for (int g4 = 0; g4 < 4; ++g4) {
-        const int i_loc = (wp * TP + ti) * 32 + g4 * 8 + fhalf * 4;
-        const int i = p0 + i_loc;
-        int32_t v[4];
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const int ci = ACT_ON_P ? j_loc : i_loc + r;
-          int32_t a = acc[ti][tj][g4 * 4 + r] + s_corr[ci];
-          if (p.acc16) a = (int32_t)(int16_t)a;
-          if (p.has_rq) a = requant_one(a, s_mult[ci], s_shift[ci], p.rs);
-          v[r] = a;
-        }
-        if (j >= Q_ext || i >= P_ext) continue;
-        // flat offset of (i, j) in the output tensor
-        int64_t off;
-        int b = 0, pix = 0;
-        if constexpr (ACT_ON_P) {
-          b = i / ohw;
-          pix = i - b * ohw;
-          off = ((int64_t)b * p.N + j) * ohw + pix;
-        } else {
-          off = (int64_t)j * p.N + i;
-        }
-        if (p.vec_out && i + 3 < P_ext) {
-          if (p.out_mode == 0)
-            *reinterpret_cast<uint32_t*>(static_cast<uint8_t*>(p.out) + off) =
-                pack4(v[0], v[1], v[2], v[3]);
-          else if (p.out_mode == 1)
-            *reinterpret_cast<int4*>(static_cast<int32_t*>(p.out) + off) =
-                make_int4(v[0], v[1], v[2], v[3]);
-          else
-            *reinterpret_cast<short4*>(static_cast<int16_t*>(p.out) + off) =
-                make_short4((short)v[0], (short)v[1], (short)v[2], (short)v[3]);
-        } else {
-#pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            if (i + r >= P_ext) break;
-            int64_t o = off + r;
-            if constexpr (ACT_ON_P) {
-              int pr = pix + r, br = b;
-              while (pr >= ohw) { pr -= ohw; ++br; }
-              o = ((int64_t)br * p.N + j) * ohw + pr;
-            }
-            if (p.out_mode == 0)
-              static_cast<uint8_t*>(p.out)[o] = (uint8_t)v[r];
-            else if (p.out_mode == 1)
-              static_cast<int32_t*>(p.out)[o] = v[r];
-            else
-              static_cast<int16_t*>(p.out)[o] = (int16_t)v[r];
-          }
-        }
-      }
-    }
-  }
+  stage_channel_terms<NT, CH>(p, w0, s_corr, s_mult, s_shift);
+  qgemm_epilogue<WP, WQ, TP, TQ, ACT_ON_P>(p, acc, p0, q0, s_corr, s_mult, s_shift);
 }
 
-QgemmParams make_params(const GemmArgs& a, const ConvGeom* cg) {
-  QgemmParams p{};
-  p.act = static_cast<const uint8_t*>(a.act);
-  p.wgt = a.wgt;
-  p.bias = a.bias;
-  p.out = a.out;
-  p.mult = a.rq.multiplier;
-  p.shift = a.rq.shift;
-  p.M = a.M; p.N = a.N; p.K = a.K;
-  p.per_channel = a.rq.per_channel;
-  p.has_rq = a.has_rq;
-  p.acc16 = a.acc16;
-  p.out_mode = a.has_rq ? 0 : (a.acc16 ? 2 : 1);
-  p.act_xor4 = a.act_unsigned ? 0x80808080u : 0u;
-  p.corr_coef = (a.act_unsigned ? 128 : 0) - a.act_zero_point;
-  p.pad_byte = ((uint32_t)a.act_zero_point ^ (a.act_unsigned ? 0x80u : 0u)) & 0xffu;
-  p.rs = RequantScalars{a.rq.z_out, a.rq.clip_lo - a.rq.z_out, a.rq.clip_hi - a.rq.z_out};
-  if (cg) p.g = *cg;
-  return p;
-}
+// ---- tile shapes ---------------------------------------------------------------------------
+// A shape is (WP, WQ, TP, TQ): wavefronts along P and Q, 32x32 sub-tiles per wavefront.
+struct TileShape { int wp, wq, tp, tq; };
+constexpr TileShape kShapes[] = {
+    {2, 2, 2, 4},  // 0: 128 x 256
+    {2, 2, 4, 2},  // 1: 256 x 128
+    {2, 2, 2, 2},  // 2: 128 x 128
+    {1, 4, 1, 2},  // 3:  32 x 256
+    {4, 1, 2, 1},  // 4: 256 x  32
+    {2, 2, 1, 2},  // 5:  64 x 128
+    {2, 2, 2, 1},  // 6: 128 x  64
+};
+constexpr int kNumShapes = sizeof(kShapes) / sizeof(kShapes[0]);
 
-inline bool aligned(const void* ptr, size_t n) { return (reinterpret_cast<uintptr_t>(ptr) & (n - 1)) == 0; }
-
-inline size_t out_elem_size(const GemmArgs& a) { return a.has_rq ? 1 : (a.acc16 ? 2 : 4); }
-
-template <int WP, int WQ, int TP, int TQ, int MODE>
+template <int WP, int WQ, int TP, int TQ, int MODE, bool VEC>
 hipError_t launch_cfg(const QgemmParams& p, hipStream_t st) {
   constexpr int BP = WP * TP * 32, BQ = WQ * TQ * 32;
+  constexpr int CH = (MODE == MODE_CONV_NCHW) ? BQ : BP;
+  constexpr size_t lds = 2 * (size_t)(BP + BQ) * kBK + 3 * CH * sizeof(int32_t);
   const int P_ext = (MODE == MODE_CONV_NCHW) ? p.M : p.N;
   const int Q_ext = (MODE == MODE_CONV_NCHW) ? p.N : p.M;
   const int64_t tiles = (int64_t)((P_ext + BP - 1) / BP) * ((Q_ext + BQ - 1) / BQ);
-  hipLaunchKernelGGL((qgemm_kernel<WP, WQ, TP, TQ, MODE>), dim3((unsigned)tiles), dim3(kThreads), 0,
-                     st, p);
+  auto kern = qgemm_kernel<WP, WQ, TP, TQ, MODE, VEC>;
+  static bool attr_set = false;  // raising the dynamic-LDS limit is needed once per kernel
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, dim3((unsigned)tiles), dim3(64 * WP * WQ), lds, st, p);
   return hipGetLastError();
+}
+
+// Whether a shape can be instantiated for a mode (im2col staging wants a fixed tile row per
+// lane and a wavefront-uniform chunk).
+constexpr bool shape_ok(int mode, int wp, int wq, int tp, int tq) {
+  if (mode == MODE_DENSE) return true;
+  const int nt = 64 * wp * wq;
+  const int ra = (mode == MODE_CONV_NCHW) ? wp * tp * 32 : wq * tq * 32;
+  return ra % 64 == 0 && (nt % ra == 0 || ra % nt == 0);
+}
+
+template <int MODE, int I>
+hipError_t launch_shape_rec(int shape, const QgemmParams& p, hipStream_t st) {
+  if constexpr (I >= kNumShapes) {
+    return launch_cfg<2, 2, 2, 2, MODE, false>(p, st);
+  } else {
+    constexpr TileShape s = kShapes[I];
+    if constexpr (shape_ok(MODE, s.wp, s.wq, s.tp, s.tq)) {
+      if (shape == I) return launch_cfg<s.wp, s.wq, s.tp, s.tq, MODE, MODE == MODE_DENSE>(p, st);
+    }
+    return launch_shape_rec<MODE, I + 1>(shape, p, st);
+  }
+}
+
+template <int MODE>
+hipError_t launch_shape(int shape, const QgemmParams& p, hipStream_t st) {
+  return launch_shape_rec<MODE, 0>(shape, p, st);
+}
+
+// Estimated cycles of the slowest CU for a tile shape: tiles are spread over 256 CUs; a tile
+// costs the larger of its MFMA time and its L1 time, plus the requantize epilogue.
+double shape_cost(const TileShape& s, int64_t P_ext, int64_t Q_ext, int64_t K) {
+  const int64_t bp = s.wp * s.tp * 32, bq = s.wq * s.tq * 32;
+  const int64_t tiles = ((P_ext + bp - 1) / bp) * ((Q_ext + bq - 1) / bq);
+  const double rounds = (double)((tiles + 255) / 256);
+  const double kk = (double)((K + kBK - 1) / kBK * kBK);
+  const double mfma = (double)bp * bq * kk / 4096.0 / 0.85;
+  const double l1 = (double)(bp + bq) * kk / 52.0;
+  const double lds_rate = 128.0 * (s.tp + s.tq) / (double)(s.tp * s.tq);  // bytes per clock needed
+  const double lds = mfma * (lds_rate > 110.0 ? lds_rate / 110.0 : 1.0);
+  const double main = mfma > l1 ? (mfma > lds ? mfma : lds) : (l1 > lds ? l1 : lds);
+  const double epi = (double)bp * bq / (64.0 * s.wp * s.wq) * 36.0 / 4.0 * 4.0;
+  return rounds * (main + epi + 1500.0);
+}
+
+int pick_shape(int mode, int64_t P_ext, int64_t Q_ext, int64_t K) {
+  const char* env = std::getenv("HAGO_QGEMM_SHAPE");  // tuning override
+  if (env && *env) {
+    const int v = std::atoi(env);
+    if (v >= 0 && v < kNumShapes &&
+        shape_ok(mode, kShapes[v].wp, kShapes[v].wq, kShapes[v].tp, kShapes[v].tq))
+      return v;
+  }
+  int best = 2;
+  double best_cost = 1e300;
+  for (int i = 0; i < kNumShapes; ++i) {
+    if (!shape_ok(mode, kShapes[i].wp, kShapes[i].wq, kShapes[i].tp, kShapes[i].tq)) continue;
+    const double c = shape_cost(kShapes[i], P_ext, Q_ext, K);
+    if (c < best_cost) { best_cost = c; best = i; }
+  }
+  return best;
 }
 
 }  // namespace
 
+hipError_t launch_qdense_dma(const QgemmParams& p, int shape, hipStream_t st);
+
 hipError_t launch_qdense(const GemmArgs& a, hipStream_t st) {
   if (a.M == 0 || a.N == 0) return hipSuccess;
-  QgemmParams p = make_params(a, nullptr);
-  p.vec_k = (a.K % 16 == 0) && aligned(a.act, 16) && aligned(a.wgt, 16);
-  p.vec_out = (a.N % 4 == 0) && aligned(a.out, 4 * out_elem_size(a));
-  if (a.N <= 32) return launch_cfg<1, 4, 1, 2, MODE_DENSE>(p, st);   // 32 x 256
-  if (a.N <= 64) return launch_cfg<2, 2, 1, 2, MODE_DENSE>(p, st);   // 64 x 128
-  return launch_cfg<2, 2, 2, 2, MODE_DENSE>(p, st);                  // 128 x 128
+  QgemmParams p = make_qgemm_params(a, nullptr);
+  p.vec_k = (a.K % 16 == 0) && ptr_aligned(a.act, 16) && ptr_aligned(a.wgt, 16);
+  p.vec_out = (a.N % 4 == 0) && ptr_aligned(a.out, 4 * qgemm_out_elem_size(a));
+  p.vec16_out = (a.N % 16 == 0) && ptr_aligned(a.out, 16);
+  if (!p.vec_k || a.K < 16) return launch_cfg<2, 2, 2, 2, MODE_DENSE, false>(p, st);
+  const char* env = std::getenv("HAGO_QGEMM_PATH");  // tuning override: "reg" forces the generic kernel
+  const bool fits32 = (int64_t)a.N * a.K < (1ll << 31) && (int64_t)a.M * a.K < (1ll << 31);
+  if (fits32 && !(env && env[0] == 'r')) {
+    const char* sh = std::getenv("HAGO_DMA_SHAPE");
+    return launch_qdense_dma(p, sh ? std::atoi(sh) : 0, st);
+  }
+  return launch_shape<MODE_DENSE>(pick_shape(MODE_DENSE, a.N, a.M, a.K), p, st);
 }
 
 hipError_t launch_qconv_gemm(const GemmArgs& a, const ConvGeom& cg, hipStream_t st) {
   if (a.M == 0 || a.N == 0) return hipSuccess;
-  QgemmParams p = make_params(a, &cg);
+  QgemmParams p = make_qgemm_params(a, &cg);
   if (cg.nhwc) {
-    p.vec_k = (cg.C % 16 == 0) && aligned(a.act, 16) && aligned(a.wgt, 16);
-    p.vec_out = (a.N % 4 == 0) && aligned(a.out, 4 * out_elem_size(a));
-    if (a.N <= 32) return launch_cfg<1, 4, 1, 2, MODE_CONV_NHWC>(p, st);
-    if (a.N <= 64) return launch_cfg<2, 2, 1, 2, MODE_CONV_NHWC>(p, st);
-    return launch_cfg<2, 2, 2, 2, MODE_CONV_NHWC>(p, st);
+    p.vec_k = (cg.C % 16 == 0) && ptr_aligned(a.act, 16) && ptr_aligned(a.wgt, 16);
+    p.vec_out = (a.N % 4 == 0) && ptr_aligned(a.out, 4 * qgemm_out_elem_size(a));
+    return launch_shape<MODE_CONV_NHWC>(pick_shape(MODE_CONV_NHWC, a.N, a.M, a.K), p, st);
   }
-  p.vec_k = (a.K % 16 == 0) && aligned(a.wgt, 16);
-  p.vec_out = ((cg.OH * cg.OW) % 4 == 0) && aligned(a.out, 4 * out_elem_size(a));
-  if (a.N <= 32) return launch_cfg<4, 1, 2, 1, MODE_CONV_NCHW>(p, st);   // 256 pixels x 32 channels
-  if (a.N <= 64) return launch_cfg<2, 2, 2, 1, MODE_CONV_NCHW>(p, st);   // 128 x 64
-  return launch_cfg<2, 2, 2, 2, MODE_CONV_NCHW>(p, st);                  // 128 x 128
+  p.vec_k = (a.K % 16 == 0) && ptr_aligned(a.wgt, 16);
+  p.vec_out = ((cg.OH * cg.OW) % 4 == 0) && ptr_aligned(a.out, 4 * qgemm_out_elem_size(a));
+  return launch_shape<MODE_CONV_NCHW>(pick_shape(MODE_CONV_NCHW, a.M, a.N, a.K), p, st);
 }
 
 }  // namespace hago

@@ -1,0 +1,399 @@
+// Pieces shared by the two int8-MFMA GEMM kernels (register-staged generic
+// kernel and the LDS-DMA dense kernel): launch parameters, the per-tile
+// channel terms and the requantize/store epilogue.
+#pragma once
+
+#include "hago_device.h"
+#include "launch.h"
+
+#include <cstdlib>
+
+namespace hago {
+
+#ifdef HAGO_PHASE_TIMING
+#define HAGO_STAMP(p, i) do { if (threadIdx.x == 0 && (p).dbg) (p).dbg[blockIdx.x * 8 + (i)] = __builtin_readcyclecounter(); } while (0)
+#else
+#define HAGO_STAMP(p, i) do { } while (0)
+#endif
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+struct QgemmParams {
+  const uint8_t* act;
+  const int8_t* wgt;
+  const int32_t* bias;
+  void* out;
+  const int32_t* mult;
+  const int32_t* shift;
+  int32_t M, N, K;
+  int32_t per_channel, has_rq, acc16;
+  int32_t out_mode;    // 0: requantized 8-bit, 1: raw int32, 2: raw int16
+  uint32_t act_xor4;   // 0x80808080 for uint8 activations, else 0
+  int32_t corr_coef;   // off - z_a
+  uint32_t pad_byte;   // staged value of a padded tap: (z_a XOR act_xor) & 0xff
+  int32_t vec_k;       // rows of both operands can be read as aligned 16-byte chunks
+  int32_t vec_out;     // four consecutive results along the packed axis form one aligned store
+  int32_t vec16_out;   // dense: output rows can be written as aligned 16-byte pieces
+  RequantScalars rs;
+  ConvGeom g;
+#ifdef HAGO_PHASE_TIMING
+  long long* dbg;  // per-workgroup phase timestamps (development builds only)
+#endif
+};
+
+inline QgemmParams make_qgemm_params(const GemmArgs& a, const ConvGeom* cg) {
+  QgemmParams p{};
+  p.act = static_cast<const uint8_t*>(a.act);
+  p.wgt = a.wgt;
+  p.bias = a.bias;
+  p.out = a.out;
+  p.mult = a.rq.multiplier;
+  p.shift = a.rq.shift;
+  p.M = a.M; p.N = a.N; p.K = a.K;
+  p.per_channel = a.rq.per_channel;
+  p.has_rq = a.has_rq;
+  p.acc16 = a.acc16;
+  p.out_mode = a.has_rq ? 0 : (a.acc16 ? 2 : 1);
+  p.act_xor4 = a.act_unsigned ? 0x80808080u : 0u;
+  p.corr_coef = (a.act_unsigned ? 128 : 0) - a.act_zero_point;
+  p.pad_byte = ((uint32_t)a.act_zero_point ^ (a.act_unsigned ? 0x80u : 0u)) & 0xffu;
+  p.rs = RequantScalars{a.rq.z_out, a.rq.clip_lo - a.rq.z_out, a.rq.clip_hi - a.rq.z_out};
+  if (cg) p.g = *cg;
+#ifdef HAGO_PHASE_TIMING
+  {
+    const char* e = std::getenv("HAGO_DBG_PTR");
+    p.dbg = e ? reinterpret_cast<long long*>(std::strtoull(e, nullptr, 0)) : nullptr;
+  }
+#endif
+  return p;
+}
+
+inline bool ptr_aligned(const void* ptr, size_t n) {
+  return (reinterpret_cast<uintptr_t>(ptr) & (n - 1)) == 0;
+}
+inline size_t qgemm_out_elem_size(const GemmArgs& a) { return a.has_rq ? 1 : (a.acc16 ? 2 : 4); }
+
+// Workgroups are handed to the 8 XCDs round-robin; remap so that the tiles an
+// XCD works on are consecutive (they then share operand panels in its L2).
+__device__ __forceinline__ int xcd_remap(int bid, int ntiles) {
+  const int x = bid & 7, slot = bid >> 3;
+  const int q = ntiles >> 3, r = ntiles & 7;
+  return x * q + (x < r ? x : r) + slot;
+}
+
+// Turn the weight row sums that sit in s_corr[0..CH) into the per-channel
+// terms of the tile: corr = bias + (off - z_a) * sum_k w, multiplier, shift.
+// Channels beyond N get zeros.  Ends with a barrier.
+template <int NT, int CH>
+__device__ __forceinline__ void stage_channel_terms(const QgemmParams& p, int w0, int32_t* s_corr,
+                                                    int32_t* s_mult, int32_t* s_shift) {
+  const int t = threadIdx.x;
+  for (int ci = t; ci < CH; ci += NT) {
+    const int n = w0 + ci;
+    int32_t corr = 0, mu = 0, sh = 0;
+    if (n < p.N) {
+      corr = (p.bias ? p.bias[n] : 0) + p.corr_coef * s_corr[ci];
+      if (p.has_rq) {
+        mu = p.mult[p.per_channel ? n : 0];
+        sh = p.shift[p.per_channel ? n : 0];
+      }
+    }
+    s_corr[ci] = corr;
+    s_mult[ci] = mu;
+    s_shift[ci] = sh;
+  }
+  __syncthreads();
+}
+
+// Per-channel epilogue inputs fetched at kernel start (so that their latency hides
+// behind the main loop); one slot per channel this lane is responsible for.
+template <int NT, int CH>
+struct ChannelRegs {
+  static constexpr int kSlots = (CH + NT - 1) / NT;
+  int32_t bias[kSlots], mult[kSlots], shift[kSlots];
+};
+
+template <int NT, int CH>
+__device__ __forceinline__ void load_channel_regs(const QgemmParams& p, int w0, ChannelRegs<NT, CH>& r) {
+#pragma unroll
+  for (int s = 0; s < ChannelRegs<NT, CH>::kSlots; ++s) {
+    const int ci = (int)threadIdx.x + NT * s;
+    const int n = w0 + ci;
+    r.bias[s] = 0; r.mult[s] = 0; r.shift[s] = 1;
+    if (ci < CH && n < p.N) {
+      if (p.bias) r.bias[s] = p.bias[n];
+      if (p.has_rq) {
+        r.mult[s] = p.mult[p.per_channel ? n : 0];
+        r.shift[s] = p.shift[p.per_channel ? n : 0];
+      }
+    }
+  }
+}
+
+// s_corr holds the weight row sums on entry; on exit s_corr/s_mult/s_shift hold the
+// per-channel terms.  Returns (block-uniform) whether some channel of the tile has shift 0.
+template <int NT, int CH>
+__device__ __forceinline__ bool finish_channel_terms(const QgemmParams& p, const ChannelRegs<NT, CH>& r,
+                                                     int32_t* s_corr, int32_t* s_mult,
+                                                     int32_t* s_shift) {
+  int any0 = 0;
+#pragma unroll
+  for (int s = 0; s < ChannelRegs<NT, CH>::kSlots; ++s) {
+    const int ci = (int)threadIdx.x + NT * s;
+    if (ci < CH) {
+      s_corr[ci] = r.bias[s] + p.corr_coef * s_corr[ci];
+      s_mult[ci] = r.mult[s];
+      s_shift[ci] = r.shift[s];
+      any0 |= (r.shift[s] == 0);
+    }
+  }
+  return __syncthreads_or(any0) != 0;
+}
+
+// r = floor((a * m + 2^(30+sh)) / 2^(31+sh)).  With SH_GE1 (sh >= 1) the shift
+// distance is at least 32, so the result is the high dword shifted by sh - 1:
+// one 32-bit shift instead of a 64-bit one.
+template <bool SH_GE1>
+__device__ __forceinline__ int32_t mul_shift_fast(int32_t a, int32_t m, int64_t rnd, int32_t sh) {
+  const int64_t pr = (int64_t)a * (int64_t)m + rnd;
+  if constexpr (SH_GE1) return (int32_t)(pr >> 32) >> (sh - 1);
+  return (int32_t)(pr >> (31 + sh));
+}
+
+// Dense epilogue of an interior tile through LDS: requantize, pack four channels
+// per dword, write the tile to LDS in output order [row m][channel n], then copy
+// it out with 16-byte stores that cover whole output rows.  s_out: BQ * BP bytes.
+template <int WP, int WQ, int TP, int TQ, bool SH_GE1>
+__device__ __forceinline__ void qgemm_epilogue_dense_staged(const QgemmParams& p,
+                                                            v16i (&acc)[TP][TQ], int p0, int q0,
+                                                            const int32_t* s_corr,
+                                                            const int32_t* s_mult,
+                                                            const int32_t* s_shift,
+                                                            uint8_t* s_out) {
+  constexpr int NT = 64 * WP * WQ;
+  constexpr int BP = WP * TP * 32, BQ = WQ * TQ * 32;
+  constexpr int CPR = BP / 16;  // 16-byte chunks per tile row
+  static_assert((CPR & (CPR - 1)) == 0, "chunk swizzle needs a power-of-two row");
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int wp = wave % WP, wq = wave / WP;
+  const int frow = lane & 31, fhalf = lane >> 5;
+  const int32_t lo = p.rs.lo_rel, hi = p.rs.hi_rel, z = p.rs.z_out;
+#pragma unroll
+  for (int ti = 0; ti < TP; ++ti) {
+#pragma unroll
+    for (int g4 = 0; g4 < 4; ++g4) {
+      const int i_loc = (wp * TP + ti) * 32 + g4 * 8 + fhalf * 4;
+      const int4 c4 = *reinterpret_cast<const int4*>(s_corr + i_loc);
+      const int4 m4 = *reinterpret_cast<const int4*>(s_mult + i_loc);
+      const int4 s4 = *reinterpret_cast<const int4*>(s_shift + i_loc);
+      const int64_t rn0 = (int64_t)1 << (30 + s4.x), rn1 = (int64_t)1 << (30 + s4.y);
+      const int64_t rn2 = (int64_t)1 << (30 + s4.z), rn3 = (int64_t)1 << (30 + s4.w);
+#pragma unroll
+      for (int tj = 0; tj < TQ; ++tj) {
+        const int row = (wq * TQ + tj) * 32 + frow;
+        int32_t r0 = mul_shift_fast<SH_GE1>(acc[ti][tj][g4 * 4 + 0] + c4.x, m4.x, rn0, s4.x);
+        int32_t r1 = mul_shift_fast<SH_GE1>(acc[ti][tj][g4 * 4 + 1] + c4.y, m4.y, rn1, s4.y);
+        int32_t r2 = mul_shift_fast<SH_GE1>(acc[ti][tj][g4 * 4 + 2] + c4.z, m4.z, rn2, s4.z);
+        int32_t r3 = mul_shift_fast<SH_GE1>(acc[ti][tj][g4 * 4 + 3] + c4.w, m4.w, rn3, s4.w);
+        r0 = med3(r0, lo, hi); r1 = med3(r1, lo, hi); r2 = med3(r2, lo, hi); r3 = med3(r3, lo, hi);
+        if (z != 0) { r0 += z; r1 += z; r2 += z; r3 += z; }
+        const int chunk = (i_loc >> 4) ^ (row & (CPR - 1));
+        *reinterpret_cast<uint32_t*>(s_out + row * BP + chunk * 16 + (i_loc & 12)) =
+            pack4_perm(r0, r1, r2, r3);
+      }
+    }
+  }
+  __syncthreads();
+  HAGO_STAMP(p, 5);
+  uint8_t* out8 = static_cast<uint8_t*>(p.out);
+#pragma unroll
+  for (int s = 0; s < (BQ * CPR) / NT; ++s) {
+    const int q = (int)threadIdx.x + NT * s;
+    const int row = q / CPR, c = q % CPR;
+    const v4i v = *reinterpret_cast<const v4i*>(s_out + row * BP + ((c ^ (row & (CPR - 1))) * 16));
+    *reinterpret_cast<v4i*>(out8 + (size_t)(q0 + row) * p.N + p0 + c * 16) = v;
+  }
+  HAGO_STAMP(p, 6);
+}
+
+// Straight-line epilogue of an interior tile whose packed stores are aligned.
+// OM: 0 requantized 8-bit, 1 raw int32, 2 raw int16.
+template <int OM>
+__device__ __forceinline__ void store_group(void* out, size_t off, int32_t v0, int32_t v1,
+                                            int32_t v2, int32_t v3) {
+  if constexpr (OM == 0)
+    *reinterpret_cast<uint32_t*>(static_cast<uint8_t*>(out) + off) = pack4(v0, v1, v2, v3);
+  else if constexpr (OM == 1)
+    *reinterpret_cast<int4*>(static_cast<int32_t*>(out) + off) = make_int4(v0, v1, v2, v3);
+  else
+    *reinterpret_cast<short4*>(static_cast<int16_t*>(out) + off) =
+        make_short4((short)v0, (short)v1, (short)v2, (short)v3);
+}
+
+template <int OM>
+__device__ __forceinline__ int32_t finish_one(int32_t a, int32_t m, int32_t sh, bool acc16,
+                                              const RequantScalars& rs) {
+  if (acc16) a = (int32_t)(int16_t)a;
+  if constexpr (OM == 0) a = requant_one(a, m, sh, rs);
+  return a;
+}
+
+template <int WP, int WQ, int TP, int TQ, bool ACT_ON_P, int OM>
+__device__ __forceinline__ void qgemm_epilogue_fast(const QgemmParams& p, v16i (&acc)[TP][TQ],
+                                                    int p0, int q0, const int32_t* s_corr,
+                                                    const int32_t* s_mult,
+                                                    const int32_t* s_shift) {
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int wp = wave % WP, wq = wave / WP;
+  const int frow = lane & 31, fhalf = lane >> 5;
+  const RequantScalars rs = p.rs;
+  const bool acc16 = p.acc16 != 0;
+  if constexpr (!ACT_ON_P) {
+#pragma unroll
+    for (int ti = 0; ti < TP; ++ti) {
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        const int i_loc = (wp * TP + ti) * 32 + g4 * 8 + fhalf * 4;
+        const int4 c4 = *reinterpret_cast<const int4*>(s_corr + i_loc);
+        const int4 m4 = *reinterpret_cast<const int4*>(s_mult + i_loc);
+        const int4 s4 = *reinterpret_cast<const int4*>(s_shift + i_loc);
+#pragma unroll
+        for (int tj = 0; tj < TQ; ++tj) {
+          const int j = q0 + (wq * TQ + tj) * 32 + frow;
+          const int32_t r0 = finish_one<OM>(acc[ti][tj][g4 * 4 + 0] + c4.x, m4.x, s4.x, acc16, rs);
+          const int32_t r1 = finish_one<OM>(acc[ti][tj][g4 * 4 + 1] + c4.y, m4.y, s4.y, acc16, rs);
+          const int32_t r2 = finish_one<OM>(acc[ti][tj][g4 * 4 + 2] + c4.z, m4.z, s4.z, acc16, rs);
+          const int32_t r3 = finish_one<OM>(acc[ti][tj][g4 * 4 + 3] + c4.w, m4.w, s4.w, acc16, rs);
+          store_group<OM>(p.out, (size_t)j * p.N + (p0 + i_loc), r0, r1, r2, r3);
+        }
+      }
+    }
+  } else {
+    const int ohw = p.g.OH * p.g.OW;
+#pragma unroll
+    for (int tj = 0; tj < TQ; ++tj) {
+      const int j_loc = (wq * TQ + tj) * 32 + frow;
+      const int j = q0 + j_loc;
+      const int32_t c = s_corr[j_loc], m = s_mult[j_loc], sh = s_shift[j_loc];
+#pragma unroll
+      for (int ti = 0; ti < TP; ++ti) {
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4) {
+          const int i = p0 + (wp * TP + ti) * 32 + g4 * 8 + fhalf * 4;
+          const int b = i / ohw;
+          const int pix = i - b * ohw;
+          const int32_t r0 = finish_one<OM>(acc[ti][tj][g4 * 4 + 0] + c, m, sh, acc16, rs);
+          const int32_t r1 = finish_one<OM>(acc[ti][tj][g4 * 4 + 1] + c, m, sh, acc16, rs);
+          const int32_t r2 = finish_one<OM>(acc[ti][tj][g4 * 4 + 2] + c, m, sh, acc16, rs);
+          const int32_t r3 = finish_one<OM>(acc[ti][tj][g4 * 4 + 3] + c, m, sh, acc16, rs);
+          store_group<OM>(p.out, ((size_t)b * p.N + j) * ohw + pix, r0, r1, r2, r3);
+        }
+      }
+    }
+  }
+}
+
+// Epilogue of one workgroup tile.  acc[ti][tj] is the 32x32 MFMA result of
+// sub-tile (ti, tj) of this wavefront: lane l owns column j = l % 32 and, in
+// registers 4g .. 4g+3, rows 8g + 4*(l / 32) + 0..3.
+//   ACT_ON_P == false (dense, NHWC): i = output channel n, j = row m, out[m*N + n]
+//   ACT_ON_P == true  (NCHW)       : i = pixel m, j = channel n, out[(b*N + n)*OHW + pix]
+// Interior tiles of the common case (8-bit requantized output, int32
+// accumulation, aligned packed stores) take a straight-line path; everything
+// else goes through the bounds-checked generic path.
+template <int WP, int WQ, int TP, int TQ, bool ACT_ON_P>
+__device__ __forceinline__ void qgemm_epilogue(const QgemmParams& p, v16i (&acc)[TP][TQ], int p0,
+                                               int q0, const int32_t* s_corr,
+                                               const int32_t* s_mult, const int32_t* s_shift) {
+  constexpr int BP = WP * TP * 32, BQ = WQ * TQ * 32;
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int wp = wave % WP, wq = wave / WP;
+  const int frow = lane & 31, fhalf = lane >> 5;
+  const int P_ext = ACT_ON_P ? p.M : p.N;
+  const int Q_ext = ACT_ON_P ? p.N : p.M;
+  const int ohw = p.g.OH * p.g.OW;
+  const bool fast = p.vec_out && p0 + BP <= P_ext && q0 + BQ <= Q_ext;
+
+  if (fast) {
+    if (p.out_mode == 0)
+      qgemm_epilogue_fast<WP, WQ, TP, TQ, ACT_ON_P, 0>(p, acc, p0, q0, s_corr, s_mult, s_shift);
+    else if (p.out_mode == 1)
+      qgemm_epilogue_fast<WP, WQ, TP, TQ, ACT_ON_P, 1>(p, acc, p0, q0, s_corr, s_mult, s_shift);
+    else
+      qgemm_epilogue_fast<WP, WQ, TP, TQ, ACT_ON_P, 2>(p, acc, p0, q0, s_corr, s_mult, s_shift);
+    return;
+  }
+
+  // ---- generic path: any output mode, partial tiles, unaligned outputs
+#pragma unroll 1
+  for (int tj = 0; tj < TQ; ++tj) {
+    const int j_loc = (wq * TQ + tj) * 32 + frow;
+    const int j = q0 + j_loc;
+#pragma unroll
+    for (int ti = 0; ti < TP; ++ti) {
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        const int i_loc = (wp * TP + ti) * 32 + g4 * 8 + fhalf * 4;
+        const int i = p0 + i_loc;
+        int32_t v[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int ci = ACT_ON_P ? j_loc : i_loc + r;
+          // acc[..][tj] with a runtime tj would need dynamic register indexing; select instead
+          int32_t raw = 0;
+#pragma unroll
+          for (int x = 0; x < TQ; ++x) raw = (x == tj) ? acc[ti][x][g4 * 4 + r] : raw;
+          int32_t a = raw + s_corr[ci];
+          if (p.acc16) a = (int32_t)(int16_t)a;
+          if (p.has_rq) a = requant_one(a, s_mult[ci], s_shift[ci], p.rs);
+          v[r] = a;
+        }
+        if (j >= Q_ext || i >= P_ext) continue;
+        // flat offset of (i, j) in the output tensor
+        int64_t off;
+        int b = 0, pix = 0;
+        if constexpr (ACT_ON_P) {
+          b = i / ohw;
+          pix = i - b * ohw;
+          off = ((int64_t)b * p.N + j) * ohw + pix;
+        } else {
+          off = (int64_t)j * p.N + i;
+        }
+        if (p.vec_out && i + 3 < P_ext) {
+          if (p.out_mode == 0)
+            *reinterpret_cast<uint32_t*>(static_cast<uint8_t*>(p.out) + off) =
+                pack4(v[0], v[1], v[2], v[3]);
+          else if (p.out_mode == 1)
+            *reinterpret_cast<int4*>(static_cast<int32_t*>(p.out) + off) =
+                make_int4(v[0], v[1], v[2], v[3]);
+          else
+            *reinterpret_cast<short4*>(static_cast<int16_t*>(p.out) + off) =
+                make_short4((short)v[0], (short)v[1], (short)v[2], (short)v[3]);
+        } else {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            if (i + r >= P_ext) break;
+            int64_t o = off + r;
+            if constexpr (ACT_ON_P) {
+              int pr = pix + r, br = b;
+              while (pr >= ohw) { pr -= ohw; ++br; }
+              o = ((int64_t)br * p.N + j) * ohw + pr;
+            }
+            if (p.out_mode == 0)
+              static_cast<uint8_t*>(p.out)[o] = (uint8_t)v[r];
+            else if (p.out_mode == 1)
+              static_cast<int32_t*>(p.out)[o] = v[r];
+            else
+              static_cast<int16_t*>(p.out)[o] = (int16_t)v[r];
+          }
+        }
+      }
+    }
+  }
+}
+
+}  // namespace hago

@@ -1,0 +1,274 @@
+// Dense int8 GEMM, fast path: operands stream from global memory straight
+// into LDS (buffer_load ... lds, 16 bytes per lane), four 64-byte k-stages
+// deep, so no vector registers and no LDS-write instructions are spent on
+// staging and three stages of loads are always in flight behind the one
+// being multiplied.
+//
+// Layout.  D[i][j] = sum_k P[i][k] Q[j][k] with P = weights [N,K] (i = output
+// channel, contiguous in the output) and Q = activations [M,K].  A stage holds
+// BP + BQ rows of 64 bytes.  One DMA instruction of a wavefront fills 1024
+// contiguous LDS bytes = 16 rows x four 16-byte slots; the lane that owns slot
+// (row, s) fetches the logical chunk s ^ f(row) of that row from memory, which
+// realises the bank swizzle on the global side because the LDS side of the DMA
+// is fixed (lane l -> byte l * 16).
+//
+// Out-of-range data.  Every load goes through a buffer descriptor whose size
+// is the tensor's exact byte count, and lanes whose row or k lies outside the
+// matrix are given an offset beyond it: the hardware then writes zeros to LDS.
+// Zero weights make the padded k contribute nothing; padded rows are never
+// stored.
+//
+// uint8 activations and the zero point are handled on the fragments: the
+// activation fragment is XORed with 0x80 per byte after it is read from LDS,
+// and the weight row sums needed for the zero-point term are accumulated from
+// the weight fragments with v_dot4 (see qgemm.hip for the identity).
+//
+// Synchronisation per stage: s_waitcnt vmcnt(2*L) (L = DMA instructions per
+// wavefront per stage; two younger stages may stay in flight), one barrier
+// (everybody's part of the stage has landed and everybody is done with the
+// buffer that is refilled next), issue the loads three stages ahead, multiply.
+#include "qgemm_common.h"
+
+#include <cstdlib>
+
+namespace hago {
+
+namespace {
+
+constexpr int kBK = 64;       // k-bytes per stage
+constexpr int kStages = 4;    // LDS ring
+constexpr uint32_t kOob = 0x80000000u;  // offset beyond any tensor (sizes are < 2^31 bytes)
+
+__device__ __forceinline__ int swz4(int row) { return ((row >> 1) ^ (row >> 3)) & 3; }
+
+__device__ __forceinline__ void dma16(v4i rsrc, uint32_t lds_addr, uint32_t voff) {
+  // m0 = LDS byte address of the wavefront's 1 KB window; lane l lands at m0 + 16 * l
+  asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+               :
+               : "s"(lds_addr), "v"(voff), "s"(rsrc)
+               : "memory");
+}
+
+__device__ __forceinline__ v4i make_rsrc(const void* base, uint32_t bytes) {
+  const uint64_t a = reinterpret_cast<uint64_t>(base);
+  v4i r;
+  r.x = __builtin_amdgcn_readfirstlane((int)(uint32_t)a);
+  r.y = __builtin_amdgcn_readfirstlane((int)(uint32_t)(a >> 32));  // stride 0, no swizzle
+  r.z = __builtin_amdgcn_readfirstlane((int)bytes);
+  r.w = 0x00020000;  // raw buffer, 32-bit data format
+  return r;
+}
+
+template <int WP, int WQ, int TP, int TQ>
+__global__ __launch_bounds__(64 * WP * WQ) void qgemm_dma_kernel(QgemmParams p) {
+  constexpr int NW = WP * WQ;          // wavefronts
+  constexpr int NT = 64 * NW;
+  constexpr int BP = WP * TP * 32;
+  constexpr int BQ = WQ * TQ * 32;
+  constexpr int STAGE = (BP + BQ) * kBK;
+  constexpr int GP = BP / 16, GQ = BQ / 16;  // 16-row groups (one DMA instruction each)
+  static_assert(GP % NW == 0 && GQ % NW == 0, "row groups must divide among the wavefronts");
+  constexpr int LP = GP / NW, LQ = GQ / NW;  // DMA instructions per wavefront per stage
+  constexpr int L = LP + LQ;
+
+  extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+  int32_t* s_corr = reinterpret_cast<int32_t*>(smem + kStages * STAGE);
+  int32_t* s_mult = s_corr + BP;
+  int32_t* s_shift = s_mult + BP;
+
+  const int t = threadIdx.x;
+  const int lane = t & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+  const int wp = wave % WP;
+  const int wq = wave / WP;
+
+  const int tiles_p = (p.N + BP - 1) / BP;
+  const int tile = xcd_remap(blockIdx.x, gridDim.x);
+  const int tile_p = tile % tiles_p;
+  const int tile_q = tile / tiles_p;
+  const int p0 = tile_p * BP;  // first output channel
+  const int q0 = tile_q * BQ;  // first row m
+
+  const v4i rs_w = make_rsrc(p.wgt, (uint32_t)p.N * (uint32_t)p.K);
+  const v4i rs_a = make_rsrc(p.act, (uint32_t)p.M * (uint32_t)p.K);
+  const uint32_t lds0 =
+      (uint32_t)(size_t)(__attribute__((address_space(3))) uint8_t*)smem;
+
+  // per-lane global offsets (without k0) of the chunks this lane fetches every stage
+  uint32_t off_p[LP], off_q[LQ];
+  const int lrow = lane >> 2;  // row inside a 16-row group
+  const int lslot = lane & 3;  // physical 16-byte slot
+#pragma unroll
+  for (int s = 0; s < LP; ++s) {
+    const int rt = (wave + NW * s) * 16 + lrow;  // row inside the P tile
+    const int row = p0 + rt;
+    const int lc = lslot ^ swz4(rt);
+    off_p[s] = row < p.N ? (uint32_t)row * (uint32_t)p.K + lc * 16 : kOob;
+  }
+#pragma unroll
+  for (int s = 0; s < LQ; ++s) {
+    const int rt = (wave + NW * s) * 16 + lrow;
+    const int row = q0 + rt;
+    const int lc = lslot ^ swz4(rt);
+    off_q[s] = row < p.M ? (uint32_t)row * (uint32_t)p.K + lc * 16 : kOob;
+  }
+  // logical chunk of each load, to mask the k tail
+  int lc_p[LP], lc_q[LQ];
+#pragma unroll
+  for (int s = 0; s < LP; ++s) lc_p[s] = (lslot ^ swz4((wave + NW * s) * 16 + lrow)) * 16;
+#pragma unroll
+  for (int s = 0; s < LQ; ++s) lc_q[s] = (lslot ^ swz4((wave + NW * s) * 16 + lrow)) * 16;
+
+  auto issue = [&](int stage_idx) {
+    const int k0 = stage_idx * kBK;
+    const uint32_t base = lds0 + (uint32_t)(stage_idx % kStages) * STAGE;
+    const bool tail = k0 + kBK > p.K;  // uniform: some chunks of this stage lie beyond K
+#pragma unroll
+    for (int s = 0; s < LP; ++s) {
+      uint32_t o = off_p[s] + (uint32_t)k0;
+      if (tail && k0 + lc_p[s] >= p.K) o = kOob;
+      dma16(rs_w, base + (uint32_t)(wave + NW * s) * 1024u, o);
+    }
+#pragma unroll
+    for (int s = 0; s < LQ; ++s) {
+      uint32_t o = off_q[s] + (uint32_t)k0;
+      if (tail && k0 + lc_q[s] >= p.K) o = kOob;
+      dma16(rs_a, base + (uint32_t)BP * kBK + (uint32_t)(wave + NW * s) * 1024u, o);
+    }
+  };
+
+  HAGO_STAMP(p, 0);
+  ChannelRegs<NT, BP> chregs;
+  load_channel_regs<NT, BP>(p, p0, chregs);
+
+  v16i acc[TP][TQ];
+#pragma unroll
+  for (int i = 0; i < TP; ++i)
+#pragma unroll
+    for (int j = 0; j < TQ; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+  int32_t wsum[TP];
+#pragma unroll
+  for (int i = 0; i < TP; ++i) wsum[i] = 0;
+
+  const int KT = (p.K + kBK - 1) / kBK;
+  // prologue: stages 0 .. kStages-2 (stages beyond K are all-zero fills, which keeps the
+  // number of outstanding loads uniform)
+#pragma unroll
+  for (int s = 0; s < kStages - 1; ++s) issue(s);
+  HAGO_STAMP(p, 1);
+
+  const int frow = lane & 31;
+  const int fhalf = lane >> 5;
+  const int x4 = (int)p.act_xor4;
+  const bool need_wsum = (p.corr_coef != 0) && (wq == 0);
+  // fragment addresses inside a stage (bytes)
+  int pa[TP][2], qa[TQ][2];
+#pragma unroll
+  for (int i = 0; i < TP; ++i) {
+    const int row = (wp * TP + i) * 32 + frow;
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) pa[i][ks] = row * kBK + (((ks * 2 + fhalf) ^ swz4(row)) * 16);
+  }
+#pragma unroll
+  for (int j = 0; j < TQ; ++j) {
+    const int row = (wq * TQ + j) * 32 + frow;
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+      qa[j][ks] = BP * kBK + row * kBK + (((ks * 2 + fhalf) ^ swz4(row)) * 16);
+  }
+
+  for (int kt = 0; kt < KT; ++kt) {
+    // stage kt has landed once at most the two younger stages are outstanding
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * L) : "memory");
+    __syncthreads();
+    if (kt == 0) HAGO_STAMP(p, 2);
+    issue(kt + kStages - 1);
+    const uint8_t* base = smem + (kt % kStages) * STAGE;
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      v4i pf[TP], qf[TQ];
+#pragma unroll
+      for (int i = 0; i < TP; ++i) pf[i] = *reinterpret_cast<const v4i*>(base + pa[i][ks]);
+#pragma unroll
+      for (int j = 0; j < TQ; ++j) {
+        const v4i v = *reinterpret_cast<const v4i*>(base + qa[j][ks]);
+        qf[j] = v4i{v.x ^ x4, v.y ^ x4, v.z ^ x4, v.w ^ x4};
+      }
+      if (need_wsum) {
+#pragma unroll
+        for (int i = 0; i < TP; ++i) {
+          wsum[i] = __builtin_amdgcn_sdot4(pf[i].x, 0x01010101, wsum[i], false);
+          wsum[i] = __builtin_amdgcn_sdot4(pf[i].y, 0x01010101, wsum[i], false);
+          wsum[i] = __builtin_amdgcn_sdot4(pf[i].z, 0x01010101, wsum[i], false);
+          wsum[i] = __builtin_amdgcn_sdot4(pf[i].w, 0x01010101, wsum[i], false);
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < TP; ++i)
+#pragma unroll
+        for (int j = 0; j < TQ; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(pf[i], qf[j], acc[i][j], 0, 0, 0);
+    }
+  }
+  HAGO_STAMP(p, 3);
+  // drain the zero-fill stages before LDS is reused and before the workgroup may exit
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+
+  // weight row sums: the two 32-lane halves hold the two k-halves of each row
+#pragma unroll
+  for (int i = 0; i < TP; ++i) {
+    int32_t v = wsum[i];
+    v += __shfl_xor(v, 32);
+    if (wq == 0 && fhalf == 0) s_corr[(wp * TP + i) * 32 + frow] = v;
+  }
+  __syncthreads();
+  const bool any_sh0 = finish_channel_terms<NT, BP>(p, chregs, s_corr, s_mult, s_shift);
+  HAGO_STAMP(p, 4);
+  constexpr bool kCanStage = ((BP / 16) & (BP / 16 - 1)) == 0 && BQ * BP <= kStages * STAGE &&
+                             (BQ * BP / 16) % NT == 0;
+  if constexpr (kCanStage) {
+    if (p.out_mode == 0 && !p.acc16 && p.vec16_out && p0 + BP <= p.N && q0 + BQ <= p.M) {
+      if (any_sh0)
+        qgemm_epilogue_dense_staged<WP, WQ, TP, TQ, false>(p, acc, p0, q0, s_corr, s_mult, s_shift, smem);
+      else
+        qgemm_epilogue_dense_staged<WP, WQ, TP, TQ, true>(p, acc, p0, q0, s_corr, s_mult, s_shift, smem);
+      return;
+    }
+  }
+  qgemm_epilogue<WP, WQ, TP, TQ, false>(p, acc, p0, q0, s_corr, s_mult, s_shift);
+}
+
+template <int WP, int WQ, int TP, int TQ>
+hipError_t launch_dma_cfg(const QgemmParams& p, hipStream_t st) {
+  constexpr int BP = WP * TP * 32, BQ = WQ * TQ * 32;
+  constexpr size_t lds = (size_t)kStages * (BP + BQ) * kBK + 3 * BP * sizeof(int32_t);
+  const int64_t tiles = (int64_t)((p.N + BP - 1) / BP) * ((p.M + BQ - 1) / BQ);
+  auto kern = qgemm_dma_kernel<WP, WQ, TP, TQ>;
+  static bool attr_set = false;  // raising the dynamic-LDS limit is needed once per kernel
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, dim3((unsigned)tiles), dim3(64 * WP * WQ), lds, st, p);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+// Requires: K % 16 == 0, K >= 16, 16-byte aligned operands, N*K and M*K below 2^31.
+hipError_t launch_qdense_dma(const QgemmParams& p, int shape, hipStream_t st) {
+  switch (shape) {
+    case 1: return launch_dma_cfg<2, 2, 2, 4>(p, st);  // 128 x 256, 4 wavefronts
+    case 2: return launch_dma_cfg<2, 2, 4, 2>(p, st);  // 256 x 128, 4 wavefronts
+    case 3: return launch_dma_cfg<2, 2, 2, 2>(p, st);  // 128 x 128, 4 wavefronts
+    case 4: return launch_dma_cfg<4, 2, 1, 2>(p, st);  // 128 x 128, 8 wavefronts
+    default: return launch_dma_cfg<4, 2, 2, 4>(p, st); // 256 x 256, 8 wavefronts
+  }
+}
+
+}  // namespace hago
