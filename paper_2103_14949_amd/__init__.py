@@ -6,7 +6,7 @@ kernels; Python only marshals arguments.  PyTorch supplies device memory and
 streams.
 """
 from .binding import (  # noqa: F401
-    HagoError, QType, Requant, lib, library_path,
+    HagoError, QType, Requant, Prepared, lib, library_path,
     simquant, requantize, qdense, qconv2d,
     U8, I8, I16, I32, F32, NCHW, NHWC, STRICT_ACC16,
 )

@@ -128,7 +128,24 @@ def _ptr(t):
     return None if t is None else t.data_ptr()
 
 
-def simquant(x, scale, zero_point, q: QType, clip_lo=None, clip_hi=None, per_channel=None, out=None):
+class Prepared:
+    """A library call with its arguments already marshalled; calling it re-issues the same
+    launch (same buffers, same stream) with one foreign-function call."""
+
+    __slots__ = ("_fn", "_args", "_keep", "out")
+
+    def __init__(self, fn, args, keep, out):
+        self._fn, self._args, self._keep, self.out = fn, args, keep, out
+
+    def __call__(self):
+        code = self._fn(*self._args)
+        if code != 0:
+            _check(code)
+        return self.out
+
+
+def simquant(x, scale, zero_point, q: QType, clip_lo=None, clip_hi=None, per_channel=None, out=None,
+             prepare=False):
     """hago_simquant over x[outer, channels, inner] (fp32, contiguous)."""
     assert x.dim() == 3 and x.is_contiguous()
     outer, channels, inner = x.shape
@@ -137,26 +154,33 @@ def simquant(x, scale, zero_point, q: QType, clip_lo=None, clip_hi=None, per_cha
     clip_hi = hi if clip_hi is None else clip_hi
     pc = int(scale.numel() > 1) if per_channel is None else int(per_channel)
     y = _torch().empty_like(x) if out is None else out
-    _check(lib().hago_simquant(_ptr(x), _ptr(y), outer, channels, inner, _ptr(scale),
-                               _ptr(zero_point), pc, q.c(), int(clip_lo), int(clip_hi), _stream()))
+    args = (_ptr(x), _ptr(y), outer, channels, inner, _ptr(scale), _ptr(zero_point), pc, q.c(),
+            int(clip_lo), int(clip_hi), _stream())
+    if prepare:
+        return Prepared(lib().hago_simquant, args, (x, y, scale, zero_point), y)
+    _check(lib().hago_simquant(*args))
     return y
 
 
-def requantize(acc, rq: Requant, out=None):
+def requantize(acc, rq: Requant, out=None, prepare=False):
     """hago_requantize over acc[outer, channels, inner] (int32 / int16)."""
     assert acc.dim() == 3 and acc.is_contiguous()
     outer, channels, inner = acc.shape
     if out is None:
         out = _torch().empty(acc.shape, dtype=_tdtype(rq.out.dtype), device=acc.device)
     st = rq.c()
-    _check(lib().hago_requantize(_ptr(acc), _code(acc), outer, channels, inner, C.byref(st),
-                                 _ptr(out), _stream()))
+    args = (_ptr(acc), _code(acc), outer, channels, inner, C.byref(st), _ptr(out), _stream())
+    if prepare:
+        return Prepared(lib().hago_requantize, args, (acc, rq, st, out), out)
+    _check(lib().hago_requantize(*args))
     return out
 
 
 def qdense(a, a_t: QType, w, w_t: QType, bias=None, acc_dtype=I32, rq: Requant | None = None,
-           flags=0, out=None):
-    """hago_qdense: a [M,K] (uint8/int8), w [N,K] int8 -> [M,N]."""
+           flags=0, out=None, prepare=False):
+    """hago_qdense: a [M,K] (uint8/int8), w [N,K] int8 -> [M,N].
+
+    prepare=True returns a Prepared call instead of launching."""
     assert a.dim() == 2 and w.dim() == 2 and a.is_contiguous() and w.is_contiguous()
     M, K = a.shape
     N = w.shape[0]
@@ -165,13 +189,16 @@ def qdense(a, a_t: QType, w, w_t: QType, bias=None, acc_dtype=I32, rq: Requant |
         dt = _tdtype(rq.out.dtype) if rq is not None else _tdtype(acc_dtype)
         out = _torch().empty((M, N), dtype=dt, device=a.device)
     st = rq.c() if rq is not None else None
-    _check(lib().hago_qdense(_ptr(a), a_t.c(), _ptr(w), w_t.c(), _ptr(bias), M, N, K, acc_dtype,
-                             C.byref(st) if st is not None else None, _ptr(out), flags, _stream()))
+    args = (_ptr(a), a_t.c(), _ptr(w), w_t.c(), _ptr(bias), M, N, K, acc_dtype,
+            C.byref(st) if st is not None else None, _ptr(out), flags, _stream())
+    if prepare:
+        return Prepared(lib().hago_qdense, args, (a, w, bias, rq, st, out), out)
+    _check(lib().hago_qdense(*args))
     return out
 
 
 def qconv2d(a, a_t: QType, w, w_t: QType, bias=None, layout=NCHW, stride=(1, 1), pad=(0, 0),
-            groups=1, acc_dtype=I32, rq: Requant | None = None, flags=0, out=None):
+            groups=1, acc_dtype=I32, rq: Requant | None = None, flags=0, out=None, prepare=False):
     """hago_qconv2d: NCHW a [B,C,H,W], w [O,C/g,KH,KW]; NHWC a [B,H,W,C], w [O,KH,KW,C/g]."""
     assert a.dim() == 4 and w.dim() == 4 and a.is_contiguous() and w.is_contiguous()
     if layout == NCHW:
@@ -187,7 +214,10 @@ def qconv2d(a, a_t: QType, w, w_t: QType, bias=None, layout=NCHW, stride=(1, 1),
         shape = (B, O, max(OH, 0), max(OW, 0)) if layout == NCHW else (B, max(OH, 0), max(OW, 0), O)
         out = _torch().empty(shape, dtype=dt, device=a.device)
     st = rq.c() if rq is not None else None
-    _check(lib().hago_qconv2d(_ptr(a), a_t.c(), _ptr(w), w_t.c(), _ptr(bias), layout, B, Cc, H, W, O,
-                              KH, KW, stride[0], stride[1], pad[0], pad[1], groups, acc_dtype,
-                              C.byref(st) if st is not None else None, _ptr(out), flags, _stream()))
+    args = (_ptr(a), a_t.c(), _ptr(w), w_t.c(), _ptr(bias), layout, B, Cc, H, W, O,
+            KH, KW, stride[0], stride[1], pad[0], pad[1], groups, acc_dtype,
+            C.byref(st) if st is not None else None, _ptr(out), flags, _stream())
+    if prepare:
+        return Prepared(lib().hago_qconv2d, args, (a, w, bias, rq, st, out), out)
+    _check(lib().hago_qconv2d(*args))
     return out

@@ -502,8 +502,10 @@ hipError_t launch_qdense(const GemmArgs& a, hipStream_t st) {
   const char* env = std::getenv("HAGO_QGEMM_PATH");  // tuning override: "reg" forces the generic kernel
   const bool fits32 = (int64_t)a.N * a.K < (1ll << 31) && (int64_t)a.M * a.K < (1ll << 31);
   if (fits32 && !(env && env[0] == 'r')) {
-    const char* sh = std::getenv("HAGO_DMA_SHAPE");
-    return launch_qdense_dma(p, sh ? std::atoi(sh) : 0, st);
+    const char* sh = std::getenv("HAGO_DMA_SHAPE");  // tuning override
+    // 256 x 256 tiles while they still occupy at least half of the 256 CUs, else 128 x 128
+    const int64_t big_tiles = (int64_t)((a.N + 255) / 256) * ((a.M + 255) / 256);
+    return launch_qdense_dma(p, sh ? std::atoi(sh) : (big_tiles >= 128 ? 0 : 3), st);
   }
   return launch_shape<MODE_DENSE>(pick_shape(MODE_DENSE, a.N, a.M, a.K), p, st);
 }

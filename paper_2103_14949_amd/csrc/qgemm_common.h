@@ -39,6 +39,7 @@ struct QgemmParams {
   ConvGeom g;
 #ifdef HAGO_PHASE_TIMING
   long long* dbg;  // per-workgroup phase timestamps (development builds only)
+  int dbg_skip;    // bit mask of main-loop parts to leave out in timing experiments
 #endif
 };
 
@@ -64,6 +65,8 @@ inline QgemmParams make_qgemm_params(const GemmArgs& a, const ConvGeom* cg) {
   {
     const char* e = std::getenv("HAGO_DBG_PTR");
     p.dbg = e ? reinterpret_cast<long long*>(std::strtoull(e, nullptr, 0)) : nullptr;
+    const char* k = std::getenv("HAGO_DBG_SKIP");
+    p.dbg_skip = k ? std::atoi(k) : 0;
   }
 #endif
   return p;

@@ -23,20 +23,23 @@
 // and the weight row sums needed for the zero-point term are accumulated from
 // the weight fragments with v_dot4 (see qgemm.hip for the identity).
 //
-// Synchronisation per stage: s_waitcnt vmcnt(2*L) (L = DMA instructions per
+// Synchronisation per stage, placed between the two 32-k halves of the stage
+// that is being multiplied: s_waitcnt vmcnt(2*L) (L = DMA instructions per
 // wavefront per stage; two younger stages may stay in flight), one barrier
-// (everybody's part of the stage has landed and everybody is done with the
-// buffer that is refilled next), issue the loads three stages ahead, multiply.
+// (everybody's part of the next stage has landed and everybody has taken its
+// last fragments of the current one), then the current buffer is refilled with
+// the stage four ahead.
 #include "qgemm_common.h"
 
 #include <cstdlib>
+#include <type_traits>
+#include <utility>
 
 namespace hago {
 
 namespace {
 
 constexpr int kBK = 64;       // k-bytes per stage
-constexpr int kStages = 4;    // LDS ring
 constexpr uint32_t kOob = 0x80000000u;  // offset beyond any tensor (sizes are < 2^31 bytes)
 
 __device__ __forceinline__ int swz4(int row) { return ((row >> 1) ^ (row >> 3)) & 3; }
@@ -59,8 +62,10 @@ __device__ __forceinline__ v4i make_rsrc(const void* base, uint32_t bytes) {
   return r;
 }
 
-template <int WP, int WQ, int TP, int TQ>
-__global__ __launch_bounds__(64 * WP * WQ) void qgemm_dma_kernel(QgemmParams p) {
+// kStages: depth of the LDS ring; OCC: wavefronts per SIMD the register budget must allow
+// (two 4-wavefront workgroups per CU keep the matrix pipe busy across each other's barriers).
+template <int WP, int WQ, int TP, int TQ, int kStages, int OCC>
+__global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParams p) {
   constexpr int NW = WP * WQ;          // wavefronts
   constexpr int NT = 64 * NW;
   constexpr int BP = WP * TP * 32;
@@ -119,23 +124,34 @@ __global__ __launch_bounds__(64 * WP * WQ) void qgemm_dma_kernel(QgemmParams p) 
 #pragma unroll
   for (int s = 0; s < LQ; ++s) lc_q[s] = (lslot ^ swz4((wave + NW * s) * 16 + lrow)) * 16;
 
-  auto issue = [&](int stage_idx) {
+  // DMA instruction d (0 .. L-1) of a stage: the first LP fill the weight tile, the rest the
+  // activation tile.  d is a compile-time constant at every call site.
+  auto issue_one = [&](int stage_idx, auto dconst) {
+    constexpr int d = decltype(dconst)::value;
     const int k0 = stage_idx * kBK;
     const uint32_t base = lds0 + (uint32_t)(stage_idx % kStages) * STAGE;
     const bool tail = k0 + kBK > p.K;  // uniform: some chunks of this stage lie beyond K
-#pragma unroll
-    for (int s = 0; s < LP; ++s) {
-      uint32_t o = off_p[s] + (uint32_t)k0;
-      if (tail && k0 + lc_p[s] >= p.K) o = kOob;
-      dma16(rs_w, base + (uint32_t)(wave + NW * s) * 1024u, o);
-    }
-#pragma unroll
-    for (int s = 0; s < LQ; ++s) {
-      uint32_t o = off_q[s] + (uint32_t)k0;
-      if (tail && k0 + lc_q[s] >= p.K) o = kOob;
-      dma16(rs_a, base + (uint32_t)BP * kBK + (uint32_t)(wave + NW * s) * 1024u, o);
+    if constexpr (d < LP) {
+      uint32_t o = off_p[d] + (uint32_t)k0;
+      if (tail && k0 + lc_p[d] >= p.K) o = kOob;
+      dma16(rs_w, base + (uint32_t)(wave + NW * d) * 1024u, o);
+    } else {
+      constexpr int e = d - LP;
+      uint32_t o = off_q[e] + (uint32_t)k0;
+      if (tail && k0 + lc_q[e] >= p.K) o = kOob;
+      dma16(rs_a, base + (uint32_t)BP * kBK + (uint32_t)(wave + NW * e) * 1024u, o);
     }
   };
+  auto issue_range = [&](int stage_idx, auto lo, auto hi) {
+    constexpr int kLo = decltype(lo)::value, kHi = decltype(hi)::value;
+    [&]<int... I>(std::integer_sequence<int, I...>) {
+      (issue_one(stage_idx, std::integral_constant<int, kLo + I>{}), ...);
+    }(std::make_integer_sequence<int, kHi - kLo>{});
+  };
+  constexpr int LH = L / 2;  // a stage is issued in two halves, spread over two MFMA groups
+  using IC0 = std::integral_constant<int, 0>;
+  using ICH = std::integral_constant<int, LH>;
+  using ICL = std::integral_constant<int, L>;
 
   HAGO_STAMP(p, 0);
   ChannelRegs<NT, BP> chregs;
@@ -153,16 +169,22 @@ __global__ __launch_bounds__(64 * WP * WQ) void qgemm_dma_kernel(QgemmParams p) 
   for (int i = 0; i < TP; ++i) wsum[i] = 0;
 
   const int KT = (p.K + kBK - 1) / kBK;
-  // prologue: stages 0 .. kStages-2 (stages beyond K are all-zero fills, which keeps the
+  // prologue: stages 0 .. kStages-1 (stages beyond K are all-zero fills, which keeps the
   // number of outstanding loads uniform)
 #pragma unroll
-  for (int s = 0; s < kStages - 1; ++s) issue(s);
+  for (int s = 0; s < kStages - 1; ++s) issue_range(s, IC0{}, ICL{});
+  issue_range(kStages - 1, IC0{}, ICH{});
   HAGO_STAMP(p, 1);
 
   const int frow = lane & 31;
   const int fhalf = lane >> 5;
+#ifdef HAGO_PHASE_TIMING
+  const int x4 = (p.dbg_skip & 4) ? 0 : (int)p.act_xor4;
+  const bool need_wsum = (p.corr_coef != 0) && (wq == 0) && !(p.dbg_skip & 4);
+#else
   const int x4 = (int)p.act_xor4;
   const bool need_wsum = (p.corr_coef != 0) && (wq == 0);
+#endif
   // fragment addresses inside a stage (bytes)
   int pa[TP][2], qa[TQ][2];
 #pragma unroll
@@ -179,38 +201,83 @@ __global__ __launch_bounds__(64 * WP * WQ) void qgemm_dma_kernel(QgemmParams p) 
       qa[j][ks] = BP * kBK + row * kBK + (((ks * 2 + fhalf) ^ swz4(row)) * 16);
   }
 
-  for (int kt = 0; kt < KT; ++kt) {
-    // stage kt has landed once at most the two younger stages are outstanding
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * L) : "memory");
-    __syncthreads();
-    if (kt == 0) HAGO_STAMP(p, 2);
-    issue(kt + kStages - 1);
-    const uint8_t* base = smem + (kt % kStages) * STAGE;
+  // Fragment sets for the two 32-k halves of a stage.  While the MFMAs of one half run, the
+  // fragments of the next half are already being read, and the stage barrier sits between the
+  // two MFMA groups so that the matrix pipe has work queued while wavefronts wait on it.
+  v4i pf0[TP], qf0[TQ], pf1[TP], qf1[TQ];
+  auto read_frags = [&](const uint8_t* base, int ks, v4i (&pf)[TP], v4i (&qf)[TQ]) {
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-      v4i pf[TP], qf[TQ];
+    for (int i = 0; i < TP; ++i) pf[i] = *reinterpret_cast<const v4i*>(base + pa[i][ks]);
 #pragma unroll
-      for (int i = 0; i < TP; ++i) pf[i] = *reinterpret_cast<const v4i*>(base + pa[i][ks]);
+    for (int j = 0; j < TQ; ++j) qf[j] = *reinterpret_cast<const v4i*>(base + qa[j][ks]);
+  };
+  // One 32-k half: per column j of the wavefront tile, flip the activation fragment, multiply it
+  // with the TP weight fragments, and (HALF = 0 / 1) drop one of the stage's DMA instructions
+  // behind some of the columns, so that the eight wavefronts feed the memory pipe a few
+  // instructions at a time instead of all at once after the barrier.
+  auto multiply = [&](v4i (&pf)[TP], v4i (&qf)[TQ], int dma_stage, auto half) {
+    constexpr int kHalf = decltype(half)::value;
+    if (need_wsum) {
 #pragma unroll
-      for (int j = 0; j < TQ; ++j) {
-        const v4i v = *reinterpret_cast<const v4i*>(base + qa[j][ks]);
-        qf[j] = v4i{v.x ^ x4, v.y ^ x4, v.z ^ x4, v.w ^ x4};
+      for (int i = 0; i < TP; ++i) {
+        wsum[i] = __builtin_amdgcn_sdot4(pf[i].x, 0x01010101, wsum[i], false);
+        wsum[i] = __builtin_amdgcn_sdot4(pf[i].y, 0x01010101, wsum[i], false);
+        wsum[i] = __builtin_amdgcn_sdot4(pf[i].z, 0x01010101, wsum[i], false);
+        wsum[i] = __builtin_amdgcn_sdot4(pf[i].w, 0x01010101, wsum[i], false);
       }
-      if (need_wsum) {
-#pragma unroll
-        for (int i = 0; i < TP; ++i) {
-          wsum[i] = __builtin_amdgcn_sdot4(pf[i].x, 0x01010101, wsum[i], false);
-          wsum[i] = __builtin_amdgcn_sdot4(pf[i].y, 0x01010101, wsum[i], false);
-          wsum[i] = __builtin_amdgcn_sdot4(pf[i].z, 0x01010101, wsum[i], false);
-          wsum[i] = __builtin_amdgcn_sdot4(pf[i].w, 0x01010101, wsum[i], false);
-        }
-      }
-#pragma unroll
-      for (int i = 0; i < TP; ++i)
-#pragma unroll
-        for (int j = 0; j < TQ; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(pf[i], qf[j], acc[i][j], 0, 0, 0);
     }
+    [&]<int... J>(std::integer_sequence<int, J...>) {
+      ([&] {
+        constexpr int j = J;
+        qf[j] = v4i{qf[j].x ^ x4, qf[j].y ^ x4, qf[j].z ^ x4, qf[j].w ^ x4};
+#pragma unroll
+        for (int i = 0; i < TP; ++i)
+          acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(pf[i], qf[j], acc[i][j], 0, 0, 0);
+        // DMA instructions [first, last) of this half go behind column j
+        constexpr int first = (j * LH) / TQ, last = ((j + 1) * LH) / TQ;
+        if constexpr (last > first) {
+#ifdef HAGO_PHASE_TIMING
+          if (!(p.dbg_skip & 1))
+#endif
+          issue_range(dma_stage, std::integral_constant<int, kHalf * LH + first>{},
+                      std::integral_constant<int, kHalf * LH + last>{});
+        }
+      }(), ...);
+    }(std::make_integer_sequence<int, TQ>{});
+  };
+
+  // stage 0 has landed once at most the younger loads (stages 1, 2 and half of 3) are outstanding
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"((kStages - 2) * L + LH) : "memory");
+  __syncthreads();
+  HAGO_STAMP(p, 2);
+  read_frags(smem, 0, pf0, qf0);
+  for (int kt = 0; kt < KT; ++kt) {
+    const uint8_t* base = smem + (kt % kStages) * STAGE;
+    const uint8_t* next = smem + ((kt + 1) % kStages) * STAGE;
+#ifdef HAGO_PHASE_TIMING
+    if (!(p.dbg_skip & 2))
+#endif
+    read_frags(base, 1, pf1, qf1);
+    __builtin_amdgcn_sched_barrier(0);
+    multiply(pf0, qf0, kt + kStages - 1, std::integral_constant<int, 1>{});
+    __builtin_amdgcn_sched_barrier(0);
+    // stage kt+1 has landed once only stages kt+2, kt+3 are outstanding; after the barrier
+    // every wavefront also holds its last fragments of stage kt, so that buffer can be refilled
+#ifdef HAGO_PHASE_TIMING
+    if (!(p.dbg_skip & 8)) {
+#endif
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((kStages - 2) * L) : "memory");
+    __syncthreads();
+#ifdef HAGO_PHASE_TIMING
+    }
+#endif
+#ifdef HAGO_PHASE_TIMING
+    if (!(p.dbg_skip & 2))
+#endif
+    read_frags(next, 0, pf0, qf0);
+    __builtin_amdgcn_sched_barrier(0);
+    multiply(pf1, qf1, kt + kStages, std::integral_constant<int, 0>{});
+    __builtin_amdgcn_sched_barrier(0);
   }
   HAGO_STAMP(p, 3);
   // drain the zero-fill stages before LDS is reused and before the workgroup may exit
@@ -241,12 +308,12 @@ __global__ __launch_bounds__(64 * WP * WQ) void qgemm_dma_kernel(QgemmParams p) 
   qgemm_epilogue<WP, WQ, TP, TQ, false>(p, acc, p0, q0, s_corr, s_mult, s_shift);
 }
 
-template <int WP, int WQ, int TP, int TQ>
+template <int WP, int WQ, int TP, int TQ, int kStages, int OCC>
 hipError_t launch_dma_cfg(const QgemmParams& p, hipStream_t st) {
   constexpr int BP = WP * TP * 32, BQ = WQ * TQ * 32;
   constexpr size_t lds = (size_t)kStages * (BP + BQ) * kBK + 3 * BP * sizeof(int32_t);
   const int64_t tiles = (int64_t)((p.N + BP - 1) / BP) * ((p.M + BQ - 1) / BQ);
-  auto kern = qgemm_dma_kernel<WP, WQ, TP, TQ>;
+  auto kern = qgemm_dma_kernel<WP, WQ, TP, TQ, kStages, OCC>;
   static bool attr_set = false;  // raising the dynamic-LDS limit is needed once per kernel
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -263,11 +330,12 @@ hipError_t launch_dma_cfg(const QgemmParams& p, hipStream_t st) {
 // Requires: K % 16 == 0, K >= 16, 16-byte aligned operands, N*K and M*K below 2^31.
 hipError_t launch_qdense_dma(const QgemmParams& p, int shape, hipStream_t st) {
   switch (shape) {
-    case 1: return launch_dma_cfg<2, 2, 2, 4>(p, st);  // 128 x 256, 4 wavefronts
-    case 2: return launch_dma_cfg<2, 2, 4, 2>(p, st);  // 256 x 128, 4 wavefronts
-    case 3: return launch_dma_cfg<2, 2, 2, 2>(p, st);  // 128 x 128, 4 wavefronts
-    case 4: return launch_dma_cfg<4, 2, 1, 2>(p, st);  // 128 x 128, 8 wavefronts
-    default: return launch_dma_cfg<4, 2, 2, 4>(p, st); // 256 x 256, 8 wavefronts
+    case 1: return launch_dma_cfg<2, 2, 2, 4, 3, 2>(p, st);  // 128 x 256, 4 wavefronts, 2 per CU
+    case 2: return launch_dma_cfg<2, 2, 4, 2, 3, 2>(p, st);  // 256 x 128, 4 wavefronts, 2 per CU
+    case 3: return launch_dma_cfg<2, 2, 2, 2, 4, 2>(p, st);  // 128 x 128, 4 wavefronts
+    case 4: return launch_dma_cfg<4, 2, 1, 2, 4, 1>(p, st);  // 128 x 128, 8 wavefronts
+    case 5: return launch_dma_cfg<2, 2, 2, 4, 4, 1>(p, st);  // 128 x 256, 4 wavefronts, 1 per CU
+    default: return launch_dma_cfg<4, 2, 2, 4, 4, 1>(p, st); // 256 x 256, 8 wavefronts
   }
 }
 
