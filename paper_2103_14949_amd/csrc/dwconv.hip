@@ -3,8 +3,13 @@
 // so there is no MFMA here; the work is 9 multiply-adds per output on the
 // vector ALUs (4 at a time with v_dot4) out of an LDS copy of the input plane.
 //
-//   plane3x3 : NCHW, 3x3, stride 1, pad 1.  One workgroup per (image, channel,
-//              band of rows).  The band plus a one-pixel halo (filled with the
+//   wave3x3  : NCHW, 3x3, stride 1, pad 1, W <= 64.  One WAVEFRONT per (image,
+//              channel) plane, four planes per workgroup.  A lane owns a strip
+//              of four output columns and a quarter of the rows and slides
+//              down it, so every staged input row is read from LDS once and
+//              serves three output rows; 12 v_dot4 per four outputs.
+//   plane3x3 : the same geometry for wider images.  One workgroup per (image,
+//              channel, band of rows).  The band plus a one-pixel halo (filled with the
 //              zero point, so padded taps contribute 0) is staged in LDS with
 //              the image column x at LDS column x + 4; four adjacent outputs
 //              share three aligned dword reads per input row.
@@ -190,6 +195,146 @@ __global__ __launch_bounds__(kThreads) void dw_plane3x3_kernel(DwArgs p, int32_t
   }
 }
 
+
+// r = floor((a * m + 2^(30+sh)) / 2^(31+sh)); sh is wavefront-uniform here.
+__device__ __forceinline__ int32_t dw_mul_shift(int32_t a, int32_t m, int64_t rnd, int32_t sh) {
+  const int64_t pr = (int64_t)a * (int64_t)m + rnd;
+  return sh >= 1 ? ((int32_t)(pr >> 32) >> (sh - 1)) : (int32_t)(pr >> 31);
+}
+
+// NCHW 3x3 stride 1 pad 1, W <= 64.  Dynamic LDS: 4 planes x (H + 2) * rs bytes,
+// rs = row stride (multiple of 4, >= W + 12).  inv_w4 = ceil(2^32 / (W / 4)) (vector path).
+__global__ __launch_bounds__(kThreads) void dw_wave3x3_kernel(DwArgs p, int32_t rs, uint32_t inv_w4,
+                                                             int32_t vec_io, int64_t planes) {
+  extern __shared__ uint32_t lds[];
+  const ConvGeom& g = p.g;
+  const int H = g.H, W = g.W;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int64_t plane = (int64_t)blockIdx.x * 4 + wave;  // b * C + c
+  const bool active = plane < planes;
+  const int c = active ? (int)(plane % g.C) : 0;
+  const int lrows = H + 2;
+  const int rs4 = rs >> 2;
+  uint32_t* pl = lds + wave * lrows * rs4;  // this wavefront's plane: image (y, x) at row y+1, column x+4
+
+  const uint32_t padb = ((uint32_t)p.z_a ^ p.act_xor) & 0xffu;
+  const uint32_t pad4 = padb * 0x01010101u;
+  if (active) {
+    const uint8_t* src = p.act + plane * (int64_t)H * W;
+    if (vec_io) {
+      const int w4 = W >> 2;
+      const uint32_t x4 = p.act_xor * 0x01010101u;
+      const uint32_t* src4 = reinterpret_cast<const uint32_t*>(src);
+      // halo (and everything else) first, then the image over it; LDS operations of one
+      // wavefront execute in order, so the second write wins
+      for (int i = lane; i < lrows * rs4; i += 64) pl[i] = pad4;
+      // image dwords in batches of 8 loads per lane, all issued before the first is used
+      const int nd = H * w4;
+      for (int i0 = 0; i0 < nd; i0 += 8 * 64) {
+        uint32_t v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int i = i0 + u * 64 + lane;
+          v[u] = src4[i < nd ? i : nd - 1];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int i = i0 + u * 64 + lane;
+          const int r = (w4 == 1) ? i : (int)__umulhi((uint32_t)i, inv_w4);  // i / w4
+          const int q = i - r * w4;
+          if (i < nd) pl[(r + 1) * rs4 + 1 + q] = v[u] ^ x4;
+        }
+      }
+    } else {
+      uint8_t* l8 = reinterpret_cast<uint8_t*>(pl);
+      for (int i = lane; i < lrows * rs; i += 64) {
+        const int r = i / rs, x = i - r * rs - 4;
+        uint32_t v = padb;
+        if (r >= 1 && r <= H && x >= 0 && x < W) v = (uint32_t)src[(int64_t)(r - 1) * W + x] ^ p.act_xor;
+        l8[i] = (uint8_t)v;
+      }
+    }
+  }
+  __syncthreads();
+  if (!active) return;
+
+  // per-channel constants (wavefront-uniform)
+  const int8_t* wc = p.wgt + (int64_t)c * 9;
+  uint32_t wrow[3];
+  int32_t wsum = 0;
+#pragma unroll
+  for (int ky = 0; ky < 3; ++ky) {
+    const int32_t w0 = wc[ky * 3 + 0], w1 = wc[ky * 3 + 1], w2 = wc[ky * 3 + 2];
+    wsum += w0 + w1 + w2;
+    wrow[ky] = (uint32_t)(w0 & 0xff) | ((uint32_t)(w1 & 0xff) << 8) | ((uint32_t)(w2 & 0xff) << 16);
+  }
+  const int32_t corr = (p.bias ? p.bias[c] : 0) + (p.act_off - p.z_a) * wsum;
+  const int pc = p.per_channel ? c : 0;
+  const int32_t m = p.has_rq ? p.mult[pc] : 0;
+  const int32_t sh = p.has_rq ? p.shift[pc] : 0;
+  const int64_t rnd = (int64_t)1 << (30 + sh);
+  const int32_t lo = p.rs.lo_rel, hi = p.rs.hi_rel, z = p.rs.z_out;
+
+  const int gx = (W + 3) >> 2;  // strips of 4 output columns (<= 16)
+  const int q = lane & 15;
+  const int rc = lane >> 4;
+  const int rpc = (H + 3) >> 2;  // rows per lane quarter
+  const int y0 = rc * rpc;
+  const int y1 = (y0 + rpc < H) ? y0 + rpc : H;
+  if (q >= gx || y0 >= y1) return;
+
+  // windows of one staged row: output x = 4q + i reads LDS columns x+3 .. x+5
+  auto windows = [&](int lrow, uint32_t (&w)[4]) {
+    const uint32_t* row = pl + lrow * rs4 + q;
+    const uint32_t d0 = row[0], d1 = row[1], d2 = row[2];
+    w[0] = __builtin_amdgcn_alignbyte(d1, d0, 3);
+    w[1] = d1;
+    w[2] = __builtin_amdgcn_alignbyte(d2, d1, 1);
+    w[3] = __builtin_amdgcn_alignbyte(d2, d1, 2);
+  };
+  uint32_t wa[4], wb[4], wcur[4];
+  windows(y0, wa);      // image row y0 - 1
+  windows(y0 + 1, wb);  // image row y0
+  const int64_t obase = plane * (int64_t)H * W;
+  for (int y = y0; y < y1; ++y) {
+    windows(y + 2, wcur);  // image row y + 1
+    int32_t acc[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      int32_t a = __builtin_amdgcn_sdot4((int)wa[i], (int)wrow[0], corr, false);
+      a = __builtin_amdgcn_sdot4((int)wb[i], (int)wrow[1], a, false);
+      a = __builtin_amdgcn_sdot4((int)wcur[i], (int)wrow[2], a, false);
+      acc[i] = wrap_acc(a, p.acc16);
+      wa[i] = wb[i];
+      wb[i] = wcur[i];
+    }
+    const int x0 = q << 2;
+    const int64_t o = obase + (int64_t)y * W + x0;
+    if (p.out_mode == 0) {
+      int32_t r[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) r[i] = med3(dw_mul_shift(acc[i], m, rnd, sh), lo, hi) + z;
+      if (vec_io) {
+        reinterpret_cast<uint32_t*>(p.out)[o >> 2] = pack4_perm(r[0], r[1], r[2], r[3]);
+      } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (x0 + i < W) static_cast<uint8_t*>(p.out)[o + i] = (uint8_t)r[i];
+      }
+    } else if (vec_io && p.out_mode == 1) {
+      reinterpret_cast<int4*>(p.out)[o >> 2] = make_int4(acc[0], acc[1], acc[2], acc[3]);
+    } else if (vec_io) {
+      reinterpret_cast<short4*>(p.out)[o >> 2] =
+          make_short4((short)acc[0], (short)acc[1], (short)acc[2], (short)acc[3]);
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if (x0 + i < W) store_one(p, o + i, acc[i], m, sh);
+    }
+  }
+}
+
 }  // namespace
 
 hipError_t launch_qconv_depthwise(const GemmArgs& a, const ConvGeom& cg, hipStream_t st) {
@@ -220,7 +365,16 @@ hipError_t launch_qconv_depthwise(const GemmArgs& a, const ConvGeom& cg, hipStre
   const size_t lds_bytes = (size_t)(band_rows + 2) * rs;
   const int64_t planes = (int64_t)cg.B * cg.C;
   const int nband = (cg.H + kBandRows - 1) / kBandRows;
-  if (plane_ok && lds_bytes <= (size_t)kMaxLdsBytes && planes * nband < (1ll << 31)) {
+  const size_t wave_lds = (size_t)4 * (cg.H + 2) * rs;
+  if (plane_ok && cg.W <= 64 && wave_lds <= (size_t)kMaxLdsBytes && planes < (1ll << 32)) {
+    const size_t esz = a.has_rq ? 1 : (a.acc16 ? 2 : 4);
+    const bool vec_io = (cg.W % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.act) & 3u) == 0) &&
+                        ((reinterpret_cast<uintptr_t>(a.out) & (4 * esz - 1)) == 0);
+    const uint32_t w4 = vec_io ? (uint32_t)cg.W / 4 : 1u;
+    const uint32_t inv_w4 = w4 > 1 ? (uint32_t)(((1ull << 32) + w4 - 1) / w4) : 0u;  // unused for w4 == 1
+    hipLaunchKernelGGL(dw_wave3x3_kernel, dim3((unsigned)((planes + 3) / 4)), dim3(kThreads),
+                       wave_lds, st, p, rs, inv_w4, vec_io ? 1 : 0, planes);
+  } else if (plane_ok && lds_bytes <= (size_t)kMaxLdsBytes && planes * nband < (1ll << 31)) {
     const size_t esz = a.has_rq ? 1 : (a.acc16 ? 2 : 4);
     const bool vec_io = (cg.W % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.act) & 3u) == 0) &&
                         ((reinterpret_cast<uintptr_t>(a.out) & (4 * esz - 1)) == 0);

@@ -16,7 +16,8 @@ namespace hago {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kSegVec = 1024;  // 128-bit vectors per row segment (4 per lane)
+constexpr int kSegVec = 256;   // 128-bit vectors per row segment: one per lane, many small workgroups
+                               // (streams faster here than fewer workgroups that loop)
 
 // Eq. 3 with zero point and saturation, in binary32.  The clip is written as
 // compare-select so that NaN propagates and the comparison structure is the
@@ -34,9 +35,17 @@ __global__ __launch_bounds__(kThreads) void simquant_rows_kernel(
     int64_t inner_vec, int32_t nseg, const float* __restrict__ scale,
     const int32_t* __restrict__ zp, int per_channel, float lo, float hi) {
   for (int64_t job = blockIdx.x; job < rows * nseg; job += gridDim.x) {
-    const int64_t row = job / nseg;
+    int64_t row;
+    int32_t c;
+    if (job <= 0xffffffffll) {  // the usual case: 32-bit division
+      const uint32_t r32 = (uint32_t)job / (uint32_t)nseg;
+      row = r32;
+      c = per_channel ? (int32_t)(r32 % (uint32_t)channels) : 0;
+    } else {
+      row = job / nseg;
+      c = per_channel ? (int32_t)(row % channels) : 0;
+    }
     const int32_t seg = (int32_t)(job - row * nseg);
-    const int32_t c = per_channel ? (int32_t)(row % channels) : 0;
     const float s = scale[c];
     const float zf = (float)zp[c];
     const int64_t v0 = (int64_t)seg * kSegVec;
@@ -78,9 +87,17 @@ __global__ __launch_bounds__(kThreads) void requant_rows_kernel(
     int64_t inner_vec, int32_t nseg, const int32_t* __restrict__ mult,
     const int32_t* __restrict__ shift, int per_channel, RequantScalars rs) {
   for (int64_t job = blockIdx.x; job < rows * nseg; job += gridDim.x) {
-    const int64_t row = job / nseg;
+    int64_t row;
+    int32_t c;
+    if (job <= 0xffffffffll) {  // the usual case: 32-bit division
+      const uint32_t r32 = (uint32_t)job / (uint32_t)nseg;
+      row = r32;
+      c = per_channel ? (int32_t)(r32 % (uint32_t)channels) : 0;
+    } else {
+      row = job / nseg;
+      c = per_channel ? (int32_t)(row % channels) : 0;
+    }
     const int32_t seg = (int32_t)(job - row * nseg);
-    const int32_t c = per_channel ? (int32_t)(row % channels) : 0;
     const int32_t m = mult[c];
     const int32_t sh = shift[c];
     const int64_t v0 = (int64_t)seg * kSegVec;
@@ -141,7 +158,7 @@ __global__ __launch_bounds__(kThreads) void requant_flat_kernel(
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 inline int grid_for(int64_t jobs) {
-  const int64_t cap = 256 * 64;  // 64 workgroups per CU is plenty for a streaming kernel
+  const int64_t cap = 1ll << 30;  // one job per workgroup; the kernels loop beyond this
   return (int)(jobs < cap ? (jobs > 0 ? jobs : 1) : cap);
 }
 
