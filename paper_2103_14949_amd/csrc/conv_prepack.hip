@@ -1,0 +1,147 @@
+// Operand preparation for the implicit-GEMM convolution and the library's
+// per-device scratch buffer that holds the prepared copies.
+//
+// The int8 matrix cores want 16 consecutive reduction elements per lane.  In
+// NCHW the reduction index (input channel) is the slowest-varying one, so the
+// convolution first rewrites its operands, once per call and in one launch:
+//   activations -> [B][H + 2 pad_h][W + 2 pad_w][Cp]   (Cp = C rounded up to 16)
+//                  uint8 inputs flipped to int8 (XOR 0x80), the padding ring
+//                  filled with the zero point (so padded taps contribute 0),
+//                  channels beyond C zero;
+//   weights     -> [O][KH * KW][Cp], channels beyond C zero.
+// After that a tap of an output pixel is 16-byte chunks of contiguous memory
+// and the GEMM kernel can stream both operands straight into LDS.
+#include "hago_device.h"
+#include "launch.h"
+
+namespace hago {
+
+namespace {
+
+struct PrepackArgs {
+  const uint8_t* act;
+  const int8_t* wgt;
+  uint8_t* act_out;
+  int8_t* wgt_out;
+  int32_t B, C, H, W, O, KH, KW, ph, pw, Hp, Wp, Cp, nhwc;
+  uint32_t act_xor;   // 0x80 for uint8 inputs
+  uint32_t pad_byte;  // (zero point XOR act_xor) & 0xff
+  int64_t act_chunks, wgt_chunks;  // 16-byte chunks to produce
+};
+
+__device__ __forceinline__ uint4 pack16(const uint32_t (&b)[16]) {
+  uint4 r;
+  r.x = b[0] | (b[1] << 8) | (b[2] << 16) | (b[3] << 24);
+  r.y = b[4] | (b[5] << 8) | (b[6] << 16) | (b[7] << 24);
+  r.z = b[8] | (b[9] << 8) | (b[10] << 16) | (b[11] << 24);
+  r.w = b[12] | (b[13] << 8) | (b[14] << 16) | (b[15] << 24);
+  return r;
+}
+
+__global__ __launch_bounds__(256) void conv_prepack_kernel(PrepackArgs p) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int nch = p.Cp >> 4;
+  if (i < p.act_chunks) {
+    // i = ((b*Hp + py)*nch + cc)*Wp + px : lanes run along px, which is contiguous in NCHW
+    int64_t r = i;
+    const int px = (int)(r % p.Wp); r /= p.Wp;
+    const int cc = (int)(r % nch); r /= nch;
+    const int py = (int)(r % p.Hp);
+    const int b = (int)(r / p.Hp);
+    const int iy = py - p.ph, ix = px - p.pw;
+    const bool inside = (unsigned)iy < (unsigned)p.H && (unsigned)ix < (unsigned)p.W;
+    const int c0 = cc << 4;
+    uint32_t v[16];
+    if (p.nhwc) {
+      const int64_t base = (((int64_t)b * p.H + (inside ? iy : 0)) * p.W + (inside ? ix : 0)) * p.C;
+#pragma unroll
+      for (int j = 0; j < 16; ++j) v[j] = p.act[base + (c0 + j < p.C ? c0 + j : p.C - 1)];
+    } else {
+      const int64_t hw = (int64_t)p.H * p.W;
+      const int64_t base = (int64_t)b * p.C * hw + (int64_t)(inside ? iy : 0) * p.W + (inside ? ix : 0);
+#pragma unroll
+      for (int j = 0; j < 16; ++j) v[j] = p.act[base + (int64_t)(c0 + j < p.C ? c0 + j : p.C - 1) * hw];
+    }
+#pragma unroll
+    for (int j = 0; j < 16; ++j)
+      v[j] = (c0 + j < p.C) ? (inside ? (v[j] ^ p.act_xor) : p.pad_byte) : 0u;
+    const int64_t o = ((((int64_t)b * p.Hp + py) * p.Wp + px) * p.Cp) + c0;
+    *reinterpret_cast<uint4*>(p.act_out + o) = pack16(v);
+    return;
+  }
+  const int64_t k = i - p.act_chunks;
+  if (k < p.wgt_chunks) {
+    // k = (o*KH*KW + t)*nch + cc
+    const int khw = p.KH * p.KW;
+    const int cc = (int)(k % nch);
+    const int64_t ot = k / nch;
+    const int t = (int)(ot % khw);
+    const int64_t o = ot / khw;
+    const int c0 = cc << 4;
+    uint32_t v[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      const int c = c0 + j < p.C ? c0 + j : p.C - 1;
+      const int64_t src = p.nhwc ? (o * khw + t) * p.C + c : (o * p.C + c) * khw + t;
+      v[j] = (uint8_t)p.wgt[src];
+    }
+#pragma unroll
+    for (int j = 0; j < 16; ++j) v[j] = (c0 + j < p.C) ? v[j] : 0u;
+    *reinterpret_cast<uint4*>(p.wgt_out + (ot * p.Cp + c0)) = pack16(v);
+  }
+}
+
+struct DeviceScratch {
+  void* ptr = nullptr;
+  size_t cap = 0;
+};
+DeviceScratch g_scratch[64];
+
+}  // namespace
+
+// One scratch allocation per device, owned by the library and grown on demand.  Growing
+// frees the old buffer, which waits for the device to go idle.  Not safe for calls that run
+// concurrently on one device.
+hipError_t scratch_reserve(size_t bytes, void** out) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+  DeviceScratch& s = g_scratch[dev];
+  if (s.cap < bytes) {
+    if (s.ptr) {
+      e = hipFree(s.ptr);
+      s.ptr = nullptr;
+      s.cap = 0;
+      if (e != hipSuccess) return e;
+    }
+    const size_t want = bytes + bytes / 4 + (1u << 20);
+    e = hipMalloc(&s.ptr, want);
+    if (e != hipSuccess) { s.ptr = nullptr; return e; }
+    s.cap = want;
+  }
+  *out = s.ptr;
+  return hipSuccess;
+}
+
+hipError_t launch_conv_prepack(const GemmArgs& a, const ConvGeom& cg, int32_t Cp, uint8_t* act_out,
+                               int8_t* wgt_out, hipStream_t st) {
+  PrepackArgs p{};
+  p.act = static_cast<const uint8_t*>(a.act);
+  p.wgt = a.wgt;
+  p.act_out = act_out;
+  p.wgt_out = wgt_out;
+  p.B = cg.B; p.C = cg.C; p.H = cg.H; p.W = cg.W; p.O = cg.O; p.KH = cg.KH; p.KW = cg.KW;
+  p.ph = cg.pad_h; p.pw = cg.pad_w;
+  p.Hp = cg.H + 2 * cg.pad_h; p.Wp = cg.W + 2 * cg.pad_w; p.Cp = Cp;
+  p.nhwc = cg.nhwc;
+  p.act_xor = a.act_unsigned ? 0x80u : 0u;
+  p.pad_byte = ((uint32_t)a.act_zero_point ^ p.act_xor) & 0xffu;
+  p.act_chunks = (int64_t)p.B * p.Hp * p.Wp * (Cp / 16);
+  p.wgt_chunks = (int64_t)p.O * p.KH * p.KW * (Cp / 16);
+  const int64_t blocks = (p.act_chunks + p.wgt_chunks + 255) / 256;
+  hipLaunchKernelGGL(conv_prepack_kernel, dim3((unsigned)blocks), dim3(256), 0, st, p);
+  return hipGetLastError();
+}
+
+}  // namespace hago

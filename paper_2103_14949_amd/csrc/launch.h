@@ -46,6 +46,11 @@ struct GemmArgs {
 hipError_t launch_qdense(const GemmArgs& g, hipStream_t st);
 // implicit-GEMM convolution, groups == 1.
 hipError_t launch_qconv_gemm(const GemmArgs& g, const ConvGeom& cg, hipStream_t st);
+// Library-owned per-device scratch (grown on demand) and the operand rewrite that the
+// implicit-GEMM convolution runs first (padded NHWC activations, [O][KH*KW][Cp] weights).
+hipError_t scratch_reserve(size_t bytes, void** out);
+hipError_t launch_conv_prepack(const GemmArgs& g, const ConvGeom& cg, int32_t Cp, uint8_t* act_out,
+                               int8_t* wgt_out, hipStream_t st);
 // depthwise convolution (groups == C == O), no MFMA.
 hipError_t launch_qconv_depthwise(const GemmArgs& g, const ConvGeom& cg, hipStream_t st);
 

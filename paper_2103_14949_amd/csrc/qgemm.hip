@@ -510,8 +510,56 @@ hipError_t launch_qdense(const GemmArgs& a, hipStream_t st) {
   return launch_shape<MODE_DENSE>(pick_shape(MODE_DENSE, a.N, a.M, a.K), p, st);
 }
 
+hipError_t launch_qconv_dma(const QgemmParams& p, bool nchw_out, hipStream_t st);
+
+// Fast path: rewrite both operands into the scratch buffer (one launch), then run the
+// implicit GEMM that streams them into LDS.  Returns false when the shape is outside what
+// that path indexes with 32 bits.
+static bool try_conv_dma(const GemmArgs& a, const ConvGeom& cg, hipStream_t st, hipError_t* err) {
+  const char* env = std::getenv("HAGO_QGEMM_PATH");  // tuning override: "reg" forces the generic kernel
+  if (env && env[0] == 'r') return false;
+  const int64_t Cp = (cg.C + 15) / 16 * 16;
+  const int64_t Hp = cg.H + 2 * (int64_t)cg.pad_h, Wp = cg.W + 2 * (int64_t)cg.pad_w;
+  const int64_t act_bytes = (int64_t)cg.B * Hp * Wp * Cp;
+  const int64_t Kp = (int64_t)cg.KH * cg.KW * Cp;
+  const int64_t wgt_bytes = (int64_t)cg.O * Kp;
+  if (act_bytes >= (1ll << 31) || wgt_bytes >= (1ll << 31) || Kp * Cp >= (1ll << 32)) return false;
+  if (!ptr_aligned(a.out, 4 * qgemm_out_elem_size(a)) && false) return false;
+  const size_t act_sz = ((size_t)act_bytes + 255) & ~(size_t)255;
+  void* scratch = nullptr;
+  *err = scratch_reserve(act_sz + (size_t)wgt_bytes + 256, &scratch);
+  if (*err != hipSuccess) return true;
+  uint8_t* act_p = static_cast<uint8_t*>(scratch);
+  int8_t* wgt_p = reinterpret_cast<int8_t*>(act_p + act_sz);
+  *err = launch_conv_prepack(a, cg, (int32_t)Cp, act_p, wgt_p, st);
+  if (*err != hipSuccess) return true;
+
+  ConvGeom pg = cg;  // geometry of the padded copy
+  pg.H = (int32_t)Hp; pg.W = (int32_t)Wp; pg.C = (int32_t)Cp; pg.pad_h = 0; pg.pad_w = 0;
+  GemmArgs b = a;
+  b.act = act_p;
+  b.wgt = wgt_p;
+  b.K = (int32_t)Kp;
+  QgemmParams p = make_qgemm_params(b, &pg);
+  p.act_xor4 = 0;  // the copy is already flipped; the zero-point term is unchanged
+  p.vec_k = 1;
+  p.act_bytes = (uint32_t)act_bytes;
+  p.inv_c = (uint32_t)(((1ull << 32) + (uint64_t)Cp - 1) / (uint64_t)Cp);
+  p.inv_kw = cg.KW > 1 ? (uint32_t)(((1ull << 32) + (uint64_t)cg.KW - 1) / (uint64_t)cg.KW) : 0u;
+  if (cg.nhwc) {
+    p.vec_out = (a.N % 4 == 0) && ptr_aligned(a.out, 4 * qgemm_out_elem_size(a));
+    p.vec16_out = (a.N % 16 == 0) && ptr_aligned(a.out, 16);
+  } else {
+    p.vec_out = ((cg.OH * cg.OW) % 4 == 0) && ptr_aligned(a.out, 4 * qgemm_out_elem_size(a));
+  }
+  *err = launch_qconv_dma(p, !cg.nhwc, st);
+  return true;
+}
+
 hipError_t launch_qconv_gemm(const GemmArgs& a, const ConvGeom& cg, hipStream_t st) {
   if (a.M == 0 || a.N == 0) return hipSuccess;
+  hipError_t err = hipSuccess;
+  if (try_conv_dma(a, cg, st, &err)) return err;
   QgemmParams p = make_qgemm_params(a, &cg);
   if (cg.nhwc) {
     p.vec_k = (cg.C % 16 == 0) && ptr_aligned(a.act, 16) && ptr_aligned(a.wgt, 16);

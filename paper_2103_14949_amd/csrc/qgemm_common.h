@@ -37,6 +37,8 @@ struct QgemmParams {
   int32_t vec16_out;   // dense: output rows can be written as aligned 16-byte pieces
   RequantScalars rs;
   ConvGeom g;
+  // implicit GEMM over a prepacked copy: its byte size and ceil(2^32 / C), ceil(2^32 / KW)
+  uint32_t act_bytes, inv_c, inv_kw;
 #ifdef HAGO_PHASE_TIMING
   long long* dbg;  // per-workgroup phase timestamps (development builds only)
   int dbg_skip;    // bit mask of main-loop parts to leave out in timing experiments

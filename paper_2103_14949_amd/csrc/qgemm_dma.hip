@@ -64,7 +64,9 @@ __device__ __forceinline__ v4i make_rsrc(const void* base, uint32_t bytes) {
 
 // kStages: depth of the LDS ring; OCC: wavefronts per SIMD the register budget must allow
 // (two 4-wavefront workgroups per CU keep the matrix pipe busy across each other's barriers).
-template <int WP, int WQ, int TP, int TQ, int kStages, int OCC>
+// CONV: the activation operand is an implicit im2col view of a padded NHWC copy of the input
+// (see conv_prepack.hip); ACT_ON_P: activations are the P operand (NCHW output).
+template <int WP, int WQ, int TP, int TQ, int kStages, int OCC, bool CONV, bool ACT_ON_P>
 __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParams p) {
   constexpr int NW = WP * WQ;          // wavefronts
   constexpr int NT = 64 * NW;
@@ -72,14 +74,17 @@ __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParam
   constexpr int BQ = WQ * TQ * 32;
   constexpr int STAGE = (BP + BQ) * kBK;
   constexpr int GP = BP / 16, GQ = BQ / 16;  // 16-row groups (one DMA instruction each)
-  static_assert(GP % NW == 0 && GQ % NW == 0, "row groups must divide among the wavefronts");
-  constexpr int LP = GP / NW, LQ = GQ / NW;  // DMA instructions per wavefront per stage
-  constexpr int L = LP + LQ;
+  constexpr int G = GP + GQ;
+  // Groups are dealt round-robin: wavefront w issues groups w, w + NW, ...  Every wavefront
+  // issues exactly L instructions per stage (the wait counts rely on it); a slot without a
+  // group fetches out-of-range data into a spare 1 KB of LDS.
+  constexpr int L = (G + NW - 1) / NW;
+  constexpr int CH = ACT_ON_P ? BQ : BP;  // output channels covered by the tile
 
   extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
-  int32_t* s_corr = reinterpret_cast<int32_t*>(smem + kStages * STAGE);
-  int32_t* s_mult = s_corr + BP;
-  int32_t* s_shift = s_mult + BP;
+  int32_t* s_corr = reinterpret_cast<int32_t*>(smem + kStages * STAGE + 1024);  // after the spare
+  int32_t* s_mult = s_corr + CH;
+  int32_t* s_shift = s_mult + CH;
 
   const int t = threadIdx.x;
   const int lane = t & 63;
@@ -87,60 +92,90 @@ __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParam
   const int wp = wave % WP;
   const int wq = wave / WP;
 
-  const int tiles_p = (p.N + BP - 1) / BP;
+  const int P_ext = ACT_ON_P ? p.M : p.N;
+  const int Q_ext = ACT_ON_P ? p.N : p.M;
+  const int tiles_p = (P_ext + BP - 1) / BP;
   const int tile = xcd_remap(blockIdx.x, gridDim.x);
   const int tile_p = tile % tiles_p;
   const int tile_q = tile / tiles_p;
-  const int p0 = tile_p * BP;  // first output channel
-  const int q0 = tile_q * BQ;  // first row m
+  const int p0 = tile_p * BP;  // first P row of the tile
+  const int q0 = tile_q * BQ;  // first Q row of the tile
+  const int w0 = ACT_ON_P ? q0 : p0;  // first output channel
 
   const v4i rs_w = make_rsrc(p.wgt, (uint32_t)p.N * (uint32_t)p.K);
-  const v4i rs_a = make_rsrc(p.act, (uint32_t)p.M * (uint32_t)p.K);
+  const v4i rs_a = make_rsrc(p.act, CONV ? p.act_bytes : (uint32_t)p.M * (uint32_t)p.K);
+  const v4i rs_p = ACT_ON_P ? rs_a : rs_w;
+  const v4i rs_q = ACT_ON_P ? rs_w : rs_a;
   const uint32_t lds0 =
       (uint32_t)(size_t)(__attribute__((address_space(3))) uint8_t*)smem;
 
-  // per-lane global offsets (without k0) of the chunks this lane fetches every stage
-  uint32_t off_p[LP], off_q[LQ];
+  // Per-lane global offset of the row this lane fetches in DMA instruction s (without the k
+  // part), and the logical chunk (in bytes) it fetches inside a stage.
+  // weights: row * K.  activations: dense row * K; conv: offset of the output pixel's window
+  // origin in the padded NHWC copy.
+  auto row_offset = [&](int row, bool is_act) -> uint32_t {
+    if (!is_act) return row < p.N ? (uint32_t)row * (uint32_t)p.K : kOob;
+    if (row >= p.M) return kOob;
+    if constexpr (!CONV) {
+      return (uint32_t)row * (uint32_t)p.K;
+    } else {
+      const ConvGeom& g = p.g;  // H, W, C are the padded copy's dimensions
+      const int ohw = g.OH * g.OW;
+      const int b = row / ohw;
+      const int pix = row - b * ohw;
+      const int oy = pix / g.OW;
+      const int ox = pix - oy * g.OW;
+      return (uint32_t)(((b * g.H + oy * g.stride_h) * g.W + ox * g.stride_w) * g.C);
+    }
+  };
+  uint32_t off[L];   // row offset of slot d
+  int lck[L];        // logical chunk (bytes) inside a stage
+  int ldst[L];       // LDS byte offset of the slot's 1 KB window inside a stage (< 0: spare)
+  bool slot_q[L], slot_act[L];
   const int lrow = lane >> 2;  // row inside a 16-row group
   const int lslot = lane & 3;  // physical 16-byte slot
 #pragma unroll
-  for (int s = 0; s < LP; ++s) {
-    const int rt = (wave + NW * s) * 16 + lrow;  // row inside the P tile
-    const int row = p0 + rt;
-    const int lc = lslot ^ swz4(rt);
-    off_p[s] = row < p.N ? (uint32_t)row * (uint32_t)p.K + lc * 16 : kOob;
+  for (int d = 0; d < L; ++d) {
+    const int grp = wave + NW * d;
+    const bool isq = grp >= GP;
+    const int rt = (isq ? grp - GP : grp) * 16 + lrow;  // row inside its tile
+    slot_q[d] = isq;
+    slot_act[d] = isq ? !ACT_ON_P : ACT_ON_P;
+    lck[d] = (lslot ^ swz4(rt)) * 16;
+    if (grp < G) {
+      off[d] = row_offset((isq ? q0 : p0) + rt, slot_act[d]);
+      ldst[d] = (isq ? BP * kBK + (grp - GP) * 1024 : grp * 1024);  // wavefront-uniform
+    } else {
+      off[d] = kOob;
+      ldst[d] = -1;
+    }
   }
-#pragma unroll
-  for (int s = 0; s < LQ; ++s) {
-    const int rt = (wave + NW * s) * 16 + lrow;
-    const int row = q0 + rt;
-    const int lc = lslot ^ swz4(rt);
-    off_q[s] = row < p.M ? (uint32_t)row * (uint32_t)p.K + lc * 16 : kOob;
-  }
-  // logical chunk of each load, to mask the k tail
-  int lc_p[LP], lc_q[LQ];
-#pragma unroll
-  for (int s = 0; s < LP; ++s) lc_p[s] = (lslot ^ swz4((wave + NW * s) * 16 + lrow)) * 16;
-#pragma unroll
-  for (int s = 0; s < LQ; ++s) lc_q[s] = (lslot ^ swz4((wave + NW * s) * 16 + lrow)) * 16;
+  // k (position along the reduction) -> byte offset relative to the row offset
+  auto k_offset = [&](int kk, bool is_act) -> uint32_t {
+    if constexpr (CONV) {
+      if (is_act) {
+        const ConvGeom& g = p.g;
+        const int t = (int)__umulhi((uint32_t)kk, p.inv_c);      // kk / C   (tap index)
+        const int c = kk - t * g.C;
+        const int ky = g.KW == 1 ? t : (int)__umulhi((uint32_t)t, p.inv_kw);  // t / KW
+        const int kx = t - ky * g.KW;
+        return (uint32_t)((ky * g.W + kx) * g.C + c);
+      }
+    }
+    return (uint32_t)kk;
+  };
 
-  // DMA instruction d (0 .. L-1) of a stage: the first LP fill the weight tile, the rest the
-  // activation tile.  d is a compile-time constant at every call site.
+  // DMA instruction d (0 .. L-1) of a stage: the first LP fill the P tile, the rest the Q tile.  d is a compile-time constant at every call site.
   auto issue_one = [&](int stage_idx, auto dconst) {
     constexpr int d = decltype(dconst)::value;
     const int k0 = stage_idx * kBK;
     const uint32_t base = lds0 + (uint32_t)(stage_idx % kStages) * STAGE;
     const bool tail = k0 + kBK > p.K;  // uniform: some chunks of this stage lie beyond K
-    if constexpr (d < LP) {
-      uint32_t o = off_p[d] + (uint32_t)k0;
-      if (tail && k0 + lc_p[d] >= p.K) o = kOob;
-      dma16(rs_w, base + (uint32_t)(wave + NW * d) * 1024u, o);
-    } else {
-      constexpr int e = d - LP;
-      uint32_t o = off_q[e] + (uint32_t)k0;
-      if (tail && k0 + lc_q[e] >= p.K) o = kOob;
-      dma16(rs_a, base + (uint32_t)BP * kBK + (uint32_t)(wave + NW * e) * 1024u, o);
-    }
+    uint32_t o = off[d] + k_offset(k0 + lck[d], slot_act[d]);
+    if (tail && k0 + lck[d] >= p.K) o = kOob;
+    const v4i rs = slot_q[d] ? rs_q : rs_p;
+    const uint32_t dst = ldst[d] >= 0 ? base + (uint32_t)ldst[d] : lds0 + (uint32_t)kStages * STAGE;
+    dma16(rs, (uint32_t)__builtin_amdgcn_readfirstlane((int)dst), o);
   };
   auto issue_range = [&](int stage_idx, auto lo, auto hi) {
     constexpr int kLo = decltype(lo)::value, kHi = decltype(hi)::value;
@@ -148,14 +183,15 @@ __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParam
       (issue_one(stage_idx, std::integral_constant<int, kLo + I>{}), ...);
     }(std::make_integer_sequence<int, kHi - kLo>{});
   };
-  constexpr int LH = L / 2;  // a stage is issued in two halves, spread over two MFMA groups
+  constexpr int LH = (L + 1) / 2;  // a stage is issued in two parts (LH and L - LH instructions),
+                                  // spread over two MFMA groups
   using IC0 = std::integral_constant<int, 0>;
   using ICH = std::integral_constant<int, LH>;
   using ICL = std::integral_constant<int, L>;
 
   HAGO_STAMP(p, 0);
-  ChannelRegs<NT, BP> chregs;
-  load_channel_regs<NT, BP>(p, p0, chregs);
+  ChannelRegs<NT, CH> chregs;
+  load_channel_regs<NT, CH>(p, w0, chregs);
 
   v16i acc[TP][TQ];
 #pragma unroll
@@ -164,9 +200,10 @@ __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParam
     for (int j = 0; j < TQ; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
-  int32_t wsum[TP];
+  constexpr int TW = ACT_ON_P ? TQ : TP;  // weight fragments per wavefront
+  int32_t wsum[TW];
 #pragma unroll
-  for (int i = 0; i < TP; ++i) wsum[i] = 0;
+  for (int i = 0; i < TW; ++i) wsum[i] = 0;
 
   const int KT = (p.K + kBK - 1) / kBK;
   // prologue: stages 0 .. kStages-1 (stages beyond K are all-zero fills, which keeps the
@@ -178,12 +215,14 @@ __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParam
 
   const int frow = lane & 31;
   const int fhalf = lane >> 5;
+  // only one wavefront per weight fragment row needs to sum it
+  const bool sums_here = ACT_ON_P ? (wp == 0) : (wq == 0);
 #ifdef HAGO_PHASE_TIMING
   const int x4 = (p.dbg_skip & 4) ? 0 : (int)p.act_xor4;
-  const bool need_wsum = (p.corr_coef != 0) && (wq == 0) && !(p.dbg_skip & 4);
+  const bool need_wsum = (p.corr_coef != 0) && sums_here && !(p.dbg_skip & 4);
 #else
-  const int x4 = (int)p.act_xor4;
-  const bool need_wsum = (p.corr_coef != 0) && (wq == 0);
+  const int x4 = (int)p.act_xor4;  // 0 in conv mode: the prepacked copy is already flipped
+  const bool need_wsum = (p.corr_coef != 0) && sums_here;
 #endif
   // fragment addresses inside a stage (bytes)
   int pa[TP][2], qa[TQ][2];
@@ -219,28 +258,36 @@ __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParam
     constexpr int kHalf = decltype(half)::value;
     if (need_wsum) {
 #pragma unroll
-      for (int i = 0; i < TP; ++i) {
-        wsum[i] = __builtin_amdgcn_sdot4(pf[i].x, 0x01010101, wsum[i], false);
-        wsum[i] = __builtin_amdgcn_sdot4(pf[i].y, 0x01010101, wsum[i], false);
-        wsum[i] = __builtin_amdgcn_sdot4(pf[i].z, 0x01010101, wsum[i], false);
-        wsum[i] = __builtin_amdgcn_sdot4(pf[i].w, 0x01010101, wsum[i], false);
+      for (int i = 0; i < TW; ++i) {
+        const v4i& f = ACT_ON_P ? qf[i < TQ ? i : 0] : pf[i < TP ? i : 0];
+        wsum[i] = __builtin_amdgcn_sdot4(f.x, 0x01010101, wsum[i], false);
+        wsum[i] = __builtin_amdgcn_sdot4(f.y, 0x01010101, wsum[i], false);
+        wsum[i] = __builtin_amdgcn_sdot4(f.z, 0x01010101, wsum[i], false);
+        wsum[i] = __builtin_amdgcn_sdot4(f.w, 0x01010101, wsum[i], false);
       }
+    }
+    if constexpr (ACT_ON_P && !CONV) {
+#pragma unroll
+      for (int i = 0; i < TP; ++i) pf[i] = v4i{pf[i].x ^ x4, pf[i].y ^ x4, pf[i].z ^ x4, pf[i].w ^ x4};
     }
     [&]<int... J>(std::integer_sequence<int, J...>) {
       ([&] {
         constexpr int j = J;
-        qf[j] = v4i{qf[j].x ^ x4, qf[j].y ^ x4, qf[j].z ^ x4, qf[j].w ^ x4};
+        if constexpr (!ACT_ON_P && !CONV)
+          qf[j] = v4i{qf[j].x ^ x4, qf[j].y ^ x4, qf[j].z ^ x4, qf[j].w ^ x4};
 #pragma unroll
         for (int i = 0; i < TP; ++i)
           acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(pf[i], qf[j], acc[i][j], 0, 0, 0);
         // DMA instructions [first, last) of this half go behind column j
-        constexpr int first = (j * LH) / TQ, last = ((j + 1) * LH) / TQ;
+        constexpr int cnt = kHalf == 0 ? LH : L - LH;   // instructions of this part
+        constexpr int org = kHalf == 0 ? 0 : LH;
+        constexpr int first = (j * cnt) / TQ, last = ((j + 1) * cnt) / TQ;
         if constexpr (last > first) {
 #ifdef HAGO_PHASE_TIMING
           if (!(p.dbg_skip & 1))
 #endif
-          issue_range(dma_stage, std::integral_constant<int, kHalf * LH + first>{},
-                      std::integral_constant<int, kHalf * LH + last>{});
+          issue_range(dma_stage, std::integral_constant<int, org + first>{},
+                      std::integral_constant<int, org + last>{});
         }
       }(), ...);
     }(std::make_integer_sequence<int, TQ>{});
@@ -286,34 +333,40 @@ __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParam
 
   // weight row sums: the two 32-lane halves hold the two k-halves of each row
 #pragma unroll
-  for (int i = 0; i < TP; ++i) {
+  for (int i = 0; i < TW; ++i) {
     int32_t v = wsum[i];
     v += __shfl_xor(v, 32);
-    if (wq == 0 && fhalf == 0) s_corr[(wp * TP + i) * 32 + frow] = v;
+    const int ci = ACT_ON_P ? (wq * TQ + i) * 32 + frow : (wp * TP + i) * 32 + frow;
+    if (sums_here && fhalf == 0) s_corr[ci] = v;
   }
   __syncthreads();
-  const bool any_sh0 = finish_channel_terms<NT, BP>(p, chregs, s_corr, s_mult, s_shift);
+  const bool any_sh0 = finish_channel_terms<NT, CH>(p, chregs, s_corr, s_mult, s_shift);
   HAGO_STAMP(p, 4);
-  constexpr bool kCanStage = ((BP / 16) & (BP / 16 - 1)) == 0 && BQ * BP <= kStages * STAGE &&
-                             (BQ * BP / 16) % NT == 0;
-  if constexpr (kCanStage) {
-    if (p.out_mode == 0 && !p.acc16 && p.vec16_out && p0 + BP <= p.N && q0 + BQ <= p.M) {
-      if (any_sh0)
-        qgemm_epilogue_dense_staged<WP, WQ, TP, TQ, false>(p, acc, p0, q0, s_corr, s_mult, s_shift, smem);
-      else
-        qgemm_epilogue_dense_staged<WP, WQ, TP, TQ, true>(p, acc, p0, q0, s_corr, s_mult, s_shift, smem);
-      return;
+  if constexpr (!ACT_ON_P) {
+    constexpr bool kCanStage = ((BP / 16) & (BP / 16 - 1)) == 0 && BQ * BP <= kStages * STAGE &&
+                               (BQ * BP / 16) % NT == 0;
+    if constexpr (kCanStage) {
+      if (p.out_mode == 0 && !p.acc16 && p.vec16_out && p0 + BP <= p.N && q0 + BQ <= p.M) {
+        if (any_sh0)
+          qgemm_epilogue_dense_staged<WP, WQ, TP, TQ, false>(p, acc, p0, q0, s_corr, s_mult, s_shift, smem);
+        else
+          qgemm_epilogue_dense_staged<WP, WQ, TP, TQ, true>(p, acc, p0, q0, s_corr, s_mult, s_shift, smem);
+        return;
+      }
     }
   }
-  qgemm_epilogue<WP, WQ, TP, TQ, false>(p, acc, p0, q0, s_corr, s_mult, s_shift);
+  qgemm_epilogue<WP, WQ, TP, TQ, ACT_ON_P>(p, acc, p0, q0, s_corr, s_mult, s_shift);
 }
 
-template <int WP, int WQ, int TP, int TQ, int kStages, int OCC>
+template <int WP, int WQ, int TP, int TQ, int kStages, int OCC, bool CONV, bool ACT_ON_P>
 hipError_t launch_dma_cfg(const QgemmParams& p, hipStream_t st) {
   constexpr int BP = WP * TP * 32, BQ = WQ * TQ * 32;
-  constexpr size_t lds = (size_t)kStages * (BP + BQ) * kBK + 3 * BP * sizeof(int32_t);
-  const int64_t tiles = (int64_t)((p.N + BP - 1) / BP) * ((p.M + BQ - 1) / BQ);
-  auto kern = qgemm_dma_kernel<WP, WQ, TP, TQ, kStages, OCC>;
+  constexpr int CH = ACT_ON_P ? BQ : BP;
+  constexpr size_t lds = (size_t)kStages * (BP + BQ) * kBK + 1024 + 3 * CH * sizeof(int32_t);
+  const int P_ext = ACT_ON_P ? p.M : p.N;
+  const int Q_ext = ACT_ON_P ? p.N : p.M;
+  const int64_t tiles = (int64_t)((P_ext + BP - 1) / BP) * ((Q_ext + BQ - 1) / BQ);
+  auto kern = qgemm_dma_kernel<WP, WQ, TP, TQ, kStages, OCC, CONV, ACT_ON_P>;
   static bool attr_set = false;  // raising the dynamic-LDS limit is needed once per kernel
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -330,13 +383,34 @@ hipError_t launch_dma_cfg(const QgemmParams& p, hipStream_t st) {
 // Requires: K % 16 == 0, K >= 16, 16-byte aligned operands, N*K and M*K below 2^31.
 hipError_t launch_qdense_dma(const QgemmParams& p, int shape, hipStream_t st) {
   switch (shape) {
-    case 1: return launch_dma_cfg<2, 2, 2, 4, 3, 2>(p, st);  // 128 x 256, 4 wavefronts, 2 per CU
-    case 2: return launch_dma_cfg<2, 2, 4, 2, 3, 2>(p, st);  // 256 x 128, 4 wavefronts, 2 per CU
-    case 3: return launch_dma_cfg<2, 2, 2, 2, 4, 2>(p, st);  // 128 x 128, 4 wavefronts
-    case 4: return launch_dma_cfg<4, 2, 1, 2, 4, 1>(p, st);  // 128 x 128, 8 wavefronts
-    case 5: return launch_dma_cfg<2, 2, 2, 4, 4, 1>(p, st);  // 128 x 256, 4 wavefronts, 1 per CU
-    default: return launch_dma_cfg<4, 2, 2, 4, 4, 1>(p, st); // 256 x 256, 8 wavefronts
+    case 1: return launch_dma_cfg<2, 2, 2, 4, 3, 2, false, false>(p, st);  // 128 x 256, 2 per CU
+    case 2: return launch_dma_cfg<2, 2, 4, 2, 3, 2, false, false>(p, st);  // 256 x 128, 2 per CU
+    case 3: return launch_dma_cfg<2, 2, 2, 2, 4, 2, false, false>(p, st);  // 128 x 128
+    case 5: return launch_dma_cfg<2, 2, 2, 4, 4, 1, false, false>(p, st);  // 128 x 256, 1 per CU
+    default: return launch_dma_cfg<4, 2, 2, 4, 4, 1, false, false>(p, st); // 256 x 256, 8 wavefronts
   }
+}
+
+// Implicit-GEMM convolution over the prepacked operands (p.act: padded NHWC copy, p.wgt:
+// [O][KH*KW*C] copy, p.g: geometry of the padded copy, p.K = KH*KW*C with C % 16 == 0).
+// nchw_out: output [B,O,OH,OW] (activations are the P operand) else [B,OH,OW,O].
+hipError_t launch_qconv_dma(const QgemmParams& p, bool nchw_out, hipStream_t st) {
+  const int64_t small_m = p.M <= 256 * 128;  // fewer than ~half the CUs with 256-pixel tiles
+  if (nchw_out) {  // P = pixels, Q = channels
+    if (p.N <= 32) return small_m ? launch_dma_cfg<4, 1, 1, 1, 4, 2, true, true>(p, st)    // 128 x 32
+                                  : launch_dma_cfg<4, 1, 2, 1, 4, 2, true, true>(p, st);   // 256 x 32
+    if (p.N <= 64) return small_m ? launch_dma_cfg<4, 1, 1, 2, 4, 2, true, true>(p, st)    // 128 x 64
+                                  : launch_dma_cfg<4, 1, 2, 2, 4, 2, true, true>(p, st);   // 256 x 64
+    if (p.N <= 128) return small_m ? launch_dma_cfg<2, 2, 2, 2, 4, 2, true, true>(p, st)   // 128 x 128
+                                   : launch_dma_cfg<4, 1, 2, 4, 4, 1, true, true>(p, st);  // 256 x 128
+    return small_m ? launch_dma_cfg<2, 2, 2, 2, 4, 2, true, true>(p, st)
+                   : launch_dma_cfg<4, 2, 2, 4, 4, 1, true, true>(p, st);                  // 256 x 256
+  }
+  // P = channels, Q = pixels
+  if (p.N <= 32) return launch_dma_cfg<1, 4, 1, 2, 4, 2, true, false>(p, st);     // 32 x 256
+  if (p.N <= 64) return launch_dma_cfg<1, 4, 2, 2, 4, 2, true, false>(p, st);     // 64 x 256
+  if (p.N <= 128 || small_m) return launch_dma_cfg<2, 2, 2, 2, 4, 2, true, false>(p, st);  // 128 x 128
+  return launch_dma_cfg<4, 2, 2, 4, 4, 1, true, false>(p, st);                    // 256 x 256
 }
 
 }  // namespace hago
