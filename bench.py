@@ -44,6 +44,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra-ops", action="store_true")
     ap.add_argument("--only", default="", help="comma list of extra-op names to time (default all)")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run plain copies of known size (for scaling rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); "
@@ -81,6 +83,15 @@ def main():
         e1.record()
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / iters
+
+    if args.pmc_calibration:
+        # 256 MiB device-to-device copies: 256 MiB fetched and 256 MiB written per kernel
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ------------------------------------------------------------------ headline: config 5
     M = 4096

@@ -12,8 +12,13 @@
  *
  * Conventions common to every call
  *   - Pointers marked "device" are GPU addresses valid on the current HIP
- *     device; "host" are ordinary pointers.  The caller owns every buffer: the
- *     library never allocates, frees or keeps a pointer after returning.
+ *     device; "host" are ordinary pointers.  The caller owns every buffer it
+ *     passes: the library never frees or keeps such a pointer after returning.
+ *   - hago_qconv2d with groups == 1 first rewrites its operands into a scratch
+ *     buffer that the library owns, one per device, allocated on first use and
+ *     reallocated when a larger one is needed (that call waits for the device
+ *     to go idle).  Calls that use it must not run concurrently on one device.
+ *     No other entry point allocates.
  *   - Tensors are dense and contiguous in the stated order.  `out` must not
  *     overlap any input.  A tensor with zero elements may be passed as NULL.
  *   - `stream` is the caller's hipStream_t (NULL = the default stream).  Calls
