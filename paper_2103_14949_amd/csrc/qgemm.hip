@@ -503,9 +503,18 @@ hipError_t launch_qdense(const GemmArgs& a, hipStream_t st) {
   const bool fits32 = (int64_t)a.N * a.K < (1ll << 31) && (int64_t)a.M * a.K < (1ll << 31);
   if (fits32 && !(env && env[0] == 'r')) {
     const char* sh = std::getenv("HAGO_DMA_SHAPE");  // tuning override
-    // 256 x 256 tiles while they still occupy at least half of the 256 CUs, else 128 x 128
-    const int64_t big_tiles = (int64_t)((a.N + 255) / 256) * ((a.M + 255) / 256);
-    return launch_qdense_dma(p, sh ? std::atoi(sh) : (big_tiles >= 128 ? 0 : 3), st);
+    // Tile shape: the one whose busiest CU has the least to do (rounds of tiles over the 256
+    // CUs x tile area), with larger tiles discounted for their better operand reuse.
+    struct Cand { int id, bp, bq; double eff; };
+    static const Cand cands[] = {{0, 256, 256, 1.0}, {1, 192, 256, 0.95}, {2, 128, 128, 0.75}};
+    int best = 0;
+    double best_cost = 0;
+    for (const Cand& c : cands) {
+      const int64_t tiles = (int64_t)((a.N + c.bp - 1) / c.bp) * ((a.M + c.bq - 1) / c.bq);
+      const double cost = (double)((tiles + 255) / 256) * c.bp * c.bq / c.eff;
+      if (c.id == 0 || cost < best_cost) { best = c.id; best_cost = cost; }
+    }
+    return launch_qdense_dma(p, sh ? std::atoi(sh) : best, st);
   }
   return launch_shape<MODE_DENSE>(pick_shape(MODE_DENSE, a.N, a.M, a.K), p, st);
 }

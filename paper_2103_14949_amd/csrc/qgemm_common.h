@@ -11,7 +11,7 @@
 namespace hago {
 
 #ifdef HAGO_PHASE_TIMING
-#define HAGO_STAMP(p, i) do { if (threadIdx.x == 0 && (p).dbg) (p).dbg[blockIdx.x * 8 + (i)] = __builtin_readcyclecounter(); } while (0)
+#define HAGO_STAMP(p, i) do { if (threadIdx.x == 0 && (p).dbg) (p).dbg[blockIdx.x * 8 + (i)] = wall_clock64(); } while (0)
 #else
 #define HAGO_STAMP(p, i) do { } while (0)
 #endif
@@ -137,23 +137,30 @@ __device__ __forceinline__ void load_channel_regs(const QgemmParams& p, int w0, 
 }
 
 // s_corr holds the weight row sums on entry; on exit s_corr/s_mult/s_shift hold the
-// per-channel terms.  Returns (block-uniform) whether some channel of the tile has shift 0.
+// per-channel terms and s_c64 the folded addend corr * mult + 2^(30+shift), with which
+// (acc + corr) * mult + rounding term is one 64-bit multiply-add per element.
+// Returns (block-uniform) whether the tile needs the general arithmetic: some channel has
+// shift 0 (the result is then not the high dword shifted right), or a correction so large
+// that acc + corr could leave int32 (whose wrap-around the folded form would not reproduce;
+// |acc| <= K * 2^14 < 2^30 for K <= 2^16).
 template <int NT, int CH>
 __device__ __forceinline__ bool finish_channel_terms(const QgemmParams& p, const ChannelRegs<NT, CH>& r,
                                                      int32_t* s_corr, int32_t* s_mult,
-                                                     int32_t* s_shift) {
-  int any0 = 0;
+                                                     int32_t* s_shift, int64_t* s_c64) {
+  int general = p.K > 65536;
 #pragma unroll
   for (int s = 0; s < ChannelRegs<NT, CH>::kSlots; ++s) {
     const int ci = (int)threadIdx.x + NT * s;
     if (ci < CH) {
-      s_corr[ci] = r.bias[s] + p.corr_coef * s_corr[ci];
+      const int32_t corr = r.bias[s] + p.corr_coef * s_corr[ci];
+      s_corr[ci] = corr;
       s_mult[ci] = r.mult[s];
       s_shift[ci] = r.shift[s];
-      any0 |= (r.shift[s] == 0);
+      s_c64[ci] = (int64_t)corr * (int64_t)r.mult[s] + ((int64_t)1 << (30 + (r.shift[s] & 31)));
+      general |= (r.shift[s] == 0) | (corr >= (1 << 30)) | (corr <= -(1 << 30));
     }
   }
-  return __syncthreads_or(any0) != 0;
+  return __syncthreads_or(general) != 0;
 }
 
 // r = floor((a * m + 2^(30+sh)) / 2^(31+sh)).  With SH_GE1 (sh >= 1) the shift
@@ -168,47 +175,86 @@ __device__ __forceinline__ int32_t mul_shift_fast(int32_t a, int32_t m, int64_t 
 
 // Dense epilogue of an interior tile through LDS: requantize, pack four channels
 // per dword, write the tile to LDS in output order [row m][channel n], then copy
-// it out with 16-byte stores that cover whole output rows.  s_out: BQ * BP bytes.
-template <int WP, int WQ, int TP, int TQ, bool SH_GE1>
+// it out with 16-byte stores that cover whole output rows.  LDS rows are BP + 16 bytes
+// apart, so the 32 rows a wavefront writes at once spread over the banks.
+// s_out: BQ * (BP + 16) bytes.  FOLDED: the tile qualifies for the folded arithmetic
+// (see finish_channel_terms); otherwise the general form is used.
+template <int WP, int WQ, int TP, int TQ, bool FOLDED>
 __device__ __forceinline__ void qgemm_epilogue_dense_staged(const QgemmParams& p,
                                                             v16i (&acc)[TP][TQ], int p0, int q0,
                                                             const int32_t* s_corr,
                                                             const int32_t* s_mult,
                                                             const int32_t* s_shift,
+                                                            const int64_t* s_c64,
                                                             uint8_t* s_out) {
   constexpr int NT = 64 * WP * WQ;
   constexpr int BP = WP * TP * 32, BQ = WQ * TQ * 32;
-  constexpr int CPR = BP / 16;  // 16-byte chunks per tile row
-  static_assert((CPR & (CPR - 1)) == 0, "chunk swizzle needs a power-of-two row");
+  constexpr int CPR = BP / 16;   // 16-byte chunks per tile row
+  constexpr int RS = BP + 16;    // LDS row stride
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const int wp = wave % WP, wq = wave / WP;
   const int frow = lane & 31, fhalf = lane >> 5;
-  const int32_t lo = p.rs.lo_rel, hi = p.rs.hi_rel, z = p.rs.z_out;
-#pragma unroll
-  for (int ti = 0; ti < TP; ++ti) {
-#pragma unroll
-    for (int g4 = 0; g4 < 4; ++g4) {
-      const int i_loc = (wp * TP + ti) * 32 + g4 * 8 + fhalf * 4;
-      const int4 c4 = *reinterpret_cast<const int4*>(s_corr + i_loc);
-      const int4 m4 = *reinterpret_cast<const int4*>(s_mult + i_loc);
-      const int4 s4 = *reinterpret_cast<const int4*>(s_shift + i_loc);
-      const int64_t rn0 = (int64_t)1 << (30 + s4.x), rn1 = (int64_t)1 << (30 + s4.y);
-      const int64_t rn2 = (int64_t)1 << (30 + s4.z), rn3 = (int64_t)1 << (30 + s4.w);
-#pragma unroll
-      for (int tj = 0; tj < TQ; ++tj) {
-        const int row = (wq * TQ + tj) * 32 + frow;
-        int32_t r0 = mul_shift_fast<SH_GE1>(acc[ti][tj][g4 * 4 + 0] + c4.x, m4.x, rn0, s4.x);
-        int32_t r1 = mul_shift_fast<SH_GE1>(acc[ti][tj][g4 * 4 + 1] + c4.y, m4.y, rn1, s4.y);
-        int32_t r2 = mul_shift_fast<SH_GE1>(acc[ti][tj][g4 * 4 + 2] + c4.z, m4.z, rn2, s4.z);
-        int32_t r3 = mul_shift_fast<SH_GE1>(acc[ti][tj][g4 * 4 + 3] + c4.w, m4.w, rn3, s4.w);
-        r0 = med3(r0, lo, hi); r1 = med3(r1, lo, hi); r2 = med3(r2, lo, hi); r3 = med3(r3, lo, hi);
-        if (z != 0) { r0 += z; r1 += z; r2 += z; r3 += z; }
-        const int chunk = (i_loc >> 4) ^ (row & (CPR - 1));
-        *reinterpret_cast<uint32_t*>(s_out + row * BP + chunk * 16 + (i_loc & 12)) =
-            pack4_perm(r0, r1, r2, r3);
-      }
+  int32_t lo = p.rs.lo_rel, hi = p.rs.hi_rel;
+  const int32_t z = p.rs.z_out;
+  // v_med3 takes one scalar operand at most: keep the bounds in vector registers once
+  asm volatile("" : "+v"(lo), "+v"(hi));
+  uint8_t* my_row = s_out + ((wq * TQ) * 32 + frow) * RS + wp * TP * 32 + fhalf * 4;
+  // Per-channel terms of group g = (ti, g4): four consecutive channels.  The terms of the next
+  // group are fetched while the current one is computed, and no further ahead (fetching all
+  // groups up front would cost more registers than the accumulators leave).
+  struct Terms { int4 m4, s4, c4; longlong2 ca, cb; };
+  auto load_terms = [&](int g) {
+    const int i_loc = (wp * TP + g / 4) * 32 + (g % 4) * 8 + fhalf * 4;
+    Terms t;
+    t.m4 = *reinterpret_cast<const int4*>(s_mult + i_loc);
+    t.s4 = *reinterpret_cast<const int4*>(s_shift + i_loc);
+    if constexpr (FOLDED) {
+      t.ca = *reinterpret_cast<const longlong2*>(s_c64 + i_loc);
+      t.cb = *reinterpret_cast<const longlong2*>(s_c64 + i_loc + 2);
+    } else {
+      t.c4 = *reinterpret_cast<const int4*>(s_corr + i_loc);
     }
+    return t;
+  };
+  Terms cur = load_terms(0);
+#pragma unroll
+  for (int g = 0; g < TP * 4; ++g) {
+    const int ti = g / 4, g4 = g % 4;
+    Terms nxt = cur;
+    if (g + 1 < TP * 4) nxt = load_terms(g + 1);
+    __builtin_amdgcn_sched_barrier(0);
+    const int32_t mm[4] = {cur.m4.x, cur.m4.y, cur.m4.z, cur.m4.w};
+    const int32_t ss[4] = {cur.s4.x, cur.s4.y, cur.s4.z, cur.s4.w};
+    int32_t r[TQ][4];
+    if constexpr (FOLDED) {
+      const int64_t c64[4] = {cur.ca.x, cur.ca.y, cur.cb.x, cur.cb.y};
+#pragma unroll
+      for (int tj = 0; tj < TQ; ++tj)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int64_t pr = (int64_t)acc[ti][tj][g4 * 4 + e] * (int64_t)mm[e] + c64[e];
+          r[tj][e] = (int32_t)(pr >> 32) >> (ss[e] - 1);
+        }
+    } else {
+      const int32_t cc[4] = {cur.c4.x, cur.c4.y, cur.c4.z, cur.c4.w};
+#pragma unroll
+      for (int tj = 0; tj < TQ; ++tj)
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          r[tj][e] = mul_shift_fast<false>(acc[ti][tj][g4 * 4 + e] + cc[e], mm[e],
+                                           (int64_t)1 << (30 + ss[e]), ss[e]);
+    }
+#pragma unroll
+    for (int tj = 0; tj < TQ; ++tj) {
+      int32_t r0 = med3(r[tj][0], lo, hi), r1 = med3(r[tj][1], lo, hi);
+      int32_t r2 = med3(r[tj][2], lo, hi), r3 = med3(r[tj][3], lo, hi);
+      if (z != 0) { r0 += z; r1 += z; r2 += z; r3 += z; }
+      *reinterpret_cast<uint32_t*>(my_row + tj * 32 * RS + ti * 32 + g4 * 8) =
+          pack4_perm(r0, r1, r2, r3);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    cur = nxt;
   }
   __syncthreads();
   HAGO_STAMP(p, 5);
@@ -217,7 +263,7 @@ __device__ __forceinline__ void qgemm_epilogue_dense_staged(const QgemmParams& p
   for (int s = 0; s < (BQ * CPR) / NT; ++s) {
     const int q = (int)threadIdx.x + NT * s;
     const int row = q / CPR, c = q % CPR;
-    const v4i v = *reinterpret_cast<const v4i*>(s_out + row * BP + ((c ^ (row & (CPR - 1))) * 16));
+    const v4i v = *reinterpret_cast<const v4i*>(s_out + row * RS + c * 16);
     *reinterpret_cast<v4i*>(out8 + (size_t)(q0 + row) * p.N + p0 + c * 16) = v;
   }
   HAGO_STAMP(p, 6);
