@@ -144,9 +144,19 @@ def main():
                           "frac": round(l["ops"] / (ms * 1e-3) / 1e12 / PEAK_INT8_TOPS, 4)})
     log("config 5 layers:", per_layer)
 
-    roofline = {"bound": "mfma", "kernel": "qgemm_kernel (int8 MFMA 32x32x32, fused requantize)",
+    # HBM bytes per launch cannot be counted from inside this process: the figure is the one the
+    # committed rocprofv3 --pmc summary of this same command ends with (null if it is absent).
+    traffic, traffic_src = None, None
+    prof = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles",
+                        "qgemm_dma_config5_hbm_traffic.md")
+    if os.path.exists(prof):
+        for line in open(prof):
+            if line.startswith("traffic_bytes_per_launch:"):
+                traffic = int(line.split(":")[1])
+                traffic_src = "profiles/qgemm_dma_config5_hbm_traffic.md (FETCH_SIZE x2 + WRITE_SIZE, KiB)"
+    roofline = {"bound": "mfma", "traffic_source": traffic_src, "kernel": "qgemm_dma_kernel (int8 MFMA 32x32x32, fused requantize)",
                 "achieved": round(achieved, 2), "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
-                "frac": round(achieved / PEAK_INT8_TOPS, 4), "traffic": None,
+                "frac": round(achieved / PEAK_INT8_TOPS, 4), "traffic": traffic,
                 "avg_launch_us": round(avg_launch_ms * 1e3, 3), "launches_per_step": len(layers),
                 "ops_per_step": total_ops, "per_layer": per_layer}
 
