@@ -3,7 +3,10 @@
 // so there is no MFMA here; the work is 9 multiply-adds per output on the
 // vector ALUs (4 at a time with v_dot4) out of an LDS copy of the input plane.
 //
-//   wave3x3  : NCHW, 3x3, stride 1, pad 1, W <= 64.  One WAVEFRONT per (image,
+//   rows3x3  : NCHW, 3x3, stride 1, pad 1, W <= 64, W % 4 == 0, aligned.  One WAVEFRONT
+//              per (image, channel) plane and no LDS: a lane loads one dword per
+//              input row and gets its neighbours' by DPP; see the kernel.
+//   wave3x3  : the same geometry without the alignment conditions.  One WAVEFRONT per (image,
 //              channel) plane, four planes per workgroup.  A lane owns a strip
 //              of four output columns and a quarter of the rows and slides
 //              down it, so every staged input row is read from LDS once and
@@ -335,6 +338,143 @@ __global__ __launch_bounds__(kThreads) void dw_wave3x3_kernel(DwArgs p, int32_t 
   }
 }
 
+
+// NCHW 3x3 stride 1 pad 1, W <= 64, W % 4 == 0, aligned tensors, planes below 2 GB: no LDS.
+// One wavefront per plane.  Lane (q, rc): strip of four output columns q, quarter rc of the
+// rows.  A lane loads ONE dword per input row (its own strip) and takes the left and right
+// neighbours' dwords by DPP row shifts (the 16 lanes of a DPP row are the strips of one image
+// row; lanes without a strip hold the zero point, which is also what a shift from outside the
+// row yields).  All 18 loads of a pass (16 output rows plus halo) and the per-channel constants
+// are in flight together.  Loads and stores go through buffer descriptors of the plane, so a
+// lane that has nothing to load or store just uses an out-of-range offset.
+// MODE 0: requantized 8-bit, 1: raw int32, 2: raw int16; ACC16: accumulator wraps to 16 bits.
+template <int MODE, bool ACC16>
+__global__ __launch_bounds__(kThreads) void dw_rows3x3_kernel(DwArgs p, int64_t planes) {
+  const ConvGeom& g = p.g;
+  const int H = g.H, W = g.W;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int64_t plane = (int64_t)blockIdx.x * 4 + wave;  // b * C + c
+  if (plane >= planes) return;  // wavefront-uniform; the kernel has no barrier
+  const int c = (int)(plane % g.C);
+  constexpr uint32_t kOob = 0x80000000u;
+  constexpr int kEsz = MODE == 0 ? 1 : (MODE == 1 ? 4 : 2);
+
+  const int q = lane & 15;
+  const int rc = lane >> 4;
+  const int rpc = (H + 3) >> 2;  // rows per quarter
+  const int y0 = rc * rpc;
+  const int y1 = (y0 + rpc < H) ? y0 + rpc : H;
+  const uint32_t lane_off = (q << 2) < W ? (uint32_t)(q << 2) : kOob;  // byte column of the strip
+  const uint32_t x4 = p.act_xor * 0x01010101u;
+  const uint32_t pad4 = (((uint32_t)p.z_a ^ p.act_xor) & 0xffu) * 0x01010101u;
+  const int64_t pbytes = (int64_t)H * W;
+  const __amdgpu_buffer_rsrc_t rin = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint8_t*>(p.act) + plane * pbytes, 0, (int)pbytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rout = __builtin_amdgcn_make_buffer_rsrc(
+      static_cast<uint8_t*>(p.out) + plane * pbytes * kEsz, 0, (int)(pbytes * kEsz), 0x00020000);
+  constexpr int kPass = 16;  // output rows per lane and pass
+
+  const int8_t* wc = p.wgt + (int64_t)c * 9;
+  int32_t wraw[9];
+#pragma unroll
+  for (int i = 0; i < 9; ++i) wraw[i] = wc[i];
+  const int32_t bias = p.bias ? p.bias[c] : 0;
+  const int pc = p.per_channel ? c : 0;
+  const int32_t m = MODE == 0 ? p.mult[pc] : 0;
+  const int32_t sh = MODE == 0 ? p.shift[pc] : 0;
+  // Rows outside the image (or beyond the quarter's halo) read as the zero point: an
+  // out-of-range buffer load returns 0, and the per-lane flip mask turns that into the
+  // zero point's byte (in range it is the plain sign flip).  The mask is opaque to the
+  // compiler: with a select on the loaded value it builds a branch around every load, each
+  // followed by a full wait.
+  auto load_rows = [&](int yb, uint32_t (&d)[kPass + 2]) {
+#pragma unroll
+    for (int i = 0; i < kPass + 2; ++i) {
+      const int y = y0 + yb + i - 1;
+      const bool ok = lane_off != kOob && (uint32_t)y < (uint32_t)H && yb + i - 1 <= rpc;
+      uint32_t flip = ok ? x4 : pad4;
+      asm volatile("" : "+v"(flip));
+      const uint32_t off = ok ? lane_off + (uint32_t)(y * W) : kOob;
+      d[i] = __builtin_amdgcn_raw_buffer_load_b32(rin, off, 0, 0) ^ flip;
+    }
+  };
+  uint32_t d[kPass + 2];
+  load_rows(0, d);
+
+  int32_t wrow[3];
+  int32_t wsum = 0;
+#pragma unroll
+  for (int ky = 0; ky < 3; ++ky) {
+    const int32_t w0 = wraw[ky * 3 + 0], w1 = wraw[ky * 3 + 1], w2 = wraw[ky * 3 + 2];
+    wsum += w0 + w1 + w2;
+    wrow[ky] = (w0 & 0xff) | ((w1 & 0xff) << 8) | ((w2 & 0xff) << 16);
+  }
+  int32_t corr = bias + (p.act_off - p.z_a) * wsum;
+  const int64_t rnd = (int64_t)1 << (30 + sh);
+  int32_t lo = p.rs.lo_rel, hi = p.rs.hi_rel;
+  const int32_t z = p.rs.z_out;
+  // vector-register copies: v_med3 takes at most one scalar operand
+  asm volatile("" : "+v"(lo), "+v"(hi));
+
+  // the four 3-byte windows of a strip: output x = 4q + i reads input columns x-1 .. x+1
+  auto windows = [&](uint32_t d1, uint32_t (&w)[4]) {
+    const uint32_t d0 = (uint32_t)__builtin_amdgcn_update_dpp((int)pad4, (int)d1, 0x111, 0xf, 0xf, false);  // row_shr:1
+    const uint32_t d2 = (uint32_t)__builtin_amdgcn_update_dpp((int)pad4, (int)d1, 0x101, 0xf, 0xf, false);  // row_shl:1
+    w[0] = __builtin_amdgcn_alignbyte(d1, d0, 3);
+    w[1] = d1;
+    w[2] = __builtin_amdgcn_alignbyte(d2, d1, 1);
+    w[3] = __builtin_amdgcn_alignbyte(d2, d1, 2);
+  };
+  // (the builtin, not inline assembly: the compiler has to see the dot instructions to keep the
+  // wait states they need before a dependent instruction)
+  auto dot4 = [](uint32_t a, int32_t b, int32_t c) {
+    return __builtin_amdgcn_sdot4((int)a, b, c, false);
+  };
+  for (int yb = 0; yb < rpc; yb += kPass) {  // uniform trip count: every lane keeps feeding the DPP
+    if (yb > 0) load_rows(yb, d);
+    uint32_t wa[4], wb[4], wcur[4];
+    windows(d[0], wa);
+    windows(d[1], wb);
+#pragma unroll
+    for (int i = 0; i < kPass; ++i) {
+      if (yb + i < rpc) {  // uniform
+        const int y = y0 + yb + i;
+        windows(d[i + 2], wcur);
+        int32_t acc[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          int32_t a = dot4(wa[e], wrow[0], corr);
+          a = dot4(wb[e], wrow[1], a);
+          a = dot4(wcur[e], wrow[2], a);
+          acc[e] = ACC16 ? (int32_t)(int16_t)a : a;
+        }
+        // lanes without a strip, and rows beyond a short last quarter, store out of range
+        const uint32_t so = (lane_off != kOob && y < y1) ? (lane_off + (uint32_t)(y * W)) * kEsz : kOob;
+        if constexpr (MODE == 0) {
+          int32_t r[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int64_t pr = (int64_t)acc[e] * (int64_t)m + rnd;
+            r[e] = med3((int32_t)(pr >> (31 + sh)), lo, hi) + z;
+          }
+          __builtin_amdgcn_raw_buffer_store_b32(pack4_perm(r[0], r[1], r[2], r[3]), rout, so, 0, 2);
+        } else if constexpr (MODE == 1) {
+          typedef int32_t v4i32 __attribute__((ext_vector_type(4)));
+          __builtin_amdgcn_raw_buffer_store_b128(v4i32{acc[0], acc[1], acc[2], acc[3]}, rout, so, 0, 2);
+        } else {
+          typedef uint32_t v2u32 __attribute__((ext_vector_type(2)));
+          __builtin_amdgcn_raw_buffer_store_b64(
+              v2u32{(uint32_t)(acc[0] & 0xffff) | ((uint32_t)acc[1] << 16),
+                    (uint32_t)(acc[2] & 0xffff) | ((uint32_t)acc[3] << 16)}, rout, so, 0, 2);
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { wa[e] = wb[e]; wb[e] = wcur[e]; }
+      }
+    }
+  }
+}
+
 }  // namespace
 
 hipError_t launch_qconv_depthwise(const GemmArgs& a, const ConvGeom& cg, hipStream_t st) {
@@ -372,8 +512,14 @@ hipError_t launch_qconv_depthwise(const GemmArgs& a, const ConvGeom& cg, hipStre
                         ((reinterpret_cast<uintptr_t>(a.out) & (4 * esz - 1)) == 0);
     const uint32_t w4 = vec_io ? (uint32_t)cg.W / 4 : 1u;
     const uint32_t inv_w4 = w4 > 1 ? (uint32_t)(((1ull << 32) + w4 - 1) / w4) : 0u;  // unused for w4 == 1
-    hipLaunchKernelGGL(dw_wave3x3_kernel, dim3((unsigned)((planes + 3) / 4)), dim3(kThreads),
-                       wave_lds, st, p, rs, inv_w4, vec_io ? 1 : 0, planes);
+    if (vec_io && (planes + 3) / 4 < (1ll << 31) && (int64_t)cg.H * cg.W * 4 < (1ll << 31)) {
+      auto kern = p.out_mode == 1 ? dw_rows3x3_kernel<1, false>
+                : p.out_mode == 2 ? dw_rows3x3_kernel<2, true>
+                : p.acc16 ? dw_rows3x3_kernel<0, true> : dw_rows3x3_kernel<0, false>;
+      hipLaunchKernelGGL(kern, dim3((unsigned)((planes + 3) / 4)), dim3(kThreads), 0, st, p, planes);
+    } else
+      hipLaunchKernelGGL(dw_wave3x3_kernel, dim3((unsigned)((planes + 3) / 4)), dim3(kThreads),
+                         wave_lds, st, p, rs, inv_w4, vec_io ? 1 : 0, planes);
   } else if (plane_ok && lds_bytes <= (size_t)kMaxLdsBytes && planes * nband < (1ll << 31)) {
     const size_t esz = a.has_rq ? 1 : (a.acc16 ? 2 : 4);
     const bool vec_io = (cg.W % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.act) & 3u) == 0) &&
