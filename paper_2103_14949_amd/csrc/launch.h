@@ -51,6 +51,9 @@ hipError_t launch_qconv_gemm(const GemmArgs& g, const ConvGeom& cg, hipStream_t 
 hipError_t scratch_reserve(size_t bytes, void** out);
 hipError_t launch_conv_prepack(const GemmArgs& g, const ConvGeom& cg, int32_t Cp, uint8_t* act_out,
                                int8_t* wgt_out, hipStream_t st);
+// 1x1 stride-1 unpadded NCHW convolution straight from the caller's buffers; false when the
+// geometry is not that kernel's (nothing is launched then).
+bool try_qconv_pointwise_nchw(const GemmArgs& g, const ConvGeom& cg, hipStream_t st, hipError_t* err);
 // depthwise convolution (groups == C == O), no MFMA.
 hipError_t launch_qconv_depthwise(const GemmArgs& g, const ConvGeom& cg, hipStream_t st);
 

@@ -1,0 +1,210 @@
+// 1x1 convolution (stride 1, no padding, groups == 1) on NCHW tensors, straight from the
+// caller's buffers: out[b][n][p] = sum_c (a[b][c][p] - z_a) * w[n][c] + bias[n], p = y * W + x.
+//
+// In NCHW the reduction index c is the slow one, while the MFMA wants, per lane, 16
+// consecutive k-bytes of one row.  The general convolution path therefore rewrites the input
+// into a channel-last copy first, which for this operator (few output channels, so hardly any
+// reuse of the input) costs more memory traffic than the convolution itself.  Here a
+// wavefront owns 32 consecutive pixels of one image and gathers its activation fragments with
+// byte loads: the 32 lanes of a half-wavefront read 32 consecutive pixels of one channel, so
+// every load instruction touches two 32-byte segments, and each input byte is fetched once.
+// The MFMA runs with the pixels as its P operand: a lane then owns one output channel and, per
+// group of four accumulator registers, four consecutive pixels, which are packed and stored
+// together.  The work is bound by memory, not by the matrix pipe (an output channel tile does
+// 1/32 of an MFMA per pixel and k-step).
+//
+// All loads of a few k-steps (32 channels each) are issued before the first is used.
+// Out-of-range channels and pixels are fetched through buffer descriptors with out-of-range
+// offsets (they read as 0; the weights of padded channels are 0 as well).
+#include "hago_device.h"
+#include "launch.h"
+
+namespace hago {
+
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+constexpr uint32_t kOob = 0x80000000u;
+
+struct PwArgs {
+  const uint8_t* act;
+  const int8_t* wgt;
+  const int32_t* bias;
+  void* out;
+  const int32_t* mult;
+  const int32_t* shift;
+  int32_t B, C, HW, N;
+  int32_t tiles_per_img;
+  int64_t tiles;
+  uint32_t act_xor4;   // 0x80808080 for uint8 activations
+  int32_t corr_coef;   // off - z_a
+  int32_t per_channel;
+  RequantScalars rs;
+};
+
+// MODE 0: requantized 8-bit, 1: raw int32, 2: raw int16; ACC16: accumulator wraps to 16 bits;
+// NT: 32-channel tiles per wavefront (N <= 32 * NT).
+template <int MODE, bool ACC16, int NT>
+__global__ __launch_bounds__(256) void pw_nchw_kernel(PwArgs p) {
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int64_t tile = (int64_t)blockIdx.x * 4 + wave;
+  if (tile >= p.tiles) return;  // wavefront-uniform; the kernel has no barrier
+  const int b = (int)(tile / p.tiles_per_img);
+  const int pix0 = (int)(tile - (int64_t)b * p.tiles_per_img) * 32;
+  const int i = lane & 31, h = lane >> 5;
+  const int C = p.C, HW = p.HW, N = p.N;
+
+  const __amdgpu_buffer_rsrc_t rin = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint8_t*>(p.act) + (int64_t)b * C * HW, 0, C * HW, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<int8_t*>(p.wgt), 0, N * C, 0x00020000);
+  const uint32_t a_lane = (pix0 + i < HW) ? (uint32_t)(pix0 + i) : kOob;  // + channel * HW
+  uint32_t w_lane[NT];                                                    // + k
+#pragma unroll
+  for (int t = 0; t < NT; ++t) w_lane[t] = (t * 32 + i < N) ? (uint32_t)((t * 32 + i) * C) : kOob;
+
+  // the lane's output channels: requantize parameters (used at the very end)
+  int32_t bias_r[NT], mult_r[NT], shift_r[NT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+    const int n = t * 32 + i;
+    bias_r[t] = 0; mult_r[t] = 0; shift_r[t] = 0;
+    if (n < N) {
+      if (p.bias) bias_r[t] = p.bias[n];
+      if (MODE == 0) {
+        mult_r[t] = p.mult[p.per_channel ? n : 0];
+        shift_r[t] = p.shift[p.per_channel ? n : 0];
+      }
+    }
+  }
+
+  v16i acc[NT];
+  int32_t wsum[NT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+    wsum[t] = 0;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[t][r] = 0;
+  }
+  // k-steps whose loads are in flight together (fewer with more accumulators, for registers)
+  constexpr int kChunk = NT == 1 ? 6 : (NT == 2 ? 4 : 2);
+  const int ksteps = (C + 31) >> 5;
+  for (int s0 = 0; s0 < ksteps; s0 += kChunk) {
+    uint32_t ab[kChunk][16];
+    v4i wb[kChunk][NT];
+#pragma unroll
+    for (int u = 0; u < kChunk; ++u) {
+      if (s0 + u < ksteps) {  // uniform
+        const int k = (s0 + u) * 32 + 16 * h;  // first channel of this lane's 16 (C % 16 == 0)
+        const bool kok = k < C;
+#pragma unroll
+        for (int j = 0; j < 16; ++j)
+          ab[u][j] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b8(
+              rin, (kok && a_lane != kOob) ? a_lane + (uint32_t)((k + j) * HW) : kOob, 0, 0);
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+          wb[u][t] = __builtin_amdgcn_raw_buffer_load_b128(
+              rw, (kok && w_lane[t] != kOob) ? w_lane[t] + (uint32_t)k : kOob, 0, 0);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kChunk; ++u) {
+      if (s0 + u < ksteps) {  // uniform
+        v4i af;
+#pragma unroll
+        for (int d = 0; d < 4; ++d)
+          af[d] = (int)((ab[u][4 * d] | (ab[u][4 * d + 1] << 8) | (ab[u][4 * d + 2] << 16) |
+                         (ab[u][4 * d + 3] << 24)) ^ p.act_xor4);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+#pragma unroll
+          for (int d = 0; d < 4; ++d)
+            wsum[t] = __builtin_amdgcn_sdot4(wb[u][t][d], 0x01010101, wsum[t], false);
+          acc[t] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af, wb[u][t], acc[t], 0, 0, 0);
+        }
+      }
+    }
+  }
+
+  // Lane l owns channel t * 32 + l % 32; registers 4g .. 4g+3 are pixels 8g + 4 * (l / 32) + 0..3.
+  const RequantScalars rs = p.rs;
+  constexpr int kEsz = MODE == 0 ? 1 : (MODE == 1 ? 4 : 2);
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+    const int n = t * 32 + i;
+    const int32_t ws = wsum[t] + __shfl_xor(wsum[t], 32);  // the two k-halves of the row sums
+    const int32_t corr = bias_r[t] + p.corr_coef * ws;
+    const int64_t rnd = (int64_t)1 << (30 + shift_r[t]);
+    uint8_t* orow = static_cast<uint8_t*>(p.out) + ((int64_t)b * N + n) * HW * kEsz;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int pg = pix0 + 8 * g + 4 * h;  // HW % 4 == 0: the group is inside the image or outside
+      if (n < N && pg < HW) {
+        int32_t v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          v[e] = acc[t][4 * g + e] + corr;
+          if (ACC16) v[e] = (int32_t)(int16_t)v[e];
+        }
+        if constexpr (MODE == 0) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int64_t pr = (int64_t)v[e] * (int64_t)mult_r[t] + rnd;
+            v[e] = med3((int32_t)(pr >> (31 + shift_r[t])), rs.lo_rel, rs.hi_rel) + rs.z_out;
+          }
+          *reinterpret_cast<uint32_t*>(orow + pg) = pack4_perm(v[0], v[1], v[2], v[3]);
+        } else if constexpr (MODE == 1) {
+          *reinterpret_cast<int4*>(orow + (int64_t)pg * 4) = make_int4(v[0], v[1], v[2], v[3]);
+        } else {
+          *reinterpret_cast<short4*>(orow + (int64_t)pg * 2) =
+              make_short4((short)v[0], (short)v[1], (short)v[2], (short)v[3]);
+        }
+      }
+    }
+  }
+}
+
+template <int MODE, bool ACC16>
+hipError_t launch_nt(const PwArgs& p, hipStream_t st) {
+  const unsigned grid = (unsigned)((p.tiles + 3) / 4);
+  if (p.N <= 32) hipLaunchKernelGGL((pw_nchw_kernel<MODE, ACC16, 1>), dim3(grid), dim3(256), 0, st, p);
+  else if (p.N <= 64) hipLaunchKernelGGL((pw_nchw_kernel<MODE, ACC16, 2>), dim3(grid), dim3(256), 0, st, p);
+  else hipLaunchKernelGGL((pw_nchw_kernel<MODE, ACC16, 4>), dim3(grid), dim3(256), 0, st, p);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+// Returns false (and launches nothing) when the geometry is not this kernel's.
+bool try_qconv_pointwise_nchw(const GemmArgs& a, const ConvGeom& cg, hipStream_t st, hipError_t* err) {
+  const int64_t HW = (int64_t)cg.H * cg.W;
+  const size_t esz = a.has_rq ? 1 : (a.acc16 ? 2 : 4);
+  if (cg.nhwc || cg.KH != 1 || cg.KW != 1 || cg.stride_h != 1 || cg.stride_w != 1 || cg.pad_h != 0 ||
+      cg.pad_w != 0 || cg.C % 16 != 0 || HW % 4 != 0 || cg.O > 128 || (int64_t)cg.C * HW >= (1ll << 31) ||
+      (int64_t)cg.O * cg.C >= (1ll << 31) || (reinterpret_cast<uintptr_t>(a.wgt) & 15u) != 0 ||
+      (reinterpret_cast<uintptr_t>(a.out) & (4 * esz - 1)) != 0)
+    return false;
+  PwArgs p{};
+  p.act = static_cast<const uint8_t*>(a.act);
+  p.wgt = a.wgt;
+  p.bias = a.bias;
+  p.out = a.out;
+  p.mult = a.rq.multiplier;
+  p.shift = a.rq.shift;
+  p.B = cg.B; p.C = cg.C; p.HW = (int32_t)HW; p.N = cg.O;
+  p.tiles_per_img = (int32_t)((HW + 31) / 32);
+  p.tiles = (int64_t)cg.B * p.tiles_per_img;
+  p.act_xor4 = a.act_unsigned ? 0x80808080u : 0u;
+  p.corr_coef = (a.act_unsigned ? 128 : 0) - a.act_zero_point;
+  p.per_channel = a.rq.per_channel;
+  p.rs = RequantScalars{a.rq.z_out, a.rq.clip_lo - a.rq.z_out, a.rq.clip_hi - a.rq.z_out};
+  if (p.tiles == 0 || p.tiles / 4 >= (1ll << 31)) return false;
+  if (a.has_rq) *err = a.acc16 ? launch_nt<0, true>(p, st) : launch_nt<0, false>(p, st);
+  else *err = a.acc16 ? launch_nt<2, true>(p, st) : launch_nt<1, false>(p, st);
+  return true;
+}
+
+}  // namespace hago

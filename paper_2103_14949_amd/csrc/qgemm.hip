@@ -568,6 +568,14 @@ static bool try_conv_dma(const GemmArgs& a, const ConvGeom& cg, hipStream_t st, 
 hipError_t launch_qconv_gemm(const GemmArgs& a, const ConvGeom& cg, hipStream_t st) {
   if (a.M == 0 || a.N == 0) return hipSuccess;
   hipError_t err = hipSuccess;
+  const char* env = std::getenv("HAGO_QGEMM_PATH");  // tuning override: "reg" / "dma" skip the special cases
+  if (!env) {
+    if (try_qconv_pointwise_nchw(a, cg, st, &err)) return err;
+    // channel-last 1x1 stride-1 unpadded convolution is a dense layer over the pixels
+    if (cg.nhwc && cg.KH == 1 && cg.KW == 1 && cg.stride_h == 1 && cg.stride_w == 1 && cg.pad_h == 0 &&
+        cg.pad_w == 0)
+      return launch_qdense(a, st);
+  }
   if (try_conv_dma(a, cg, st, &err)) return err;
   QgemmParams p = make_qgemm_params(a, &cg);
   if (cg.nhwc) {

@@ -118,6 +118,41 @@ def test_qconv2d_raw(case, adt, za, layout):
     assert_same(np.ascontiguousarray(got), want, f"qconv2d {layout} {case}")
 
 
+POINTWISE_CASES = [
+    # B C H W O: 1x1 stride-1 unpadded NCHW convolutions with C % 16 == 0 and H*W % 4 == 0 (the
+    # direct kernel): partial pixel tiles, one / two / four channel tiles per wavefront
+    (2, 16, 6, 6, 5), (1, 48, 5, 8, 33), (3, 32, 10, 10, 70), (1, 160, 4, 7, 128), (2, 208, 16, 12, 24),
+]
+
+
+@pytest.mark.parametrize("case", POINTWISE_CASES)
+@pytest.mark.parametrize("adt,za", [(np.uint8, 7), (np.int8, -3)])
+def test_pointwise_nchw_all_output_modes(case, adt, za):
+    B, C, H, W, O = case
+    rng = np.random.default_rng(abs(hash((case, za))) % 2 ** 31)
+    a = rnd_act(rng, (B, C, H, W), adt)
+    w = rnd_w(rng, (O, C, 1, 1))
+    bias = rng.integers(-5000, 5000, O).astype(np.int32)
+    args = (hago.NCHW, (1, 1), (0, 0), 1)
+    rargs = (ref.NCHW, (1, 1), (0, 0), 1)
+    a_t, w_t = act_qtype(a, za), hago.QType(hago.I8)
+    want = ref.qconv2d(a, za, w, bias, *rargs)
+    assert_same(host(hago.qconv2d(dev(a), a_t, dev(w), w_t, dev(bias), *args)), want, f"pointwise raw {case}")
+    mult, shift = datagen.requant_params(rng, np.full(O, 74.0 * 73.0 * np.sqrt(C)), 40.0)
+    for out_u8, z_out, clip in ((False, 0, (-128, 127)), (True, 9, (9, 255))):
+        want = ref.qconv2d(a, za, w, bias, *rargs, ref.I32, ref_requant(mult, shift, out_u8, z_out, clip))
+        got = hago.qconv2d(dev(a), a_t, dev(w), w_t, dev(bias), *args, hago.I32,
+                           gpu_requant(mult, shift, out_u8, z_out, clip))
+        assert_same(host(got), want, f"pointwise rq {case} u8={out_u8}")
+        assert np.mean((want == clip[0]) | (want == clip[1])) < 0.9
+    want = ref.qconv2d(a, za, w, bias, *rargs, ref.I16)
+    assert_same(host(hago.qconv2d(dev(a), a_t, dev(w), w_t, dev(bias), *args, hago.I16)), want, f"pointwise acc16 {case}")
+    m16, s16 = datagen.requant_params(rng, np.full(O, 19000.0), 40.0)
+    want = ref.qconv2d(a, za, w, bias, *rargs, ref.I16, ref_requant(m16[:1], s16[:1]))
+    got = hago.qconv2d(dev(a), a_t, dev(w), w_t, dev(bias), *args, hago.I16, gpu_requant(m16[:1], s16[:1]))
+    assert_same(host(got), want, f"pointwise acc16 requant per-tensor {case}")
+
+
 def test_qconv2d_config2_full_size():
     for z_a in (0, 128):
         c = datagen.config2(z_a=z_a)
