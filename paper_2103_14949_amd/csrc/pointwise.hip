@@ -5,9 +5,11 @@
 // consecutive k-bytes of one row.  The general convolution path therefore rewrites the input
 // into a channel-last copy first, which for this operator (few output channels, so hardly any
 // reuse of the input) costs more memory traffic than the convolution itself.  Here a
-// wavefront owns 32 consecutive pixels of one image and gathers its activation fragments with
-// byte loads: the 32 lanes of a half-wavefront read 32 consecutive pixels of one channel, so
-// every load instruction touches two 32-byte segments, and each input byte is fetched once.
+// wavefront owns 32 consecutive pixels of one image.  A lane loads dwords (four consecutive
+// pixels of one channel); the four lanes of a quad load four consecutive channels of the same
+// four pixels and transpose that 4x4 byte block among themselves (two DPP quad permutes and two
+// byte permutes), after which each lane holds four consecutive channels of ITS pixel: one dword
+// of its MFMA operand.  Each input byte is fetched once, 256 bytes per load instruction.
 // The MFMA runs with the pixels as its P operand: a lane then owns one output channel and, per
 // group of four accumulator registers, four consecutive pixels, which are packed and stored
 // together.  The work is bound by memory, not by the matrix pipe (an output channel tile does
@@ -61,7 +63,12 @@ __global__ __launch_bounds__(256) void pw_nchw_kernel(PwArgs p) {
       const_cast<uint8_t*>(p.act) + (int64_t)b * C * HW, 0, C * HW, 0x00020000);
   const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<int8_t*>(p.wgt), 0, N * C, 0x00020000);
-  const uint32_t a_lane = (pix0 + i < HW) ? (uint32_t)(pix0 + i) : kOob;  // + channel * HW
+  // the quad's four pixels (H * W % 4 == 0: all inside the image or all outside); + channel * HW
+  const int q = lane & 3;
+  const uint32_t a_lane = (pix0 + (i & ~3) < HW) ? (uint32_t)(pix0 + (i & ~3)) : kOob;
+  // byte selectors of the two transpose steps (own dword in S1: bytes 0-3, partner's in S0: 4-7)
+  const uint32_t sel1 = (q & 2) ? 0x03020706u : 0x05040100u;  // halves swapped with lane q ^ 2
+  const uint32_t sel2 = (q & 1) ? 0x03070105u : 0x06020400u;  // bytes swapped with lane q ^ 1
   uint32_t w_lane[NT];                                                    // + k
 #pragma unroll
   for (int t = 0; t < NT; ++t) w_lane[t] = (t * 32 + i < N) ? (uint32_t)((t * 32 + i) * C) : kOob;
@@ -90,10 +97,10 @@ __global__ __launch_bounds__(256) void pw_nchw_kernel(PwArgs p) {
     for (int r = 0; r < 16; ++r) acc[t][r] = 0;
   }
   // k-steps whose loads are in flight together (fewer with more accumulators, for registers)
-  constexpr int kChunk = NT == 1 ? 6 : (NT == 2 ? 4 : 2);
+  constexpr int kChunk = NT == 4 ? 4 : 6;
   const int ksteps = (C + 31) >> 5;
   for (int s0 = 0; s0 < ksteps; s0 += kChunk) {
-    uint32_t ab[kChunk][16];
+    uint32_t ab[kChunk][4];
     v4i wb[kChunk][NT];
 #pragma unroll
     for (int u = 0; u < kChunk; ++u) {
@@ -101,9 +108,9 @@ __global__ __launch_bounds__(256) void pw_nchw_kernel(PwArgs p) {
         const int k = (s0 + u) * 32 + 16 * h;  // first channel of this lane's 16 (C % 16 == 0)
         const bool kok = k < C;
 #pragma unroll
-        for (int j = 0; j < 16; ++j)
-          ab[u][j] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b8(
-              rin, (kok && a_lane != kOob) ? a_lane + (uint32_t)((k + j) * HW) : kOob, 0, 0);
+        for (int d = 0; d < 4; ++d)  // channel k + 4d + q, four pixels
+          ab[u][d] = __builtin_amdgcn_raw_buffer_load_b32(
+              rin, (kok && a_lane != kOob) ? a_lane + (uint32_t)((k + 4 * d + q) * HW) : kOob, 0, 0);
 #pragma unroll
         for (int t = 0; t < NT; ++t)
           wb[u][t] = __builtin_amdgcn_raw_buffer_load_b128(
@@ -115,9 +122,13 @@ __global__ __launch_bounds__(256) void pw_nchw_kernel(PwArgs p) {
       if (s0 + u < ksteps) {  // uniform
         v4i af;
 #pragma unroll
-        for (int d = 0; d < 4; ++d)
-          af[d] = (int)((ab[u][4 * d] | (ab[u][4 * d + 1] << 8) | (ab[u][4 * d + 2] << 16) |
-                         (ab[u][4 * d + 3] << 24)) ^ p.act_xor4);
+        for (int d = 0; d < 4; ++d) {
+          const uint32_t x = ab[u][d];  // pixels 0..3 of channel q  ->  channels 0..3 of pixel q
+          const uint32_t t = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x4E, 0xf, 0xf, true);  // quad_perm [2,3,0,1]
+          const uint32_t a2 = __builtin_amdgcn_perm(t, x, sel1);
+          const uint32_t v = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)a2, 0xB1, 0xf, 0xf, true);  // quad_perm [1,0,3,2]
+          af[d] = (int)(__builtin_amdgcn_perm(v, a2, sel2) ^ p.act_xor4);
+        }
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
 #pragma unroll
@@ -185,6 +196,7 @@ bool try_qconv_pointwise_nchw(const GemmArgs& a, const ConvGeom& cg, hipStream_t
   if (cg.nhwc || cg.KH != 1 || cg.KW != 1 || cg.stride_h != 1 || cg.stride_w != 1 || cg.pad_h != 0 ||
       cg.pad_w != 0 || cg.C % 16 != 0 || HW % 4 != 0 || cg.O > 128 || (int64_t)cg.C * HW >= (1ll << 31) ||
       (int64_t)cg.O * cg.C >= (1ll << 31) || (reinterpret_cast<uintptr_t>(a.wgt) & 15u) != 0 ||
+      (reinterpret_cast<uintptr_t>(a.act) & 3u) != 0 ||
       (reinterpret_cast<uintptr_t>(a.out) & (4 * esz - 1)) != 0)
     return false;
   PwArgs p{};

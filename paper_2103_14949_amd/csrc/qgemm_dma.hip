@@ -45,10 +45,6 @@ namespace hago {
 
 namespace {
 
-#ifndef HAGO_ABLATE
-#define HAGO_ABLATE 0
-#endif
-constexpr int kAblate = HAGO_ABLATE;  // timing experiments only: drop parts of the main loop
 constexpr int kBK = 64;       // k-bytes per stage
 constexpr uint32_t kOob = 0x80000000u;  // offset beyond any tensor (sizes are < 2^31 bytes)
 
@@ -222,7 +218,6 @@ __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParam
   constexpr int LH = (L + 1) / 2;  // a stage is issued in two parts (LH and L - LH instructions),
                                   // spread over two MFMA groups
   using IC0 = std::integral_constant<int, 0>;
-  using ICH = std::integral_constant<int, LH>;
   using ICL = std::integral_constant<int, L>;
 
   HAGO_STAMP(p, 0);
@@ -301,8 +296,8 @@ __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParam
   auto multiply = [&](v4i (&pf)[TP], v4i (&qf)[TQ], v4i (&pn)[TP], v4i (&qn)[TQ], const uint8_t* next,
                       auto kshalf, int dma_stage, auto dma_slot, auto flipc, auto wsumc) {
     constexpr int KS = decltype(kshalf)::value;
-    constexpr bool FLIP = decltype(flipc)::value && (kAblate & 4) == 0;
-    constexpr bool WSUM = decltype(wsumc)::value && (kAblate & 8) == 0;
+    constexpr bool FLIP = decltype(flipc)::value;
+    constexpr bool WSUM = decltype(wsumc)::value;
     [&]<int... Mi>(std::integer_sequence<int, Mi...>) {
       ([&] {
         constexpr int m = Mi;
@@ -321,25 +316,21 @@ __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParam
 #pragma unroll
           for (int r = TQ; r < TP; ++r) flip(pn[r]);
         }
-        if constexpr ((kAblate & 2) == 0) {
-          // refills: qf[j] after the last MFMA of column j, the pf after the last column
-          if constexpr (i == TP - 1)
-            qf[j] = *reinterpret_cast<const v4i*>(next + qa[KS] + kQBase + j * kFrag);
-          if constexpr (m == NM - 1) {
+        // refills: qf[j] after the last MFMA of column j, the pf after the last column
+        if constexpr (i == TP - 1)
+          qf[j] = *reinterpret_cast<const v4i*>(next + qa[KS] + kQBase + j * kFrag);
+        if constexpr (m == NM - 1) {
 #pragma unroll
-            for (int r = 0; r < TP; ++r)
-              pf[r] = *reinterpret_cast<const v4i*>(next + pa[KS] + r * kFrag);
-          }
+          for (int r = 0; r < TP; ++r)
+            pf[r] = *reinterpret_cast<const v4i*>(next + pa[KS] + r * kFrag);
         }
         // DMA instructions [first, last) of this half go behind MFMA m
-        if constexpr ((kAblate & 1) == 0) {
-          constexpr int cnt = KS == 0 ? LH : L - LH;   // instructions of this half
-          constexpr int org = KS == 0 ? 0 : LH;
-          constexpr int first = (m * cnt) / NM, last = ((m + 1) * cnt) / NM;
-          if constexpr (last > first)
-            issue_range(dma_stage, dma_slot, std::integral_constant<int, org + first>{},
-                        std::integral_constant<int, org + last>{});
-        }
+        constexpr int cnt = KS == 0 ? LH : L - LH;   // instructions of this half
+        constexpr int org = KS == 0 ? 0 : LH;
+        constexpr int first = (m * cnt) / NM, last = ((m + 1) * cnt) / NM;
+        if constexpr (last > first)
+          issue_range(dma_stage, dma_slot, std::integral_constant<int, org + first>{},
+                      std::integral_constant<int, org + last>{});
         __builtin_amdgcn_sched_barrier(0);
       }(), ...);
     }(std::make_integer_sequence<int, NM>{});
@@ -356,13 +347,11 @@ __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParam
     constexpr int R = decltype(ring)::value;
     constexpr int RN = (R + 1) % kStages;             // slot of stage kt + 1
     constexpr int RD = (R + kStages - 1) % kStages;   // slot of stage kt - 1 and kt + kStages - 1
-    if constexpr ((kAblate & 16) == 0) {
-      // A bare s_barrier: fragment reads still in flight here belong to stage kt, whose slot
-      // stays untouched until the next barrier, so they need not be waited for.
-      asm volatile("s_waitcnt vmcnt(%0)" ::"n"((kStages - 3) * L) : "memory");
-      __builtin_amdgcn_s_barrier();
-      asm volatile("" ::: "memory");
-    }
+    // A bare s_barrier: fragment reads still in flight here belong to stage kt, whose slot
+    // stays untouched until the next barrier, so they need not be waited for.
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((kStages - 3) * L) : "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
     multiply(pf0, qf0, pf1, qf1, smem + RN * STAGE, std::integral_constant<int, 0>{},
              kt + kStages - 1, std::integral_constant<int, RD>{}, flipc, wsumc);
     multiply(pf1, qf1, pf0, qf0, smem + RN * STAGE, std::integral_constant<int, 1>{},
