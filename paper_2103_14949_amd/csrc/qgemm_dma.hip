@@ -34,7 +34,14 @@
 // before it is needed, and the flips are applied to the set that is not being
 // multiplied.  DMA instructions, flips, sums and fragment reads are dealt out
 // behind individual MFMAs.  The k offset of a full stage travels in the DMA
-// instruction's scalar offset, so the steady state computes no addresses.
+// instruction's scalar offset, so the steady state computes no addresses and has no branches:
+// stages whose refill is such a full stage run a straight-line body, the last few stages of a
+// tile (K tail, zero fills) a general one.
+//
+// Weight row sums.  Each 32-row block of the weight tile is summed by one wavefront, which reads
+// it from LDS a second time (two 16-byte reads per lane and stage), independent of the
+// fragments it multiplies; summing the fragments themselves would repeat the work in every
+// wavefront that holds the same weights.
 #include "qgemm_common.h"
 
 #include <cstdlib>
@@ -48,7 +55,9 @@ namespace {
 constexpr int kBK = 64;       // k-bytes per stage
 constexpr uint32_t kOob = 0x80000000u;  // offset beyond any tensor (sizes are < 2^31 bytes)
 
-__device__ __forceinline__ int swz4(int row) { return ((row >> 1) ^ (row >> 3)) & 3; }
+// With this chunk permutation a fragment read (lane -> row lane % 32, chunk 2 ks + lane / 32)
+// runs at the full LDS rate (measured; patterns that XOR in other row bits run at half rate).
+__device__ __forceinline__ int swz4(int row) { return (row >> 2) & 3; }
 
 __device__ __forceinline__ void dma16(v4i rsrc, uint32_t lds_addr, uint32_t voff) {
   // m0 = LDS byte address of the wavefront's 1 KB window; lane l lands at m0 + 16 * l
@@ -80,8 +89,15 @@ __device__ __forceinline__ v4i make_rsrc(const void* base, uint32_t bytes) {
 // (two 4-wavefront workgroups per CU keep the matrix pipe busy across each other's barriers).
 // CONV: the activation operand is an implicit im2col view of a padded NHWC copy of the input
 // (see conv_prepack.hip); ACT_ON_P: activations are the P operand (NCHW output).
-template <int WP, int WQ, int TP, int TQ, int kStages, int OCC, bool CONV, bool ACT_ON_P>
+// FLIP: uint8 activations (dense only; the convolution's copy is already flipped).
+// UNIFORM: K (and the channel count of a convolution) is a multiple of 64, so every stage has one
+// k offset for all lanes, which travels in the DMA instruction's scalar offset: the main loop
+// then computes no addresses and has no branches.  Otherwise every DMA instruction gets per-lane
+// offsets (K tail, stages that straddle filter taps).
+template <int WP, int WQ, int TP, int TQ, int kStages, int OCC, bool CONV, bool ACT_ON_P, bool FLIP,
+          bool UNIFORM>
 __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParams p) {
+  static_assert(!FLIP || (!CONV && !ACT_ON_P), "only dense layers flip, and keep activations on Q");
   HAGO_STAMP(p, 7);
   constexpr int NW = WP * WQ;          // wavefronts
   constexpr int NT = 64 * NW;
@@ -144,32 +160,30 @@ __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParam
       return (uint32_t)(((b * g.H + oy * g.stride_h) * g.W + ox * g.stride_w) * g.C);
     }
   };
+  // DMA slot d of wavefront w is group w + NW * d of the stage (P groups first, then Q groups),
+  // whose 1 KB window lies (w + NW * d) * 1024 bytes into the stage.  When the wavefront count
+  // divides both group counts (kEven) the operand of a slot is the same in every wavefront and
+  // every slot has a group; otherwise both are per-wavefront values.
+  constexpr bool kEven = (GP % NW == 0) && (G % NW == 0);
   uint32_t voff[L];  // row offset + chunk: the per-lane part of a full stage's address
-  uint32_t m0s[L];   // LDS address of the slot's 1 KB window in ring slot 0 (wavefront-uniform)
   bool slot_real[L]; // false: the slot has no group, it fetches zeros into the spare window
-  bool slot_q[L], slot_act[L];
+  bool slot_q[L];
   const int lrow = lane >> 2;  // row inside a 16-row group
   const int lslot = lane & 3;  // physical 16-byte slot
   const uint32_t spare = lds0 + (uint32_t)kStages * STAGE;
-  // The swizzle depends on the row inside a 32-row block only, and a wavefront's groups all
-  // have the parity of its index, so the logical chunk is the same in every slot.
-  static_assert(NW % 2 == 0 && GP % 2 == 0, "group parity must not depend on the slot");
-  const int lck = (lslot ^ swz4((wave & 1) * 16 + lrow)) * 16;  // chunk (bytes) inside a stage
+  const uint32_t wave_lds = lds0 + (uint32_t)wave * 1024u;
+  // The swizzle depends on the row inside a 16-row group only, so the logical chunk is the same
+  // in every slot.
+  const int lck = (lslot ^ swz4(lrow)) * 16;  // chunk (bytes) inside a stage
 #pragma unroll
   for (int d = 0; d < L; ++d) {
     const int grp = wave + NW * d;
-    const bool isq = grp >= GP;
+    const bool isq = kEven ? (d >= GP / NW) : (grp >= GP);
     const int rt = (isq ? grp - GP : grp) * 16 + lrow;  // row inside its tile
     slot_q[d] = isq;
-    slot_act[d] = isq ? !ACT_ON_P : ACT_ON_P;
-    slot_real[d] = grp < G;
+    slot_real[d] = kEven || grp < G;
     uint32_t off = kOob;
-    m0s[d] = spare;
-    if (grp < G) {
-      off = row_offset((isq ? q0 : p0) + rt, slot_act[d]);
-      m0s[d] = (uint32_t)__builtin_amdgcn_readfirstlane(
-          (int)(lds0 + (uint32_t)(isq ? BP * kBK + (grp - GP) * 1024 : grp * 1024)));
-    }
+    if (slot_real[d]) off = row_offset((isq ? q0 : p0) + rt, isq ? !ACT_ON_P : ACT_ON_P);
     voff[d] = off == kOob ? kOob : off + (uint32_t)lck;
   }
   // k (position along the reduction) -> byte offset relative to the row offset
@@ -186,34 +200,50 @@ __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParam
     }
     return (uint32_t)kk;
   };
-  // A stage whose 64 k lie inside K and (conv) inside one filter tap has the same k offset in
-  // every lane: it travels in the instruction's scalar offset, which is not range checked, and
-  // the per-lane offsets never change.  Other stages (the K tail, the zero fills beyond K,
-  // conv stages that straddle taps) compute per-lane offsets.
-  const int KF = p.K / kBK;  // stages that lie fully inside K
-  const bool uniform_k = !CONV || (p.g.C % kBK == 0);
+  const int KT = (p.K + kBK - 1) / kBK;
+  const v4i rs_null = {rs_w.x, rs_w.y, 0, rs_w.w};  // zero records: every access reads zeros
 
-  // DMA slot d (0 .. L-1) of stage stage_idx into ring slot RS.  d and RS are compile-time
-  // constants at every call site.
-  auto issue_one = [&](int stage_idx, auto rsconst, auto dconst) {
+  // DMA slot d (0 .. L-1) of stage stage_idx into ring slot RS; d and RS are compile-time
+  // constants at every call site.  UNIFORM: dp / dq are the stage's descriptors (the null
+  // descriptor for stages beyond K, which only keep the count of outstanding loads uniform),
+  // soff_w / soff_a its scalar k offsets for weight and activation slots.
+  auto issue_one = [&](int stage_idx, const v4i& dp, const v4i& dq, uint32_t soff_w, uint32_t soff_a,
+                       auto rsconst, auto dconst) {
     constexpr int d = decltype(dconst)::value;
     constexpr int RS = decltype(rsconst)::value;
-    const int k0 = stage_idx * kBK;
-    const v4i rs = slot_q[d] ? rs_q : rs_p;
-    const uint32_t dst = slot_real[d] ? m0s[d] + (uint32_t)(RS * STAGE) : spare;
-    if (uniform_k && stage_idx < KF) {
-      dma16s(rs, dst, voff[d], k_offset(k0, slot_act[d]));
+    const bool isq = kEven ? (d >= GP / NW) : slot_q[d];
+    const bool is_act = isq ? !ACT_ON_P : ACT_ON_P;
+    const uint32_t dst =
+        slot_real[d] ? wave_lds + (uint32_t)(NW * d * 1024 + RS * STAGE) : spare;
+    if constexpr (UNIFORM) {
+      dma16s(isq ? dq : dp, dst, voff[d], is_act ? soff_a : soff_w);
     } else {
-      uint32_t o = voff[d] - (uint32_t)lck + k_offset(k0 + lck, slot_act[d]);
+      const int k0 = stage_idx * kBK;
+      uint32_t o = voff[d] - (uint32_t)lck + k_offset(k0 + lck, is_act);
       if (voff[d] == kOob || k0 + lck >= p.K) o = kOob;
-      dma16(rs, dst, o);
+      dma16(isq ? rs_q : rs_p, dst, o);
     }
   };
-  auto issue_range = [&](int stage_idx, auto rsconst, auto lo, auto hi) {
+  auto issue_range = [&](int stage_idx, const v4i& dp, const v4i& dq, uint32_t soff_w,
+                         uint32_t soff_a, auto rsconst, auto lo, auto hi) {
     constexpr int kLo = decltype(lo)::value, kHi = decltype(hi)::value;
     [&]<int... I>(std::integer_sequence<int, I...>) {
-      (issue_one(stage_idx, rsconst, std::integral_constant<int, kLo + I>{}), ...);
+      (issue_one(stage_idx, dp, dq, soff_w, soff_a, rsconst, std::integral_constant<int, kLo + I>{}),
+       ...);
     }(std::make_integer_sequence<int, kHi - kLo>{});
+  };
+  // descriptors and scalar offsets of a stage (UNIFORM)
+  struct StageArgs { v4i dp, dq; uint32_t soff_w, soff_a; };
+  auto stage_args = [&](int stage_idx) {
+    StageArgs a{rs_p, rs_q, 0u, 0u};
+    if constexpr (UNIFORM) {
+      const bool valid = stage_idx < KT;
+      a.dp = valid ? rs_p : rs_null;
+      a.dq = valid ? rs_q : rs_null;
+      a.soff_w = (uint32_t)__builtin_amdgcn_readfirstlane((int)k_offset(stage_idx * kBK, false));
+      a.soff_a = (uint32_t)__builtin_amdgcn_readfirstlane((int)k_offset(stage_idx * kBK, true));
+    }
+    return a;
   };
   constexpr int LH = (L + 1) / 2;  // a stage is issued in two parts (LH and L - LH instructions),
                                   // spread over two MFMA groups
@@ -231,24 +261,25 @@ __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParam
     for (int j = 0; j < TQ; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
-  constexpr int TW = ACT_ON_P ? TQ : TP;  // weight fragments per wavefront
-  uint32_t wsum[TW];  // biased: every byte counts as w + 128
+  // Weight tile rows are summed in 32-row blocks, block w + NW * n by wavefront w.
+  constexpr int WBLK = (ACT_ON_P ? BQ : BP) / 32;
+  constexpr int NSB = (WBLK + NW - 1) / NW;
+  uint32_t wsum[NSB];  // biased: every byte counts as w + 128
 #pragma unroll
-  for (int i = 0; i < TW; ++i) wsum[i] = 0;
+  for (int i = 0; i < NSB; ++i) wsum[i] = 0;
 
-  const int KT = (p.K + kBK - 1) / kBK;
   // prologue: stages 0 .. kStages-2 (stages beyond K are all-zero fills, which keeps the
   // number of outstanding loads uniform)
   [&]<int... S>(std::integer_sequence<int, S...>) {
-    (issue_range(S, std::integral_constant<int, S>{}, IC0{}, ICL{}), ...);
+    ([&] {
+      const StageArgs a = stage_args(S);
+      issue_range(S, a.dp, a.dq, a.soff_w, a.soff_a, std::integral_constant<int, S>{}, IC0{}, ICL{});
+    }(), ...);
   }(std::make_integer_sequence<int, kStages - 1>{});
   HAGO_STAMP(p, 1);
 
   const int frow = lane & 31;
   const int fhalf = lane >> 5;
-  // every wavefront sums its weight fragments (no branch); one per fragment row stores them
-  const bool sums_here = ACT_ON_P ? (wp == 0) : (wq == 0);
-  const bool need_wsum = (p.corr_coef != 0);
   // Fragment addresses inside a stage (bytes).  Fragment i of a wavefront lies i * 32 rows
   // after fragment 0 and has the same swizzle (it depends on the row inside a 32-row block
   // only), so one register per operand and k-half serves every fragment, ring slot and
@@ -262,6 +293,17 @@ __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParam
   }
   constexpr int kFrag = 32 * kBK;     // bytes between consecutive fragments of a wavefront
   constexpr int kQBase = BP * kBK;    // the Q rows follow the P rows inside a stage
+  // weight row block wave + NW * n, read like a fragment; wavefronts without such a block read
+  // the last one again (and do not store their sums)
+  int sa[NSB][2];
+#pragma unroll
+  for (int n = 0; n < NSB; ++n) {
+    const int blk = wave + NW * n < WBLK ? wave + NW * n : WBLK - 1;
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+      sa[n][ks] = (ACT_ON_P ? kQBase : 0) + (blk * 32 + frow) * kBK +
+                  ((ks * 2 + fhalf) ^ swz4(frow)) * 16;
+  }
 
   // Fragment sets for the two 32-k halves of a stage.  A fragment register is refilled with the
   // NEXT stage's data right after the last MFMA that reads it, a whole stage of MFMAs before it
@@ -274,62 +316,68 @@ __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParam
     for (int j = 0; j < TQ; ++j)
       qf[j] = *reinterpret_cast<const v4i*>(base + qa[ks] + kQBase + j * kFrag);
   };
-  // Flipping the sign bit of uint8 activation fragments and summing the weight fragments are
-  // vector instructions that a wavefront can issue in the shadow of its own MFMAs, a few per
-  // MFMA, as long as the next MFMA does not wait for them: the flips are applied to the OTHER
-  // fragment set (read during the previous half), the sums to the current one before its refill.
-  // FLIP / WSUM are compile-time, so that the steady state has no branches.
+  // Flipping the sign bit of uint8 activation fragments and summing weight rows are vector
+  // instructions dealt out one or two per MFMA: the flips are applied to the OTHER fragment set
+  // (read during the previous half); the rows to sum (of the next stage, like the refills) are
+  // read early in a half and summed in its second part.
   constexpr int NM = TP * TQ;  // MFMAs per half
-  auto flip = [&](v4i& f) {
-    const int x4 = (int)p.act_xor4;
-    f = v4i{f.x ^ x4, f.y ^ x4, f.z ^ x4, f.w ^ x4};
+  constexpr int NFL = TQ * 4;  // dwords to flip per half (dense: the activations are on Q)
+  auto flip1 = [&](v4i& f, int u) {
+    // in place, so that no copy of the fragment is made
+    int x = f[u];
+    asm volatile("v_xor_b32 %0, %1, %0" : "+v"(x) : "s"(p.act_xor4));
+    f[u] = x;
   };
-  auto sum4 = [&](uint32_t& a, const v4i& f) {
-    // sum of the bytes, each + 128 (v_dot4 would stall the matrix pipe, v_sad_u8 does not)
-#pragma unroll
-    for (int u = 0; u < 4; ++u) a = __builtin_amdgcn_sad_u8((uint32_t)f[u] ^ 0x80808080u, 0u, a);
+  auto sum1 = [&](uint32_t& a, int f) {
+    // bytes + 128 each (v_dot4 would stall the matrix pipe, v_sad_u8 does not)
+    a = __builtin_amdgcn_sad_u8((uint32_t)f ^ 0x80808080u, 0u, a);
   };
+  v4i sd[NSB];  // rows being summed
   // One 32-k half KS of a stage: multiply the current set (pf, qf); behind the MFMAs go the
-  // weight sums, the flips of the other set's activation fragments (pn, qn), the refills of the
+  // weight sums, the flips of the other set's activation fragments (qn), the refills of the
   // current set from the next stage (at `next`), and this half's share of a stage's DMA
   // instructions (so the memory pipe is fed a few instructions at a time).
-  auto multiply = [&](v4i (&pf)[TP], v4i (&qf)[TQ], v4i (&pn)[TP], v4i (&qn)[TQ], const uint8_t* next,
-                      auto kshalf, int dma_stage, auto dma_slot, auto flipc, auto wsumc) {
+  auto multiply = [&](v4i (&pf)[TP], v4i (&qf)[TQ], v4i (&qn)[TQ], const uint8_t* next, auto kshalf,
+                      int dma_stage, const StageArgs& sa_, auto dma_slot) {
     constexpr int KS = decltype(kshalf)::value;
-    constexpr bool FLIP = decltype(flipc)::value;
-    constexpr bool WSUM = decltype(wsumc)::value;
     [&]<int... Mi>(std::integer_sequence<int, Mi...>) {
       ([&] {
         constexpr int m = Mi;
         constexpr int j = m / TP, i = m % TP;
         acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(pf[i], qf[j], acc[i][j], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
-        if constexpr (WSUM) {  // at the first use of a weight fragment
-          if constexpr (!ACT_ON_P && j == 0) sum4(wsum[i], pf[i]);
-          if constexpr (ACT_ON_P && i == 0) sum4(wsum[j], qf[j]);
-        }
-        if constexpr (FLIP && i == TP - 1) {
-          if constexpr (!ACT_ON_P) flip(qn[j]);
-          else if constexpr (j < TP) flip(pn[j]);
-        }
-        if constexpr (FLIP && ACT_ON_P && TP > TQ && m == NM - 1) {
+        {
+          // the reads go behind the first MFMA(s), the sums behind the last NSB * 4 (or fewer)
+          if constexpr (m < NSB) sd[m] = *reinterpret_cast<const v4i*>(next + sa[m][KS]);
+          constexpr int lo = NM > NSB * 4 ? NM - NSB * 4 : (NM > 1 ? 1 : 0);
 #pragma unroll
-          for (int r = TQ; r < TP; ++r) flip(pn[r]);
+          for (int e = 0; e < NSB * 4; ++e) {
+            const int at = lo + (e * (NM - lo)) / (NSB * 4);
+            if (at == m) sum1(wsum[e / 4], sd[e / 4][e % 4]);
+          }
         }
-        // refills: qf[j] after the last MFMA of column j, the pf after the last column
+        if constexpr (FLIP) {
+          // flips of the other set, dealt over the later MFMAs of the half (its last refills
+          // were issued at the end of the previous half)
+          constexpr int lo = NM / 4;
+#pragma unroll
+          for (int e = 0; e < NFL; ++e) {
+            const int at = lo + (e * (NM - lo)) / NFL;
+            if (at == m) flip1(qn[e / 4], e % 4);
+          }
+        }
+        // refills: qf[j] after the last MFMA of column j, pf[r] after its MFMA of the last column
         if constexpr (i == TP - 1)
           qf[j] = *reinterpret_cast<const v4i*>(next + qa[KS] + kQBase + j * kFrag);
-        if constexpr (m == NM - 1) {
-#pragma unroll
-          for (int r = 0; r < TP; ++r)
-            pf[r] = *reinterpret_cast<const v4i*>(next + pa[KS] + r * kFrag);
-        }
+        if constexpr (j == TQ - 1)
+          pf[i] = *reinterpret_cast<const v4i*>(next + pa[KS] + i * kFrag);
         // DMA instructions [first, last) of this half go behind MFMA m
         constexpr int cnt = KS == 0 ? LH : L - LH;   // instructions of this half
         constexpr int org = KS == 0 ? 0 : LH;
         constexpr int first = (m * cnt) / NM, last = ((m + 1) * cnt) / NM;
         if constexpr (last > first)
-          issue_range(dma_stage, dma_slot, std::integral_constant<int, org + first>{},
+          issue_range(dma_stage, sa_.dp, sa_.dq, sa_.soff_w, sa_.soff_a, dma_slot,
+                      std::integral_constant<int, org + first>{},
                       std::integral_constant<int, org + last>{});
         __builtin_amdgcn_sched_barrier(0);
       }(), ...);
@@ -343,33 +391,46 @@ __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParam
   // everybody has received its fragments of stage kt-1, whose slot is refilled by this
   // iteration's DMA instructions with stage kt + kStages - 1.
   static_assert(kStages >= 3, "ring: one stage being read, one landing, one in flight");
-  auto stage_body = [&](int kt, auto ring, auto flipc, auto wsumc) {
+  auto stage_body = [&](int kt, auto ring) {
     constexpr int R = decltype(ring)::value;
     constexpr int RN = (R + 1) % kStages;             // slot of stage kt + 1
     constexpr int RD = (R + kStages - 1) % kStages;   // slot of stage kt - 1 and kt + kStages - 1
+    const int ds = kt + kStages - 1;
+    const StageArgs a = stage_args(ds);
     // A bare s_barrier: fragment reads still in flight here belong to stage kt, whose slot
     // stays untouched until the next barrier, so they need not be waited for.
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"((kStages - 3) * L) : "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    multiply(pf0, qf0, pf1, qf1, smem + RN * STAGE, std::integral_constant<int, 0>{},
-             kt + kStages - 1, std::integral_constant<int, RD>{}, flipc, wsumc);
-    multiply(pf1, qf1, pf0, qf0, smem + RN * STAGE, std::integral_constant<int, 1>{},
-             kt + kStages - 1, std::integral_constant<int, RD>{}, flipc, wsumc);
+    multiply(pf0, qf0, qf1, smem + RN * STAGE, std::integral_constant<int, 0>{}, ds, a,
+             std::integral_constant<int, RD>{});
+    multiply(pf1, qf1, qf0, smem + RN * STAGE, std::integral_constant<int, 1>{}, ds, a,
+             std::integral_constant<int, RD>{});
   };
-  auto main_loop = [&](auto flipc, auto wsumc) {
+  auto main_loop = [&] {
     read_frags(smem, 0, pf0, qf0);
     read_frags(smem, 1, pf1, qf1);
-    if constexpr (decltype(flipc)::value) {  // the first half's fragments
-      if constexpr (ACT_ON_P) { for (int i = 0; i < TP; ++i) flip(pf0[i]); }
-      else { for (int j = 0; j < TQ; ++j) flip(qf0[j]); }
+    if constexpr (FLIP) {  // the first half's fragments
+#pragma unroll
+      for (int j = 0; j < TQ; ++j)
+#pragma unroll
+        for (int u = 0; u < 4; ++u) flip1(qf0[j], u);
     }
+    // stage 0's rows (the loop sums stage kt + 1)
+#pragma unroll
+    for (int n = 0; n < NSB; ++n)
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        const v4i r = *reinterpret_cast<const v4i*>(smem + sa[n][ks]);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) sum1(wsum[n], r[u]);
+      }
     for (int kt0 = 0; kt0 < KT; kt0 += kStages) {
       bool done = false;
       [&]<int... R>(std::integer_sequence<int, R...>) {
         ([&] {
           if (!done) {
-            if (kt0 + R < KT) stage_body(kt0 + R, std::integral_constant<int, R>{}, flipc, wsumc);
+            if (kt0 + R < KT) stage_body(kt0 + R, std::integral_constant<int, R>{});
             else done = true;
           }
         }(), ...);
@@ -381,22 +442,21 @@ __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParam
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"((kStages - 2) * L) : "memory");
   __syncthreads();
   HAGO_STAMP(p, 2);
-  if (!CONV && p.act_xor4 != 0) main_loop(std::true_type{}, std::true_type{});
-  else if (need_wsum) main_loop(std::false_type{}, std::true_type{});
-  else main_loop(std::false_type{}, std::false_type{});
+  main_loop();
   HAGO_STAMP(p, 3);
   // drain the zero-fill stages before LDS is reused and before the workgroup may exit
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
 
-  // weight row sums: the two 32-lane halves hold the two k-halves of each row
+  // weight row sums: the two 32-lane halves hold the two halves of each 32-k group of a row.
+  // Each lane has summed 32 bytes (biased by 128 each) per stage for stages 0 .. KT: the loop's
+  // last iteration added the first zero-fill stage, whose bytes are all zero.
 #pragma unroll
-  for (int i = 0; i < TW; ++i) {
-    // remove the bias: each lane has summed 32 bytes per stage, zero fills included
-    int32_t v = (int32_t)(wsum[i] - (uint32_t)KT * (32u * 128u));
+  for (int n = 0; n < NSB; ++n) {
+    int32_t v = (int32_t)(wsum[n] - (uint32_t)(KT + 1) * (32u * 128u));
     v += __shfl_xor(v, 32);
-    const int ci = ACT_ON_P ? (wq * TQ + i) * 32 + frow : (wp * TP + i) * 32 + frow;
-    if (sums_here && fhalf == 0) s_corr[ci] = v;
+    const int blk = wave + NW * n;
+    if (blk < WBLK && fhalf == 0) s_corr[blk * 32 + frow] = v;
   }
   __syncthreads();
   const bool general = finish_channel_terms<NT, CH>(p, chregs, s_corr, s_mult, s_shift, s_c64);
@@ -418,15 +478,16 @@ __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParam
   qgemm_epilogue<WP, WQ, TP, TQ, ACT_ON_P>(p, acc, p0, q0, s_corr, s_mult, s_shift);
 }
 
-template <int WP, int WQ, int TP, int TQ, int kStages, int OCC, bool CONV, bool ACT_ON_P>
-hipError_t launch_dma_cfg(const QgemmParams& p, hipStream_t st) {
+template <int WP, int WQ, int TP, int TQ, int kStages, int OCC, bool CONV, bool ACT_ON_P, bool FLIP,
+          bool UNIFORM>
+hipError_t launch_dma_kernel(const QgemmParams& p, hipStream_t st) {
   constexpr int BP = WP * TP * 32, BQ = WQ * TQ * 32;
   constexpr int CH = ACT_ON_P ? BQ : BP;
   constexpr size_t lds = (size_t)kStages * (BP + BQ) * kBK + 1024 + 5 * CH * sizeof(int32_t);
   const int P_ext = ACT_ON_P ? p.M : p.N;
   const int Q_ext = ACT_ON_P ? p.N : p.M;
   const int64_t tiles = (int64_t)((P_ext + BP - 1) / BP) * ((Q_ext + BQ - 1) / BQ);
-  auto kern = qgemm_dma_kernel<WP, WQ, TP, TQ, kStages, OCC, CONV, ACT_ON_P>;
+  auto kern = qgemm_dma_kernel<WP, WQ, TP, TQ, kStages, OCC, CONV, ACT_ON_P, FLIP, UNIFORM>;
   static bool attr_set = false;  // raising the dynamic-LDS limit is needed once per kernel
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -438,14 +499,28 @@ hipError_t launch_dma_cfg(const QgemmParams& p, hipStream_t st) {
   return hipGetLastError();
 }
 
+// Picks the kernel variant: uint8 dense activations are flipped in the loop; shapes whose
+// stages are uniform take the scalar-offset loop.
+template <int WP, int WQ, int TP, int TQ, int kStages, int OCC, bool CONV, bool ACT_ON_P>
+hipError_t launch_dma_cfg(const QgemmParams& p, hipStream_t st) {
+  const bool uniform = p.K % kBK == 0 && (!CONV || p.g.C % kBK == 0);
+  if constexpr (!CONV) {
+    if (p.act_xor4 != 0)
+      return uniform ? launch_dma_kernel<WP, WQ, TP, TQ, kStages, OCC, CONV, ACT_ON_P, true, true>(p, st)
+                     : launch_dma_kernel<WP, WQ, TP, TQ, kStages, OCC, CONV, ACT_ON_P, true, false>(p, st);
+  }
+  return uniform ? launch_dma_kernel<WP, WQ, TP, TQ, kStages, OCC, CONV, ACT_ON_P, false, true>(p, st)
+                 : launch_dma_kernel<WP, WQ, TP, TQ, kStages, OCC, CONV, ACT_ON_P, false, false>(p, st);
+}
+
 }  // namespace
 
 // Requires: K % 16 == 0, K >= 16, 16-byte aligned operands, N*K and M*K below 2^31.
 hipError_t launch_qdense_dma(const QgemmParams& p, int shape, hipStream_t st) {
   switch (shape) {
     case 1: return launch_dma_cfg<2, 4, 3, 2, 4, 1, false, false>(p, st);   // 192 x 256
-    case 2: return launch_dma_cfg<4, 2, 1, 2, 4, 1, false, false>(p, st);   // 128 x 128
-    default: return launch_dma_cfg<4, 2, 2, 4, 4, 1, false, false>(p, st);  // 256 x 256
+    case 2: return launch_dma_cfg<2, 4, 2, 1, 4, 1, false, false>(p, st);   // 128 x 128
+    default: return launch_dma_cfg<2, 4, 4, 2, 4, 1, false, false>(p, st);  // 256 x 256
   }
 }
 
