@@ -11,7 +11,12 @@
 namespace hago {
 
 #ifdef HAGO_PHASE_TIMING
-#define HAGO_STAMP(p, i) do { if (threadIdx.x == 0 && (p).dbg) (p).dbg[blockIdx.x * 8 + (i)] = wall_clock64(); } while (0)
+#ifdef HAGO_STAMP_CYCLES
+#define HAGO_STAMP_CLOCK clock64       // shader clock cycles
+#else
+#define HAGO_STAMP_CLOCK wall_clock64  // 100 MHz
+#endif
+#define HAGO_STAMP(p, i) do { if (threadIdx.x == 0 && (p).dbg) (p).dbg[blockIdx.x * 8 + (i)] = HAGO_STAMP_CLOCK(); } while (0)
 #else
 #define HAGO_STAMP(p, i) do { } while (0)
 #endif

@@ -128,8 +128,28 @@ __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParam
   const int Q_ext = ACT_ON_P ? p.N : p.M;
   const int tiles_p = (P_ext + BP - 1) / BP;
   const int tile = xcd_remap(blockIdx.x, gridDim.x);
-  const int tile_p = tile % tiles_p;
-  const int tile_q = tile / tiles_p;
+  // Tiles are numbered panel by panel (kPanel tiles wide along P, all of Q), row by row inside
+  // a panel: the tiles that run on an XCD at the same time then form a compact block and share
+  // both operands' rows in its L2.
+  constexpr int kPanel = 8;
+  int tile_p, tile_q;
+  {
+    const int tiles_q = (Q_ext + BQ - 1) / BQ;
+    const int full = tiles_p / kPanel;
+    const int per_panel = kPanel * tiles_q;
+    int r = tile, w = kPanel, base = 0;
+    if (tile >= full * per_panel) {
+      r = tile - full * per_panel;
+      w = tiles_p - full * kPanel;
+      base = full * kPanel;
+    } else {
+      const int pn = tile / per_panel;
+      r = tile - pn * per_panel;
+      base = pn * kPanel;
+    }
+    tile_q = r / w;
+    tile_p = base + (r - tile_q * w);
+  }
   const int p0 = tile_p * BP;  // first P row of the tile
   const int q0 = tile_q * BQ;  // first Q row of the tile
   const int w0 = ACT_ON_P ? q0 : p0;  // first output channel
