@@ -141,7 +141,8 @@ __device__ __forceinline__ void load_channel_regs(const QgemmParams& p, int w0, 
   }
 }
 
-// s_corr holds the weight row sums on entry; on exit s_corr/s_mult/s_shift hold the
+// s_corr holds the weight row sums on entry (s_sum2, if given, a second part to add; it may be
+// s_mult); on exit s_corr/s_mult/s_shift hold the
 // per-channel terms and s_c64 the folded addend corr * mult + 2^(30+shift), with which
 // (acc + corr) * mult + rounding term is one 64-bit multiply-add per element.
 // Returns (block-uniform) whether the tile needs the general arithmetic: some channel has
@@ -151,13 +152,15 @@ __device__ __forceinline__ void load_channel_regs(const QgemmParams& p, int w0, 
 template <int NT, int CH>
 __device__ __forceinline__ bool finish_channel_terms(const QgemmParams& p, const ChannelRegs<NT, CH>& r,
                                                      int32_t* s_corr, int32_t* s_mult,
-                                                     int32_t* s_shift, int64_t* s_c64) {
+                                                     int32_t* s_shift, int64_t* s_c64,
+                                                     const int32_t* s_sum2 = nullptr) {
   int general = p.K > 65536;
 #pragma unroll
   for (int s = 0; s < ChannelRegs<NT, CH>::kSlots; ++s) {
     const int ci = (int)threadIdx.x + NT * s;
     if (ci < CH) {
-      const int32_t corr = r.bias[s] + p.corr_coef * s_corr[ci];
+      const int32_t wsum = s_corr[ci] + (s_sum2 ? s_sum2[ci] : 0);
+      const int32_t corr = r.bias[s] + p.corr_coef * wsum;
       s_corr[ci] = corr;
       s_mult[ci] = r.mult[s];
       s_shift[ci] = r.shift[s];

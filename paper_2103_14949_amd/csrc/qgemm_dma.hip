@@ -282,7 +282,9 @@ __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParam
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
   // Weight tile rows are summed in 32-row blocks, block w + NW * n by wavefront w.
+  // With at least two wavefronts per block a block is shared by two, one per 32-k half.
   constexpr int WBLK = (ACT_ON_P ? BQ : BP) / 32;
+  constexpr bool kSplitSum = NW >= 2 * WBLK;
   constexpr int NSB = (WBLK + NW - 1) / NW;
   uint32_t wsum[NSB];  // biased: every byte counts as w + 128
 #pragma unroll
@@ -318,11 +320,15 @@ __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParam
   int sa[NSB][2];
 #pragma unroll
   for (int n = 0; n < NSB; ++n) {
-    const int blk = wave + NW * n < WBLK ? wave + NW * n : WBLK - 1;
+    int blk = wave + NW * n < WBLK ? wave + NW * n : WBLK - 1;
+    if constexpr (kSplitSum) blk = wave % WBLK;
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks)
+    for (int ks = 0; ks < 2; ++ks) {
+      // split: both entries address this wavefront's own k-half
+      const int kh = kSplitSum ? ((wave / WBLK) & 1) : ks;
       sa[n][ks] = (ACT_ON_P ? kQBase : 0) + (blk * 32 + frow) * kBK +
-                  ((ks * 2 + fhalf) ^ swz4(frow)) * 16;
+                  ((kh * 2 + fhalf) ^ swz4(frow)) * 16;
+    }
   }
 
   // Fragment sets for the two 32-k halves of a stage.  A fragment register is refilled with the
@@ -367,13 +373,17 @@ __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParam
         acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(pf[i], qf[j], acc[i][j], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
         {
-          // the reads go behind the first MFMA(s), the sums behind the last NSB * 4 (or fewer)
-          if constexpr (m < NSB) sd[m] = *reinterpret_cast<const v4i*>(next + sa[m][KS]);
+          // the reads go behind the first MFMA(s), the sums behind the last NSB * 4 (or fewer);
+          // split sums: one read per stage (first half), summed during the second half
+          if constexpr (m < NSB && (!kSplitSum || KS == 0))
+            sd[m] = *reinterpret_cast<const v4i*>(next + sa[m][KS]);
           constexpr int lo = NM > NSB * 4 ? NM - NSB * 4 : (NM > 1 ? 1 : 0);
+          if constexpr (!kSplitSum || KS == 1) {
 #pragma unroll
-          for (int e = 0; e < NSB * 4; ++e) {
-            const int at = lo + (e * (NM - lo)) / (NSB * 4);
-            if (at == m) sum1(wsum[e / 4], sd[e / 4][e % 4]);
+            for (int e = 0; e < NSB * 4; ++e) {
+              const int at = lo + (e * (NM - lo)) / (NSB * 4);
+              if (at == m) sum1(wsum[e / 4], sd[e / 4][e % 4]);
+            }
           }
         }
         if constexpr (FLIP) {
@@ -440,7 +450,7 @@ __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParam
 #pragma unroll
     for (int n = 0; n < NSB; ++n)
 #pragma unroll
-      for (int ks = 0; ks < 2; ++ks) {
+      for (int ks = 0; ks < (kSplitSum ? 1 : 2); ++ks) {
         const v4i r = *reinterpret_cast<const v4i*>(smem + sa[n][ks]);
 #pragma unroll
         for (int u = 0; u < 4; ++u) sum1(wsum[n], r[u]);
@@ -469,17 +479,24 @@ __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParam
   __syncthreads();
 
   // weight row sums: the two 32-lane halves hold the two halves of each 32-k group of a row.
-  // Each lane has summed 32 bytes (biased by 128 each) per stage for stages 0 .. KT: the loop's
-  // last iteration added the first zero-fill stage, whose bytes are all zero.
+  // Each lane has summed 32 bytes (16 when a block is split; biased by 128 each) per stage for
+  // stages 0 .. KT: the loop's last iteration added the first zero-fill stage, whose bytes are
+  // all zero.  Split blocks: the second k-half's sums wait in s_mult until the terms are formed.
 #pragma unroll
   for (int n = 0; n < NSB; ++n) {
-    int32_t v = (int32_t)(wsum[n] - (uint32_t)(KT + 1) * (32u * 128u));
+    int32_t v = (int32_t)(wsum[n] - (uint32_t)(KT + 1) * ((kSplitSum ? 16u : 32u) * 128u));
     v += __shfl_xor(v, 32);
-    const int blk = wave + NW * n;
-    if (blk < WBLK && fhalf == 0) s_corr[blk * 32 + frow] = v;
+    if constexpr (kSplitSum) {
+      const int part = wave / WBLK;
+      if (part < 2 && fhalf == 0) (part == 0 ? s_corr : s_mult)[(wave % WBLK) * 32 + frow] = v;
+    } else {
+      const int blk = wave + NW * n;
+      if (blk < WBLK && fhalf == 0) s_corr[blk * 32 + frow] = v;
+    }
   }
   __syncthreads();
-  const bool general = finish_channel_terms<NT, CH>(p, chregs, s_corr, s_mult, s_shift, s_c64);
+  const bool general = finish_channel_terms<NT, CH>(p, chregs, s_corr, s_mult, s_shift, s_c64,
+                                                    kSplitSum ? s_mult : nullptr);
   HAGO_STAMP(p, 4);
   if constexpr (!ACT_ON_P) {
     constexpr bool kCanStage = BQ * (BP + 16) <= kStages * STAGE && (BQ * BP / 16) % NT == 0;
