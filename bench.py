@@ -44,6 +44,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra-ops", action="store_true")
     ap.add_argument("--only", default="", help="comma list of extra-op names to time (default all)")
+    ap.add_argument("--gemm", default="", help="M,N,K: only time hago_qdense on this shape (uniform random "
+                    "uint8 activations and int8 weights) and print its line; for counter runs")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run plain copies of known size (for scaling rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
@@ -83,6 +85,23 @@ def main():
         e1.record()
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / iters
+
+    if args.gemm:
+        Mg, Ng, Kg = (int(v) for v in args.gemm.split(","))
+        rng = np.random.default_rng(7)
+        a = to_dev(rng.integers(0, 256, (Mg, Kg), dtype=np.uint8))
+        w = to_dev(rng.integers(-127, 128, (Ng, Kg), dtype=np.int8))
+        rq = rq_of(rng.integers(2 ** 30, 2 ** 31, Ng, dtype=np.int64).astype(np.int32),
+                   np.full(Ng, 12, dtype=np.int32))
+        out = torch.empty((Mg, Ng), dtype=torch.int8, device=dev)
+        f = hago.qdense(a, hago.QType(hago.U8, 8, False, 121), w, hago.QType(hago.I8), None, hago.I32,
+                        rq, out=out, prepare=True)
+        ms = event_time_ms(f, args.steps, args.warmup)
+        ops_g = 2.0 * Mg * Ng * Kg
+        print(json.dumps({"gemm": [Mg, Ng, Kg], "us": round(ms * 1e3, 2),
+                          "tops": round(ops_g / (ms * 1e-3) / 1e12, 1),
+                          "frac_mfma": round(ops_g / (ms * 1e-3) / 1e12 / PEAK_INT8_TOPS, 4)}), flush=True)
+        return
 
     if args.pmc_calibration:
         # 256 MiB device-to-device copies: 256 MiB fetched and 256 MiB written per kernel
