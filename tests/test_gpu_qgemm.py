@@ -60,6 +60,28 @@ def test_qdense_requant_and_acc16(M, N, K):
     assert_same(host(got), want, "acc16 requant")
 
 
+@pytest.mark.parametrize("tile", [0, 1, 2])  # 256 x 256, 192 x 256, 128 x 128 workgroup tiles
+@pytest.mark.parametrize("K", [448, 400, 64, 16])  # whole 64-byte stages / a 16-byte tail / one stage
+@pytest.mark.parametrize("adt,za", [(np.uint8, 121), (np.uint8, 128), (np.int8, -4)])
+def test_qdense_every_tile_shape(tile, K, adt, za, monkeypatch):
+    """Each dense tile shape of the LDS-DMA kernel on a shape with several tiles and ragged edges
+    in both directions, requantized (staged and plain epilogues) and raw."""
+    monkeypatch.setenv("HAGO_DMA_SHAPE", str(tile))
+    M, N = 600, 528
+    rng = np.random.default_rng(tile * 1000 + K + za)
+    a, w = rnd_act(rng, (M, K), adt), rnd_w(rng, (N, K))
+    bias = rng.integers(-10 ** 5, 10 ** 5, N).astype(np.int32)
+    mult, shift = datagen.requant_params(rng, np.full(N, 74.0 * 73.0 * np.sqrt(K)), 40.0)
+    want = ref.qdense(a, za, w, bias, ref.I32, ref_requant(mult, shift))
+    got = hago.qdense(dev(a), act_qtype(a, za), dev(w), hago.QType(hago.I8), dev(bias), hago.I32,
+                      gpu_requant(mult, shift))
+    assert_same(host(got), want, f"tile {tile} K={K} requantized")
+    assert np.mean((want == -128) | (want == 127)) < 0.5
+    want = ref.qdense(a, za, w, bias)
+    got = hago.qdense(dev(a), act_qtype(a, za), dev(w), hago.QType(hago.I8), dev(bias))
+    assert_same(host(got), want, f"tile {tile} K={K} raw")
+
+
 def test_qdense_config1_both_variants():
     for variant in ("as_specified", "discriminating"):
         c = datagen.config1(variant=variant)
