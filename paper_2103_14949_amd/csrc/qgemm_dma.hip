@@ -52,12 +52,20 @@ namespace hago {
 
 namespace {
 
-constexpr int kBK = 64;       // k-bytes per stage
+constexpr int kBK = 64;       // k-bytes per stage (default; small tiles use 128)
 constexpr uint32_t kOob = 0x80000000u;  // offset beyond any tensor (sizes are < 2^31 bytes)
 
-// With this chunk permutation a fragment read (lane -> row lane % 32, chunk 2 ks + lane / 32)
-// runs at the full LDS rate (measured; patterns that XOR in other row bits run at half rate).
-__device__ __forceinline__ int swz4(int row) { return (row >> 2) & 3; }
+// Chunk permutation of an LDS row of BK bytes.  With these a fragment read (lane -> row lane % 32,
+// chunk 2 h + lane / 32 for 32-k group h) runs at the full LDS rate (measured; other XOR patterns
+// of the row bits run at half rate or less).  It depends on the row inside a 16-row block only.
+template <int BK>
+__device__ __forceinline__ int swz(int row) {
+  return BK == 64 ? (row >> 2) & 3 : (row >> 1) & 7;
+}
+
+// The L DMA instructions of a stage are dealt over its nh 32-k groups: group h issues
+// [dma_first(h), dma_first(h + 1)).
+constexpr int dma_first(int h, int l, int nh) { return (h * l + nh - 1) / nh; }
 
 __device__ __forceinline__ void dma16(v4i rsrc, uint32_t lds_addr, uint32_t voff) {
   // m0 = LDS byte address of the wavefront's 1 KB window; lane l lands at m0 + 16 * l
@@ -94,17 +102,23 @@ __device__ __forceinline__ v4i make_rsrc(const void* base, uint32_t bytes) {
 // k offset for all lanes, which travels in the DMA instruction's scalar offset: the main loop
 // then computes no addresses and has no branches.  Otherwise every DMA instruction gets per-lane
 // offsets (K tail, stages that straddle filter taps).
+// BK: k-bytes per stage, 64 or 128.  With 128 a DMA instruction fetches whole 128-byte lines (8 rows)
+// and a stage has four 32-k groups instead of two, i.e. half as many barriers per k.
 template <int WP, int WQ, int TP, int TQ, int kStages, int OCC, bool CONV, bool ACT_ON_P, bool FLIP,
-          bool UNIFORM>
+          bool UNIFORM, int BK = kBK>
 __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParams p) {
   static_assert(!FLIP || (!CONV && !ACT_ON_P), "only dense layers flip, and keep activations on Q");
+  static_assert(BK == 64 || BK == 128, "stage width");
+  constexpr int NH = BK / 32;       // 32-k groups per stage
+  constexpr int RPI = 1024 / BK;    // rows per DMA instruction
+  constexpr int CPR = BK / 16;      // 16-byte chunks per row
   HAGO_STAMP(p, 7);
   constexpr int NW = WP * WQ;          // wavefronts
   constexpr int NT = 64 * NW;
   constexpr int BP = WP * TP * 32;
   constexpr int BQ = WQ * TQ * 32;
-  constexpr int STAGE = (BP + BQ) * kBK;
-  constexpr int GP = BP / 16, GQ = BQ / 16;  // 16-row groups (one DMA instruction each)
+  constexpr int STAGE = (BP + BQ) * BK;
+  constexpr int GP = BP / RPI, GQ = BQ / RPI;  // row groups (one DMA instruction each)
   constexpr int G = GP + GQ;
   // Groups are dealt round-robin: wavefront w issues groups w, w + NW, ...  Every wavefront
   // issues exactly L instructions per stage (the wait counts rely on it); a slot without a
@@ -188,18 +202,20 @@ __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParam
   uint32_t voff[L];  // row offset + chunk: the per-lane part of a full stage's address
   bool slot_real[L]; // false: the slot has no group, it fetches zeros into the spare window
   bool slot_q[L];
-  const int lrow = lane >> 2;  // row inside a 16-row group
-  const int lslot = lane & 3;  // physical 16-byte slot
+  const int lrow = lane / CPR;  // row inside a group
+  const int lslot = lane % CPR;  // physical 16-byte slot
   const uint32_t spare = lds0 + (uint32_t)kStages * STAGE;
   const uint32_t wave_lds = lds0 + (uint32_t)wave * 1024u;
-  // The swizzle depends on the row inside a 16-row group only, so the logical chunk is the same
-  // in every slot.
-  const int lck = (lslot ^ swz4(lrow)) * 16;  // chunk (bytes) inside a stage
+  // The swizzle depends on the row inside a 16-row block only; an 8-row group is the half of
+  // such a block that its parity says, and every group of a wavefront has the wavefront's
+  // parity, so the logical chunk is the same in every slot.
+  static_assert(RPI == 16 || NW % 2 == 0, "group parity must not depend on the slot");
+  const int lck = (lslot ^ swz<BK>((RPI == 16 ? 0 : (wave & 1) * 8) + lrow)) * 16;  // chunk (bytes) inside a stage
 #pragma unroll
   for (int d = 0; d < L; ++d) {
     const int grp = wave + NW * d;
     const bool isq = kEven ? (d >= GP / NW) : (grp >= GP);
-    const int rt = (isq ? grp - GP : grp) * 16 + lrow;  // row inside its tile
+    const int rt = (isq ? grp - GP : grp) * RPI + lrow;  // row inside its tile
     slot_q[d] = isq;
     slot_real[d] = kEven || grp < G;
     uint32_t off = kOob;
@@ -220,7 +236,7 @@ __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParam
     }
     return (uint32_t)kk;
   };
-  const int KT = (p.K + kBK - 1) / kBK;
+  const int KT = (p.K + BK - 1) / BK;
   const v4i rs_null = {rs_w.x, rs_w.y, 0, rs_w.w};  // zero records: every access reads zeros
 
   // DMA slot d (0 .. L-1) of stage stage_idx into ring slot RS; d and RS are compile-time
@@ -238,7 +254,7 @@ __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParam
     if constexpr (UNIFORM) {
       dma16s(isq ? dq : dp, dst, voff[d], is_act ? soff_a : soff_w);
     } else {
-      const int k0 = stage_idx * kBK;
+      const int k0 = stage_idx * BK;
       uint32_t o = voff[d] - (uint32_t)lck + k_offset(k0 + lck, is_act);
       if (voff[d] == kOob || k0 + lck >= p.K) o = kOob;
       dma16(isq ? rs_q : rs_p, dst, o);
@@ -260,8 +276,8 @@ __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParam
       const bool valid = stage_idx < KT;
       a.dp = valid ? rs_p : rs_null;
       a.dq = valid ? rs_q : rs_null;
-      a.soff_w = (uint32_t)__builtin_amdgcn_readfirstlane((int)k_offset(stage_idx * kBK, false));
-      a.soff_a = (uint32_t)__builtin_amdgcn_readfirstlane((int)k_offset(stage_idx * kBK, true));
+      a.soff_w = (uint32_t)__builtin_amdgcn_readfirstlane((int)k_offset(stage_idx * BK, false));
+      a.soff_a = (uint32_t)__builtin_amdgcn_readfirstlane((int)k_offset(stage_idx * BK, true));
     }
     return a;
   };
@@ -281,11 +297,13 @@ __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParam
     for (int j = 0; j < TQ; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
-  // Weight tile rows are summed in 32-row blocks, block w + NW * n by wavefront w.
-  // With at least two wavefronts per block a block is shared by two, one per 32-k half.
+  // Weight tile rows are summed in 32-row blocks, block w + NW * n by wavefront w, one 32-k group
+  // (one 16-byte read per lane) at a time.  With at least two wavefronts per block a block is
+  // shared by two, which take the even and the odd 32-k groups.
   constexpr int WBLK = (ACT_ON_P ? BQ : BP) / 32;
   constexpr bool kSplitSum = NW >= 2 * WBLK;
   constexpr int NSB = (WBLK + NW - 1) / NW;
+  constexpr int NSG = kSplitSum ? NH / 2 : NH;  // 32-k groups a wavefront sums per stage and block
   uint32_t wsum[NSB];  // biased: every byte counts as w + 128
 #pragma unroll
   for (int i = 0; i < NSB; ++i) wsum[i] = 0;
@@ -303,51 +321,45 @@ __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParam
   const int frow = lane & 31;
   const int fhalf = lane >> 5;
   // Fragment addresses inside a stage (bytes).  Fragment i of a wavefront lies i * 32 rows
-  // after fragment 0 and has the same swizzle (it depends on the row inside a 32-row block
-  // only), so one register per operand and k-half serves every fragment, ring slot and
+  // after fragment 0 and has the same swizzle (it depends on the row inside a 16-row block
+  // only), so one register per operand and 32-k group serves every fragment, ring slot and
   // operand region through constant offsets.
-  int pa[2], qa[2];
+  int pa[NH], qa[NH];
 #pragma unroll
-  for (int ks = 0; ks < 2; ++ks) {
-    const int chunk = ((ks * 2 + fhalf) ^ swz4(frow)) * 16;
-    pa[ks] = (wp * TP * 32 + frow) * kBK + chunk;
-    qa[ks] = (wq * TQ * 32 + frow) * kBK + chunk;
+  for (int h = 0; h < NH; ++h) {
+    const int chunk = ((h * 2 + fhalf) ^ swz<BK>(frow & 15)) * 16;
+    pa[h] = (wp * TP * 32 + frow) * BK + chunk;
+    qa[h] = (wq * TQ * 32 + frow) * BK + chunk;
   }
-  constexpr int kFrag = 32 * kBK;     // bytes between consecutive fragments of a wavefront
-  constexpr int kQBase = BP * kBK;    // the Q rows follow the P rows inside a stage
+  constexpr int kFrag = 32 * BK;     // bytes between consecutive fragments of a wavefront
+  constexpr int kQBase = BP * BK;    // the Q rows follow the P rows inside a stage
   // weight row block wave + NW * n, read like a fragment; wavefronts without such a block read
-  // the last one again (and do not store their sums)
-  int sa[NSB][2];
+  // the last one again (and do not store their sums).  Entry g is the g-th 32-k group this
+  // wavefront sums.
+  int sa[NSB][NSG];
 #pragma unroll
   for (int n = 0; n < NSB; ++n) {
     int blk = wave + NW * n < WBLK ? wave + NW * n : WBLK - 1;
     if constexpr (kSplitSum) blk = wave % WBLK;
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-      // split: both entries address this wavefront's own k-half
-      const int kh = kSplitSum ? ((wave / WBLK) & 1) : ks;
-      sa[n][ks] = (ACT_ON_P ? kQBase : 0) + (blk * 32 + frow) * kBK +
-                  ((kh * 2 + fhalf) ^ swz4(frow)) * 16;
+    for (int g = 0; g < NSG; ++g) {
+      const int h = kSplitSum ? 2 * g + ((wave / WBLK) & 1) : g;
+      sa[n][g] = (ACT_ON_P ? kQBase : 0) + (blk * 32 + frow) * BK +
+                 ((h * 2 + fhalf) ^ swz<BK>(frow & 15)) * 16;
     }
   }
 
-  // Fragment sets for the two 32-k halves of a stage.  A fragment register is refilled with the
-  // NEXT stage's data right after the last MFMA that reads it, a whole stage of MFMAs before it
-  // is needed again, so LDS latency (and the burst of reads after a barrier) stays hidden.
-  v4i pf0[TP], qf0[TQ], pf1[TP], qf1[TQ];
-  auto read_frags = [&](const uint8_t* base, int ks, v4i (&pf)[TP], v4i (&qf)[TQ]) {
-#pragma unroll
-    for (int i = 0; i < TP; ++i) pf[i] = *reinterpret_cast<const v4i*>(base + pa[ks] + i * kFrag);
-#pragma unroll
-    for (int j = 0; j < TQ; ++j)
-      qf[j] = *reinterpret_cast<const v4i*>(base + qa[ks] + kQBase + j * kFrag);
-  };
+  // One fragment set per 32-k group of a stage.  A fragment register is refilled with the NEXT
+  // stage's data right after the last MFMA that reads it, a whole stage of MFMAs before it is
+  // needed again, so LDS latency (and the burst of reads after a barrier) stays hidden.
+  v4i pf[NH][TP], qf[NH][TQ];
   // Flipping the sign bit of uint8 activation fragments and summing weight rows are vector
-  // instructions dealt out one or two per MFMA: the flips are applied to the OTHER fragment set
-  // (read during the previous half); the rows to sum (of the next stage, like the refills) are
-  // read early in a half and summed in its second part.
-  constexpr int NM = TP * TQ;  // MFMAs per half
-  constexpr int NFL = TQ * 4;  // dwords to flip per half (dense: the activations are on Q)
+  // instructions dealt out one or two per MFMA: the flips are applied to the NEXT group's
+  // fragment set (read a stage earlier); the rows to sum (of the next stage, like the refills)
+  // are read early in a group and summed later in it (split sums: read in an even group, summed
+  // in the odd one after it).
+  constexpr int NM = TP * TQ;  // MFMAs per 32-k group
+  constexpr int NFL = TQ * 4;  // dwords to flip per group (dense: the activations are on Q)
   auto flip1 = [&](v4i& f, int u) {
     // in place, so that no copy of the fragment is made
     int x = f[u];
@@ -359,26 +371,27 @@ __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParam
     a = __builtin_amdgcn_sad_u8((uint32_t)f ^ 0x80808080u, 0u, a);
   };
   v4i sd[NSB];  // rows being summed
-  // One 32-k half KS of a stage: multiply the current set (pf, qf); behind the MFMAs go the
-  // weight sums, the flips of the other set's activation fragments (qn), the refills of the
-  // current set from the next stage (at `next`), and this half's share of a stage's DMA
-  // instructions (so the memory pipe is fed a few instructions at a time).
-  auto multiply = [&](v4i (&pf)[TP], v4i (&qf)[TQ], v4i (&qn)[TQ], const uint8_t* next, auto kshalf,
-                      int dma_stage, const StageArgs& sa_, auto dma_slot) {
-    constexpr int KS = decltype(kshalf)::value;
+  // One 32-k group H of a stage: multiply its set; behind the MFMAs go the weight sums, the flips
+  // of the next group's activation fragments, the refills of this set from the next stage (at
+  // `next`), and this group's share of a stage's DMA instructions (so the memory pipe is fed a few
+  // instructions at a time).
+  auto multiply = [&](const uint8_t* next, auto hconst, int dma_stage, const StageArgs& sa_,
+                      auto dma_slot) {
+    constexpr int H = decltype(hconst)::value;
+    constexpr int HN = (H + 1) % NH;  // the set multiplied next
     [&]<int... Mi>(std::integer_sequence<int, Mi...>) {
       ([&] {
         constexpr int m = Mi;
         constexpr int j = m / TP, i = m % TP;
-        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(pf[i], qf[j], acc[i][j], 0, 0, 0);
+        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(pf[H][i], qf[H][j], acc[i][j], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
         {
-          // the reads go behind the first MFMA(s), the sums behind the last NSB * 4 (or fewer);
-          // split sums: one read per stage (first half), summed during the second half
-          if constexpr (m < NSB && (!kSplitSum || KS == 0))
-            sd[m] = *reinterpret_cast<const v4i*>(next + sa[m][KS]);
+          constexpr bool kRead = !kSplitSum || H % 2 == 0;
+          constexpr bool kSum = !kSplitSum || H % 2 == 1;
+          constexpr int g = kSplitSum ? H / 2 : H;
+          if constexpr (kRead && m < NSB) sd[m] = *reinterpret_cast<const v4i*>(next + sa[m][g]);
           constexpr int lo = NM > NSB * 4 ? NM - NSB * 4 : (NM > 1 ? 1 : 0);
-          if constexpr (!kSplitSum || KS == 1) {
+          if constexpr (kSum) {
 #pragma unroll
             for (int e = 0; e < NSB * 4; ++e) {
               const int at = lo + (e * (NM - lo)) / (NSB * 4);
@@ -387,23 +400,22 @@ __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParam
           }
         }
         if constexpr (FLIP) {
-          // flips of the other set, dealt over the later MFMAs of the half (its last refills
-          // were issued at the end of the previous half)
+          // dealt over the later MFMAs of the group
           constexpr int lo = NM / 4;
 #pragma unroll
           for (int e = 0; e < NFL; ++e) {
             const int at = lo + (e * (NM - lo)) / NFL;
-            if (at == m) flip1(qn[e / 4], e % 4);
+            if (at == m) flip1(qf[HN][e / 4], e % 4);
           }
         }
-        // refills: qf[j] after the last MFMA of column j, pf[r] after its MFMA of the last column
+        // refills: qf[j] after the last MFMA of column j, pf[i] after its MFMA of the last column
         if constexpr (i == TP - 1)
-          qf[j] = *reinterpret_cast<const v4i*>(next + qa[KS] + kQBase + j * kFrag);
+          qf[H][j] = *reinterpret_cast<const v4i*>(next + qa[H] + kQBase + j * kFrag);
         if constexpr (j == TQ - 1)
-          pf[i] = *reinterpret_cast<const v4i*>(next + pa[KS] + i * kFrag);
-        // DMA instructions [first, last) of this half go behind MFMA m
-        constexpr int cnt = KS == 0 ? LH : L - LH;   // instructions of this half
-        constexpr int org = KS == 0 ? 0 : LH;
+          pf[H][i] = *reinterpret_cast<const v4i*>(next + pa[H] + i * kFrag);
+        // DMA instructions [first, last) of this group go behind MFMA m
+        constexpr int org = dma_first(H, L, NH);
+        constexpr int cnt = dma_first(H + 1, L, NH) - org;
         constexpr int first = (m * cnt) / NM, last = ((m + 1) * cnt) / NM;
         if constexpr (last > first)
           issue_range(dma_stage, sa_.dp, sa_.dq, sa_.soff_w, sa_.soff_a, dma_slot,
@@ -416,7 +428,7 @@ __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParam
 
   // The main loop is unrolled over the ring, so every LDS address in it is the sum of a
   // loop-invariant register and a constant.  R: ring slot of stage kt.
-  // At the top of iteration kt both fragment sets hold stage kt.  The barrier there says: stage
+  // At the top of iteration kt every fragment set holds stage kt.  The barrier there says: stage
   // kt+1 has landed for everybody (only the youngest stages may still be in flight), and
   // everybody has received its fragments of stage kt-1, whose slot is refilled by this
   // iteration's DMA instructions with stage kt + kStages - 1.
@@ -432,26 +444,33 @@ __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParam
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"((kStages - 3) * L) : "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    multiply(pf0, qf0, qf1, smem + RN * STAGE, std::integral_constant<int, 0>{}, ds, a,
-             std::integral_constant<int, RD>{});
-    multiply(pf1, qf1, qf0, smem + RN * STAGE, std::integral_constant<int, 1>{}, ds, a,
-             std::integral_constant<int, RD>{});
+    [&]<int... Hi>(std::integer_sequence<int, Hi...>) {
+      (multiply(smem + RN * STAGE, std::integral_constant<int, Hi>{}, ds, a,
+                std::integral_constant<int, RD>{}), ...);
+    }(std::make_integer_sequence<int, NH>{});
   };
   auto main_loop = [&] {
-    read_frags(smem, 0, pf0, qf0);
-    read_frags(smem, 1, pf1, qf1);
-    if constexpr (FLIP) {  // the first half's fragments
+#pragma unroll
+    for (int h = 0; h < NH; ++h) {
+#pragma unroll
+      for (int i = 0; i < TP; ++i)
+        pf[h][i] = *reinterpret_cast<const v4i*>(smem + pa[h] + i * kFrag);
+#pragma unroll
+      for (int j = 0; j < TQ; ++j)
+        qf[h][j] = *reinterpret_cast<const v4i*>(smem + qa[h] + kQBase + j * kFrag);
+    }
+    if constexpr (FLIP) {  // the first group's fragments
 #pragma unroll
       for (int j = 0; j < TQ; ++j)
 #pragma unroll
-        for (int u = 0; u < 4; ++u) flip1(qf0[j], u);
+        for (int u = 0; u < 4; ++u) flip1(qf[0][j], u);
     }
     // stage 0's rows (the loop sums stage kt + 1)
 #pragma unroll
     for (int n = 0; n < NSB; ++n)
 #pragma unroll
-      for (int ks = 0; ks < (kSplitSum ? 1 : 2); ++ks) {
-        const v4i r = *reinterpret_cast<const v4i*>(smem + sa[n][ks]);
+      for (int g = 0; g < NSG; ++g) {
+        const v4i r = *reinterpret_cast<const v4i*>(smem + sa[n][g]);
 #pragma unroll
         for (int u = 0; u < 4; ++u) sum1(wsum[n], r[u]);
       }
@@ -479,12 +498,12 @@ __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParam
   __syncthreads();
 
   // weight row sums: the two 32-lane halves hold the two halves of each 32-k group of a row.
-  // Each lane has summed 32 bytes (16 when a block is split; biased by 128 each) per stage for
+  // Each lane has summed 16 bytes per 32-k group it covers (biased by 128 each) per stage for
   // stages 0 .. KT: the loop's last iteration added the first zero-fill stage, whose bytes are
   // all zero.  Split blocks: the second k-half's sums wait in s_mult until the terms are formed.
 #pragma unroll
   for (int n = 0; n < NSB; ++n) {
-    int32_t v = (int32_t)(wsum[n] - (uint32_t)(KT + 1) * ((kSplitSum ? 16u : 32u) * 128u));
+    int32_t v = (int32_t)(wsum[n] - (uint32_t)(KT + 1) * ((uint32_t)NSG * 16u * 128u));
     v += __shfl_xor(v, 32);
     if constexpr (kSplitSum) {
       const int part = wave / WBLK;
@@ -516,15 +535,15 @@ __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParam
 }
 
 template <int WP, int WQ, int TP, int TQ, int kStages, int OCC, bool CONV, bool ACT_ON_P, bool FLIP,
-          bool UNIFORM>
+          bool UNIFORM, int BK>
 hipError_t launch_dma_kernel(const QgemmParams& p, hipStream_t st) {
   constexpr int BP = WP * TP * 32, BQ = WQ * TQ * 32;
   constexpr int CH = ACT_ON_P ? BQ : BP;
-  constexpr size_t lds = (size_t)kStages * (BP + BQ) * kBK + 1024 + 5 * CH * sizeof(int32_t);
+  constexpr size_t lds = (size_t)kStages * (BP + BQ) * BK + 1024 + 5 * CH * sizeof(int32_t);
   const int P_ext = ACT_ON_P ? p.M : p.N;
   const int Q_ext = ACT_ON_P ? p.N : p.M;
   const int64_t tiles = (int64_t)((P_ext + BP - 1) / BP) * ((Q_ext + BQ - 1) / BQ);
-  auto kern = qgemm_dma_kernel<WP, WQ, TP, TQ, kStages, OCC, CONV, ACT_ON_P, FLIP, UNIFORM>;
+  auto kern = qgemm_dma_kernel<WP, WQ, TP, TQ, kStages, OCC, CONV, ACT_ON_P, FLIP, UNIFORM, BK>;
   static bool attr_set = false;  // raising the dynamic-LDS limit is needed once per kernel
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -538,16 +557,18 @@ hipError_t launch_dma_kernel(const QgemmParams& p, hipStream_t st) {
 
 // Picks the kernel variant: uint8 dense activations are flipped in the loop; shapes whose
 // stages are uniform take the scalar-offset loop.
-template <int WP, int WQ, int TP, int TQ, int kStages, int OCC, bool CONV, bool ACT_ON_P>
+template <int WP, int WQ, int TP, int TQ, int kStages, int OCC, bool CONV, bool ACT_ON_P, int BK = kBK>
 hipError_t launch_dma_cfg(const QgemmParams& p, hipStream_t st) {
-  const bool uniform = p.K % kBK == 0 && (!CONV || p.g.C % kBK == 0);
+  const bool uniform = p.K % BK == 0 && (!CONV || p.g.C % BK == 0);
   if constexpr (!CONV) {
     if (p.act_xor4 != 0)
-      return uniform ? launch_dma_kernel<WP, WQ, TP, TQ, kStages, OCC, CONV, ACT_ON_P, true, true>(p, st)
-                     : launch_dma_kernel<WP, WQ, TP, TQ, kStages, OCC, CONV, ACT_ON_P, true, false>(p, st);
+      return uniform
+                 ? launch_dma_kernel<WP, WQ, TP, TQ, kStages, OCC, CONV, ACT_ON_P, true, true, BK>(p, st)
+                 : launch_dma_kernel<WP, WQ, TP, TQ, kStages, OCC, CONV, ACT_ON_P, true, false, BK>(p, st);
   }
-  return uniform ? launch_dma_kernel<WP, WQ, TP, TQ, kStages, OCC, CONV, ACT_ON_P, false, true>(p, st)
-                 : launch_dma_kernel<WP, WQ, TP, TQ, kStages, OCC, CONV, ACT_ON_P, false, false>(p, st);
+  return uniform
+             ? launch_dma_kernel<WP, WQ, TP, TQ, kStages, OCC, CONV, ACT_ON_P, false, true, BK>(p, st)
+             : launch_dma_kernel<WP, WQ, TP, TQ, kStages, OCC, CONV, ACT_ON_P, false, false, BK>(p, st);
 }
 
 }  // namespace
@@ -556,7 +577,8 @@ hipError_t launch_dma_cfg(const QgemmParams& p, hipStream_t st) {
 hipError_t launch_qdense_dma(const QgemmParams& p, int shape, hipStream_t st) {
   switch (shape) {
     case 1: return launch_dma_cfg<2, 4, 3, 2, 4, 1, false, false>(p, st);   // 192 x 256
-    case 2: return launch_dma_cfg<2, 4, 2, 1, 4, 1, false, false>(p, st);   // 128 x 128
+    case 2: return launch_dma_cfg<2, 4, 2, 1, 4, 1, false, false, 128>(p, st);   // 128 x 128, 128-byte stages
+    case 3: return launch_dma_cfg<2, 4, 2, 1, 4, 1, false, false>(p, st);   // 128 x 128, 64-byte stages
     default: return launch_dma_cfg<2, 4, 4, 2, 4, 1, false, false>(p, st);  // 256 x 256
   }
 }
