@@ -119,6 +119,11 @@ CONV_CASES = [
     (1, 64, 14, 14, 130, 1, 1, (1, 1), (0, 0)),
     (2, 48, 8, 8, 24, 1, 1, (1, 1), (0, 0)),
     (1, 3, 33, 33, 16, 7, 7, (2, 2), (3, 3)),
+    # stride 1 with channel counts that are multiples of 32; ragged tiles in pixels and channels
+    (2, 64, 19, 37, 72, 3, 3, (1, 1), (1, 1)),
+    (1, 96, 10, 33, 64, 5, 5, (1, 1), (2, 2)),
+    (1, 128, 9, 40, 130, 3, 3, (1, 1), (0, 0)),
+    (2, 32, 17, 30, 8, 1, 3, (1, 1), (0, 1)),
 ]
 
 
@@ -138,6 +143,34 @@ def test_qconv2d_raw(case, adt, za, layout):
         got = host(hago.qconv2d(dev(a.transpose(0, 2, 3, 1)), act_qtype(a, za), dev(w.transpose(0, 2, 3, 1)),
                                 hago.QType(hago.I8), dev(bias), hago.NHWC, stride, pad)).transpose(0, 3, 1, 2)
     assert_same(np.ascontiguousarray(got), want, f"qconv2d {layout} {case}")
+
+
+@pytest.mark.parametrize("case", [c for c in CONV_CASES if c[1] % 32 == 0 and c[7] == (1, 1) and c[5] * c[6] > 1])
+def test_qconv2d_output_modes(case):
+    """Requantized (int8 and uint8 with a zero point), raw int16 and requantized int16-accumulation
+    outputs of the implicit-GEMM convolution on multi-tile shapes."""
+    B, C, H, W, O, KH, KW, stride, pad = case
+    rng = np.random.default_rng(B * 100 + C + W)
+    a = rnd_act(rng, (B, C, H, W), np.uint8)
+    w = rnd_w(rng, (O, C, KH, KW))
+    bias = rng.integers(-5000, 5000, O).astype(np.int32)
+    mult, shift = datagen.requant_params(rng, np.full(O, 74.0 * 73.0 * np.sqrt(C * KH * KW)), 40.0)
+    for out_u8, z_out, clip in ((False, 0, (-128, 127)), (True, 7, (7, 255))):
+        want = ref.qconv2d(a, 99, w, bias, ref.NCHW, stride, pad, 1, ref.I32,
+                           ref_requant(mult, shift, out_u8, z_out, clip))
+        got = hago.qconv2d(dev(a), act_qtype(a, 99), dev(w), hago.QType(hago.I8), dev(bias), hago.NCHW,
+                           stride, pad, 1, hago.I32, gpu_requant(mult, shift, out_u8, z_out, clip))
+        assert_same(host(got), want, f"conv requantized u8={out_u8}")
+        assert np.mean((want == clip[0]) | (want == clip[1])) < 0.6
+    want = ref.qconv2d(a, 99, w, bias, ref.NCHW, stride, pad, 1, ref.I16)
+    got = hago.qconv2d(dev(a), act_qtype(a, 99), dev(w), hago.QType(hago.I8), dev(bias), hago.NCHW, stride,
+                       pad, 1, hago.I16)
+    assert_same(host(got), want, "conv raw int16")
+    m16, s16 = datagen.requant_params(rng, np.full(O, 19000.0), 40.0)
+    want = ref.qconv2d(a, 99, w, bias, ref.NCHW, stride, pad, 1, ref.I16, ref_requant(m16, s16))
+    got = hago.qconv2d(dev(a), act_qtype(a, 99), dev(w), hago.QType(hago.I8), dev(bias), hago.NCHW, stride,
+                       pad, 1, hago.I16, gpu_requant(m16, s16))
+    assert_same(host(got), want, "conv int16 accumulation requantized")
 
 
 POINTWISE_CASES = [
