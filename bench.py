@@ -271,6 +271,16 @@ def extra_ops(torch, hago, datagen, to_dev, rq_of, event_time_ms, only):
                note="fp32 [32,144,56,56], per-channel, 8 B/elem")
         del f
 
+    # ---- max-abs calibration of the same tensor (Eq. 2)
+    if want("absmax_c4"):
+        c = datagen.config4_simquant()
+        x0 = to_dev(c["x"].reshape(32, 144, -1))
+        nb = x0.numel() * 4
+        f = rotating(lambda i: hago.absmax(x0.clone(), True, prepare=True), nb)
+        record("absmax_c4", event_time_ms(f, 60, 6), bytes_=nb, bound="hbm",
+               note="fp32 [32,144,56,56] -> 144 thresholds, 4 B/elem (zero fill + reduction, two launches)")
+        del f
+
     # ---- depthwise + pointwise, config 4
     c4 = datagen.config4()
     a_t, w_t = hago.QType(hago.I8, 8, True, 0), hago.QType(hago.I8)

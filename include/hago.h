@@ -9,6 +9,7 @@
  *   hago_qdense     -- integer dense, integer accumulate, fused requantize
  *   hago_qconv2d    -- integer conv2d (groups == 1 or depthwise), same epilogue
  *   hago_requantize -- the standalone requantize operator (Sec. 6.1, 6.2)
+ *   hago_absmax     -- max-abs calibration thresholds (Eq. 2)
  *
  * Conventions common to every call
  *   - Pointers marked "device" are GPU addresses valid on the current HIP
@@ -163,6 +164,22 @@ hago_status hago_qconv2d(const void* a, hago_qtype a_t, const void* w,
                          int32_t pad_w, int32_t groups, hago_dtype acc_dtype,
                          const hago_requant* rq, void* out, uint32_t flags,
                          void* stream);
+
+/*
+ * Max-abs calibration (Sec. 2, Eq. 2: threshold = max |x|; Sec. 5.1 statistics
+ * collection): the thresholds that Eq. 1 turns into the scales of
+ * simulated_quantize.  x[outer, channels, inner] (device, fp32);
+ *     threshold[c] = max over o, i of |x[o, c, i]|      (per_channel != 0)
+ *     threshold[0] = max over the whole tensor           (per_channel == 0)
+ * threshold (device) has `channels` entries, or one.  NaN elements are ignored
+ * (they never win a comparison); an empty reduction gives 0; the result is
+ * never -0.  The result is exact (a maximum does not depend on the order).
+ * Errors: NULL, SHAPE (negative dim or overflowing element count), PARAM
+ * (per_channel not 0/1), DEVICE.
+ */
+hago_status hago_absmax(const float* x, int64_t outer, int64_t channels,
+                        int64_t inner, int32_t per_channel, float* threshold,
+                        void* stream);
 
 /*
  * Standalone requantize (Sec. 6.1, 6.2): acc[outer, channels, inner] (device,

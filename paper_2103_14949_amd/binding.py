@@ -16,7 +16,7 @@ STRICT_ACC16 = 1
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libhago.so")
 
-EXPORTS = ("hago_simquant", "hago_qdense", "hago_qconv2d", "hago_requantize", "hago_status_string")
+EXPORTS = ("hago_simquant", "hago_absmax", "hago_qdense", "hago_qconv2d", "hago_requantize", "hago_status_string")
 
 
 class _QType(C.Structure):
@@ -56,6 +56,8 @@ def lib():
         L.hago_status_string.argtypes = [i32]
         L.hago_simquant.restype = i32
         L.hago_simquant.argtypes = [vp, vp, i64, i64, i64, vp, vp, i32, _QType, i32, i32, vp]
+        L.hago_absmax.restype = i32
+        L.hago_absmax.argtypes = [vp, i64, i64, i64, i32, vp, vp]
         L.hago_requantize.restype = i32
         L.hago_requantize.argtypes = [vp, i32, i64, i64, i64, C.POINTER(_Requant), vp, vp]
         L.hago_qdense.restype = i32
@@ -160,6 +162,19 @@ def simquant(x, scale, zero_point, q: QType, clip_lo=None, clip_hi=None, per_cha
         return Prepared(lib().hago_simquant, args, (x, y, scale, zero_point), y)
     _check(lib().hago_simquant(*args))
     return y
+
+
+def absmax(x, per_channel=True, out=None, prepare=False):
+    """hago_absmax over x[outer, channels, inner] (fp32, contiguous): thresholds [channels] or [1]."""
+    assert x.dim() == 3 and x.is_contiguous()
+    outer, channels, inner = x.shape
+    n = channels if per_channel else 1
+    thr = _torch().empty(n, dtype=_torch().float32, device=x.device) if out is None else out
+    args = (_ptr(x), outer, channels, inner, int(bool(per_channel)), _ptr(thr), _stream())
+    if prepare:
+        return Prepared(lib().hago_absmax, args, (x, thr), thr)
+    _check(lib().hago_absmax(*args))
+    return thr
 
 
 def requantize(acc, rq: Requant, out=None, prepare=False):

@@ -162,6 +162,20 @@ hago_status hago_simquant(const float* x, float* y, int64_t outer, int64_t chann
                                         static_cast<hipStream_t>(stream)));
 }
 
+hago_status hago_absmax(const float* x, int64_t outer, int64_t channels, int64_t inner,
+                        int32_t per_channel, float* threshold, void* stream) {
+  if (outer < 0 || channels < 0 || inner < 0) return HAGO_ERR_SHAPE;
+  if (per_channel != 0 && per_channel != 1) return HAGO_ERR_PARAM;
+  const bool empty = outer == 0 || channels == 0 || inner == 0;
+  const int64_t nthr = per_channel ? channels : 1;
+  if ((!x && !empty) || (!threshold && nthr > 0)) return HAGO_ERR_NULL;
+  if (!empty) {
+    if (outer > INT64_MAX / channels || outer * channels > INT64_MAX / inner) return HAGO_ERR_SHAPE;
+  }
+  return from_hip(hago::launch_absmax(x, outer, channels, inner, per_channel, threshold,
+                                      static_cast<hipStream_t>(stream)));
+}
+
 hago_status hago_requantize(const void* acc, hago_dtype acc_dtype, int64_t outer, int64_t channels,
                             int64_t inner, const hago_requant* rq, void* out, void* stream) {
   if (outer < 0 || channels < 0 || inner < 0) return HAGO_ERR_SHAPE;

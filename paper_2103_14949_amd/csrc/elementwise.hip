@@ -1,7 +1,8 @@
-// Bandwidth-bound elementwise kernels: fp32 simulated_quantize and the
-// standalone integer requantize.  Both stream [outer, channels, inner] tensors
-// once (read) and once (write); the only reuse is the per-channel parameter,
-// which is block-uniform in the row kernels and so lives in scalar registers.
+// Bandwidth-bound elementwise kernels: fp32 simulated_quantize, the standalone
+// integer requantize and the max-abs calibration reduction.  The first two stream
+// [outer, channels, inner] tensors once (read) and once (write); the only reuse is
+// the per-channel parameter, which is block-uniform in the row kernels and so lives
+// in scalar registers.  The reduction reads the tensor once.
 //
 // Two launch shapes per operator:
 //   rows : one workgroup per (row = outer*channels index, segment of inner);
@@ -185,6 +186,88 @@ __global__ __launch_bounds__(kThreads) void requant_flat_kernel(
   }
 }
 
+// ---- max-abs calibration (Eq. 2): thr[c] = max |x[o, c, i]| over o, i.  NaN never wins a
+// comparison and is therefore ignored; the result is never negative zero.  |x| of a non-NaN
+// float orders like its bit pattern as an unsigned integer, so partial results are merged with
+// one integer atomic max per workgroup (order-independent: the result is exact).
+__device__ __forceinline__ float absmax_step(float m, float v) {
+  const float a = fabsf(v);
+  return a > m ? a : m;
+}
+
+__device__ __forceinline__ float wave_max(float m) {
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) {
+    const float o = __shfl_xor(m, d);
+    m = o > m ? o : m;
+  }
+  return m;
+}
+
+// thr must hold zeros on entry.
+__device__ __forceinline__ void block_merge_max(float m, uint32_t* thr_c) {
+  __shared__ float s_m[kThreads / 64];
+  m = wave_max(m);
+  if ((threadIdx.x & 63) == 0) s_m[threadIdx.x >> 6] = m;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+#pragma unroll
+    for (int w = 1; w < kThreads / 64; ++w) m = s_m[w] > m ? s_m[w] : m;
+    if (m > 0.0f) atomicMax(thr_c, __float_as_uint(m));
+  }
+  __syncthreads();
+}
+
+__global__ __launch_bounds__(kThreads) void fill_zero_kernel(uint32_t* p, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i < n) p[i] = 0u;
+}
+
+// rows: as the other row kernels (row = outer * channels index, 128-bit nontemporal loads, U
+// vectors per lane in flight); jobs are dealt to a bounded grid, one atomic per job.
+template <int U>
+__global__ __launch_bounds__(kThreads) void absmax_rows_kernel(
+    const v4f* __restrict__ x, int64_t rows, int32_t channels, int64_t inner_vec, int32_t nseg,
+    int32_t seg_len, int per_channel, uint32_t* __restrict__ thr) {
+  for (int64_t job = blockIdx.x; job < rows * nseg; job += gridDim.x) {
+    const int64_t row = job / nseg;
+    const int32_t c = per_channel ? (int32_t)(row % channels) : 0;
+    const int32_t seg = (int32_t)(job - row * nseg);
+    const int64_t v0 = (int64_t)seg * seg_len;
+    const int64_t v1 = (v0 + seg_len < inner_vec) ? v0 + seg_len : inner_vec;
+    const v4f* xr = x + row * inner_vec;
+    float m = 0.0f;
+    for (int64_t vb = v0 + threadIdx.x; vb < v1; vb += (int64_t)kThreads * U) {
+      v4f a[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        a[u] = vb + u * kThreads < v1 ? __builtin_nontemporal_load(xr + vb + u * kThreads)
+                                      : v4f{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        m = absmax_step(m, a[u].x); m = absmax_step(m, a[u].y);
+        m = absmax_step(m, a[u].z); m = absmax_step(m, a[u].w);
+      }
+    }
+    block_merge_max(m, thr + c);
+  }
+}
+
+// columns: the tensor as [outer][channels * inner]; a lane owns one column j (channel j / inner)
+// and walks a chunk of `orows` outer rows, so neighbouring lanes read neighbouring addresses.
+// Used for short, unaligned or channel-last rows.  One atomic per lane and chunk.
+__global__ __launch_bounds__(kThreads) void absmax_cols_kernel(
+    const float* __restrict__ x, int64_t outer, int64_t cols, int64_t inner, int64_t orows,
+    int per_channel, uint32_t* __restrict__ thr) {
+  const int64_t j = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (j >= cols) return;
+  const int64_t o0 = (int64_t)blockIdx.y * orows;
+  const int64_t o1 = (o0 + orows < outer) ? o0 + orows : outer;
+  float m = 0.0f;
+  for (int64_t o = o0; o < o1; ++o) m = absmax_step(m, x[o * cols + j]);
+  if (m > 0.0f) atomicMax(thr + (per_channel ? j / inner : 0), __float_as_uint(m));
+}
+
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 inline int grid_for(int64_t jobs) {
@@ -218,6 +301,46 @@ hipError_t launch_simquant(const float* x, float* y, int64_t outer, int64_t chan
     hipLaunchKernelGGL(simquant_flat_kernel, dim3(grid_for((total + kThreads - 1) / kThreads)),
                        dim3(kThreads), 0, st, x, y, total, inner, channels, scale, zp, per_channel,
                        lo, hi);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_absmax(const float* x, int64_t outer, int64_t channels, int64_t inner,
+                         int per_channel, float* thr, hipStream_t st) {
+  const int64_t nthr = per_channel ? channels : 1;
+  if (nthr == 0) return hipSuccess;
+  uint32_t* t = reinterpret_cast<uint32_t*>(thr);
+  // (a fill kernel, not hipMemsetAsync: the call may be captured into a graph)
+  hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((nthr + kThreads - 1) / kThreads)),
+                     dim3(kThreads), 0, st, t, nthr);
+  const int64_t total = outer * channels * inner;
+  if (total == 0) return hipGetLastError();
+  const int64_t rows = per_channel ? outer * channels : 1;
+  const int64_t row_len = per_channel ? inner : total;
+  if (row_len % 4 == 0 && row_len >= 512 && aligned16(x)) {
+    const int64_t inner_vec = row_len / 4;
+    int32_t nseg, seg_len;
+    split_row(inner_vec, kVecPerLane, &nseg, &seg_len);
+    const int64_t jobs = rows * nseg;
+    const int64_t cap = 256 * 32;  // a few workgroups per CU at a time keep the atomics few
+    hipLaunchKernelGGL(absmax_rows_kernel<kVecPerLane>, dim3((unsigned)(jobs < cap ? jobs : cap)),
+                       dim3(kThreads), 0, st, reinterpret_cast<const v4f*>(x), rows,
+                       (int32_t)(per_channel ? channels : 1), inner_vec, nseg, seg_len, per_channel,
+                       t);
+  } else {
+    const int64_t cols = per_channel ? channels * inner : inner * channels;
+    const int64_t col_inner = per_channel ? inner : cols;
+    const int64_t xblocks = (cols + kThreads - 1) / kThreads;
+    if (xblocks >= (1ll << 31)) return hipErrorInvalidValue;
+    // enough row chunks to fill the chip, at most 65535
+    int64_t chunks = (256 * 8 + xblocks - 1) / xblocks;
+    if (chunks > outer) chunks = outer;
+    if (chunks > 65535) chunks = 65535;
+    if (chunks < 1) chunks = 1;
+    const int64_t orows = (outer + chunks - 1) / chunks;
+    chunks = (outer + orows - 1) / orows;
+    hipLaunchKernelGGL(absmax_cols_kernel, dim3((unsigned)xblocks, (unsigned)chunks), dim3(kThreads),
+                       0, st, x, outer, cols, col_inner, orows, per_channel, t);
   }
   return hipGetLastError();
 }

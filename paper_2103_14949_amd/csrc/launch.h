@@ -20,6 +20,10 @@ hipError_t launch_simquant(const float* x, float* y, int64_t outer, int64_t chan
                            const float* scale, const int32_t* zp, int per_channel, int32_t clip_lo,
                            int32_t clip_hi, hipStream_t st);
 
+// max-abs calibration over [outer, channels, inner]: thr[channels] (or [1]).
+hipError_t launch_absmax(const float* x, int64_t outer, int64_t channels, int64_t inner,
+                         int per_channel, float* thr, hipStream_t st);
+
 // standalone requantize over [outer, channels, inner]; acc16 != 0: int16 input.
 hipError_t launch_requantize(const void* acc, int acc16, int64_t outer, int64_t channels,
                              int64_t inner, const RequantArgs& rq, void* out, hipStream_t st);

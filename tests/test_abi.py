@@ -23,7 +23,8 @@ def L():
 def test_every_declared_symbol_is_exported(L):
     header = open(os.path.join(ROOT, "include", "hago.h")).read()
     declared = set(re.findall(r"\b(hago_[a-z0-9_]+)\s*\(", header))
-    assert {"hago_simquant", "hago_qdense", "hago_qconv2d", "hago_requantize", "hago_status_string"} <= declared
+    assert {"hago_simquant", "hago_qdense", "hago_qconv2d", "hago_requantize", "hago_absmax",
+            "hago_status_string"} <= declared
     for name in declared:
         assert hasattr(L, name), name
     assert set(binding.EXPORTS) == declared
@@ -107,6 +108,15 @@ def test_simquant_and_requantize_argument_errors(L):
     assert req(BAD, hago.I32, 1, 1, 1, None, BAD, None) == 1
     assert req(BAD, hago.I8, 1, 1, 1, C.byref(rq), BAD, None) == 3
     assert req(BAD, hago.I32, 1, -1, 1, C.byref(rq), BAD, None) == 2
+
+
+def test_absmax_argument_errors(L):
+    am = lambda *a: L.hago_absmax(*a)  # noqa: E731
+    assert am(None, 1, 1, 1, 1, BAD, None) == 1
+    assert am(BAD, 1, 1, 1, 1, None, None) == 1
+    assert am(BAD, 1, -1, 1, 1, BAD, None) == 2
+    assert am(BAD, 2 ** 40, 2 ** 40, 2, 1, BAD, None) == 2
+    assert am(BAD, 1, 1, 1, 2, BAD, None) == 5
 
 
 def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):

@@ -77,6 +77,55 @@ def test_simquant_config4_full_size():
     assert np.abs(want).max() <= thr.max()
 
 
+AM_SHAPES = [(1, 1, 1), (3, 5, 7), (2, 4, 512), (2, 3, 516), (64, 128, 1), (33, 52, 1), (4, 6, 2048),
+             (2, 24, 3136), (1, 1, 70000), (3, 2, 5000), (1000, 3, 2), (300, 1, 1), (1, 7, 4100)]
+
+
+@pytest.mark.parametrize("shape", AM_SHAPES)
+@pytest.mark.parametrize("per_channel", [True, False])
+def test_absmax_shapes(shape, per_channel):
+    """Max-abs thresholds (Eq. 2) are exact: bit patterns equal the oracle's, for row-shaped,
+    column-shaped and unaligned tensors; NaN is ignored, infinities and -0 count by magnitude."""
+    rng = np.random.default_rng(abs(hash((shape, per_channel))) % 2 ** 31)
+    x = (rng.standard_normal(shape) * rng.uniform(0.01, 100.0, (1, shape[1], 1))).astype(np.float32)
+    flat = x.reshape(-1)
+    if flat.size >= 8:
+        flat[rng.integers(0, flat.size, 3)] = np.nan
+        flat[rng.integers(0, flat.size)] = -0.0
+    want = ref.absmax(x, per_channel)
+    got = hago.absmax(dev(x), per_channel)
+    assert_same_bits(host(got), want, f"absmax {shape} per_channel={per_channel}")
+    if flat.size >= 8:
+        flat[rng.integers(0, flat.size)] = -np.inf
+        assert_same_bits(host(hago.absmax(dev(x), per_channel)), ref.absmax(x, per_channel), "with -inf")
+
+
+def test_absmax_degenerate_and_overwrite():
+    # the output is overwritten, not accumulated into; all-NaN and all-zero tensors give 0
+    x = np.full((2, 3, 600), np.nan, np.float32)
+    out = dev(np.full(3, 123.0, np.float32))
+    hago.absmax(dev(x), True, out=out)
+    assert_same_bits(host(out), np.zeros(3, np.float32), "all NaN")
+    x = np.zeros((2, 3, 5), np.float32)
+    x[1, 2, 4] = -0.0
+    assert_same_bits(host(hago.absmax(dev(x), True)), np.zeros(3, np.float32), "zeros")
+    e = torch.empty((0, 4, 9), dtype=torch.float32, device=DEV)
+    assert_same_bits(host(hago.absmax(e, True)), np.zeros(4, np.float32), "empty reduction")
+
+
+def test_absmax_config4_full_size_feeds_simquant():
+    """Calibration -> Eq. 1 scale -> simulated quantize, thresholds from the GPU reduction."""
+    c = datagen.config4_simquant()
+    x = c["x"].reshape(32, 144, -1)
+    thr = host(hago.absmax(dev(x), True))
+    assert_same_bits(thr, ref.absmax(x, True), "config 4 thresholds")
+    assert_same_bits(host(hago.absmax(dev(x), False)), ref.absmax(x, False), "config 4 per-tensor threshold")
+    scale = np.array([ref.scale(float(t), 8, 1) for t in thr], np.float32)
+    want = ref.simquant(x, scale, c["zp"], -128, 127)
+    got = hago.simquant(dev(x), dev(scale), dev(c["zp"]), hago.QType(hago.I8))
+    assert_same_bits(host(got), want, "simquant with GPU-calibrated scales")
+
+
 RQ_SHAPES = [(1, 1, 1), (3, 5, 7), (2, 4, 512), (2, 3, 516), (64, 128, 1), (33, 52, 1), (7, 9, 1),
              (2, 24, 3136), (1, 1, 70000), (5, 16, 2048), (4096, 768, 1)]
 
