@@ -127,6 +127,50 @@ int hago_ref_simquant(const float* x, float* y, int64_t outer,
   return REF_OK;
 }
 
+int hago_ref_quantize(const float* x, int32_t* q, int64_t outer,
+                      int64_t channels, int64_t inner, const float* scale,
+                      const int32_t* zero_point, int32_t per_channel,
+                      int32_t clip_lo, int32_t clip_hi) {
+  if (!x || !q || !scale || !zero_point) return REF_ERR_NULL;
+  if (outer < 0 || channels < 0 || inner < 0) return REF_ERR_SHAPE;
+  if (clip_lo > clip_hi) return REF_ERR_BITS;
+  for (int64_t o = 0; o < outer; ++o)
+    for (int64_t c = 0; c < channels; ++c) {
+      const float s = scale[per_channel ? c : 0];
+      const int64_t z = zero_point[per_channel ? c : 0];
+      for (int64_t i = 0; i < inner; ++i) {
+        const int64_t idx = (o * channels + c) * inner + i;
+        const float u = std::nearbyintf(x[idx] / s); /* round(r / s) */
+        int64_t code;
+        if (u != u) code = z;                        /* NaN: real zero */
+        else if (u >= 4.0e18f) code = INT64_MAX / 2; /* saturates below */
+        else if (u <= -4.0e18f) code = -(INT64_MAX / 2);
+        else code = (int64_t)u + z;                  /* u is an integer */
+        if (code < clip_lo) code = clip_lo;
+        if (code > clip_hi) code = clip_hi;
+        q[idx] = (int32_t)code;
+      }
+    }
+  return REF_OK;
+}
+
+int hago_ref_dequantize(const int32_t* q, float* y, int64_t outer,
+                        int64_t channels, int64_t inner, const float* scale,
+                        const int32_t* zero_point, int32_t per_channel) {
+  if (!q || !y || !scale || !zero_point) return REF_ERR_NULL;
+  if (outer < 0 || channels < 0 || inner < 0) return REF_ERR_SHAPE;
+  for (int64_t o = 0; o < outer; ++o)
+    for (int64_t c = 0; c < channels; ++c) {
+      const float s = scale[per_channel ? c : 0];
+      const float zf = (float)zero_point[per_channel ? c : 0];
+      for (int64_t i = 0; i < inner; ++i) {
+        const int64_t idx = (o * channels + c) * inner + i;
+        y[idx] = ((float)q[idx] - zf) * s; /* r ~= q * s */
+      }
+    }
+  return REF_OK;
+}
+
 int hago_ref_encode_multiplier(double m, int32_t* multiplier, int32_t* shift) {
   if (!multiplier || !shift) return REF_ERR_NULL;
   if (!(m > 0.0) || !std::isfinite(m)) return REF_ERR_PARAM;

@@ -72,6 +72,21 @@ int hago_ref_simquant(const float* x, float* y, int64_t outer,
                       const int32_t* zero_point, int32_t per_channel,
                       int32_t clip_lo, int32_t clip_hi);
 
+/* quantize (Sec. 6.1: the operator that enters the integer domain; the inner
+ * part of Eq. 3): code = clip(rint(x / s) + z, lo, hi), with x / s and the
+ * rounding in IEEE binary32 as in simulated_quantize.  NaN quantizes to the
+ * code of real zero, clip(z).  q receives the codes as int32. */
+int hago_ref_quantize(const float* x, int32_t* q, int64_t outer,
+                      int64_t channels, int64_t inner, const float* scale,
+                      const int32_t* zero_point, int32_t per_channel,
+                      int32_t clip_lo, int32_t clip_hi);
+
+/* dequantize (Sec. 6.1: back to real values; Eq. 3's r ~= q * s):
+ * y = ((float)q - (float)z) * s in IEEE binary32. */
+int hago_ref_dequantize(const int32_t* q, float* y, int64_t outer,
+                        int64_t channels, int64_t inner, const float* scale,
+                        const int32_t* zero_point, int32_t per_channel);
+
 /* Real multiplier m in (2^-32, 1) -> (Q31 multiplier in [2^30, 2^31), shift
  * in [0, 31]) with m ~= multiplier * 2^-(31+shift). */
 int hago_ref_encode_multiplier(double m, int32_t* multiplier, int32_t* shift);

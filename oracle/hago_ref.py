@@ -61,6 +61,8 @@ def lib(path: str | None = None):
             L.hago_ref_scale.restype = dbl
             L.hago_ref_scale.argtypes = [dbl, i32, i32]
             L.hago_ref_absmax.argtypes = [vp, i64, i64, i64, i32, vp]
+            L.hago_ref_quantize.argtypes = [vp, vp, i64, i64, i64, vp, vp, i32, i32, i32]
+            L.hago_ref_dequantize.argtypes = [vp, vp, i64, i64, i64, vp, vp, i32]
             L.hago_ref_bit_range.argtypes = [i32, i32, vp, vp]
             L.hago_ref_simquant.argtypes = [vp, vp, i64, i64, i64, vp, vp, i32, i32, i32]
             L.hago_ref_encode_multiplier.argtypes = [dbl, vp, vp]
@@ -139,6 +141,30 @@ def simquant(x, scale, zero_point, clip_lo, clip_hi, per_channel=None):
     y = np.empty_like(x)
     _chk(lib().hago_ref_simquant(_p(x), _p(y), o, c, i, _p(s), _p(z), pc,
                                  int(clip_lo), int(clip_hi)))
+    return y
+
+
+def quantize(x, scale, zero_point, clip_lo, clip_hi, per_channel=None):
+    """x: float32 [outer, channels, inner] -> int32 codes of the same shape."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    o, c, i = x.shape
+    s = np.ascontiguousarray(scale, dtype=np.float32).reshape(-1)
+    z = np.ascontiguousarray(zero_point, dtype=np.int32).reshape(-1)
+    pc = int(s.size > 1) if per_channel is None else int(per_channel)
+    q = np.empty(x.shape, np.int32)
+    _chk(lib().hago_ref_quantize(_p(x), _p(q), o, c, i, _p(s), _p(z), pc, int(clip_lo), int(clip_hi)))
+    return q
+
+
+def dequantize(q, scale, zero_point, per_channel=None):
+    """q: integer codes [outer, channels, inner] -> float32."""
+    q = np.ascontiguousarray(q, dtype=np.int32)
+    o, c, i = q.shape
+    s = np.ascontiguousarray(scale, dtype=np.float32).reshape(-1)
+    z = np.ascontiguousarray(zero_point, dtype=np.int32).reshape(-1)
+    pc = int(s.size > 1) if per_channel is None else int(per_channel)
+    y = np.empty(q.shape, np.float32)
+    _chk(lib().hago_ref_dequantize(_p(q), _p(y), o, c, i, _p(s), _p(z), pc))
     return y
 
 
