@@ -271,6 +271,25 @@ def extra_ops(torch, hago, datagen, to_dev, rq_of, event_time_ms, only):
                note="fp32 [32,144,56,56], per-channel, 8 B/elem")
         del f
 
+    # ---- quantize / dequantize of the same tensor (int8 codes)
+    if want("quantize_c4") or want("dequantize_c4"):
+        c = datagen.config4_simquant()
+        x0 = to_dev(c["x"].reshape(32, 144, -1))
+        scale, zp = to_dev(c["scale"]), to_dev(c["zp"])
+        q = hago.QType(hago.I8)
+        nb = x0.numel() * 5
+        if want("quantize_c4"):
+            f = rotating(lambda i: hago.quantize(x0.clone(), scale, zp, q, prepare=True), nb)
+            record("quantize_c4", event_time_ms(f, 60, 6), bytes_=nb, bound="hbm",
+                   note="fp32 [32,144,56,56] -> int8 codes, 5 B/elem")
+            del f
+        if want("dequantize_c4"):
+            codes0 = hago.quantize(x0, scale, zp, q)
+            f = rotating(lambda i: hago.dequantize(codes0.clone(), q, scale, zp, prepare=True), nb)
+            record("dequantize_c4", event_time_ms(f, 60, 6), bytes_=nb, bound="hbm",
+                   note="int8 codes [32,144,56,56] -> fp32, 5 B/elem")
+            del f
+
     # ---- max-abs calibration of the same tensor (Eq. 2)
     if want("absmax_c4"):
         c = datagen.config4_simquant()

@@ -10,6 +10,7 @@
  *   hago_qconv2d    -- integer conv2d (groups == 1 or depthwise), same epilogue
  *   hago_requantize -- the standalone requantize operator (Sec. 6.1, 6.2)
  *   hago_absmax     -- max-abs calibration thresholds (Eq. 2)
+ *   hago_quantize, hago_dequantize -- fp32 <-> integer codes (Sec. 6.1; Eq. 3)
  *
  * Conventions common to every call
  *   - Pointers marked "device" are GPU addresses valid on the current HIP
@@ -164,6 +165,32 @@ hago_status hago_qconv2d(const void* a, hago_qtype a_t, const void* w,
                          int32_t pad_w, int32_t groups, hago_dtype acc_dtype,
                          const hago_requant* rq, void* out, uint32_t flags,
                          void* stream);
+
+/*
+ * quantize and dequantize (Sec. 6.1: the operators with which the realized
+ * graph enters and leaves the integer domain; the two halves of Eq. 3).
+ *     q = clip(rint(x / s) + z, clip_lo, clip_hi)      stored as qt.dtype
+ *     y = ((float)q - (float)z) * s
+ * x, y: device fp32 [outer, channels, inner]; q: device, container qt.dtype
+ * (HAGO_I8, HAGO_U8, HAGO_I16 or HAGO_I32), same shape.  s, z as for
+ * hago_simquant.  The code is formed exactly as in hago_simquant (binary32
+ * division, round half to even, compare-select clip), so
+ * hago_dequantize(hago_quantize(x)) equals hago_simquant(x) bit for bit; a NaN
+ * input takes the code of real zero, clip(z).  clip_lo/clip_hi must lie within
+ * qt's effective-bit range and within +-2^24.  hago_dequantize converts q to
+ * binary32 first (exact for |q| <= 2^24).
+ * Errors: NULL, SHAPE, DTYPE (qt.dtype HAGO_F32 or unknown), BITS, PARAM
+ * (per_channel not 0/1), DEVICE.  Empty tensors are a no-op.
+ */
+hago_status hago_quantize(const float* x, void* q, int64_t outer,
+                          int64_t channels, int64_t inner, const float* scale,
+                          const int32_t* zero_point, int32_t per_channel,
+                          hago_qtype qt, int32_t clip_lo, int32_t clip_hi,
+                          void* stream);
+hago_status hago_dequantize(const void* q, hago_qtype qt, float* y,
+                            int64_t outer, int64_t channels, int64_t inner,
+                            const float* scale, const int32_t* zero_point,
+                            int32_t per_channel, void* stream);
 
 /*
  * Max-abs calibration (Sec. 2, Eq. 2: threshold = max |x|; Sec. 5.1 statistics

@@ -16,7 +16,7 @@ STRICT_ACC16 = 1
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libhago.so")
 
-EXPORTS = ("hago_simquant", "hago_absmax", "hago_qdense", "hago_qconv2d", "hago_requantize", "hago_status_string")
+EXPORTS = ("hago_simquant", "hago_absmax", "hago_quantize", "hago_dequantize", "hago_qdense", "hago_qconv2d", "hago_requantize", "hago_status_string")
 
 
 class _QType(C.Structure):
@@ -56,6 +56,10 @@ def lib():
         L.hago_status_string.argtypes = [i32]
         L.hago_simquant.restype = i32
         L.hago_simquant.argtypes = [vp, vp, i64, i64, i64, vp, vp, i32, _QType, i32, i32, vp]
+        L.hago_quantize.restype = i32
+        L.hago_quantize.argtypes = [vp, vp, i64, i64, i64, vp, vp, i32, _QType, i32, i32, vp]
+        L.hago_dequantize.restype = i32
+        L.hago_dequantize.argtypes = [vp, _QType, vp, i64, i64, i64, vp, vp, i32, vp]
         L.hago_absmax.restype = i32
         L.hago_absmax.argtypes = [vp, i64, i64, i64, i32, vp, vp]
         L.hago_requantize.restype = i32
@@ -161,6 +165,43 @@ def simquant(x, scale, zero_point, q: QType, clip_lo=None, clip_hi=None, per_cha
     if prepare:
         return Prepared(lib().hago_simquant, args, (x, y, scale, zero_point), y)
     _check(lib().hago_simquant(*args))
+    return y
+
+
+_TORCH_OF = {U8: "uint8", I8: "int8", I16: "int16", I32: "int32"}
+
+
+def quantize(x, scale, zero_point, q: QType, clip_lo=None, clip_hi=None, per_channel=None, out=None,
+             prepare=False):
+    """hago_quantize over x[outer, channels, inner] (fp32): integer codes in q's container."""
+    assert x.dim() == 3 and x.is_contiguous()
+    outer, channels, inner = x.shape
+    lo, hi = ((-(1 << (q.bits - 1)), (1 << (q.bits - 1)) - 1) if q.is_signed else (0, (1 << q.bits) - 1))
+    clip_lo = lo if clip_lo is None else clip_lo
+    clip_hi = hi if clip_hi is None else clip_hi
+    pc = int(scale.numel() > 1) if per_channel is None else int(per_channel)
+    t = _torch()
+    codes = t.empty(x.shape, dtype=getattr(t, _TORCH_OF[q.dtype]), device=x.device) if out is None else out
+    args = (_ptr(x), _ptr(codes), outer, channels, inner, _ptr(scale), _ptr(zero_point), pc, q.c(),
+            int(clip_lo), int(clip_hi), _stream())
+    if prepare:
+        return Prepared(lib().hago_quantize, args, (x, codes, scale, zero_point), codes)
+    _check(lib().hago_quantize(*args))
+    return codes
+
+
+def dequantize(codes, q: QType, scale, zero_point, per_channel=None, out=None, prepare=False):
+    """hago_dequantize over codes[outer, channels, inner] in q's container: fp32."""
+    assert codes.dim() == 3 and codes.is_contiguous()
+    outer, channels, inner = codes.shape
+    pc = int(scale.numel() > 1) if per_channel is None else int(per_channel)
+    t = _torch()
+    y = t.empty(codes.shape, dtype=t.float32, device=codes.device) if out is None else out
+    args = (_ptr(codes), q.c(), _ptr(y), outer, channels, inner, _ptr(scale), _ptr(zero_point), pc,
+            _stream())
+    if prepare:
+        return Prepared(lib().hago_dequantize, args, (codes, y, scale, zero_point), y)
+    _check(lib().hago_dequantize(*args))
     return y
 
 

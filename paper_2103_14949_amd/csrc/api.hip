@@ -162,6 +162,53 @@ hago_status hago_simquant(const float* x, float* y, int64_t outer, int64_t chann
                                         static_cast<hipStream_t>(stream)));
 }
 
+namespace {
+// Shared checks of quantize / dequantize; container id for launch_quant.
+hago_status check_quant(hago_qtype q, int32_t per_channel, int64_t outer, int64_t channels,
+                        int64_t inner, const void* scale, const void* zero_point, int* container) {
+  if (outer < 0 || channels < 0 || inner < 0) return HAGO_ERR_SHAPE;
+  if (!scale || !zero_point) return HAGO_ERR_NULL;
+  if (per_channel != 0 && per_channel != 1) return HAGO_ERR_PARAM;
+  if (q.dtype == HAGO_F32) return HAGO_ERR_DTYPE;
+  hago_status s = check_qtype(q, false);
+  if (s != HAGO_OK) return s;
+  if (outer && channels && inner) {
+    if (outer > INT64_MAX / channels || outer * channels > INT64_MAX / inner) return HAGO_ERR_SHAPE;
+  }
+  *container = q.dtype == HAGO_I8 ? 0 : (q.dtype == HAGO_U8 ? 1 : (q.dtype == HAGO_I16 ? 2 : 3));
+  return HAGO_OK;
+}
+}  // namespace
+
+hago_status hago_quantize(const float* x, void* q, int64_t outer, int64_t channels, int64_t inner,
+                          const float* scale, const int32_t* zero_point, int32_t per_channel,
+                          hago_qtype qt, int32_t clip_lo, int32_t clip_hi, void* stream) {
+  int container = 0;
+  hago_status s = check_quant(qt, per_channel, outer, channels, inner, scale, zero_point, &container);
+  if (s != HAGO_OK) return s;
+  const bool empty = outer == 0 || channels == 0 || inner == 0;
+  if ((!x || !q) && !empty) return HAGO_ERR_NULL;
+  int64_t blo, bhi;
+  bit_range(qt.bits, qt.is_signed != 0, &blo, &bhi);
+  if (clip_lo > clip_hi || clip_lo < blo || clip_hi > bhi) return HAGO_ERR_BITS;
+  // codes are formed in binary32
+  if (clip_lo < -(1 << 24) || clip_hi > (1 << 24)) return HAGO_ERR_BITS;
+  return from_hip(hago::launch_quant(x, q, container, 0, outer, channels, inner, scale, zero_point,
+                                     per_channel, clip_lo, clip_hi, static_cast<hipStream_t>(stream)));
+}
+
+hago_status hago_dequantize(const void* q, hago_qtype qt, float* y, int64_t outer, int64_t channels,
+                            int64_t inner, const float* scale, const int32_t* zero_point,
+                            int32_t per_channel, void* stream) {
+  int container = 0;
+  hago_status s = check_quant(qt, per_channel, outer, channels, inner, scale, zero_point, &container);
+  if (s != HAGO_OK) return s;
+  const bool empty = outer == 0 || channels == 0 || inner == 0;
+  if ((!q || !y) && !empty) return HAGO_ERR_NULL;
+  return from_hip(hago::launch_quant(q, y, container, 1, outer, channels, inner, scale, zero_point,
+                                     per_channel, 0, 0, static_cast<hipStream_t>(stream)));
+}
+
 hago_status hago_absmax(const float* x, int64_t outer, int64_t channels, int64_t inner,
                         int32_t per_channel, float* threshold, void* stream) {
   if (outer < 0 || channels < 0 || inner < 0) return HAGO_ERR_SHAPE;

@@ -186,6 +186,111 @@ __global__ __launch_bounds__(kThreads) void requant_flat_kernel(
   }
 }
 
+// ---- quantize / dequantize (the two halves of Eq. 3; Sec. 6.1): the code is formed exactly as in
+// simulated_quantize (binary32 division, round half to even, zero point added as a float,
+// compare-select clip), then stored in the integer container; NaN takes the code of real zero.
+__device__ __forceinline__ int32_t quantize_one(float x, float s, float zf, float lo, float hi) {
+  const float u = rintf(x / s);
+  float v = (u != u) ? zf : u + zf;
+  v = (v < lo) ? lo : ((v > hi) ? hi : v);
+  return (int32_t)v;  // integral and within +-2^24
+}
+
+__device__ __forceinline__ float dequantize_one(int32_t q, float s, float zf) {
+  return ((float)q - zf) * s;
+}
+
+template <typename Q> struct QVec;  // four codes of a container as one store / load
+template <> struct QVec<int8_t> { typedef uint32_t T; };
+template <> struct QVec<uint8_t> { typedef uint32_t T; };
+template <> struct QVec<int16_t> { typedef v4i16 T; };
+template <> struct QVec<int32_t> { typedef v4i32 T; };
+
+template <typename Q>
+__device__ __forceinline__ typename QVec<Q>::T pack_codes(int32_t a, int32_t b, int32_t c, int32_t d) {
+  if constexpr (sizeof(Q) == 1) return pack4(a, b, c, d);
+  else if constexpr (sizeof(Q) == 2) return v4i16{(int16_t)a, (int16_t)b, (int16_t)c, (int16_t)d};
+  else return v4i32{a, b, c, d};
+}
+
+template <typename Q>
+__device__ __forceinline__ void unpack_codes(typename QVec<Q>::T v, int32_t (&q)[4]) {
+  if constexpr (sizeof(Q) == 1) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) q[e] = (int32_t)(Q)((v >> (8 * e)) & 0xffu);
+  } else {
+    q[0] = (int32_t)v.x; q[1] = (int32_t)v.y; q[2] = (int32_t)v.z; q[3] = (int32_t)v.w;
+  }
+}
+
+// Row kernels as for simulated_quantize; DEQ: codes -> fp32, else fp32 -> codes.
+template <typename Q, bool DEQ, int U>
+__global__ __launch_bounds__(kThreads) void quant_rows_kernel(
+    const void* __restrict__ in, void* __restrict__ out, int64_t rows, int32_t channels,
+    int64_t inner_vec, int32_t nseg, int32_t seg_len, const float* __restrict__ scale,
+    const int32_t* __restrict__ zp, int per_channel, float lo, float hi) {
+  using VQ = typename QVec<Q>::T;
+  for (int64_t job = blockIdx.x; job < rows * nseg; job += gridDim.x) {
+    const int64_t row = job / nseg;
+    const int32_t c = per_channel ? (int32_t)(row % channels) : 0;
+    const int32_t seg = (int32_t)(job - row * nseg);
+    const float s = scale[c];
+    const float zf = (float)zp[c];
+    const int64_t v0 = (int64_t)seg * seg_len;
+    const int64_t v1 = (v0 + seg_len < inner_vec) ? v0 + seg_len : inner_vec;
+    for (int64_t vb = v0 + threadIdx.x; vb < v1; vb += (int64_t)kThreads * U) {
+      if constexpr (DEQ) {
+        const VQ* qr = static_cast<const VQ*>(in) + row * inner_vec;
+        v4f* yr = static_cast<v4f*>(out) + row * inner_vec;
+        VQ a[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+          if (vb + u * kThreads < v1) a[u] = __builtin_nontemporal_load(qr + vb + u * kThreads);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          if (vb + u * kThreads < v1) {
+            int32_t q[4];
+            unpack_codes<Q>(a[u], q);
+            const v4f r = {dequantize_one(q[0], s, zf), dequantize_one(q[1], s, zf),
+                           dequantize_one(q[2], s, zf), dequantize_one(q[3], s, zf)};
+            __builtin_nontemporal_store(r, yr + vb + u * kThreads);
+          }
+        }
+      } else {
+        const v4f* xr = static_cast<const v4f*>(in) + row * inner_vec;
+        VQ* qr = static_cast<VQ*>(out) + row * inner_vec;
+        v4f a[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+          if (vb + u * kThreads < v1) a[u] = __builtin_nontemporal_load(xr + vb + u * kThreads);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          if (vb + u * kThreads < v1) {
+            const VQ r = pack_codes<Q>(quantize_one(a[u].x, s, zf, lo, hi), quantize_one(a[u].y, s, zf, lo, hi),
+                                       quantize_one(a[u].z, s, zf, lo, hi), quantize_one(a[u].w, s, zf, lo, hi));
+            __builtin_nontemporal_store(r, qr + vb + u * kThreads);
+          }
+        }
+      }
+    }
+  }
+}
+
+template <typename Q, bool DEQ>
+__global__ __launch_bounds__(kThreads) void quant_flat_kernel(
+    const void* __restrict__ in, void* __restrict__ out, int64_t total, int64_t inner,
+    int64_t channels, const float* __restrict__ scale, const int32_t* __restrict__ zp,
+    int per_channel, float lo, float hi) {
+  const int64_t stride = (int64_t)gridDim.x * kThreads;
+  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += stride) {
+    const int64_t c = per_channel ? (i / inner) % channels : 0;
+    if constexpr (DEQ)
+      static_cast<float*>(out)[i] = dequantize_one((int32_t)static_cast<const Q*>(in)[i], scale[c], (float)zp[c]);
+    else
+      static_cast<Q*>(out)[i] = (Q)quantize_one(static_cast<const float*>(in)[i], scale[c], (float)zp[c], lo, hi);
+  }
+}
+
 // ---- max-abs calibration (Eq. 2): thr[c] = max |x[o, c, i]| over o, i.  NaN never wins a
 // comparison and is therefore ignored; the result is never negative zero.  |x| of a non-NaN
 // float orders like its bit pattern as an unsigned integer, so partial results are merged with
@@ -303,6 +408,50 @@ hipError_t launch_simquant(const float* x, float* y, int64_t outer, int64_t chan
                        lo, hi);
   }
   return hipGetLastError();
+}
+
+template <typename Q, bool DEQ>
+static hipError_t launch_quant_t(const void* in, void* out, int64_t outer, int64_t channels,
+                                 int64_t inner, const float* scale, const int32_t* zp,
+                                 int per_channel, int32_t clip_lo, int32_t clip_hi, hipStream_t st) {
+  const int64_t total = outer * channels * inner;
+  if (total == 0) return hipSuccess;
+  const float lo = (float)clip_lo, hi = (float)clip_hi;
+  const int64_t rows = per_channel ? outer * channels : 1;
+  const int64_t row_len = per_channel ? inner : total;
+  if (row_len % 4 == 0 && row_len >= 512 && aligned16(in) && aligned16(out)) {
+    const int64_t inner_vec = row_len / 4;
+    int32_t nseg, seg_len;
+    split_row(inner_vec, kVecPerLane, &nseg, &seg_len);
+    hipLaunchKernelGGL((quant_rows_kernel<Q, DEQ, kVecPerLane>), dim3(grid_for(rows * nseg)),
+                       dim3(kThreads), 0, st, in, out, rows, (int32_t)(per_channel ? channels : 1),
+                       inner_vec, nseg, seg_len, scale, zp, per_channel, lo, hi);
+  } else {
+    hipLaunchKernelGGL((quant_flat_kernel<Q, DEQ>), dim3(grid_for((total + kThreads - 1) / kThreads)),
+                       dim3(kThreads), 0, st, in, out, total, inner, channels, scale, zp, per_channel,
+                       lo, hi);
+  }
+  return hipGetLastError();
+}
+
+// container: 0 int8, 1 uint8, 2 int16, 3 int32.  deq != 0: codes -> fp32.
+hipError_t launch_quant(const void* in, void* out, int container, int deq, int64_t outer,
+                        int64_t channels, int64_t inner, const float* scale, const int32_t* zp,
+                        int per_channel, int32_t clip_lo, int32_t clip_hi, hipStream_t st) {
+#define HAGO_QUANT_CASE(ID, T)                                                                       \
+  case ID:                                                                                           \
+    return deq ? launch_quant_t<T, true>(in, out, outer, channels, inner, scale, zp, per_channel,    \
+                                         clip_lo, clip_hi, st)                                       \
+               : launch_quant_t<T, false>(in, out, outer, channels, inner, scale, zp, per_channel,   \
+                                          clip_lo, clip_hi, st);
+  switch (container) {
+    HAGO_QUANT_CASE(0, int8_t)
+    HAGO_QUANT_CASE(1, uint8_t)
+    HAGO_QUANT_CASE(2, int16_t)
+    HAGO_QUANT_CASE(3, int32_t)
+    default: return hipErrorInvalidValue;
+  }
+#undef HAGO_QUANT_CASE
 }
 
 hipError_t launch_absmax(const float* x, int64_t outer, int64_t channels, int64_t inner,

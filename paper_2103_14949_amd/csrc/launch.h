@@ -20,6 +20,12 @@ hipError_t launch_simquant(const float* x, float* y, int64_t outer, int64_t chan
                            const float* scale, const int32_t* zp, int per_channel, int32_t clip_lo,
                            int32_t clip_hi, hipStream_t st);
 
+// quantize (fp32 -> codes) / dequantize (codes -> fp32) over [outer, channels, inner].
+// container: 0 int8, 1 uint8, 2 int16, 3 int32.
+hipError_t launch_quant(const void* in, void* out, int container, int deq, int64_t outer,
+                        int64_t channels, int64_t inner, const float* scale, const int32_t* zp,
+                        int per_channel, int32_t clip_lo, int32_t clip_hi, hipStream_t st);
+
 // max-abs calibration over [outer, channels, inner]: thr[channels] (or [1]).
 hipError_t launch_absmax(const float* x, int64_t outer, int64_t channels, int64_t inner,
                          int per_channel, float* thr, hipStream_t st);

@@ -24,6 +24,7 @@ def test_every_declared_symbol_is_exported(L):
     header = open(os.path.join(ROOT, "include", "hago.h")).read()
     declared = set(re.findall(r"\b(hago_[a-z0-9_]+)\s*\(", header))
     assert {"hago_simquant", "hago_qdense", "hago_qconv2d", "hago_requantize", "hago_absmax",
+            "hago_quantize", "hago_dequantize",
             "hago_status_string"} <= declared
     for name in declared:
         assert hasattr(L, name), name
@@ -108,6 +109,24 @@ def test_simquant_and_requantize_argument_errors(L):
     assert req(BAD, hago.I32, 1, 1, 1, None, BAD, None) == 1
     assert req(BAD, hago.I8, 1, 1, 1, C.byref(rq), BAD, None) == 3
     assert req(BAD, hago.I32, 1, -1, 1, C.byref(rq), BAD, None) == 2
+
+
+def test_quantize_and_dequantize_argument_errors(L):
+    q = _qt(hago.I8)
+    qz = lambda *a: L.hago_quantize(*a)  # noqa: E731
+    assert qz(None, BAD, 1, 1, 1, BAD, BAD, 0, q, -128, 127, None) == 1
+    assert qz(BAD, BAD, 1, 1, 1, BAD, None, 0, q, -128, 127, None) == 1
+    assert qz(BAD, BAD, 1, -1, 1, BAD, BAD, 0, q, -128, 127, None) == 2
+    assert qz(BAD, BAD, 1, 1, 1, BAD, BAD, 0, _qt(hago.F32), -128, 127, None) == 3
+    assert qz(BAD, BAD, 1, 1, 1, BAD, BAD, 0, q, -129, 127, None) == 4
+    assert qz(BAD, BAD, 1, 1, 1, BAD, BAD, 0, _qt(hago.I32, 32), -2 ** 31, 2 ** 31 - 1, None) == 4
+    assert qz(BAD, BAD, 1, 1, 1, BAD, BAD, 3, q, -128, 127, None) == 5
+    dq = lambda *a: L.hago_dequantize(*a)  # noqa: E731
+    assert dq(None, q, BAD, 1, 1, 1, BAD, BAD, 0, None) == 1
+    assert dq(BAD, q, None, 1, 1, 1, BAD, BAD, 0, None) == 1
+    assert dq(BAD, q, BAD, 1, 1, -1, BAD, BAD, 0, None) == 2
+    assert dq(BAD, _qt(hago.F32), BAD, 1, 1, 1, BAD, BAD, 0, None) == 3
+    assert dq(BAD, q, BAD, 1, 1, 1, BAD, BAD, 2, None) == 5
 
 
 def test_absmax_argument_errors(L):

@@ -77,6 +77,51 @@ def test_simquant_config4_full_size():
     assert np.abs(want).max() <= thr.max()
 
 
+QZ_SHAPES = [(1, 1, 1), (3, 5, 7), (2, 4, 512), (2, 3, 516), (64, 128, 1), (2, 24, 3136), (1, 1, 70000),
+             (5, 16, 2048)]
+QZ_TYPES = [(hago.I8, np.int8, 8, True, 0, None), (hago.U8, np.uint8, 8, False, 128, None),
+            (hago.I8, np.int8, 4, True, 1, (-8, 7)), (hago.I16, np.int16, 16, True, -300, None),
+            (hago.I32, np.int32, 20, True, 7, None)]
+
+
+@pytest.mark.parametrize("shape", QZ_SHAPES)
+@pytest.mark.parametrize("qt", QZ_TYPES)
+@pytest.mark.parametrize("per_channel", [True, False])
+def test_quantize_dequantize_shapes(shape, qt, per_channel):
+    """Codes equal the oracle's in every container; dequantized values have the oracle's bits; and
+    dequantize(quantize(x)) is simulated_quantize(x) bit for bit."""
+    code, npdt, bits, signed, z0, clip = qt
+    rng = np.random.default_rng(abs(hash((shape, code, bits, per_channel))) % 2 ** 31)
+    c = shape[1] if per_channel else 1
+    lo, hi = clip if clip else ((-(1 << (bits - 1)), (1 << (bits - 1)) - 1) if signed else (0, (1 << bits) - 1))
+    scale = (rng.uniform(0.5, 2.0, c) * 3.0 / (hi - lo + 1)).astype(np.float32)
+    zp = (z0 + rng.integers(-2, 3, c)).astype(np.int32)
+    x = (rng.standard_normal(shape) * 1.2).astype(np.float32)
+    flat = x.reshape(-1)
+    if flat.size >= 8:
+        flat[:5] = [np.nan, np.inf, -np.inf, -0.0, 1e30]
+    q = hago.QType(code, bits, signed)
+    want = ref.quantize(x, scale, zp, lo, hi, per_channel)
+    got = hago.quantize(dev(x), dev(scale), dev(zp), q, lo, hi, per_channel)
+    assert got.dtype == getattr(torch, np.dtype(npdt).name)
+    assert_same(host(got).astype(np.int64), want.astype(np.int64), f"quantize {shape} {np.dtype(npdt).name}")
+    y = hago.dequantize(got, q, dev(scale), dev(zp), per_channel)
+    assert_same_bits(host(y), ref.dequantize(want, scale, zp, per_channel), "dequantize")
+    finite = ~np.isnan(x)
+    sq = host(hago.simquant(dev(x), dev(scale), dev(zp), q, lo, hi, per_channel))
+    assert np.array_equal(host(y).view(np.uint32)[finite], sq.view(np.uint32)[finite])
+
+
+def test_quantize_config4_full_size():
+    c = datagen.config4_simquant()
+    x = c["x"].reshape(32, 144, -1)
+    want = ref.quantize(x, c["scale"], c["zp"], *c["clip"])
+    got = hago.quantize(dev(x), dev(c["scale"]), dev(c["zp"]), hago.QType(hago.I8), *c["clip"])
+    assert_same(host(got).astype(np.int32), want, "config 4 quantize")
+    y = hago.dequantize(got, hago.QType(hago.I8), dev(c["scale"]), dev(c["zp"]))
+    assert_same_bits(host(y), ref.simquant(x, c["scale"], c["zp"], *c["clip"]), "config 4 round trip")
+
+
 AM_SHAPES = [(1, 1, 1), (3, 5, 7), (2, 4, 512), (2, 3, 516), (64, 128, 1), (33, 52, 1), (4, 6, 2048),
              (2, 24, 3136), (1, 1, 70000), (3, 2, 5000), (1000, 3, 2), (300, 1, 1), (1, 7, 4100)]
 
