@@ -144,6 +144,20 @@ def simquant(x, scale, zero_point, clip_lo, clip_hi, per_channel=None):
     return y
 
 
+def simquant_batched(x, scales, zero_points, clip_lo, clip_hi, per_channel=True):
+    """Batched search evaluation (Sec. 6.3): candidate b applies simulated_quantize with its own
+    scales[b], zero_points[b] ([channels] each, or one entry) and clip range to the SAME tensor x.
+    Returns y[b, outer, channels, inner].  By definition: one simquant per candidate."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    nb = len(clip_lo)
+    s = np.ascontiguousarray(scales, dtype=np.float32).reshape(nb, -1)
+    z = np.ascontiguousarray(zero_points, dtype=np.int32).reshape(nb, -1)
+    y = np.empty((nb,) + x.shape, np.float32)
+    for b in range(nb):
+        y[b] = simquant(x, s[b], z[b], int(clip_lo[b]), int(clip_hi[b]), per_channel)
+    return y
+
+
 def quantize(x, scale, zero_point, clip_lo, clip_hi, per_channel=None):
     """x: float32 [outer, channels, inner] -> int32 codes of the same shape."""
     x = np.ascontiguousarray(x, dtype=np.float32)

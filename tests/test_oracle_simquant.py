@@ -146,3 +146,26 @@ def test_scale_eq1_and_absmax_eq2(ref):
     assert ref.bit_range(8, False) == (0, 255)
     with pytest.raises(ref.RefError):
         ref.bit_range(0, True)
+
+
+def test_batched_candidates_on_the_worked_vectors(ref):
+    # Sec. 6.3: several candidate parameter sets over one tensor.  The golden rows with s = 0.25
+    # give two candidates (signed with z = 0, unsigned with z = 128) whose expected outputs are
+    # the hand-worked ones; this pins the [candidate][...] layout and the parameter indexing.
+    rows = read_golden("simquant_vectors.txt")
+    cand = {(0, -128, 127): {}, (128, 0, 255): {}}
+    for x, s, z, lo, hi, want in rows:
+        if float(s) == 0.25 and (int(z), int(lo), int(hi)) in cand:
+            cand[(int(z), int(lo), int(hi))][np.float32(x).tobytes()] = np.float32(want)
+    xs = sorted(set(cand[(0, -128, 127)]) | set(cand[(128, 0, 255)]))
+    x = np.frombuffer(b"".join(xs), np.float32).reshape(1, 1, -1)
+    y = ref.simquant_batched(x, [[0.25], [0.25]], [[0], [128]], [-128, 0], [127, 255], per_channel=False)
+    assert y.shape == (2, 1, 1, len(xs))
+    for b, key in enumerate(((0, -128, 127), (128, 0, 255))):
+        for i, xb in enumerate(xs):
+            if xb in cand[key]:
+                assert y[b, 0, 0, i].tobytes() == cand[key][xb].tobytes()
+    # per-channel candidates: channel c of candidate b uses scales[b][c]
+    x = np.array([[[0.375], [0.375]]], np.float32)          # [1, 2, 1]
+    y = ref.simquant_batched(x, [[0.25, 0.125], [0.5, 0.25]], [[0, 0], [0, 0]], [-128, -128], [127, 127])
+    assert y[:, 0, :, 0].tolist() == [[0.5, 0.375], [0.5, 0.5]]   # 1.5->2, 3->3 | 0.75->1, 1.5->2
