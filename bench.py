@@ -271,6 +271,23 @@ def extra_ops(torch, hago, datagen, to_dev, rq_of, event_time_ms, only):
                note="fp32 [32,144,56,56], per-channel, 8 B/elem")
         del f
 
+    # ---- eight search candidates in one launch (Sec. 6.3)
+    if want("simquant_batched8_c4"):
+        c = datagen.config4_simquant()
+        x0 = to_dev(c["x"].reshape(32, 144, -1))
+        bits = [8, 8, 7, 7, 6, 6, 5, 4]
+        lo = [-(1 << (b - 1)) for b in bits]
+        hi = [(1 << (b - 1)) - 1 for b in bits]
+        scales = to_dev(np.stack([c["scale"] * (128.0 / (1 << (b - 1))) for b in bits]).astype(np.float32))
+        zps = to_dev(np.zeros((8, 144), np.int32))
+        nb = x0.numel() * 4 * 9
+        f = rotating(lambda i: hago.simquant_batched(x0.clone(), scales, zps, hago.QType(hago.I8), lo, hi,
+                                                     prepare=True), nb)
+        record("simquant_batched8_c4", event_time_ms(f, 30, 4), bytes_=nb, bound="hbm",
+               note="fp32 [32,144,56,56], 8 candidates in one launch, 4 + 32 B/elem "
+                    "(8 separate simquant launches move 64 B/elem)")
+        del f
+
     # ---- quantize / dequantize of the same tensor (int8 codes)
     if want("quantize_c4") or want("dequantize_c4"):
         c = datagen.config4_simquant()

@@ -9,6 +9,7 @@
  *   hago_qdense     -- integer dense, integer accumulate, fused requantize
  *   hago_qconv2d    -- integer conv2d (groups == 1 or depthwise), same epilogue
  *   hago_requantize -- the standalone requantize operator (Sec. 6.1, 6.2)
+ *   hago_simquant_batched -- several candidate settings over one tensor (Sec. 6.3)
  *   hago_absmax     -- max-abs calibration thresholds (Eq. 2)
  *   hago_quantize, hago_dequantize -- fp32 <-> integer codes (Sec. 6.1; Eq. 3)
  *
@@ -165,6 +166,27 @@ hago_status hago_qconv2d(const void* a, hago_qtype a_t, const void* w,
                          int32_t pad_w, int32_t groups, hago_dtype acc_dtype,
                          const hago_requant* rq, void* out, uint32_t flags,
                          void* stream);
+
+/*
+ * Batched candidate evaluation of simulated_quantize (Sec. 6.3 "Batched GPU
+ * Search": quantization parameters are runtime arguments, and a batch of
+ * candidate settings is evaluated in one go).  The tensor x[outer, channels,
+ * inner] (device, fp32) is read once; candidate b = 0..nbatch-1 (at most 16)
+ * writes y[b, outer, channels, inner] (device, fp32) = hago_simquant(x) with
+ * scale[b*P + c], zero_point[b*P + c] (device; P = channels if per_channel
+ * else 1) and the clip range clip_lo[b]..clip_hi[b] (HOST arrays, read before
+ * the call returns).  q bounds every clip range as in hago_simquant (use the
+ * widest candidate's bits).  y must not overlap x.
+ * Errors: NULL, SHAPE, DTYPE, BITS (some clip range outside q or +-2^24),
+ * PARAM (per_channel not 0/1, nbatch > 16), DEVICE.  Empty is a no-op.
+ */
+hago_status hago_simquant_batched(const float* x, float* y, int64_t outer,
+                                  int64_t channels, int64_t inner,
+                                  int32_t nbatch, const float* scale,
+                                  const int32_t* zero_point,
+                                  int32_t per_channel, hago_qtype q,
+                                  const int32_t* clip_lo,
+                                  const int32_t* clip_hi, void* stream);
 
 /*
  * quantize and dequantize (Sec. 6.1: the operators with which the realized

@@ -16,7 +16,7 @@ STRICT_ACC16 = 1
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libhago.so")
 
-EXPORTS = ("hago_simquant", "hago_absmax", "hago_quantize", "hago_dequantize", "hago_qdense", "hago_qconv2d", "hago_requantize", "hago_status_string")
+EXPORTS = ("hago_simquant", "hago_simquant_batched", "hago_absmax", "hago_quantize", "hago_dequantize", "hago_qdense", "hago_qconv2d", "hago_requantize", "hago_status_string")
 
 
 class _QType(C.Structure):
@@ -56,6 +56,8 @@ def lib():
         L.hago_status_string.argtypes = [i32]
         L.hago_simquant.restype = i32
         L.hago_simquant.argtypes = [vp, vp, i64, i64, i64, vp, vp, i32, _QType, i32, i32, vp]
+        L.hago_simquant_batched.restype = i32
+        L.hago_simquant_batched.argtypes = [vp, vp, i64, i64, i64, i32, vp, vp, i32, _QType, vp, vp, vp]
         L.hago_quantize.restype = i32
         L.hago_quantize.argtypes = [vp, vp, i64, i64, i64, vp, vp, i32, _QType, i32, i32, vp]
         L.hago_dequantize.restype = i32
@@ -165,6 +167,26 @@ def simquant(x, scale, zero_point, q: QType, clip_lo=None, clip_hi=None, per_cha
     if prepare:
         return Prepared(lib().hago_simquant, args, (x, y, scale, zero_point), y)
     _check(lib().hago_simquant(*args))
+    return y
+
+
+def simquant_batched(x, scales, zero_points, q: QType, clip_lo, clip_hi, per_channel=True, out=None,
+                     prepare=False):
+    """hago_simquant_batched: candidates b over x[outer, channels, inner]; scales / zero_points are
+    device tensors [nbatch, channels] (or [nbatch, 1]); clip_lo / clip_hi are host sequences."""
+    assert x.dim() == 3 and x.is_contiguous() and scales.is_contiguous() and zero_points.is_contiguous()
+    outer, channels, inner = x.shape
+    nb = len(clip_lo)
+    assert len(clip_hi) == nb and scales.shape[0] == nb and zero_points.shape[0] == nb
+    t = _torch()
+    y = t.empty((nb,) + tuple(x.shape), dtype=t.float32, device=x.device) if out is None else out
+    lo = (C.c_int32 * max(nb, 1))(*[int(v) for v in clip_lo])
+    hi = (C.c_int32 * max(nb, 1))(*[int(v) for v in clip_hi])
+    args = (_ptr(x), _ptr(y), outer, channels, inner, nb, _ptr(scales), _ptr(zero_points),
+            int(bool(per_channel)), q.c(), C.cast(lo, C.c_void_p), C.cast(hi, C.c_void_p), _stream())
+    if prepare:
+        return Prepared(lib().hago_simquant_batched, args, (x, y, scales, zero_points, lo, hi), y)
+    _check(lib().hago_simquant_batched(*args))
     return y
 
 

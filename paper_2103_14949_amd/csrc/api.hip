@@ -162,6 +162,35 @@ hago_status hago_simquant(const float* x, float* y, int64_t outer, int64_t chann
                                         static_cast<hipStream_t>(stream)));
 }
 
+hago_status hago_simquant_batched(const float* x, float* y, int64_t outer, int64_t channels,
+                                  int64_t inner, int32_t nbatch, const float* scale,
+                                  const int32_t* zero_point, int32_t per_channel, hago_qtype q,
+                                  const int32_t* clip_lo, const int32_t* clip_hi, void* stream) {
+  if (outer < 0 || channels < 0 || inner < 0 || nbatch < 0) return HAGO_ERR_SHAPE;
+  if (nbatch > 16) return HAGO_ERR_PARAM;
+  const bool empty = outer == 0 || channels == 0 || inner == 0 || nbatch == 0;
+  if (((!x || !y) && !empty) || !scale || !zero_point || ((!clip_lo || !clip_hi) && nbatch > 0))
+    return HAGO_ERR_NULL;
+  if (per_channel != 0 && per_channel != 1) return HAGO_ERR_PARAM;
+  if (q.dtype == HAGO_F32) return HAGO_ERR_DTYPE;
+  hago_status s = check_qtype(q, false);
+  if (s != HAGO_OK) return s;
+  int64_t blo, bhi;
+  bit_range(q.bits, q.is_signed != 0, &blo, &bhi);
+  for (int b = 0; b < nbatch; ++b) {
+    if (clip_lo[b] > clip_hi[b] || clip_lo[b] < blo || clip_hi[b] > bhi) return HAGO_ERR_BITS;
+    if (clip_lo[b] < -(1 << 24) || clip_hi[b] > (1 << 24)) return HAGO_ERR_BITS;
+  }
+  if (!empty) {
+    if (outer > INT64_MAX / channels || outer * channels > INT64_MAX / inner ||
+        outer * channels * inner > INT64_MAX / nbatch)
+      return HAGO_ERR_SHAPE;
+  }
+  return from_hip(hago::launch_simquant_batched(x, y, outer, channels, inner, nbatch, scale,
+                                                zero_point, per_channel, clip_lo, clip_hi,
+                                                static_cast<hipStream_t>(stream)));
+}
+
 namespace {
 // Shared checks of quantize / dequantize; container id for launch_quant.
 hago_status check_quant(hago_qtype q, int32_t per_channel, int64_t outer, int64_t channels,

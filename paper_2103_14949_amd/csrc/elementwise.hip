@@ -91,6 +91,69 @@ __global__ __launch_bounds__(kThreads) void simquant_rows_kernel(
   }
 }
 
+// Batched candidates (Sec. 6.3): x is read ONCE and every candidate b writes its own
+// y[b][...] with scale[b][c], zero_point[b][c] and clip range b.  4 + 4 B bytes per element
+// instead of 8 B for B separate launches.
+constexpr int kMaxCandidates = 16;
+struct CandidateClips {
+  float lo[kMaxCandidates], hi[kMaxCandidates];
+};
+
+template <int U>
+__global__ __launch_bounds__(kThreads) void simquant_batched_rows_kernel(
+    const v4f* __restrict__ x, v4f* __restrict__ y, int64_t rows, int32_t channels,
+    int64_t inner_vec, int32_t nseg, int32_t seg_len, int32_t nbatch, int32_t nparam,
+    const float* __restrict__ scale, const int32_t* __restrict__ zp, int per_channel,
+    CandidateClips clips) {
+  const int64_t batch_stride = rows * inner_vec;  // vectors per candidate output
+  for (int64_t job = blockIdx.x; job < rows * nseg; job += gridDim.x) {
+    const int64_t row = job / nseg;
+    const int32_t c = per_channel ? (int32_t)(row % channels) : 0;
+    const int32_t seg = (int32_t)(job - row * nseg);
+    const int64_t v0 = (int64_t)seg * seg_len;
+    const int64_t v1 = (v0 + seg_len < inner_vec) ? v0 + seg_len : inner_vec;
+    const v4f* xr = x + row * inner_vec;
+    v4f* yr = y + row * inner_vec;
+    for (int64_t vb = v0 + threadIdx.x; vb < v1; vb += (int64_t)kThreads * U) {
+      v4f a[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        if (vb + u * kThreads < v1) a[u] = __builtin_nontemporal_load(xr + vb + u * kThreads);
+      for (int b = 0; b < nbatch; ++b) {
+        const float s = scale[(int64_t)b * nparam + c];
+        const float zf = (float)zp[(int64_t)b * nparam + c];
+        const float lo = clips.lo[b], hi = clips.hi[b];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          if (vb + u * kThreads < v1) {
+            v4f r;
+            r.x = simquant_one(a[u].x, s, zf, lo, hi);
+            r.y = simquant_one(a[u].y, s, zf, lo, hi);
+            r.z = simquant_one(a[u].z, s, zf, lo, hi);
+            r.w = simquant_one(a[u].w, s, zf, lo, hi);
+            __builtin_nontemporal_store(r, yr + b * batch_stride + vb + u * kThreads);
+          }
+        }
+      }
+    }
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void simquant_batched_flat_kernel(
+    const float* __restrict__ x, float* __restrict__ y, int64_t total, int64_t inner,
+    int64_t channels, int32_t nbatch, int32_t nparam, const float* __restrict__ scale,
+    const int32_t* __restrict__ zp, int per_channel, CandidateClips clips) {
+  const int64_t stride = (int64_t)gridDim.x * kThreads;
+  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += stride) {
+    const int64_t c = per_channel ? (i / inner) % channels : 0;
+    const float v = x[i];
+    for (int b = 0; b < nbatch; ++b)
+      y[(int64_t)b * total + i] = simquant_one(v, scale[(int64_t)b * nparam + c],
+                                               (float)zp[(int64_t)b * nparam + c], clips.lo[b],
+                                               clips.hi[b]);
+  }
+}
+
 __global__ __launch_bounds__(kThreads) void simquant_flat_kernel(
     const float* __restrict__ x, float* __restrict__ y, int64_t total, int64_t inner,
     int64_t channels, const float* __restrict__ scale, const int32_t* __restrict__ zp,
@@ -406,6 +469,38 @@ hipError_t launch_simquant(const float* x, float* y, int64_t outer, int64_t chan
     hipLaunchKernelGGL(simquant_flat_kernel, dim3(grid_for((total + kThreads - 1) / kThreads)),
                        dim3(kThreads), 0, st, x, y, total, inner, channels, scale, zp, per_channel,
                        lo, hi);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_simquant_batched(const float* x, float* y, int64_t outer, int64_t channels,
+                                   int64_t inner, int32_t nbatch, const float* scale,
+                                   const int32_t* zp, int per_channel, const int32_t* clip_lo,
+                                   const int32_t* clip_hi, hipStream_t st) {
+  const int64_t total = outer * channels * inner;
+  if (total == 0 || nbatch == 0) return hipSuccess;
+  if (nbatch > kMaxCandidates) return hipErrorInvalidValue;
+  CandidateClips clips{};
+  for (int b = 0; b < nbatch; ++b) {
+    clips.lo[b] = (float)clip_lo[b];
+    clips.hi[b] = (float)clip_hi[b];
+  }
+  const int32_t nparam = (int32_t)(per_channel ? channels : 1);
+  const int64_t rows = per_channel ? outer * channels : 1;
+  const int64_t row_len = per_channel ? inner : total;
+  if (row_len % 4 == 0 && row_len >= 512 && aligned16(x) && aligned16(y)) {
+    const int64_t inner_vec = row_len / 4;
+    constexpr int kU = 2;  // fewer vectors in flight per lane: every one is stored nbatch times
+    int32_t nseg, seg_len;
+    split_row(inner_vec, kU, &nseg, &seg_len);
+    hipLaunchKernelGGL(simquant_batched_rows_kernel<kU>, dim3(grid_for(rows * nseg)), dim3(kThreads),
+                       0, st, reinterpret_cast<const v4f*>(x), reinterpret_cast<v4f*>(y), rows,
+                       nparam, inner_vec, nseg, seg_len, nbatch, nparam, scale, zp, per_channel,
+                       clips);
+  } else {
+    hipLaunchKernelGGL(simquant_batched_flat_kernel, dim3(grid_for((total + kThreads - 1) / kThreads)),
+                       dim3(kThreads), 0, st, x, y, total, inner, channels, nbatch, nparam, scale, zp,
+                       per_channel, clips);
   }
   return hipGetLastError();
 }

@@ -20,6 +20,13 @@ hipError_t launch_simquant(const float* x, float* y, int64_t outer, int64_t chan
                            const float* scale, const int32_t* zp, int per_channel, int32_t clip_lo,
                            int32_t clip_hi, hipStream_t st);
 
+// nbatch (<= 16) candidate parameter sets over one tensor: y[nbatch][outer][channels][inner];
+// scale / zp: [nbatch][channels] (or [nbatch]); clip_lo / clip_hi: host arrays [nbatch].
+hipError_t launch_simquant_batched(const float* x, float* y, int64_t outer, int64_t channels,
+                                   int64_t inner, int32_t nbatch, const float* scale,
+                                   const int32_t* zp, int per_channel, const int32_t* clip_lo,
+                                   const int32_t* clip_hi, hipStream_t st);
+
 // quantize (fp32 -> codes) / dequantize (codes -> fp32) over [outer, channels, inner].
 // container: 0 int8, 1 uint8, 2 int16, 3 int32.
 hipError_t launch_quant(const void* in, void* out, int container, int deq, int64_t outer,

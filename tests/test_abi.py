@@ -24,7 +24,7 @@ def test_every_declared_symbol_is_exported(L):
     header = open(os.path.join(ROOT, "include", "hago.h")).read()
     declared = set(re.findall(r"\b(hago_[a-z0-9_]+)\s*\(", header))
     assert {"hago_simquant", "hago_qdense", "hago_qconv2d", "hago_requantize", "hago_absmax",
-            "hago_quantize", "hago_dequantize",
+            "hago_quantize", "hago_dequantize", "hago_simquant_batched",
             "hago_status_string"} <= declared
     for name in declared:
         assert hasattr(L, name), name
@@ -127,6 +127,20 @@ def test_quantize_and_dequantize_argument_errors(L):
     assert dq(BAD, q, BAD, 1, 1, -1, BAD, BAD, 0, None) == 2
     assert dq(BAD, _qt(hago.F32), BAD, 1, 1, 1, BAD, BAD, 0, None) == 3
     assert dq(BAD, q, BAD, 1, 1, 1, BAD, BAD, 2, None) == 5
+
+
+def test_simquant_batched_argument_errors(L):
+    q = _qt(hago.I8)
+    lo = (C.c_int32 * 2)(-128, -8)
+    hi = (C.c_int32 * 2)(127, 7)
+    sb = lambda *a: L.hago_simquant_batched(*a)  # noqa: E731
+    assert sb(None, BAD, 1, 1, 1, 2, BAD, BAD, 1, q, lo, hi, None) == 1
+    assert sb(BAD, BAD, 1, 1, 1, 2, BAD, BAD, 1, q, None, hi, None) == 1
+    assert sb(BAD, BAD, 1, 1, -1, 2, BAD, BAD, 1, q, lo, hi, None) == 2
+    assert sb(BAD, BAD, 1, 1, 1, 17, BAD, BAD, 1, q, lo, hi, None) == 5
+    assert sb(BAD, BAD, 1, 1, 1, 2, BAD, BAD, 1, _qt(hago.F32), lo, hi, None) == 3
+    bad_hi = (C.c_int32 * 2)(127, 200)
+    assert sb(BAD, BAD, 1, 1, 1, 2, BAD, BAD, 1, q, lo, bad_hi, None) == 4
 
 
 def test_absmax_argument_errors(L):

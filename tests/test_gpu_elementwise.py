@@ -77,6 +77,46 @@ def test_simquant_config4_full_size():
     assert np.abs(want).max() <= thr.max()
 
 
+@pytest.mark.parametrize("shape", [(1, 1, 1), (3, 5, 7), (2, 4, 512), (2, 3, 516), (2, 24, 3136), (1, 1, 70000),
+                                   (64, 128, 1)])
+@pytest.mark.parametrize("per_channel", [True, False])
+def test_simquant_batched(shape, per_channel):
+    """Every candidate of one batched launch equals its own simulated quantize, bit for bit:
+    candidates with different scales, zero points and effective bits (clip ranges)."""
+    rng = np.random.default_rng(abs(hash((shape, per_channel, "b"))) % 2 ** 31)
+    x = (rng.standard_normal(shape) * 1.5).astype(np.float32)
+    if x.size >= 4:
+        x.reshape(-1)[:3] = [np.nan, np.inf, -0.0]
+    c = shape[1] if per_channel else 1
+    bits = [8, 7, 6, 5, 4, 8, 3]
+    lo = [-(1 << (b - 1)) for b in bits]
+    hi = [(1 << (b - 1)) - 1 for b in bits]
+    scales = np.stack([(rng.uniform(0.5, 2.0, c) * 6.0 / (1 << b)).astype(np.float32) for b in bits])
+    zps = rng.integers(-2, 3, (len(bits), c)).astype(np.int32)
+    want = ref.simquant_batched(x, scales, zps, lo, hi, per_channel)
+    got = hago.simquant_batched(dev(x), dev(scales), dev(zps), hago.QType(hago.I8), lo, hi, per_channel)
+    assert_same_bits(host(got), want, f"batched simquant {shape}")
+    # a single candidate is plain simquant
+    one = hago.simquant_batched(dev(x), dev(scales[:1]), dev(zps[:1]), hago.QType(hago.I8), lo[:1], hi[:1],
+                                per_channel)
+    assert_same_bits(host(one)[0], ref.simquant(x, scales[0], zps[0], lo[0], hi[0], per_channel), "one candidate")
+
+
+def test_simquant_batched_config4_eight_candidates():
+    c = datagen.config4_simquant()
+    x = c["x"].reshape(32, 144, -1)[:8]          # a quarter of the tensor keeps the oracle fast
+    bits = [8, 8, 7, 7, 6, 6, 5, 4]
+    lo = [-(1 << (b - 1)) for b in bits]
+    hi = [(1 << (b - 1)) - 1 for b in bits]
+    thr = ref.absmax(x, True)
+    rng = np.random.default_rng(3)
+    scales = np.stack([(thr * rng.uniform(0.7, 1.0) / (1 << (b - 1))).astype(np.float32) for b in bits])
+    zps = np.zeros((8, 144), np.int32)
+    want = ref.simquant_batched(x, scales, zps, lo, hi)
+    got = hago.simquant_batched(dev(x), dev(scales), dev(zps), hago.QType(hago.I8), lo, hi)
+    assert_same_bits(host(got), want, "config 4, eight candidates")
+
+
 QZ_SHAPES = [(1, 1, 1), (3, 5, 7), (2, 4, 512), (2, 3, 516), (64, 128, 1), (2, 24, 3136), (1, 1, 70000),
              (5, 16, 2048)]
 QZ_TYPES = [(hago.I8, np.int8, 8, True, 0, None), (hago.U8, np.uint8, 8, False, 128, None),
