@@ -204,12 +204,13 @@ def main():
 
 
 def cpu_baseline(datagen, layers):
-    """The oracle as it stands on a bounded sample: the first rows of every layer."""
+    """The oracle as it stands on a bounded sample: one whole step (all 4096 rows of the four
+    layers, 58 GOP: about a second on 16 cores, i.e. some 16 s of CPU work)."""
     from oracle import hago_ref as ref
     ref.build()
     threads = int(os.environ.get("OMP_NUM_THREADS", "0")) or (os.cpu_count() or 1)
     threads = max(1, min(threads, os.cpu_count() or 1))
-    rows = 1024
+    rows = 4096
     ops = 0.0
     t0 = time.perf_counter()
     for l in layers:
@@ -220,7 +221,7 @@ def cpu_baseline(datagen, layers):
     dt = time.perf_counter() - t0
     log(f"cpu oracle: {ops / 1e9:.2f} GOP in {dt:.2f} s on {threads} threads")
     return {"value": round(ops / dt / 1e12, 5), "unit": "TOP/s", "cores": threads, "kind": "oracle",
-            "sample": f"first {rows} of 4096 rows of each of the 4 layers ({ops / 1e9:.1f} GOP), "
+            "sample": f"all {rows} rows of each of the 4 layers, one step ({ops / 1e9:.1f} GOP), "
                       f"row slices on {threads} threads, {dt:.2f} s wall"}
 
 
