@@ -153,7 +153,8 @@ template <int NT, int CH>
 __device__ __forceinline__ bool finish_channel_terms(const QgemmParams& p, const ChannelRegs<NT, CH>& r,
                                                      int32_t* s_corr, int32_t* s_mult,
                                                      int32_t* s_shift, int64_t* s_c64,
-                                                     const int32_t* s_sum2 = nullptr) {
+                                                     const int32_t* s_sum2 = nullptr,
+                                                     int32_t* s_shm1 = nullptr) {
   int general = p.K > 65536;
 #pragma unroll
   for (int s = 0; s < ChannelRegs<NT, CH>::kSlots; ++s) {
@@ -164,6 +165,7 @@ __device__ __forceinline__ bool finish_channel_terms(const QgemmParams& p, const
       s_corr[ci] = corr;
       s_mult[ci] = r.mult[s];
       s_shift[ci] = r.shift[s];
+      if (s_shm1) s_shm1[ci] = r.shift[s] - 1;  // the folded form shifts the high dword by this
       s_c64[ci] = (int64_t)corr * (int64_t)r.mult[s] + ((int64_t)1 << (30 + (r.shift[s] & 31)));
       general |= (r.shift[s] == 0) | (corr >= (1 << 30)) | (corr <= -(1 << 30));
     }
@@ -194,6 +196,7 @@ __device__ __forceinline__ void qgemm_epilogue_dense_staged(const QgemmParams& p
                                                             const int32_t* s_mult,
                                                             const int32_t* s_shift,
                                                             const int64_t* s_c64,
+                                                            const int32_t* s_shm1,
                                                             uint8_t* s_out) {
   constexpr int NT = 64 * WP * WQ;
   constexpr int BP = WP * TP * 32, BQ = WQ * TQ * 32;
@@ -216,7 +219,7 @@ __device__ __forceinline__ void qgemm_epilogue_dense_staged(const QgemmParams& p
     const int i_loc = (wp * TP + g / 4) * 32 + (g % 4) * 8 + fhalf * 4;
     Terms t;
     t.m4 = *reinterpret_cast<const int4*>(s_mult + i_loc);
-    t.s4 = *reinterpret_cast<const int4*>(s_shift + i_loc);
+    t.s4 = *reinterpret_cast<const int4*>((FOLDED ? s_shm1 : s_shift) + i_loc);
     if constexpr (FOLDED) {
       t.ca = *reinterpret_cast<const longlong2*>(s_c64 + i_loc);
       t.cb = *reinterpret_cast<const longlong2*>(s_c64 + i_loc + 2);
@@ -242,7 +245,7 @@ __device__ __forceinline__ void qgemm_epilogue_dense_staged(const QgemmParams& p
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int64_t pr = (int64_t)acc[ti][tj][g4 * 4 + e] * (int64_t)mm[e] + c64[e];
-          r[tj][e] = (int32_t)(pr >> 32) >> (ss[e] - 1);
+          r[tj][e] = (int32_t)(pr >> 32) >> ss[e];  // ss = shift - 1 here
         }
     } else {
       const int32_t cc[4] = {cur.c4.x, cur.c4.y, cur.c4.z, cur.c4.w};

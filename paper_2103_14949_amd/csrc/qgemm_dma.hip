@@ -131,6 +131,7 @@ __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParam
   int32_t* s_mult = s_corr + CH;
   int32_t* s_shift = s_mult + CH;
   int64_t* s_c64 = reinterpret_cast<int64_t*>(s_shift + CH);
+  int32_t* s_shm1 = reinterpret_cast<int32_t*>(s_c64 + CH);  // shift - 1
 
   const int t = threadIdx.x;
   const int lane = t & 63;
@@ -493,9 +494,9 @@ __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParam
   HAGO_STAMP(p, 2);
   main_loop();
   HAGO_STAMP(p, 3);
-  // drain the zero-fill stages before LDS is reused and before the workgroup may exit
+  // drain the zero-fill stages before LDS is reused and before the workgroup may exit (the
+  // barriers of the channel terms below come before anything is written to the ring's memory)
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  __syncthreads();
 
   // weight row sums: the two 32-lane halves hold the two halves of each 32-k group of a row.
   // Each lane has summed 16 bytes per 32-k group it covers (biased by 128 each) per stage for
@@ -515,7 +516,7 @@ __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParam
   }
   __syncthreads();
   const bool general = finish_channel_terms<NT, CH>(p, chregs, s_corr, s_mult, s_shift, s_c64,
-                                                    kSplitSum ? s_mult : nullptr);
+                                                    kSplitSum ? s_mult : nullptr, s_shm1);
   HAGO_STAMP(p, 4);
   if constexpr (!ACT_ON_P) {
     constexpr bool kCanStage = BQ * (BP + 16) <= kStages * STAGE && (BQ * BP / 16) % NT == 0;
@@ -523,10 +524,10 @@ __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParam
       if (p.out_mode == 0 && !p.acc16 && p.vec16_out && p0 + BP <= p.N && q0 + BQ <= p.M) {
         if (general)
           qgemm_epilogue_dense_staged<WP, WQ, TP, TQ, false>(p, acc, p0, q0, s_corr, s_mult, s_shift,
-                                                             s_c64, smem);
+                                                             s_c64, s_shm1, smem);
         else
           qgemm_epilogue_dense_staged<WP, WQ, TP, TQ, true>(p, acc, p0, q0, s_corr, s_mult, s_shift,
-                                                            s_c64, smem);
+                                                            s_c64, s_shm1, smem);
         return;
       }
     }
@@ -539,7 +540,7 @@ template <int WP, int WQ, int TP, int TQ, int kStages, int OCC, bool CONV, bool 
 hipError_t launch_dma_kernel(const QgemmParams& p, hipStream_t st) {
   constexpr int BP = WP * TP * 32, BQ = WQ * TQ * 32;
   constexpr int CH = ACT_ON_P ? BQ : BP;
-  constexpr size_t lds = (size_t)kStages * (BP + BQ) * BK + 1024 + 5 * CH * sizeof(int32_t);
+  constexpr size_t lds = (size_t)kStages * (BP + BQ) * BK + 1024 + 6 * CH * sizeof(int32_t);
   const int P_ext = ACT_ON_P ? p.M : p.N;
   const int Q_ext = ACT_ON_P ? p.N : p.M;
   const int64_t tiles = (int64_t)((P_ext + BP - 1) / BP) * ((Q_ext + BQ - 1) / BQ);
