@@ -339,140 +339,192 @@ __global__ __launch_bounds__(kThreads) void dw_wave3x3_kernel(DwArgs p, int32_t 
 }
 
 
-// NCHW 3x3 stride 1 pad 1, W <= 64, W % 4 == 0, aligned tensors, planes below 2 GB: no LDS.
-// One wavefront per plane.  Lane (q, rc): strip of four output columns q, quarter rc of the
-// rows.  A lane loads ONE dword per input row (its own strip) and takes the left and right
-// neighbours' dwords by DPP row shifts (the 16 lanes of a DPP row are the strips of one image
-// row; lanes without a strip hold the zero point, which is also what a shift from outside the
-// row yields).  All 18 loads of a pass (16 output rows plus halo) and the per-channel constants
-// are in flight together.  Loads and stores go through buffer descriptors of the plane, so a
-// lane that has nothing to load or store just uses an out-of-range offset.
+// NCHW 3x3 stride 1 pad 1, W <= 64, W % 4 == 0, 4-byte aligned tensors and weights, planes
+// below 2 GB: no LDS.  One wavefront per (plane, band of 4 * rpc rows), rpc <= 16.  Lane (q, rc):
+// strip of four output columns q, quarter rc of the band's rows.  A lane loads ONE dword per
+// input row (its own strip) and takes the left and right neighbours' dwords by DPP row shifts
+// (the 16 lanes of a DPP row are the strips of one image row; lanes without a strip hold the
+// zero point, which is also what a shift from outside the row yields).  All rpc + 2 loads are
+// in flight together.  Loads and stores go through buffer descriptors of the plane, so a lane
+// that has nothing to load or store just uses an out-of-range offset.
+// The kernel is bound by vector-ALU instruction issue (about 40 per row of four outputs against
+// 5 bytes of traffic), so everything that is the same for the whole wavefront -- the channel's
+// weights, bias and multiplier -- comes through scalar loads and scalar arithmetic, and the
+// per-output work is three dot products, one 64-bit multiply-add, one shift and one clamp.
 // MODE 0: requantized 8-bit, 1: raw int32, 2: raw int16; ACC16: accumulator wraps to 16 bits.
 template <int MODE, bool ACC16>
-__global__ __launch_bounds__(kThreads) void dw_rows3x3_kernel(DwArgs p, int64_t planes) {
+__global__ __launch_bounds__(kThreads) void dw_rows3x3_kernel(DwArgs p, int32_t rpc) {
+  // grid: x = groups of four channels, y = image, z = band
   const ConvGeom& g = p.g;
   const int H = g.H, W = g.W;
   const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int64_t plane = (int64_t)blockIdx.x * 4 + wave;  // b * C + c
-  if (plane >= planes) return;  // wavefront-uniform; the kernel has no barrier
-  const int c = (int)(plane % g.C);
+  const int c = (int)(blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6));
+  if (c >= g.C) return;  // wavefront-uniform; the kernel has no barrier
+  const int64_t plane = (int64_t)blockIdx.y * g.C + c;
+  const int band = (int)blockIdx.z;
   constexpr uint32_t kOob = 0x80000000u;
   constexpr int kEsz = MODE == 0 ? 1 : (MODE == 1 ? 4 : 2);
+  constexpr int kPass = 16;  // most output rows per lane
 
   const int q = lane & 15;
   const int rc = lane >> 4;
-  const int rpc = (H + 3) >> 2;  // rows per quarter
-  const int y0 = rc * rpc;
-  const int y1 = (y0 + rpc < H) ? y0 + rpc : H;
-  const uint32_t lane_off = (q << 2) < W ? (uint32_t)(q << 2) : kOob;  // byte column of the strip
+  const int y0 = (band * 4 + rc) * rpc;  // first output row of the lane
+  const bool has_strip = (q << 2) < W;
+  const uint32_t lane_off = has_strip ? (uint32_t)(q << 2) : kOob;  // byte column of the strip
   const uint32_t x4 = p.act_xor * 0x01010101u;
   const uint32_t pad4 = (((uint32_t)p.z_a ^ p.act_xor) & 0xffu) * 0x01010101u;
   const int64_t pbytes = (int64_t)H * W;
   const __amdgpu_buffer_rsrc_t rin = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<uint8_t*>(p.act) + plane * pbytes, 0, (int)pbytes, 0x00020000);
+      const_cast<uint8_t*>(p.act) + (int64_t)plane * pbytes, 0, (int)pbytes, 0x00020000);
   const __amdgpu_buffer_rsrc_t rout = __builtin_amdgcn_make_buffer_rsrc(
-      static_cast<uint8_t*>(p.out) + plane * pbytes * kEsz, 0, (int)(pbytes * kEsz), 0x00020000);
-  constexpr int kPass = 16;  // output rows per lane and pass
+      static_cast<uint8_t*>(p.out) + (int64_t)plane * pbytes * kEsz, 0, (int)(pbytes * kEsz), 0x00020000);
 
-  const int8_t* wc = p.wgt + (int64_t)c * 9;
-  int32_t wraw[9];
-#pragma unroll
-  for (int i = 0; i < 9; ++i) wraw[i] = wc[i];
-  const int32_t bias = p.bias ? p.bias[c] : 0;
-  const int pc = p.per_channel ? c : 0;
-  const int32_t m = MODE == 0 ? p.mult[pc] : 0;
-  const int32_t sh = MODE == 0 ? p.shift[pc] : 0;
-  // Rows outside the image (or beyond the quarter's halo) read as the zero point: an
-  // out-of-range buffer load returns 0, and the per-lane flip mask turns that into the
-  // zero point's byte (in range it is the plain sign flip).  The mask is opaque to the
-  // compiler: with a select on the loaded value it builds a branch around every load, each
-  // followed by a full wait.
-  auto load_rows = [&](int yb, uint32_t (&d)[kPass + 2]) {
+  // Row i of the lane is image row y0 + i - 1.  A row outside the image, and a lane without a
+  // strip, read as the zero point: their offsets are out of the descriptor's range (a negative
+  // row wraps to a huge offset, a row >= H lies beyond the plane, a strip-less lane starts at
+  // 2^31), such a load returns 0, and the flip mask turns that into the zero point's byte (in
+  // range it is the plain sign flip).  The mask is opaque to the compiler: with a select on the
+  // loaded value it builds a branch around every load, each followed by a full wait.
+  uint32_t flip_lane = has_strip ? x4 : pad4;
+  asm volatile("" : "+v"(flip_lane));
+  uint32_t d[kPass + 2];  // as loaded; the flip is applied where a row is used, so that no row waits for a later one
+  {
+    const uint32_t off0 = lane_off + (uint32_t)((y0 - 1) * W);
 #pragma unroll
     for (int i = 0; i < kPass + 2; ++i) {
-      const int y = y0 + yb + i - 1;
-      const bool ok = lane_off != kOob && (uint32_t)y < (uint32_t)H && yb + i - 1 <= rpc;
-      uint32_t flip = ok ? x4 : pad4;
-      asm volatile("" : "+v"(flip));
-      const uint32_t off = ok ? lane_off + (uint32_t)(y * W) : kOob;
-      d[i] = __builtin_amdgcn_raw_buffer_load_b32(rin, off, 0, 0) ^ flip;
+      uint32_t off = off0 + (uint32_t)(i * W);
+      if (i >= 3) off = (i - 1 <= rpc) ? off : kOob;  // uniform: rows beyond the lane's halo
+      d[i] = __builtin_amdgcn_raw_buffer_load_b32(rin, off, 0, 0);
     }
+  }
+  const int rows_in = H + 1 - y0;  // rows 1 .. rows_in - 1 of the lane lie in the image
+  auto row = [&](int i) {
+    uint32_t flip = (i == 0 ? y0 > 0 : i < rows_in) ? flip_lane : pad4;
+    asm volatile("" : "+v"(flip));
+    return d[i] ^ flip;
   };
-  uint32_t d[kPass + 2];
-  load_rows(0, d);
 
+  // The channel's constants, through scalar loads (the addresses are the same for the whole
+  // wavefront; scalar loads have their own counter, so waiting for them here, behind the row
+  // loads, does not wait for a row).  The nine weights: the three aligned dwords that hold bytes
+  // 9c .. 9c+8.  Each of the three holds at least one of the nine bytes, and an aligned dword
+  // lies within one page, so the bytes read before and after the channel's weights are never a
+  // fault.  A pointer the mode does not use is replaced by the weights' address.
+  const uint32_t wb = (uint32_t)c * 9u;
+  const int pc = p.per_channel ? c : 0;
+  const uint32_t* wp = reinterpret_cast<const uint32_t*>(p.wgt + (wb & ~3u));
+  const uint32_t* bp = p.bias ? reinterpret_cast<const uint32_t*>(p.bias + c) : wp;
+  const uint32_t* mp = MODE == 0 ? reinterpret_cast<const uint32_t*>(p.mult + pc) : wp;
+  const uint32_t* sp = MODE == 0 ? reinterpret_cast<const uint32_t*>(p.shift + pc) : wp;
+  uint64_t d01;
+  uint32_t d2, bias_raw, m_raw, sh_raw;
+  asm volatile(
+      "s_load_dwordx2 %0, %5, 0x0\n\t"
+      "s_load_dword %1, %5, 0x8\n\t"
+      "s_load_dword %2, %6, 0x0\n\t"
+      "s_load_dword %3, %7, 0x0\n\t"
+      "s_load_dword %4, %8, 0x0\n\t"
+      "s_waitcnt lgkmcnt(0)"
+      : "=&s"(d01), "=&s"(d2), "=&s"(bias_raw), "=&s"(m_raw), "=&s"(sh_raw)
+      : "s"(wp), "s"(bp), "s"(mp), "s"(sp));
+  const uint32_t d0 = (uint32_t)d01, d1 = (uint32_t)(d01 >> 32);
+  const uint32_t o8 = (wb & 3u) * 8u;
+  const uint32_t w03 = (uint32_t)((((uint64_t)d1 << 32) | d0) >> o8);  // weights 0..3
+  const uint32_t w47 = (uint32_t)((((uint64_t)d2 << 32) | d1) >> o8);  // weights 4..7
+  const uint32_t w8 = (d2 >> o8) & 0xffu;
   int32_t wrow[3];
+  wrow[0] = (int32_t)(w03 & 0xffffffu);
+  wrow[1] = (int32_t)((w03 >> 24) | ((w47 & 0xffffu) << 8));
+  wrow[2] = (int32_t)((w47 >> 16) | (w8 << 16));
   int32_t wsum = 0;
 #pragma unroll
-  for (int ky = 0; ky < 3; ++ky) {
-    const int32_t w0 = wraw[ky * 3 + 0], w1 = wraw[ky * 3 + 1], w2 = wraw[ky * 3 + 2];
-    wsum += w0 + w1 + w2;
-    wrow[ky] = (w0 & 0xff) | ((w1 & 0xff) << 8) | ((w2 & 0xff) << 16);
-  }
-  int32_t corr = bias + (p.act_off - p.z_a) * wsum;
+  for (int ky = 0; ky < 3; ++ky)
+#pragma unroll
+    for (int kx = 0; kx < 3; ++kx) wsum += (int32_t)(int8_t)(wrow[ky] >> (8 * kx));
+  const int32_t bias = p.bias ? (int32_t)bias_raw : 0;
+  const int32_t m = MODE == 0 ? (int32_t)m_raw : 0;
+  const int32_t sh = MODE == 0 ? (int32_t)sh_raw : 0;
+  // sum (a - z) w = sum (a' + off - z) w = sum a' w + (off - z) * sum w, a' = flipped byte
+  const int32_t corr = bias + (p.act_off - p.z_a) * wsum;
   const int64_t rnd = (int64_t)1 << (30 + sh);
-  int32_t lo = p.rs.lo_rel, hi = p.rs.hi_rel;
   const int32_t z = p.rs.z_out;
-  // vector-register copies: v_med3 takes at most one scalar operand
-  asm volatile("" : "+v"(lo), "+v"(hi));
 
   // the four 3-byte windows of a strip: output x = 4q + i reads input columns x-1 .. x+1
+  // The shifted copies live in two registers of their own, which start as the zero point in
+  // every lane: a shift never writes the lane at the end of a DPP row it has no source for, so
+  // that lane keeps the zero point from one shift to the next and needs no fresh copy.
+  uint32_t left = pad4, right = pad4;
   auto windows = [&](uint32_t d1, uint32_t (&w)[4]) {
-    const uint32_t d0 = (uint32_t)__builtin_amdgcn_update_dpp((int)pad4, (int)d1, 0x111, 0xf, 0xf, false);  // row_shr:1
-    const uint32_t d2 = (uint32_t)__builtin_amdgcn_update_dpp((int)pad4, (int)d1, 0x101, 0xf, 0xf, false);  // row_shl:1
-    w[0] = __builtin_amdgcn_alignbyte(d1, d0, 3);
+    left = (uint32_t)__builtin_amdgcn_update_dpp((int)left, (int)d1, 0x111, 0xf, 0xf, false);    // row_shr:1
+    right = (uint32_t)__builtin_amdgcn_update_dpp((int)right, (int)d1, 0x101, 0xf, 0xf, false);  // row_shl:1
+    w[0] = __builtin_amdgcn_alignbyte(d1, left, 3);
     w[1] = d1;
-    w[2] = __builtin_amdgcn_alignbyte(d2, d1, 1);
-    w[3] = __builtin_amdgcn_alignbyte(d2, d1, 2);
+    w[2] = __builtin_amdgcn_alignbyte(right, d1, 1);
+    w[3] = __builtin_amdgcn_alignbyte(right, d1, 2);
   };
   // (the builtin, not inline assembly: the compiler has to see the dot instructions to keep the
   // wait states they need before a dependent instruction)
   auto dot4 = [](uint32_t a, int32_t b, int32_t c) {
     return __builtin_amdgcn_sdot4((int)a, b, c, false);
   };
-  for (int yb = 0; yb < rpc; yb += kPass) {  // uniform trip count: every lane keeps feeding the DPP
-    if (yb > 0) load_rows(yb, d);
-    uint32_t wa[4], wb[4], wcur[4];
-    windows(d[0], wa);
-    windows(d[1], wb);
+  // A store beyond the image lies beyond the plane, and a strip-less lane's offset starts at
+  // 2^31: both are out of the descriptor's range and dropped.
+  const uint32_t so0 = has_strip ? (uint32_t)((q << 2) + y0 * W) * kEsz : kOob;
+
+  // FOLD (requantized, 32-bit accumulator, and the channel's constants small enough): the
+  // correction term, the rounding term and the output zero point all go into one 64-bit
+  // constant k64, so that an output is clamp((dots * m + k64) >> (31 + sh)) against the
+  // absolute bounds: (acc * m + rnd) >> s + z == (acc * m + rnd + z * 2^s) >> s exactly, and
+  // acc = dots + corr cannot wrap when |corr| <= 2^30 (|dots| < 2^19).  With sh <= 19 and an
+  // 8-bit z nothing here leaves 63 bits.
+  auto rows = [&]<bool FOLD>() {
+    int32_t lo = p.rs.lo_rel + (FOLD ? z : 0), hi = p.rs.hi_rel + (FOLD ? z : 0);
+    // vector-register copies: v_med3 takes at most one scalar operand
+    asm volatile("" : "+v"(lo), "+v"(hi));
+    const int64_t k64 = FOLD ? (int64_t)corr * m + rnd + ((int64_t)z << (31 + sh)) : rnd;
+    const int32_t init = FOLD ? 0 : corr;
+    uint32_t w[3][4];  // windows of three consecutive rows, slot = row % 3
+    windows(row(0), w[0]);
+    windows(row(1), w[1]);
 #pragma unroll
     for (int i = 0; i < kPass; ++i) {
-      if (yb + i < rpc) {  // uniform
-        const int y = y0 + yb + i;
-        windows(d[i + 2], wcur);
+      if (i < rpc) {  // uniform
+        windows(row(i + 2), w[(i + 2) % 3]);
         int32_t acc[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          int32_t a = dot4(wa[e], wrow[0], corr);
-          a = dot4(wb[e], wrow[1], a);
-          a = dot4(wcur[e], wrow[2], a);
+          int32_t a = dot4(w[i % 3][e], wrow[0], init);
+          a = dot4(w[(i + 1) % 3][e], wrow[1], a);
+          a = dot4(w[(i + 2) % 3][e], wrow[2], a);
           acc[e] = ACC16 ? (int32_t)(int16_t)a : a;
         }
-        // lanes without a strip, and rows beyond a short last quarter, store out of range
-        const uint32_t so = (lane_off != kOob && y < y1) ? (lane_off + (uint32_t)(y * W)) * kEsz : kOob;
+        const uint32_t so = so0 + (uint32_t)(i * W * kEsz);
         if constexpr (MODE == 0) {
           int32_t r[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            const int64_t pr = (int64_t)acc[e] * (int64_t)m + rnd;
-            r[e] = med3((int32_t)(pr >> (31 + sh)), lo, hi) + z;
+            const int64_t pr = (int64_t)acc[e] * (int64_t)m + k64;
+            r[e] = med3((int32_t)(pr >> (31 + sh)), lo, hi) + (FOLD ? 0 : z);
           }
-          __builtin_amdgcn_raw_buffer_store_b32(pack4_perm(r[0], r[1], r[2], r[3]), rout, so, 0, 2);
+          __builtin_amdgcn_raw_buffer_store_b32(pack4_perm(r[0], r[1], r[2], r[3]), rout, so, 0, 0);
         } else if constexpr (MODE == 1) {
           typedef int32_t v4i32 __attribute__((ext_vector_type(4)));
-          __builtin_amdgcn_raw_buffer_store_b128(v4i32{acc[0], acc[1], acc[2], acc[3]}, rout, so, 0, 2);
+          __builtin_amdgcn_raw_buffer_store_b128(v4i32{acc[0], acc[1], acc[2], acc[3]}, rout, so, 0, 0);
         } else {
           typedef uint32_t v2u32 __attribute__((ext_vector_type(2)));
           __builtin_amdgcn_raw_buffer_store_b64(
               v2u32{(uint32_t)(acc[0] & 0xffff) | ((uint32_t)acc[1] << 16),
-                    (uint32_t)(acc[2] & 0xffff) | ((uint32_t)acc[3] << 16)}, rout, so, 0, 2);
+                    (uint32_t)(acc[2] & 0xffff) | ((uint32_t)acc[3] << 16)}, rout, so, 0, 0);
         }
-#pragma unroll
-        for (int e = 0; e < 4; ++e) { wa[e] = wb[e]; wb[e] = wcur[e]; }
       }
     }
-  }
+  };
+  const bool fold = MODE == 0 && !ACC16 && sh >= 0 && sh <= 19 && corr >= -(1 << 30) && corr <= (1 << 30) &&
+                    z >= -256 && z <= 255;
+  if (fold)
+    rows.template operator()<true>();
+  else
+    rows.template operator()<false>();
 }
 
 }  // namespace
@@ -506,24 +558,26 @@ hipError_t launch_qconv_depthwise(const GemmArgs& a, const ConvGeom& cg, hipStre
   const int64_t planes = (int64_t)cg.B * cg.C;
   const int nband = (cg.H + kBandRows - 1) / kBandRows;
   const size_t wave_lds = (size_t)4 * (cg.H + 2) * rs;
-  if (plane_ok && cg.W <= 64 && wave_lds <= (size_t)kMaxLdsBytes && planes < (1ll << 32)) {
-    const size_t esz = a.has_rq ? 1 : (a.acc16 ? 2 : 4);
-    const bool vec_io = (cg.W % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.act) & 3u) == 0) &&
-                        ((reinterpret_cast<uintptr_t>(a.out) & (4 * esz - 1)) == 0);
+  const size_t esz = a.has_rq ? 1 : (a.acc16 ? 2 : 4);
+  const bool vec_io = (cg.W % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.act) & 3u) == 0) &&
+                      ((reinterpret_cast<uintptr_t>(a.out) & (4 * esz - 1)) == 0);
+  // the register kernel: bands of 4 * rpc rows, one wavefront each
+  const int32_t rpc = (cg.H + 3) / 4 < 16 ? (cg.H + 3) / 4 : 16;
+  const int64_t nband_r = (cg.H + 4 * rpc - 1) / (4 * rpc);
+  if (plane_ok && cg.W <= 64 && vec_io && (reinterpret_cast<uintptr_t>(a.wgt) & 3u) == 0 &&
+      cg.B <= 65535 && nband_r <= 65535 && (int64_t)cg.H * cg.W * 4 < (1ll << 31) &&
+      (int64_t)cg.C * 9 < (1ll << 30)) {
+    auto kern = p.out_mode == 1 ? dw_rows3x3_kernel<1, false>
+              : p.out_mode == 2 ? dw_rows3x3_kernel<2, true>
+              : p.acc16 ? dw_rows3x3_kernel<0, true> : dw_rows3x3_kernel<0, false>;
+    hipLaunchKernelGGL(kern, dim3((unsigned)((cg.C + 3) / 4), (unsigned)cg.B, (unsigned)nband_r), dim3(kThreads),
+                       0, st, p, rpc);
+  } else if (plane_ok && cg.W <= 64 && wave_lds <= (size_t)kMaxLdsBytes && planes < (1ll << 32)) {
     const uint32_t w4 = vec_io ? (uint32_t)cg.W / 4 : 1u;
     const uint32_t inv_w4 = w4 > 1 ? (uint32_t)(((1ull << 32) + w4 - 1) / w4) : 0u;  // unused for w4 == 1
-    if (vec_io && (planes + 3) / 4 < (1ll << 31) && (int64_t)cg.H * cg.W * 4 < (1ll << 31)) {
-      auto kern = p.out_mode == 1 ? dw_rows3x3_kernel<1, false>
-                : p.out_mode == 2 ? dw_rows3x3_kernel<2, true>
-                : p.acc16 ? dw_rows3x3_kernel<0, true> : dw_rows3x3_kernel<0, false>;
-      hipLaunchKernelGGL(kern, dim3((unsigned)((planes + 3) / 4)), dim3(kThreads), 0, st, p, planes);
-    } else
-      hipLaunchKernelGGL(dw_wave3x3_kernel, dim3((unsigned)((planes + 3) / 4)), dim3(kThreads),
-                         wave_lds, st, p, rs, inv_w4, vec_io ? 1 : 0, planes);
+    hipLaunchKernelGGL(dw_wave3x3_kernel, dim3((unsigned)((planes + 3) / 4)), dim3(kThreads),
+                       wave_lds, st, p, rs, inv_w4, vec_io ? 1 : 0, planes);
   } else if (plane_ok && lds_bytes <= (size_t)kMaxLdsBytes && planes * nband < (1ll << 31)) {
-    const size_t esz = a.has_rq ? 1 : (a.acc16 ? 2 : 4);
-    const bool vec_io = (cg.W % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.act) & 3u) == 0) &&
-                        ((reinterpret_cast<uintptr_t>(a.out) & (4 * esz - 1)) == 0);
     hipLaunchKernelGGL(dw_plane3x3_kernel, dim3((unsigned)(planes * nband)), dim3(kThreads),
                        lds_bytes, st, p, rs, nband, vec_io ? 1 : 0);
   } else {

@@ -294,6 +294,37 @@ def test_depthwise(case, adt, za):
     assert_same(host(got), want, f"depthwise nhwc {case}")
 
 
+@pytest.mark.parametrize("out_u8,z_out", [(False, 0), (False, -7), (True, 131)])
+@pytest.mark.parametrize("with_bias", [True, False])
+def test_depthwise_requant_constant_ranges(out_u8, z_out, with_bias):
+    """The register kernel folds a channel's bias term, rounding term and output zero point into one 64-bit
+    constant when they are small enough and takes its general form otherwise; both kinds of channel, and the
+    bounds between them, in one launch."""
+    B, C, H, W = 2, 12, 23, 24
+    rng = np.random.default_rng(77 + z_out)
+    a = rnd_act(rng, (B, C, H, W), np.uint8)
+    w = rnd_w(rng, (C, 1, 3, 3))
+    bias = rng.integers(-5000, 5000, C).astype(np.int64)
+    bias[4], bias[5], bias[6], bias[7] = 2 ** 30 + 12345, -(2 ** 30) - 999, 2 ** 31 - 1, -(2 ** 31)
+    bias[10], bias[11] = 2 ** 30 - 200000, -(2 ** 30) + 200000
+    bias = bias.astype(np.int32)
+    shift = np.array([0, 1, 5, 19, 20, 31, 3, 3, 19, 20, 30, 30], np.int32)
+    mult = rng.integers(2 ** 30, 2 ** 31, size=C).astype(np.int32)
+    a_t, w_t = act_qtype(a, 128), hago.QType(hago.I8)
+    b_ref, b_gpu = (bias, dev(bias)) if with_bias else (None, None)
+    want = ref.qconv2d(a, 128, w, b_ref, ref.NCHW, (1, 1), (1, 1), C, ref.I32, ref_requant(mult, shift, out_u8, z_out))
+    got = hago.qconv2d(dev(a), a_t, dev(w), w_t, b_gpu, hago.NCHW, (1, 1), (1, 1), C, hago.I32,
+                       gpu_requant(mult, shift, out_u8, z_out))
+    assert_same(host(got), want, "depthwise per-channel")
+    assert len(np.unique(want)) > 50
+    # one multiplier and shift for the whole tensor
+    want = ref.qconv2d(a, 128, w, b_ref, ref.NCHW, (1, 1), (1, 1), C, ref.I32,
+                       ref_requant(mult[:1], np.array([9], np.int32), out_u8, z_out))
+    got = hago.qconv2d(dev(a), a_t, dev(w), w_t, b_gpu, hago.NCHW, (1, 1), (1, 1), C, hago.I32,
+                       gpu_requant(mult[:1], np.array([9], np.int32), out_u8, z_out))
+    assert_same(host(got), want, "depthwise per-tensor")
+
+
 def test_empty_inputs_are_a_no_op():
     a = torch.empty((0, 16), dtype=torch.uint8, device=DEV)
     w = torch.zeros((8, 16), dtype=torch.int8, device=DEV)
