@@ -170,6 +170,14 @@ def quantize(x, scale, zero_point, clip_lo, clip_hi, per_channel=None):
     return q
 
 
+def simquant_codes(x, scale, zero_point, clip_lo, clip_hi, per_channel=None):
+    """simulated_quantize that also hands out the integer codes it passes through (Sec. 6.1: the
+    realized graph keeps q, the simulated graph keeps q * s; Eq. 3).  By definition the pair
+    (simquant(x), quantize(x)): a NaN stays NaN in y and takes the code of real zero in q."""
+    return (simquant(x, scale, zero_point, clip_lo, clip_hi, per_channel),
+            quantize(x, scale, zero_point, clip_lo, clip_hi, per_channel))
+
+
 def dequantize(q, scale, zero_point, per_channel=None):
     """q: integer codes [outer, channels, inner] -> float32."""
     q = np.ascontiguousarray(q, dtype=np.int32)

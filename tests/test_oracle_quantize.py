@@ -83,3 +83,18 @@ def test_monotone_and_idempotent_codes(ref):
     assert np.all(np.diff(q) >= 0)
     y = ref.dequantize(q.reshape(1, 1, -1), [np.float32(0.02)], [3])
     assert np.array_equal(ref.quantize(y, [np.float32(0.02)], [3], -128, 127).reshape(-1), q)
+
+
+def test_simquant_codes_pair(ref):
+    """The variant of simulated_quantize that also emits its codes: on the hand-worked vectors the
+    codes are the golden ones, and y is q * s recomputed here in exact arithmetic (NaN aside)."""
+    rows = read_golden("quantize_codes.txt")
+    for x, s, z, lo, hi, want in rows:
+        y, q = ref.simquant_codes(np.float32(x).reshape(1, 1, 1), [np.float32(s)], [int(z)], int(lo), int(hi))
+        assert int(q.reshape(-1)[0]) == int(want)
+        exact = np.float32(float(Fraction(int(want) - int(z)) * Fraction(float(np.float32(s)))))
+        assert y.reshape(-1)[0].tobytes() == exact.tobytes(), (x, s, z, y, exact)
+    x = np.array([np.nan, 1.0, -np.inf], np.float32).reshape(1, 1, -1)
+    y, q = ref.simquant_codes(x, [np.float32(0.5)], [3], -8, 7)
+    assert np.isnan(y.reshape(-1)[0]) and q.reshape(-1).tolist() == [3, 5, -8]
+    assert y.reshape(-1)[1:].tolist() == [1.0, -5.5]
