@@ -290,7 +290,7 @@ def extra_ops(torch, hago, datagen, to_dev, rq_of, event_time_ms, only):
         del f
 
     # ---- quantize / dequantize of the same tensor (int8 codes)
-    if want("quantize_c4") or want("dequantize_c4"):
+    if want("quantize_c4") or want("dequantize_c4") or want("simquant_codes_c4"):
         c = datagen.config4_simquant()
         x0 = to_dev(c["x"].reshape(32, 144, -1))
         scale, zp = to_dev(c["scale"]), to_dev(c["zp"])
@@ -300,6 +300,11 @@ def extra_ops(torch, hago, datagen, to_dev, rq_of, event_time_ms, only):
             f = rotating(lambda i: hago.quantize(x0.clone(), scale, zp, q, prepare=True), nb)
             record("quantize_c4", event_time_ms(f, 60, 6), bytes_=nb, bound="hbm",
                    note="fp32 [32,144,56,56] -> int8 codes, 5 B/elem")
+            del f
+        if want("simquant_codes_c4"):
+            f = rotating(lambda i: hago.simquant_codes(x0.clone(), scale, zp, q, prepare=True), x0.numel() * 9)
+            record("simquant_codes_c4", event_time_ms(f, 60, 6), bytes_=x0.numel() * 9, bound="hbm",
+                   note="fp32 [32,144,56,56] -> fp32 + int8 codes in one pass, 9 B/elem")
             del f
         if want("dequantize_c4"):
             codes0 = hago.quantize(x0, scale, zp, q)

@@ -12,6 +12,7 @@
  *   hago_simquant_batched -- several candidate settings over one tensor (Sec. 6.3)
  *   hago_absmax     -- max-abs calibration thresholds (Eq. 2)
  *   hago_quantize, hago_dequantize -- fp32 <-> integer codes (Sec. 6.1; Eq. 3)
+ *   hago_simquant_codes -- simulated_quantize plus its integer codes, one pass
  *
  * Conventions common to every call
  *   - Pointers marked "device" are GPU addresses valid on the current HIP
@@ -213,6 +214,22 @@ hago_status hago_dequantize(const void* q, hago_qtype qt, float* y,
                             int64_t outer, int64_t channels, int64_t inner,
                             const float* scale, const int32_t* zero_point,
                             int32_t per_channel, void* stream);
+
+/*
+ * simulated_quantize that also emits the integer codes it passes through
+ * (Sec. 6.1: realization replaces simulated_quantize by operators on q, so the
+ * codes are what the realized graph carries where the simulated graph carries
+ * q * s; Eq. 3).  One pass over x: y = hago_simquant(x) and q = hago_quantize(x)
+ * with the same arguments, bit for bit (a NaN stays NaN in y and takes the
+ * code of real zero in q).  x, y: device fp32 [outer, channels, inner]; q:
+ * device, container qt.dtype, same shape; none of them may overlap.
+ * Errors as for hago_quantize.  Empty tensors are a no-op.
+ */
+hago_status hago_simquant_codes(const float* x, float* y, void* q,
+                                int64_t outer, int64_t channels, int64_t inner,
+                                const float* scale, const int32_t* zero_point,
+                                int32_t per_channel, hago_qtype qt,
+                                int32_t clip_lo, int32_t clip_hi, void* stream);
 
 /*
  * Max-abs calibration (Sec. 2, Eq. 2: threshold = max |x|; Sec. 5.1 statistics

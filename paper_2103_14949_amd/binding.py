@@ -16,7 +16,7 @@ STRICT_ACC16 = 1
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libhago.so")
 
-EXPORTS = ("hago_simquant", "hago_simquant_batched", "hago_absmax", "hago_quantize", "hago_dequantize", "hago_qdense", "hago_qconv2d", "hago_requantize", "hago_status_string")
+EXPORTS = ("hago_simquant", "hago_simquant_batched", "hago_absmax", "hago_quantize", "hago_dequantize", "hago_simquant_codes", "hago_qdense", "hago_qconv2d", "hago_requantize", "hago_status_string")
 
 
 class _QType(C.Structure):
@@ -60,6 +60,8 @@ def lib():
         L.hago_simquant_batched.argtypes = [vp, vp, i64, i64, i64, i32, vp, vp, i32, _QType, vp, vp, vp]
         L.hago_quantize.restype = i32
         L.hago_quantize.argtypes = [vp, vp, i64, i64, i64, vp, vp, i32, _QType, i32, i32, vp]
+        L.hago_simquant_codes.restype = i32
+        L.hago_simquant_codes.argtypes = [vp, vp, vp, i64, i64, i64, vp, vp, i32, _QType, i32, i32, vp]
         L.hago_dequantize.restype = i32
         L.hago_dequantize.argtypes = [vp, _QType, vp, i64, i64, i64, vp, vp, i32, vp]
         L.hago_absmax.restype = i32
@@ -210,6 +212,27 @@ def quantize(x, scale, zero_point, q: QType, clip_lo=None, clip_hi=None, per_cha
         return Prepared(lib().hago_quantize, args, (x, codes, scale, zero_point), codes)
     _check(lib().hago_quantize(*args))
     return codes
+
+
+def simquant_codes(x, scale, zero_point, q: QType, clip_lo=None, clip_hi=None, per_channel=None, out=None,
+                   out_codes=None, prepare=False):
+    """hago_simquant_codes over x[outer, channels, inner] (fp32): (simulated-quantized fp32, integer codes)."""
+    assert x.dim() == 3 and x.is_contiguous()
+    outer, channels, inner = x.shape
+    lo, hi = ((-(1 << (q.bits - 1)), (1 << (q.bits - 1)) - 1) if q.is_signed else (0, (1 << q.bits) - 1))
+    clip_lo = lo if clip_lo is None else clip_lo
+    clip_hi = hi if clip_hi is None else clip_hi
+    pc = int(scale.numel() > 1) if per_channel is None else int(per_channel)
+    t = _torch()
+    y = t.empty_like(x) if out is None else out
+    codes = (t.empty(x.shape, dtype=getattr(t, _TORCH_OF[q.dtype]), device=x.device)
+             if out_codes is None else out_codes)
+    args = (_ptr(x), _ptr(y), _ptr(codes), outer, channels, inner, _ptr(scale), _ptr(zero_point), pc, q.c(),
+            int(clip_lo), int(clip_hi), _stream())
+    if prepare:
+        return Prepared(lib().hago_simquant_codes, args, (x, y, codes, scale, zero_point), (y, codes))
+    _check(lib().hago_simquant_codes(*args))
+    return y, codes
 
 
 def dequantize(codes, q: QType, scale, zero_point, per_channel=None, out=None, prepare=False):

@@ -222,7 +222,24 @@ hago_status hago_quantize(const float* x, void* q, int64_t outer, int64_t channe
   if (clip_lo > clip_hi || clip_lo < blo || clip_hi > bhi) return HAGO_ERR_BITS;
   // codes are formed in binary32
   if (clip_lo < -(1 << 24) || clip_hi > (1 << 24)) return HAGO_ERR_BITS;
-  return from_hip(hago::launch_quant(x, q, container, 0, outer, channels, inner, scale, zero_point,
+  return from_hip(hago::launch_quant(x, q, nullptr, container, 0, outer, channels, inner, scale, zero_point,
+                                     per_channel, clip_lo, clip_hi, static_cast<hipStream_t>(stream)));
+}
+
+hago_status hago_simquant_codes(const float* x, float* y, void* q, int64_t outer, int64_t channels,
+                                int64_t inner, const float* scale, const int32_t* zero_point,
+                                int32_t per_channel, hago_qtype qt, int32_t clip_lo, int32_t clip_hi,
+                                void* stream) {
+  int container = 0;
+  hago_status s = check_quant(qt, per_channel, outer, channels, inner, scale, zero_point, &container);
+  if (s != HAGO_OK) return s;
+  const bool empty = outer == 0 || channels == 0 || inner == 0;
+  if ((!x || !y || !q) && !empty) return HAGO_ERR_NULL;
+  int64_t blo, bhi;
+  bit_range(qt.bits, qt.is_signed != 0, &blo, &bhi);
+  if (clip_lo > clip_hi || clip_lo < blo || clip_hi > bhi) return HAGO_ERR_BITS;
+  if (clip_lo < -(1 << 24) || clip_hi > (1 << 24)) return HAGO_ERR_BITS;
+  return from_hip(hago::launch_quant(x, q, y, container, 2, outer, channels, inner, scale, zero_point,
                                      per_channel, clip_lo, clip_hi, static_cast<hipStream_t>(stream)));
 }
 
@@ -234,7 +251,7 @@ hago_status hago_dequantize(const void* q, hago_qtype qt, float* y, int64_t oute
   if (s != HAGO_OK) return s;
   const bool empty = outer == 0 || channels == 0 || inner == 0;
   if ((!q || !y) && !empty) return HAGO_ERR_NULL;
-  return from_hip(hago::launch_quant(q, y, container, 1, outer, channels, inner, scale, zero_point,
+  return from_hip(hago::launch_quant(q, y, nullptr, container, 1, outer, channels, inner, scale, zero_point,
                                      per_channel, 0, 0, static_cast<hipStream_t>(stream)));
 }
 

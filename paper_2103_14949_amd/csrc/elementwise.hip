@@ -286,10 +286,11 @@ __device__ __forceinline__ void unpack_codes(typename QVec<Q>::T v, int32_t (&q)
   }
 }
 
-// Row kernels as for simulated_quantize; DEQ: codes -> fp32, else fp32 -> codes.
-template <typename Q, bool DEQ, int U>
+// Row kernels as for simulated_quantize.  OP 0: fp32 -> codes; 1: codes -> fp32; 2: fp32 -> codes
+// (out) and the simulated_quantize value (out2) in one pass over x.
+template <typename Q, int OP, int U>
 __global__ __launch_bounds__(kThreads) void quant_rows_kernel(
-    const void* __restrict__ in, void* __restrict__ out, int64_t rows, int32_t channels,
+    const void* __restrict__ in, void* __restrict__ out, float* __restrict__ out2, int64_t rows, int32_t channels,
     int64_t inner_vec, int32_t nseg, int32_t seg_len, const float* __restrict__ scale,
     const int32_t* __restrict__ zp, int per_channel, float lo, float hi) {
   using VQ = typename QVec<Q>::T;
@@ -302,7 +303,7 @@ __global__ __launch_bounds__(kThreads) void quant_rows_kernel(
     const int64_t v0 = (int64_t)seg * seg_len;
     const int64_t v1 = (v0 + seg_len < inner_vec) ? v0 + seg_len : inner_vec;
     for (int64_t vb = v0 + threadIdx.x; vb < v1; vb += (int64_t)kThreads * U) {
-      if constexpr (DEQ) {
+      if constexpr (OP == 1) {
         const VQ* qr = static_cast<const VQ*>(in) + row * inner_vec;
         v4f* yr = static_cast<v4f*>(out) + row * inner_vec;
         VQ a[U];
@@ -332,6 +333,11 @@ __global__ __launch_bounds__(kThreads) void quant_rows_kernel(
             const VQ r = pack_codes<Q>(quantize_one(a[u].x, s, zf, lo, hi), quantize_one(a[u].y, s, zf, lo, hi),
                                        quantize_one(a[u].z, s, zf, lo, hi), quantize_one(a[u].w, s, zf, lo, hi));
             __builtin_nontemporal_store(r, qr + vb + u * kThreads);
+            if constexpr (OP == 2) {
+              const v4f y = {simquant_one(a[u].x, s, zf, lo, hi), simquant_one(a[u].y, s, zf, lo, hi),
+                             simquant_one(a[u].z, s, zf, lo, hi), simquant_one(a[u].w, s, zf, lo, hi)};
+              __builtin_nontemporal_store(y, reinterpret_cast<v4f*>(out2) + row * inner_vec + vb + u * kThreads);
+            }
           }
         }
       }
@@ -339,18 +345,21 @@ __global__ __launch_bounds__(kThreads) void quant_rows_kernel(
   }
 }
 
-template <typename Q, bool DEQ>
+template <typename Q, int OP>
 __global__ __launch_bounds__(kThreads) void quant_flat_kernel(
-    const void* __restrict__ in, void* __restrict__ out, int64_t total, int64_t inner,
+    const void* __restrict__ in, void* __restrict__ out, float* __restrict__ out2, int64_t total, int64_t inner,
     int64_t channels, const float* __restrict__ scale, const int32_t* __restrict__ zp,
     int per_channel, float lo, float hi) {
   const int64_t stride = (int64_t)gridDim.x * kThreads;
   for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += stride) {
     const int64_t c = per_channel ? (i / inner) % channels : 0;
-    if constexpr (DEQ)
+    if constexpr (OP == 1) {
       static_cast<float*>(out)[i] = dequantize_one((int32_t)static_cast<const Q*>(in)[i], scale[c], (float)zp[c]);
-    else
-      static_cast<Q*>(out)[i] = (Q)quantize_one(static_cast<const float*>(in)[i], scale[c], (float)zp[c], lo, hi);
+    } else {
+      const float x = static_cast<const float*>(in)[i];
+      static_cast<Q*>(out)[i] = (Q)quantize_one(x, scale[c], (float)zp[c], lo, hi);
+      if constexpr (OP == 2) out2[i] = simquant_one(x, scale[c], (float)zp[c], lo, hi);
+    }
   }
 }
 
@@ -505,8 +514,8 @@ hipError_t launch_simquant_batched(const float* x, float* y, int64_t outer, int6
   return hipGetLastError();
 }
 
-template <typename Q, bool DEQ>
-static hipError_t launch_quant_t(const void* in, void* out, int64_t outer, int64_t channels,
+template <typename Q, int OP>
+static hipError_t launch_quant_t(const void* in, void* out, float* out2, int64_t outer, int64_t channels,
                                  int64_t inner, const float* scale, const int32_t* zp,
                                  int per_channel, int32_t clip_lo, int32_t clip_hi, hipStream_t st) {
   const int64_t total = outer * channels * inner;
@@ -514,31 +523,34 @@ static hipError_t launch_quant_t(const void* in, void* out, int64_t outer, int64
   const float lo = (float)clip_lo, hi = (float)clip_hi;
   const int64_t rows = per_channel ? outer * channels : 1;
   const int64_t row_len = per_channel ? inner : total;
-  if (row_len % 4 == 0 && row_len >= 512 && aligned16(in) && aligned16(out)) {
+  if (row_len % 4 == 0 && row_len >= 512 && aligned16(in) && aligned16(out) && aligned16(out2)) {
     const int64_t inner_vec = row_len / 4;
     int32_t nseg, seg_len;
     split_row(inner_vec, kVecPerLane, &nseg, &seg_len);
-    hipLaunchKernelGGL((quant_rows_kernel<Q, DEQ, kVecPerLane>), dim3(grid_for(rows * nseg)),
-                       dim3(kThreads), 0, st, in, out, rows, (int32_t)(per_channel ? channels : 1),
+    hipLaunchKernelGGL((quant_rows_kernel<Q, OP, kVecPerLane>), dim3(grid_for(rows * nseg)),
+                       dim3(kThreads), 0, st, in, out, out2, rows, (int32_t)(per_channel ? channels : 1),
                        inner_vec, nseg, seg_len, scale, zp, per_channel, lo, hi);
   } else {
-    hipLaunchKernelGGL((quant_flat_kernel<Q, DEQ>), dim3(grid_for((total + kThreads - 1) / kThreads)),
-                       dim3(kThreads), 0, st, in, out, total, inner, channels, scale, zp, per_channel,
+    hipLaunchKernelGGL((quant_flat_kernel<Q, OP>), dim3(grid_for((total + kThreads - 1) / kThreads)),
+                       dim3(kThreads), 0, st, in, out, out2, total, inner, channels, scale, zp, per_channel,
                        lo, hi);
   }
   return hipGetLastError();
 }
 
-// container: 0 int8, 1 uint8, 2 int16, 3 int32.  deq != 0: codes -> fp32.
-hipError_t launch_quant(const void* in, void* out, int container, int deq, int64_t outer,
+// container: 0 int8, 1 uint8, 2 int16, 3 int32.  op 0: fp32 -> codes; 1: codes -> fp32;
+// 2: fp32 -> codes and the simulated_quantize value (out2).
+hipError_t launch_quant(const void* in, void* out, float* out2, int container, int op, int64_t outer,
                         int64_t channels, int64_t inner, const float* scale, const int32_t* zp,
                         int per_channel, int32_t clip_lo, int32_t clip_hi, hipStream_t st) {
 #define HAGO_QUANT_CASE(ID, T)                                                                       \
   case ID:                                                                                           \
-    return deq ? launch_quant_t<T, true>(in, out, outer, channels, inner, scale, zp, per_channel,    \
-                                         clip_lo, clip_hi, st)                                       \
-               : launch_quant_t<T, false>(in, out, outer, channels, inner, scale, zp, per_channel,   \
-                                          clip_lo, clip_hi, st);
+    return op == 1 ? launch_quant_t<T, 1>(in, out, nullptr, outer, channels, inner, scale, zp,       \
+                                          per_channel, clip_lo, clip_hi, st)                         \
+         : op == 2 ? launch_quant_t<T, 2>(in, out, out2, outer, channels, inner, scale, zp,          \
+                                          per_channel, clip_lo, clip_hi, st)                         \
+                   : launch_quant_t<T, 0>(in, out, nullptr, outer, channels, inner, scale, zp,       \
+                                          per_channel, clip_lo, clip_hi, st);
   switch (container) {
     HAGO_QUANT_CASE(0, int8_t)
     HAGO_QUANT_CASE(1, uint8_t)

@@ -27,9 +27,10 @@ hipError_t launch_simquant_batched(const float* x, float* y, int64_t outer, int6
                                    const int32_t* zp, int per_channel, const int32_t* clip_lo,
                                    const int32_t* clip_hi, hipStream_t st);
 
-// quantize (fp32 -> codes) / dequantize (codes -> fp32) over [outer, channels, inner].
+// op 0: quantize (fp32 -> codes), 1: dequantize (codes -> fp32), 2: quantize plus the
+// simulated_quantize value into out2, over [outer, channels, inner].
 // container: 0 int8, 1 uint8, 2 int16, 3 int32.
-hipError_t launch_quant(const void* in, void* out, int container, int deq, int64_t outer,
+hipError_t launch_quant(const void* in, void* out, float* out2, int container, int op, int64_t outer,
                         int64_t channels, int64_t inner, const float* scale, const int32_t* zp,
                         int per_channel, int32_t clip_lo, int32_t clip_hi, hipStream_t st);
 

@@ -24,7 +24,7 @@ def test_every_declared_symbol_is_exported(L):
     header = open(os.path.join(ROOT, "include", "hago.h")).read()
     declared = set(re.findall(r"\b(hago_[a-z0-9_]+)\s*\(", header))
     assert {"hago_simquant", "hago_qdense", "hago_qconv2d", "hago_requantize", "hago_absmax",
-            "hago_quantize", "hago_dequantize", "hago_simquant_batched",
+            "hago_quantize", "hago_dequantize", "hago_simquant_codes", "hago_simquant_batched",
             "hago_status_string"} <= declared
     for name in declared:
         assert hasattr(L, name), name
@@ -121,6 +121,14 @@ def test_quantize_and_dequantize_argument_errors(L):
     assert qz(BAD, BAD, 1, 1, 1, BAD, BAD, 0, q, -129, 127, None) == 4
     assert qz(BAD, BAD, 1, 1, 1, BAD, BAD, 0, _qt(hago.I32, 32), -2 ** 31, 2 ** 31 - 1, None) == 4
     assert qz(BAD, BAD, 1, 1, 1, BAD, BAD, 3, q, -128, 127, None) == 5
+    sc = lambda *a: L.hago_simquant_codes(*a)  # noqa: E731
+    assert sc(BAD, None, BAD, 1, 1, 1, BAD, BAD, 0, q, -128, 127, None) == 1
+    assert sc(BAD, BAD, None, 1, 1, 1, BAD, BAD, 0, q, -128, 127, None) == 1
+    assert sc(BAD, BAD, BAD, -1, 1, 1, BAD, BAD, 0, q, -128, 127, None) == 2
+    assert sc(BAD, BAD, BAD, 1, 1, 1, BAD, BAD, 0, _qt(hago.F32), -128, 127, None) == 3
+    assert sc(BAD, BAD, BAD, 1, 1, 1, BAD, BAD, 0, q, -128, 128, None) == 4
+    assert sc(BAD, BAD, BAD, 1, 1, 1, BAD, BAD, 2, q, -128, 127, None) == 5
+    assert sc(None, None, None, 0, 4, 4, BAD, BAD, 0, q, -128, 127, None) == 0   # empty: a no-op
     dq = lambda *a: L.hago_dequantize(*a)  # noqa: E731
     assert dq(None, q, BAD, 1, 1, 1, BAD, BAD, 0, None) == 1
     assert dq(BAD, q, None, 1, 1, 1, BAD, BAD, 0, None) == 1

@@ -150,6 +150,13 @@ def test_quantize_dequantize_shapes(shape, qt, per_channel):
     finite = ~np.isnan(x)
     sq = host(hago.simquant(dev(x), dev(scale), dev(zp), q, lo, hi, per_channel))
     assert np.array_equal(host(y).view(np.uint32)[finite], sq.view(np.uint32)[finite])
+    # the one-pass variant: simulated_quantize's value and its codes together
+    want_y, want_q = ref.simquant_codes(x, scale, zp, lo, hi, per_channel)
+    y2, q2 = hago.simquant_codes(dev(x), dev(scale), dev(zp), q, lo, hi, per_channel)
+    assert q2.dtype == got.dtype
+    assert_same(host(q2).astype(np.int64), want_q.astype(np.int64), f"simquant_codes codes {shape}")
+    assert np.array_equal(np.isnan(host(y2)), np.isnan(want_y))
+    assert np.array_equal(host(y2).view(np.uint32)[finite], want_y.view(np.uint32)[finite])
 
 
 def test_quantize_config4_full_size():
@@ -160,6 +167,9 @@ def test_quantize_config4_full_size():
     assert_same(host(got).astype(np.int32), want, "config 4 quantize")
     y = hago.dequantize(got, hago.QType(hago.I8), dev(c["scale"]), dev(c["zp"]))
     assert_same_bits(host(y), ref.simquant(x, c["scale"], c["zp"], *c["clip"]), "config 4 round trip")
+    y2, q2 = hago.simquant_codes(dev(x), dev(c["scale"]), dev(c["zp"]), hago.QType(hago.I8), *c["clip"])
+    assert_same(host(q2).astype(np.int32), want, "config 4 simquant_codes codes")
+    assert_same_bits(host(y2), host(y), "config 4 simquant_codes values")
 
 
 AM_SHAPES = [(1, 1, 1), (3, 5, 7), (2, 4, 512), (2, 3, 516), (64, 128, 1), (33, 52, 1), (4, 6, 2048),
