@@ -178,11 +178,155 @@ __global__ __launch_bounds__(256) void pw_nchw_kernel(PwArgs p) {
   }
 }
 
+// N <= 32: a wavefront owns 128 consecutive pixels of one image, as four MFMA row tiles.
+// Lane (i, h) loads, for each of its 16 channels (k-half h), the dword of pixels 4i .. 4i+3:
+// consecutive lanes read consecutive dwords, so a load instruction covers 128 contiguous bytes
+// of a channel (two channels per instruction) and every byte is fetched once.  Four 4x4 byte
+// transposes inside the lane (eight byte permutes each, no lane exchange) turn the 16 dwords
+// into the 16 k-bytes of each of the lane's four pixels, and pixel 4i + j becomes row i of row
+// tile j: four MFMAs share one weight operand.  On the way out lane (n, h) then holds, for its
+// output channel, registers (g, e) of tile j = pixel 4 * (8g + 4h + e) + j: the four tiles pack
+// into one dword and the four e into 16 contiguous bytes, so a store instruction writes 32
+// contiguous bytes of each channel.
+template <int MODE, bool ACC16>
+__global__ __launch_bounds__(64) void pw_nchw_quad_kernel(PwArgs p) {
+  const int lane = threadIdx.x;
+  const int64_t tile = blockIdx.x;
+  const int b = (int)(tile / p.tiles_per_img);
+  const int pix0 = (int)(tile - (int64_t)b * p.tiles_per_img) * 128;
+  const int i = lane & 31, h = lane >> 5;
+  const int C = p.C, HW = p.HW, N = p.N;
+
+  const __amdgpu_buffer_rsrc_t rin = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint8_t*>(p.act) + (int64_t)b * C * HW, 0, C * HW, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<int8_t*>(p.wgt), 0, N * C, 0x00020000);
+  // the lane's four pixels (H * W % 4 == 0: all inside the image or all outside); + channel * HW
+  const uint32_t a_lane = (pix0 + 4 * i < HW) ? (uint32_t)(pix0 + 4 * i) : kOob;
+  const uint32_t w_lane = (i < N) ? (uint32_t)(i * C) : kOob;  // + k
+
+  // the lane's output channel: requantize parameters (used at the very end)
+  int32_t bias_r = 0, mult_r = 0, shift_r = 0;
+  if (i < N) {
+    if (p.bias) bias_r = p.bias[i];
+    if (MODE == 0) {
+      mult_r = p.mult[p.per_channel ? i : 0];
+      shift_r = p.shift[p.per_channel ? i : 0];
+    }
+  }
+
+  v16i acc[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[j][r] = 0;
+  int32_t wsum = 0;
+  constexpr int kChunk = 5;  // k-steps (32 channels each) whose loads are in flight together
+  const int ksteps = (C + 31) >> 5;
+  // FULL: all kChunk steps exist, so the code has no branches and the compiler waits for each
+  // step's loads separately (the first MFMAs run while later steps are still arriving)
+  auto chunk = [&]<bool FULL>(int s0) {
+    uint32_t ab[kChunk][16];
+    v4i wb[kChunk];
+#pragma unroll
+    for (int u = 0; u < kChunk; ++u) {
+      if (FULL || s0 + u < ksteps) {  // uniform
+        const int k = (s0 + u) * 32 + 16 * h;  // first channel of this lane's 16 (C % 16 == 0)
+        const bool kok = k < C;
+        const uint32_t a0 = (kok && a_lane != kOob) ? a_lane + (uint32_t)(k * HW) : kOob;
+#pragma unroll
+        for (int d = 0; d < 16; ++d)  // channel k + d, four pixels (an out-of-range base stays out of range)
+          ab[u][d] = __builtin_amdgcn_raw_buffer_load_b32(rin, a0 + (a0 != kOob ? (uint32_t)(d * HW) : 0u), 0, 0);
+        wb[u] = __builtin_amdgcn_raw_buffer_load_b128(
+            rw, (kok && w_lane != kOob) ? w_lane + (uint32_t)k : kOob, 0, 0);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kChunk; ++u) {
+      if (FULL || s0 + u < ksteps) {  // uniform
+        v4i af[4];
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+          // rows a..d = channels 4m .. 4m+3, bytes = pixels 0..3  ->  rows = pixels, bytes = channels
+          const uint32_t a = ab[u][4 * m], bq = ab[u][4 * m + 1], c = ab[u][4 * m + 2], d = ab[u][4 * m + 3];
+          const uint32_t t0 = __builtin_amdgcn_perm(bq, a, 0x05010400u);  // a0 b0 a1 b1
+          const uint32_t t1 = __builtin_amdgcn_perm(bq, a, 0x07030602u);  // a2 b2 a3 b3
+          const uint32_t t2 = __builtin_amdgcn_perm(d, c, 0x05010400u);   // c0 d0 c1 d1
+          const uint32_t t3 = __builtin_amdgcn_perm(d, c, 0x07030602u);   // c2 d2 c3 d3
+          af[0][m] = (int)(__builtin_amdgcn_perm(t2, t0, 0x05040100u) ^ p.act_xor4);
+          af[1][m] = (int)(__builtin_amdgcn_perm(t2, t0, 0x07060302u) ^ p.act_xor4);
+          af[2][m] = (int)(__builtin_amdgcn_perm(t3, t1, 0x05040100u) ^ p.act_xor4);
+          af[3][m] = (int)(__builtin_amdgcn_perm(t3, t1, 0x07060302u) ^ p.act_xor4);
+        }
+#pragma unroll
+        for (int d = 0; d < 4; ++d) wsum = __builtin_amdgcn_sdot4(wb[u][d], 0x01010101, wsum, false);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[j], wb[u], acc[j], 0, 0, 0);
+      }
+    }
+  };
+  for (int s0 = 0; s0 < ksteps; s0 += kChunk) {
+    if (s0 + kChunk <= ksteps)
+      chunk.template operator()<true>(s0);
+    else
+      chunk.template operator()<false>(s0);
+  }
+
+  const RequantScalars rs = p.rs;
+  constexpr int kEsz = MODE == 0 ? 1 : (MODE == 1 ? 4 : 2);
+  const int n = i;
+  const int32_t ws = wsum + __shfl_xor(wsum, 32);  // the two k-halves of the row sums
+  const int32_t corr = bias_r + p.corr_coef * ws;
+  const int64_t rnd = (int64_t)1 << (30 + shift_r);
+  uint8_t* orow = static_cast<uint8_t*>(p.out) + ((int64_t)b * N + n) * HW * kEsz;
+  const bool vec16 = (HW & 15) == 0 && (reinterpret_cast<uintptr_t>(p.out) & 15u) == 0;
+#pragma unroll
+  for (int g = 0; g < 4; ++g) {
+    uint32_t dw[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int pq = pix0 + 4 * (8 * g + 4 * h + e);  // first of the four pixels; HW % 4 == 0
+      int32_t v[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        v[j] = acc[j][4 * g + e] + corr;
+        if (ACC16) v[j] = (int32_t)(int16_t)v[j];
+      }
+      if constexpr (MODE == 0) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int64_t pr = (int64_t)v[j] * (int64_t)mult_r + rnd;
+          v[j] = med3((int32_t)(pr >> (31 + shift_r)), rs.lo_rel, rs.hi_rel) + rs.z_out;
+        }
+        dw[e] = pack4_perm(v[0], v[1], v[2], v[3]);
+        if (!vec16 && n < N && pq < HW) *reinterpret_cast<uint32_t*>(orow + pq) = dw[e];
+      } else if constexpr (MODE == 1) {
+        if (n < N && pq < HW) *reinterpret_cast<int4*>(orow + (int64_t)pq * 4) = make_int4(v[0], v[1], v[2], v[3]);
+      } else {
+        if (n < N && pq < HW)
+          *reinterpret_cast<short4*>(orow + (int64_t)pq * 2) =
+              make_short4((short)v[0], (short)v[1], (short)v[2], (short)v[3]);
+      }
+    }
+    if constexpr (MODE == 0) {
+      const int pg = pix0 + 32 * g + 16 * h;  // HW % 16 == 0: the 16 pixels are inside the image or outside
+      if (vec16 && n < N && pg < HW)
+        *reinterpret_cast<uint4*>(orow + pg) = make_uint4(dw[0], dw[1], dw[2], dw[3]);
+    }
+  }
+}
+
 template <int MODE, bool ACC16>
 hipError_t launch_nt(const PwArgs& p, hipStream_t st) {
+  if (p.N <= 32) {  // 128 pixels per wavefront, one wavefront per workgroup
+    PwArgs q = p;
+    q.tiles_per_img = (p.HW + 127) / 128;
+    q.tiles = (int64_t)p.B * q.tiles_per_img;  // < 2^31: B and H*W are 32-bit and B * H*W fits the tensor
+    hipLaunchKernelGGL((pw_nchw_quad_kernel<MODE, ACC16>), dim3((unsigned)q.tiles), dim3(64), 0, st, q);
+    return hipGetLastError();
+  }
   const unsigned grid = (unsigned)((p.tiles + 3) / 4);
-  if (p.N <= 32) hipLaunchKernelGGL((pw_nchw_kernel<MODE, ACC16, 1>), dim3(grid), dim3(256), 0, st, p);
-  else if (p.N <= 64) hipLaunchKernelGGL((pw_nchw_kernel<MODE, ACC16, 2>), dim3(grid), dim3(256), 0, st, p);
+  if (p.N <= 64) hipLaunchKernelGGL((pw_nchw_kernel<MODE, ACC16, 2>), dim3(grid), dim3(256), 0, st, p);
   else hipLaunchKernelGGL((pw_nchw_kernel<MODE, ACC16, 4>), dim3(grid), dim3(256), 0, st, p);
   return hipGetLastError();
 }

@@ -177,6 +177,8 @@ POINTWISE_CASES = [
     # B C H W O: 1x1 stride-1 unpadded NCHW convolutions with C % 16 == 0 and H*W % 4 == 0 (the
     # direct kernel): partial pixel tiles, one / two / four channel tiles per wavefront
     (2, 16, 6, 6, 5), (1, 48, 5, 8, 33), (3, 32, 10, 10, 70), (1, 160, 4, 7, 128), (2, 208, 16, 12, 24),
+    # up to 32 output channels: 128 pixels per wavefront, 16-byte stores when H*W % 16 == 0
+    (1, 144, 28, 28, 24), (2, 32, 9, 16, 32), (1, 16, 2, 2, 1), (1, 336, 13, 12, 17),
 ]
 
 
