@@ -280,40 +280,58 @@ __global__ __launch_bounds__(64) void pw_nchw_quad_kernel(PwArgs p) {
   const int64_t rnd = (int64_t)1 << (30 + shift_r);
   uint8_t* orow = static_cast<uint8_t*>(p.out) + ((int64_t)b * N + n) * HW * kEsz;
   const bool vec16 = (HW & 15) == 0 && (reinterpret_cast<uintptr_t>(p.out) & 15u) == 0;
+  // FOLD (requantized, 32-bit accumulator, every lane's constants small enough): the correction
+  // term, the rounding term and the output zero point go into one 64-bit constant per lane, so
+  // an output is clamp((acc * m + k64) >> (31 + sh)) against the absolute bounds:
+  // ((acc + corr) * m + rnd) >> s + z == (acc * m + corr * m + rnd + z * 2^s) >> s exactly, and
+  // acc + corr cannot wrap when |corr| <= 2^30 and |acc| <= 2^30 (|acc| <= C * 2^15 < 2^30 for
+  // C < 2^15).  With sh <= 19 and an 8-bit z nothing leaves 63 bits.
+  auto store_all = [&]<bool FOLD>() {
+    const int32_t lo = rs.lo_rel + (FOLD ? rs.z_out : 0), hi = rs.hi_rel + (FOLD ? rs.z_out : 0);
+    const int64_t k64 = FOLD ? (int64_t)corr * mult_r + rnd + ((int64_t)rs.z_out << (31 + shift_r)) : rnd;
+    const int32_t add = FOLD ? 0 : corr;
 #pragma unroll
-  for (int g = 0; g < 4; ++g) {
-    uint32_t dw[4];
+    for (int g = 0; g < 4; ++g) {
+      uint32_t dw[4];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const int pq = pix0 + 4 * (8 * g + 4 * h + e);  // first of the four pixels; HW % 4 == 0
-      int32_t v[4];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        v[j] = acc[j][4 * g + e] + corr;
-        if (ACC16) v[j] = (int32_t)(int16_t)v[j];
-      }
-      if constexpr (MODE == 0) {
+      for (int e = 0; e < 4; ++e) {
+        const int pq = pix0 + 4 * (8 * g + 4 * h + e);  // first of the four pixels; HW % 4 == 0
+        int32_t v[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-          const int64_t pr = (int64_t)v[j] * (int64_t)mult_r + rnd;
-          v[j] = med3((int32_t)(pr >> (31 + shift_r)), rs.lo_rel, rs.hi_rel) + rs.z_out;
+          v[j] = acc[j][4 * g + e] + add;
+          if (ACC16) v[j] = (int32_t)(int16_t)v[j];
         }
-        dw[e] = pack4_perm(v[0], v[1], v[2], v[3]);
-        if (!vec16 && n < N && pq < HW) *reinterpret_cast<uint32_t*>(orow + pq) = dw[e];
-      } else if constexpr (MODE == 1) {
-        if (n < N && pq < HW) *reinterpret_cast<int4*>(orow + (int64_t)pq * 4) = make_int4(v[0], v[1], v[2], v[3]);
-      } else {
-        if (n < N && pq < HW)
-          *reinterpret_cast<short4*>(orow + (int64_t)pq * 2) =
-              make_short4((short)v[0], (short)v[1], (short)v[2], (short)v[3]);
+        if constexpr (MODE == 0) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const int64_t pr = (int64_t)v[j] * (int64_t)mult_r + k64;
+            v[j] = med3((int32_t)(pr >> (31 + shift_r)), lo, hi) + (FOLD ? 0 : rs.z_out);
+          }
+          dw[e] = pack4_perm(v[0], v[1], v[2], v[3]);
+          if (!vec16 && n < N && pq < HW) *reinterpret_cast<uint32_t*>(orow + pq) = dw[e];
+        } else if constexpr (MODE == 1) {
+          if (n < N && pq < HW) *reinterpret_cast<int4*>(orow + (int64_t)pq * 4) = make_int4(v[0], v[1], v[2], v[3]);
+        } else {
+          if (n < N && pq < HW)
+            *reinterpret_cast<short4*>(orow + (int64_t)pq * 2) =
+                make_short4((short)v[0], (short)v[1], (short)v[2], (short)v[3]);
+        }
+      }
+      if constexpr (MODE == 0) {
+        const int pg = pix0 + 32 * g + 16 * h;  // HW % 16 == 0: the 16 pixels are inside the image or outside
+        if (vec16 && n < N && pg < HW)
+          *reinterpret_cast<uint4*>(orow + pg) = make_uint4(dw[0], dw[1], dw[2], dw[3]);
       }
     }
-    if constexpr (MODE == 0) {
-      const int pg = pix0 + 32 * g + 16 * h;  // HW % 16 == 0: the 16 pixels are inside the image or outside
-      if (vec16 && n < N && pg < HW)
-        *reinterpret_cast<uint4*>(orow + pg) = make_uint4(dw[0], dw[1], dw[2], dw[3]);
-    }
-  }
+  };
+  const bool lane_ok = shift_r >= 0 && shift_r <= 19 && corr >= -(1 << 30) && corr <= (1 << 30);
+  const bool fold = MODE == 0 && !ACC16 && C < (1 << 15) && rs.z_out >= -256 && rs.z_out <= 255 &&
+                    __builtin_amdgcn_ballot_w64(!lane_ok) == 0;  // wavefront-uniform
+  if (fold)
+    store_all.template operator()<true>();
+  else
+    store_all.template operator()<false>();
 }
 
 template <int MODE, bool ACC16>

@@ -210,6 +210,33 @@ def test_pointwise_nchw_all_output_modes(case, adt, za):
     assert_same(host(got), want, f"pointwise acc16 requant per-tensor {case}")
 
 
+@pytest.mark.parametrize("big", [False, True])
+@pytest.mark.parametrize("out_u8,z_out", [(False, -7), (True, 131)])
+def test_pointwise_requant_constant_ranges(big, out_u8, z_out):
+    """The 128-pixel pointwise kernel folds bias term, rounding term and output zero point into one 64-bit
+    constant per channel when every channel's constants are small enough (big=False: at the bounds) and
+    takes the general form otherwise (big=True: beyond them)."""
+    B, C, H, W, O = 2, 48, 12, 12, 24
+    rng = np.random.default_rng(500 + z_out + big)
+    a = rnd_act(rng, (B, C, H, W), np.uint8)
+    w = rnd_w(rng, (O, C, 1, 1))
+    bias = rng.integers(-5000, 5000, O).astype(np.int64)
+    shift = rng.integers(5, 12, O).astype(np.int32)
+    shift[:4] = [0, 1, 19, 19]
+    bias[4], bias[5] = 2 ** 30 - 2 ** 22, -(2 ** 30) + 2 ** 22
+    if big:
+        shift[6:9] = [20, 31, 25]
+        bias[9], bias[10], bias[11] = 2 ** 31 - 1, -(2 ** 31), 2 ** 30 + 2 ** 23
+    bias = bias.astype(np.int32)
+    mult = rng.integers(2 ** 30, 2 ** 31, size=O).astype(np.int32)
+    a_t, w_t = act_qtype(a, 121), hago.QType(hago.I8)
+    want = ref.qconv2d(a, 121, w, bias, ref.NCHW, (1, 1), (0, 0), 1, ref.I32, ref_requant(mult, shift, out_u8, z_out))
+    got = hago.qconv2d(dev(a), a_t, dev(w), w_t, dev(bias), hago.NCHW, (1, 1), (0, 0), 1, hago.I32,
+                       gpu_requant(mult, shift, out_u8, z_out))
+    assert_same(host(got), want, "pointwise requant ranges")
+    assert len(np.unique(want)) > 50
+
+
 def test_qconv2d_config2_full_size():
     for z_a in (0, 128):
         c = datagen.config2(z_a=z_a)
