@@ -302,7 +302,14 @@ __device__ __forceinline__ int32_t finish_one(int32_t a, int32_t m, int32_t sh, 
   return a;
 }
 
-template <int WP, int WQ, int TP, int TQ, bool ACT_ON_P, int OM>
+// Row r of a 32-row block holds pixel pix_perm(r) of the block when the loader placed the pixels
+// that way (PIXPERM): registers 4g + e of lane half h are then the 16 consecutive pixels
+// 16h + 4g + e, which go out as one 16-byte store per channel instead of four scattered dwords.
+__device__ __forceinline__ constexpr int pix_perm(int r) {
+  return 16 * ((r >> 2) & 1) + 4 * (r >> 3) + (r & 3);
+}
+
+template <int WP, int WQ, int TP, int TQ, bool ACT_ON_P, int OM, bool PIXPERM = false>
 __device__ __forceinline__ void qgemm_epilogue_fast(const QgemmParams& p, v16i (&acc)[TP][TQ],
                                                     int p0, int q0, const int32_t* s_corr,
                                                     const int32_t* s_mult,
@@ -335,6 +342,8 @@ __device__ __forceinline__ void qgemm_epilogue_fast(const QgemmParams& p, v16i (
     }
   } else {
     const int ohw = p.g.OH * p.g.OW;
+    // 16 consecutive pixels of a lane lie in one image and form one aligned store
+    const bool vec16 = PIXPERM && OM == 0 && (ohw & 15) == 0 && (reinterpret_cast<uintptr_t>(p.out) & 15u) == 0;
 #pragma unroll
     for (int tj = 0; tj < TQ; ++tj) {
       const int j_loc = (wq * TQ + tj) * 32 + frow;
@@ -342,9 +351,47 @@ __device__ __forceinline__ void qgemm_epilogue_fast(const QgemmParams& p, v16i (
       const int32_t c = s_corr[j_loc], m = s_mult[j_loc], sh = s_shift[j_loc];
 #pragma unroll
       for (int ti = 0; ti < TP; ++ti) {
+        if constexpr (PIXPERM && OM == 0) {
+          if (vec16) {
+            const int i = p0 + (wp * TP + ti) * 32 + fhalf * 16;
+            const int b = i / ohw;
+            const int pix = i - b * ohw;
+            uint32_t dw[4];
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4)
+              dw[g4] = pack4(finish_one<OM>(acc[ti][tj][g4 * 4 + 0] + c, m, sh, acc16, rs),
+                             finish_one<OM>(acc[ti][tj][g4 * 4 + 1] + c, m, sh, acc16, rs),
+                             finish_one<OM>(acc[ti][tj][g4 * 4 + 2] + c, m, sh, acc16, rs),
+                             finish_one<OM>(acc[ti][tj][g4 * 4 + 3] + c, m, sh, acc16, rs));
+            *reinterpret_cast<uint4*>(static_cast<uint8_t*>(p.out) + ((size_t)b * p.N + j) * ohw + pix) =
+                make_uint4(dw[0], dw[1], dw[2], dw[3]);
+            continue;
+          }
+        }
+        if constexpr (PIXPERM && OM == 2) {
+          // raw int16: the lane's 16 pixels are 32 contiguous bytes, two aligned 16-byte stores
+          if ((ohw & 7) == 0 && (reinterpret_cast<uintptr_t>(p.out) & 15u) == 0) {
+#pragma unroll
+            for (int g2 = 0; g2 < 2; ++g2) {
+              const int i = p0 + (wp * TP + ti) * 32 + fhalf * 16 + g2 * 8;
+              const int b = i / ohw;
+              const int pix = i - b * ohw;
+              uint32_t dw[4];
+#pragma unroll
+              for (int x = 0; x < 4; ++x) {
+                const int32_t lo16 = finish_one<OM>(acc[ti][tj][g2 * 8 + 2 * x] + c, m, sh, acc16, rs);
+                const int32_t hi16 = finish_one<OM>(acc[ti][tj][g2 * 8 + 2 * x + 1] + c, m, sh, acc16, rs);
+                dw[x] = ((uint32_t)lo16 & 0xffffu) | ((uint32_t)hi16 << 16);
+              }
+              *reinterpret_cast<uint4*>(static_cast<int16_t*>(p.out) + ((size_t)b * p.N + j) * ohw + pix) =
+                  make_uint4(dw[0], dw[1], dw[2], dw[3]);
+            }
+            continue;
+          }
+        }
 #pragma unroll
         for (int g4 = 0; g4 < 4; ++g4) {
-          const int i = p0 + (wp * TP + ti) * 32 + g4 * 8 + fhalf * 4;
+          const int i = p0 + (wp * TP + ti) * 32 + (PIXPERM ? fhalf * 16 + g4 * 4 : g4 * 8 + fhalf * 4);
           const int b = i / ohw;
           const int pix = i - b * ohw;
           const int32_t r0 = finish_one<OM>(acc[ti][tj][g4 * 4 + 0] + c, m, sh, acc16, rs);
@@ -366,7 +413,7 @@ __device__ __forceinline__ void qgemm_epilogue_fast(const QgemmParams& p, v16i (
 // Interior tiles of the common case (8-bit requantized output, int32
 // accumulation, aligned packed stores) take a straight-line path; everything
 // else goes through the bounds-checked generic path.
-template <int WP, int WQ, int TP, int TQ, bool ACT_ON_P>
+template <int WP, int WQ, int TP, int TQ, bool ACT_ON_P, bool PIXPERM = false>
 __device__ __forceinline__ void qgemm_epilogue(const QgemmParams& p, v16i (&acc)[TP][TQ], int p0,
                                                int q0, const int32_t* s_corr,
                                                const int32_t* s_mult, const int32_t* s_shift) {
@@ -382,11 +429,11 @@ __device__ __forceinline__ void qgemm_epilogue(const QgemmParams& p, v16i (&acc)
 
   if (fast) {
     if (p.out_mode == 0)
-      qgemm_epilogue_fast<WP, WQ, TP, TQ, ACT_ON_P, 0>(p, acc, p0, q0, s_corr, s_mult, s_shift);
+      qgemm_epilogue_fast<WP, WQ, TP, TQ, ACT_ON_P, 0, PIXPERM>(p, acc, p0, q0, s_corr, s_mult, s_shift);
     else if (p.out_mode == 1)
-      qgemm_epilogue_fast<WP, WQ, TP, TQ, ACT_ON_P, 1>(p, acc, p0, q0, s_corr, s_mult, s_shift);
+      qgemm_epilogue_fast<WP, WQ, TP, TQ, ACT_ON_P, 1, PIXPERM>(p, acc, p0, q0, s_corr, s_mult, s_shift);
     else
-      qgemm_epilogue_fast<WP, WQ, TP, TQ, ACT_ON_P, 2>(p, acc, p0, q0, s_corr, s_mult, s_shift);
+      qgemm_epilogue_fast<WP, WQ, TP, TQ, ACT_ON_P, 2, PIXPERM>(p, acc, p0, q0, s_corr, s_mult, s_shift);
     return;
   }
 
@@ -399,7 +446,7 @@ __device__ __forceinline__ void qgemm_epilogue(const QgemmParams& p, v16i (&acc)
     for (int ti = 0; ti < TP; ++ti) {
 #pragma unroll
       for (int g4 = 0; g4 < 4; ++g4) {
-        const int i_loc = (wp * TP + ti) * 32 + g4 * 8 + fhalf * 4;
+        const int i_loc = (wp * TP + ti) * 32 + (PIXPERM ? fhalf * 16 + g4 * 4 : g4 * 8 + fhalf * 4);
         const int i = p0 + i_loc;
         int32_t v[4];
 #pragma unroll

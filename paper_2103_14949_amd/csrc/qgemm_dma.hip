@@ -108,6 +108,7 @@ template <int WP, int WQ, int TP, int TQ, int kStages, int OCC, bool CONV, bool 
           bool UNIFORM, int BK = kBK>
 __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParams p) {
   static_assert(!FLIP || (!CONV && !ACT_ON_P), "only dense layers flip, and keep activations on Q");
+  constexpr bool kPixPerm = CONV && ACT_ON_P;
   static_assert(BK == 64 || BK == 128, "stage width");
   constexpr int NH = BK / 32;       // 32-k groups per stage
   constexpr int RPI = 1024 / BK;    // rows per DMA instruction
@@ -216,7 +217,12 @@ __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParam
   for (int d = 0; d < L; ++d) {
     const int grp = wave + NW * d;
     const bool isq = kEven ? (d >= GP / NW) : (grp >= GP);
-    const int rt = (isq ? grp - GP : grp) * RPI + lrow;  // row inside its tile
+    int rt = (isq ? grp - GP : grp) * RPI + lrow;  // row inside its tile
+    // NCHW convolution: the pixels of a 32-row block are placed so that a lane's accumulator
+    // registers are 16 consecutive pixels (one 16-byte store per channel in the epilogue)
+    if constexpr (kPixPerm) {
+      if (!isq) rt = (rt & ~31) | pix_perm(rt & 31);
+    }
     slot_q[d] = isq;
     slot_real[d] = kEven || grp < G;
     uint32_t off = kOob;
@@ -532,7 +538,7 @@ __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParam
       }
     }
   }
-  qgemm_epilogue<WP, WQ, TP, TQ, ACT_ON_P>(p, acc, p0, q0, s_corr, s_mult, s_shift);
+  qgemm_epilogue<WP, WQ, TP, TQ, ACT_ON_P, kPixPerm>(p, acc, p0, q0, s_corr, s_mult, s_shift);
 }
 
 template <int WP, int WQ, int TP, int TQ, int kStages, int OCC, bool CONV, bool ACT_ON_P, bool FLIP,
