@@ -124,6 +124,12 @@ CONV_CASES = [
     (1, 96, 10, 33, 64, 5, 5, (1, 1), (2, 2)),
     (1, 128, 9, 40, 130, 3, 3, (1, 1), (0, 0)),
     (2, 32, 17, 30, 8, 1, 3, (1, 1), (0, 1)),
+    # NCHW widths that are multiples of 4 (the transposing operand rewrite): channel counts off the
+    # 16- and 64-channel groups, padding that differs between the axes or is absent on one
+    (1, 80, 6, 8, 20, 3, 3, (1, 1), (1, 1)),
+    (2, 3, 5, 8, 4, 3, 5, (1, 1), (1, 2)),
+    (1, 20, 7, 12, 9, 3, 1, (1, 1), (1, 0)),
+    (3, 70, 4, 4, 5, 3, 3, (1, 1), (1, 1)),
 ]
 
 
