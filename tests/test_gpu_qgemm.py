@@ -275,6 +275,29 @@ def test_qconv2d_config3_int16_accumulation_full_size():
         assert e.value.code == 6
 
 
+@pytest.mark.parametrize("O", [128, 100])
+def test_qconv2d_many_pixels_128_channels(O):
+    """3x3 convolution with 128 input channels over more than 2^15 output pixels (the 256-pixel
+    implicit-GEMM tiles, full and ragged in the channels), all three output modes."""
+    B, C, H, W = 44, 128, 28, 28
+    rng = np.random.default_rng(31 + O)
+    a = rnd_act(rng, (B, C, H, W), np.uint8)
+    w = rnd_w(rng, (O, C, 3, 3))
+    bias = rng.integers(-5000, 5000, O).astype(np.int32)
+    a_t, w_t = act_qtype(a, 119), hago.QType(hago.I8)
+    args = (hago.NCHW, (1, 1), (1, 1), 1)
+    rargs = (ref.NCHW, (1, 1), (1, 1), 1)
+    want = ref.qconv2d(a, 119, w, bias, *rargs)
+    assert_same(host(hago.qconv2d(dev(a), a_t, dev(w), w_t, dev(bias), *args)), want, "raw int32")
+    mult, shift = datagen.requant_params(rng, np.full(O, 74.0 * 73.0 * np.sqrt(9 * C)), 40.0)
+    want = ref.qconv2d(a, 119, w, bias, *rargs, ref.I32, ref_requant(mult, shift))
+    got = hago.qconv2d(dev(a), a_t, dev(w), w_t, dev(bias), *args, hago.I32, gpu_requant(mult, shift))
+    assert_same(host(got), want, "requantized")
+    assert len(np.unique(want)) > 100
+    want = ref.qconv2d(a, 119, w, bias, *rargs, ref.I16)
+    assert_same(host(hago.qconv2d(dev(a), a_t, dev(w), w_t, dev(bias), *args, hago.I16)), want, "raw int16")
+
+
 def test_config4_mobilenet_block_full_size():
     c = datagen.config4()
     a_t = hago.QType(hago.I8, 8, True, 0)
