@@ -183,7 +183,7 @@ __device__ __forceinline__ int32_t mul_shift_fast(int32_t a, int32_t m, int64_t 
   return (int32_t)(pr >> (31 + sh));
 }
 
-// Dense epilogue of an interior tile through LDS: requantize, pack four channels
+// Dense epilogue of a tile (interior or ragged, N % 16 == 0) through LDS: requantize, pack four channels
 // per dword, write the tile to LDS in output order [row m][channel n], then copy
 // it out with 16-byte stores that cover whole output rows.  LDS rows are BP + 16 bytes
 // apart, so the 32 rows a wavefront writes at once spread over the banks.
@@ -275,7 +275,9 @@ __device__ __forceinline__ void qgemm_epilogue_dense_staged(const QgemmParams& p
     const int q = (int)threadIdx.x + NT * s;
     const int row = q / CPR, c = q % CPR;
     const v4i v = *reinterpret_cast<const v4i*>(s_out + row * RS + c * 16);
-    *reinterpret_cast<v4i*>(out8 + (size_t)(q0 + row) * p.N + p0 + c * 16) = v;
+    // ragged tiles: rows beyond M and 16-channel chunks beyond N (N % 16 == 0) stay in LDS
+    if (q0 + row < p.M && p0 + c * 16 < p.N)
+      *reinterpret_cast<v4i*>(out8 + (size_t)(q0 + row) * p.N + p0 + c * 16) = v;
   }
   HAGO_STAMP(p, 6);
 }
