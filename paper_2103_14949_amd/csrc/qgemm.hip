@@ -212,7 +212,6 @@ __global__ __launch_bounds__(64 * WP * WQ) void qgemm_kernel(QgemmParams p) {
   const int wq = wave / WP;
 
   const int P_ext = ACT_ON_P ? p.M : p.N;
-  const int Q_ext = ACT_ON_P ? p.N : p.M;
   const int tiles_p = (P_ext + BP - 1) / BP;
   const int tile = xcd_remap(blockIdx.x, gridDim.x);
   const int tile_p = tile % tiles_p;

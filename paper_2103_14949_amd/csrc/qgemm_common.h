@@ -282,7 +282,7 @@ __device__ __forceinline__ void qgemm_epilogue_dense_staged(const QgemmParams& p
   HAGO_STAMP(p, 6);
 }
 
-// Straight-line epilogue of an interior tile whose packed stores are aligned.
+// Straight-line epilogue of a tile (interior or ragged) whose packed stores are aligned.
 // OM: 0 requantized 8-bit, 1 raw int32, 2 raw int16.
 template <int OM>
 __device__ __forceinline__ void store_group(void* out, size_t off, int32_t v0, int32_t v1,
@@ -311,7 +311,7 @@ __device__ __forceinline__ constexpr int pix_perm(int r) {
   return 16 * ((r >> 2) & 1) + 4 * (r >> 3) + (r & 3);
 }
 
-template <int WP, int WQ, int TP, int TQ, bool ACT_ON_P, int OM, bool PIXPERM = false>
+template <int WP, int WQ, int TP, int TQ, bool ACT_ON_P, int OM, bool PIXPERM, bool RAGGED>
 __device__ __forceinline__ void qgemm_epilogue_fast(const QgemmParams& p, v16i (&acc)[TP][TQ],
                                                     int p0, int q0, const int32_t* s_corr,
                                                     const int32_t* s_mult,
@@ -322,6 +322,10 @@ __device__ __forceinline__ void qgemm_epilogue_fast(const QgemmParams& p, v16i (
   const int frow = lane & 31, fhalf = lane >> 5;
   const RequantScalars rs = p.rs;
   const bool acc16 = p.acc16 != 0;
+  // ragged tiles: a group of four results along the packed axis is inside the tensor or outside
+  // (the packed extent is a multiple of 4, of 16 where 16-byte stores are used)
+  const int P_ext = ACT_ON_P ? p.M : p.N;
+  const int Q_ext = ACT_ON_P ? p.N : p.M;
   if constexpr (!ACT_ON_P) {
 #pragma unroll
     for (int ti = 0; ti < TP; ++ti) {
@@ -338,7 +342,8 @@ __device__ __forceinline__ void qgemm_epilogue_fast(const QgemmParams& p, v16i (
           const int32_t r1 = finish_one<OM>(acc[ti][tj][g4 * 4 + 1] + c4.y, m4.y, s4.y, acc16, rs);
           const int32_t r2 = finish_one<OM>(acc[ti][tj][g4 * 4 + 2] + c4.z, m4.z, s4.z, acc16, rs);
           const int32_t r3 = finish_one<OM>(acc[ti][tj][g4 * 4 + 3] + c4.w, m4.w, s4.w, acc16, rs);
-          store_group<OM>(p.out, (size_t)j * p.N + (p0 + i_loc), r0, r1, r2, r3);
+          if (!RAGGED || (j < Q_ext && p0 + i_loc < P_ext))
+            store_group<OM>(p.out, (size_t)j * p.N + (p0 + i_loc), r0, r1, r2, r3);
         }
       }
     }
@@ -365,8 +370,9 @@ __device__ __forceinline__ void qgemm_epilogue_fast(const QgemmParams& p, v16i (
                              finish_one<OM>(acc[ti][tj][g4 * 4 + 1] + c, m, sh, acc16, rs),
                              finish_one<OM>(acc[ti][tj][g4 * 4 + 2] + c, m, sh, acc16, rs),
                              finish_one<OM>(acc[ti][tj][g4 * 4 + 3] + c, m, sh, acc16, rs));
-            *reinterpret_cast<uint4*>(static_cast<uint8_t*>(p.out) + ((size_t)b * p.N + j) * ohw + pix) =
-                make_uint4(dw[0], dw[1], dw[2], dw[3]);
+            if (!RAGGED || (j < Q_ext && i < P_ext))
+              *reinterpret_cast<uint4*>(static_cast<uint8_t*>(p.out) + ((size_t)b * p.N + j) * ohw + pix) =
+                  make_uint4(dw[0], dw[1], dw[2], dw[3]);
             continue;
           }
         }
@@ -385,8 +391,9 @@ __device__ __forceinline__ void qgemm_epilogue_fast(const QgemmParams& p, v16i (
                 const int32_t hi16 = finish_one<OM>(acc[ti][tj][g2 * 8 + 2 * x + 1] + c, m, sh, acc16, rs);
                 dw[x] = ((uint32_t)lo16 & 0xffffu) | ((uint32_t)hi16 << 16);
               }
-              *reinterpret_cast<uint4*>(static_cast<int16_t*>(p.out) + ((size_t)b * p.N + j) * ohw + pix) =
-                  make_uint4(dw[0], dw[1], dw[2], dw[3]);
+              if (!RAGGED || (j < Q_ext && i < P_ext))
+                *reinterpret_cast<uint4*>(static_cast<int16_t*>(p.out) + ((size_t)b * p.N + j) * ohw + pix) =
+                    make_uint4(dw[0], dw[1], dw[2], dw[3]);
             }
             continue;
           }
@@ -400,7 +407,8 @@ __device__ __forceinline__ void qgemm_epilogue_fast(const QgemmParams& p, v16i (
           const int32_t r1 = finish_one<OM>(acc[ti][tj][g4 * 4 + 1] + c, m, sh, acc16, rs);
           const int32_t r2 = finish_one<OM>(acc[ti][tj][g4 * 4 + 2] + c, m, sh, acc16, rs);
           const int32_t r3 = finish_one<OM>(acc[ti][tj][g4 * 4 + 3] + c, m, sh, acc16, rs);
-          store_group<OM>(p.out, ((size_t)b * p.N + j) * ohw + pix, r0, r1, r2, r3);
+          if (!RAGGED || (j < Q_ext && i < P_ext))
+            store_group<OM>(p.out, ((size_t)b * p.N + j) * ohw + pix, r0, r1, r2, r3);
         }
       }
     }
@@ -412,9 +420,9 @@ __device__ __forceinline__ void qgemm_epilogue_fast(const QgemmParams& p, v16i (
 // registers 4g .. 4g+3, rows 8g + 4*(l / 32) + 0..3.
 //   ACT_ON_P == false (dense, NHWC): i = output channel n, j = row m, out[m*N + n]
 //   ACT_ON_P == true  (NCHW)       : i = pixel m, j = channel n, out[(b*N + n)*OHW + pix]
-// Interior tiles of the common case (8-bit requantized output, int32
-// accumulation, aligned packed stores) take a straight-line path; everything
-// else goes through the bounds-checked generic path.
+// Tensors whose groups of four results along the packed axis are aligned stores
+// take a straight-line path (ragged tiles included: a group is inside or outside);
+// everything else goes through the element-wise generic path.
 template <int WP, int WQ, int TP, int TQ, bool ACT_ON_P, bool PIXPERM = false>
 __device__ __forceinline__ void qgemm_epilogue(const QgemmParams& p, v16i (&acc)[TP][TQ], int p0,
                                                int q0, const int32_t* s_corr,
@@ -427,15 +435,23 @@ __device__ __forceinline__ void qgemm_epilogue(const QgemmParams& p, v16i (&acc)
   const int P_ext = ACT_ON_P ? p.M : p.N;
   const int Q_ext = ACT_ON_P ? p.N : p.M;
   const int ohw = p.g.OH * p.g.OW;
-  const bool fast = p.vec_out && p0 + BP <= P_ext && q0 + BQ <= Q_ext;
+  const bool fast = p.vec_out;  // groups of four along the packed axis are aligned stores
 
   if (fast) {
+    // interior tiles (block-uniform) run without the per-store bounds checks
+    const bool ragged = p0 + BP > P_ext || q0 + BQ > Q_ext;
+#define HAGO_FAST_EPILOGUE(OM)                                                                          \
+  (ragged ? qgemm_epilogue_fast<WP, WQ, TP, TQ, ACT_ON_P, OM, PIXPERM, true>(p, acc, p0, q0, s_corr,    \
+                                                                             s_mult, s_shift)          \
+          : qgemm_epilogue_fast<WP, WQ, TP, TQ, ACT_ON_P, OM, PIXPERM, false>(p, acc, p0, q0, s_corr,   \
+                                                                              s_mult, s_shift))
     if (p.out_mode == 0)
-      qgemm_epilogue_fast<WP, WQ, TP, TQ, ACT_ON_P, 0, PIXPERM>(p, acc, p0, q0, s_corr, s_mult, s_shift);
+      HAGO_FAST_EPILOGUE(0);
     else if (p.out_mode == 1)
-      qgemm_epilogue_fast<WP, WQ, TP, TQ, ACT_ON_P, 1, PIXPERM>(p, acc, p0, q0, s_corr, s_mult, s_shift);
+      HAGO_FAST_EPILOGUE(1);
     else
-      qgemm_epilogue_fast<WP, WQ, TP, TQ, ACT_ON_P, 2, PIXPERM>(p, acc, p0, q0, s_corr, s_mult, s_shift);
+      HAGO_FAST_EPILOGUE(2);
+#undef HAGO_FAST_EPILOGUE
     return;
   }
 

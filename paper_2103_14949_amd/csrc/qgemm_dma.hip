@@ -288,8 +288,6 @@ __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParam
     }
     return a;
   };
-  constexpr int LH = (L + 1) / 2;  // a stage is issued in two parts (LH and L - LH instructions),
-                                  // spread over two MFMA groups
   using IC0 = std::integral_constant<int, 0>;
   using ICL = std::integral_constant<int, L>;
 
