@@ -270,13 +270,14 @@ __device__ __forceinline__ void qgemm_epilogue_dense_staged(const QgemmParams& p
   __syncthreads();
   HAGO_STAMP(p, 5);
   uint8_t* out8 = static_cast<uint8_t*>(p.out);
+  const bool ragged = q0 + BQ > p.M || p0 + BP > p.N;  // block-uniform
 #pragma unroll
   for (int s = 0; s < (BQ * CPR) / NT; ++s) {
     const int q = (int)threadIdx.x + NT * s;
     const int row = q / CPR, c = q % CPR;
     const v4i v = *reinterpret_cast<const v4i*>(s_out + row * RS + c * 16);
     // ragged tiles: rows beyond M and 16-channel chunks beyond N (N % 16 == 0) stay in LDS
-    if (q0 + row < p.M && p0 + c * 16 < p.N)
+    if (!ragged || (q0 + row < p.M && p0 + c * 16 < p.N))
       *reinterpret_cast<v4i*>(out8 + (size_t)(q0 + row) * p.N + p0 + c * 16) = v;
   }
   HAGO_STAMP(p, 6);
