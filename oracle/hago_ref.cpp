@@ -38,6 +38,7 @@ bool requant_ok(const ref_requant* rq, int64_t channels) {
   if (!rq->multiplier || !rq->shift) return false;
   if (rq->out_dtype != REF_I8 && rq->out_dtype != REF_U8) return false;
   if (rq->clip_lo > rq->clip_hi) return false;
+  if (rq->rounding != REF_ROUND_UPWARD && rq->rounding != REF_ROUND_HALF_AWAY) return false;
   const int64_t n = rq->per_channel ? channels : 1;
   for (int64_t c = 0; c < n; ++c)
     if (rq->shift[c] < 0 || rq->shift[c] > 31) return false;
@@ -56,8 +57,9 @@ inline void emit(void* out, int64_t i, int64_t c, int32_t acc,
   }
   const int64_t pc = rq->per_channel ? c : 0;
   const int64_t v =
-      hago_ref_requantize_one(acc, rq->multiplier[pc], rq->shift[pc],
-                              rq->out_zero_point, rq->clip_lo, rq->clip_hi);
+      hago_ref_requantize_one_mode(acc, rq->multiplier[pc], rq->shift[pc],
+                                   rq->out_zero_point, rq->clip_lo, rq->clip_hi,
+                                   rq->rounding);
   if (rq->out_dtype == REF_U8)
     static_cast<uint8_t*>(out)[i] = (uint8_t)v;
   else
@@ -195,6 +197,23 @@ int64_t hago_ref_requantize_one(int32_t acc, int32_t multiplier, int32_t shift,
   /* add one half in units of 2^-t, then floor: arithmetic right shift */
   const int64_t r = (p + ((int64_t)1 << (t - 1))) >> t;
   int64_t o = r + (int64_t)z_out;
+  if (o < (int64_t)lo) o = lo;
+  if (o > (int64_t)hi) o = hi;
+  return o;
+}
+
+int64_t hago_ref_requantize_one_mode(int32_t acc, int32_t multiplier,
+                                     int32_t shift, int32_t z_out, int32_t lo,
+                                     int32_t hi, int32_t rounding) {
+  if (rounding == REF_ROUND_UPWARD)
+    return hago_ref_requantize_one(acc, multiplier, shift, z_out, lo, hi);
+  /* nearest integer to p / 2^t, halves away from zero: round the magnitude
+   * half up and give it the sign back */
+  const int64_t p = (int64_t)acc * (int64_t)multiplier; /* |p| < 2^62 */
+  const int t = 31 + shift;
+  const int64_t half = (int64_t)1 << (t - 1);
+  const int64_t mag = ((p < 0 ? -p : p) + half) >> t;
+  int64_t o = (p < 0 ? -mag : mag) + (int64_t)z_out;
   if (o < (int64_t)lo) o = lo;
   if (o > (int64_t)hi) o = hi;
   return o;

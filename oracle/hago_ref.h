@@ -48,7 +48,13 @@ typedef struct {
   int32_t out_dtype;
   int32_t out_zero_point;
   int32_t clip_lo, clip_hi; /* inclusive, in the output's quantized domain */
+  int32_t rounding;         /* REF_ROUND_UPWARD or REF_ROUND_HALF_AWAY */
 } ref_requant;
+
+/* Tie rule of the requantize rounding.  The paper names the operator only;
+ * the two rules are the ones of the compiler stack it generates code with:
+ * ties toward +infinity, and ties away from zero. */
+enum { REF_ROUND_UPWARD = 0, REF_ROUND_HALF_AWAY = 1 };
 
 /* Sec. 2 (Background), Eq. 1: s = threshold / 2^(bit - sign). */
 double hago_ref_scale(double threshold, int32_t bits, int32_t sign);
@@ -96,6 +102,11 @@ int hago_ref_encode_multiplier(double m, int32_t* multiplier, int32_t* shift);
  * clip(r + z_out, lo, hi).  Exposed so tests can probe single values. */
 int64_t hago_ref_requantize_one(int32_t acc, int32_t multiplier, int32_t shift,
                                 int32_t z_out, int32_t lo, int32_t hi);
+/* The same with the tie rule chosen: REF_ROUND_HALF_AWAY rounds
+ * acc*M / 2^(31+sh) to the nearest integer, halves away from zero. */
+int64_t hago_ref_requantize_one_mode(int32_t acc, int32_t multiplier,
+                                     int32_t shift, int32_t z_out, int32_t lo,
+                                     int32_t hi, int32_t rounding);
 
 /* Standalone requantize over acc[outer, channels, inner] (REF_I32 or REF_I16;
  * int16 is sign-extended) -> out (REF_I8 / REF_U8). */

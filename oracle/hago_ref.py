@@ -45,7 +45,7 @@ class _Requant(C.Structure):
     _fields_ = [("multiplier", C.c_void_p), ("shift", C.c_void_p),
                 ("per_channel", C.c_int32), ("out_dtype", C.c_int32),
                 ("out_zero_point", C.c_int32), ("clip_lo", C.c_int32),
-                ("clip_hi", C.c_int32)]
+                ("clip_hi", C.c_int32), ("rounding", C.c_int32)]
 
 
 _lib = None
@@ -68,6 +68,8 @@ def lib(path: str | None = None):
             L.hago_ref_encode_multiplier.argtypes = [dbl, vp, vp]
             L.hago_ref_requantize_one.restype = i64
             L.hago_ref_requantize_one.argtypes = [i32] * 6
+            L.hago_ref_requantize_one_mode.restype = i64
+            L.hago_ref_requantize_one_mode.argtypes = [i32] * 7
             L.hago_ref_requantize.argtypes = [vp, i32, i64, i64, i64, vp, vp]
             L.hago_ref_acc16_safe.argtypes = [i64, i64, i64]
             L.hago_ref_qdense.argtypes = [vp, i32, i32, vp, vp, i64, i64, i64, i32, vp, vp]
@@ -97,7 +99,7 @@ class Requant:
     """Requantize parameters (host arrays)."""
 
     def __init__(self, multiplier, shift, out_dtype=I8, out_zero_point=0,
-                 clip_lo=-128, clip_hi=127, per_channel=None):
+                 clip_lo=-128, clip_hi=127, per_channel=None, rounding=0):
         self.multiplier = np.ascontiguousarray(multiplier, dtype=np.int32).reshape(-1)
         self.shift = np.ascontiguousarray(shift, dtype=np.int32).reshape(-1)
         self.per_channel = int(self.multiplier.size > 1) if per_channel is None else int(per_channel)
@@ -105,11 +107,12 @@ class Requant:
         self.out_zero_point = int(out_zero_point)
         self.clip_lo = int(clip_lo)
         self.clip_hi = int(clip_hi)
+        self.rounding = int(rounding)   # ROUND_UPWARD or ROUND_HALF_AWAY
 
     def c_struct(self):
         return _Requant(self.multiplier.ctypes.data, self.shift.ctypes.data,
                         self.per_channel, self.out_dtype, self.out_zero_point,
-                        self.clip_lo, self.clip_hi)
+                        self.clip_lo, self.clip_hi, self.rounding)
 
 
 def scale(threshold, bits, sign):
@@ -196,9 +199,12 @@ def encode_multiplier(m):
     return q.value, s.value
 
 
-def requantize_one(acc, multiplier, shift, z_out=0, lo=-(2 ** 31), hi=2 ** 31 - 1):
-    return lib().hago_ref_requantize_one(int(acc), int(multiplier), int(shift),
-                                         int(z_out), int(lo), int(hi))
+ROUND_UPWARD, ROUND_HALF_AWAY = 0, 1
+
+
+def requantize_one(acc, multiplier, shift, z_out=0, lo=-(2 ** 31), hi=2 ** 31 - 1, rounding=ROUND_UPWARD):
+    return lib().hago_ref_requantize_one_mode(int(acc), int(multiplier), int(shift),
+                                              int(z_out), int(lo), int(hi), int(rounding))
 
 
 def requantize(acc, rq: Requant):

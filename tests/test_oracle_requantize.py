@@ -146,3 +146,84 @@ def test_bad_arguments_are_rejected(ref):
         ref.requantize(acc, ref.Requant([2 ** 30, 2 ** 30], [0, 32]))
     with pytest.raises(ref.RefError):
         ref.requantize(acc, ref.Requant([2 ** 30, 2 ** 30], [0, 1], clip_lo=5, clip_hi=4))
+
+
+# ---- the second tie rule: nearest integer, halves away from zero
+
+def exact_half_away(acc, M, sh):
+    """Nearest integer to acc*M/2^(31+sh), ties away from zero, in exact rationals."""
+    q = Fraction(acc * M, 2 ** (31 + sh))
+    mag = math.floor(abs(q) + Fraction(1, 2))
+    return mag if q >= 0 else -mag
+
+
+def test_half_away_hand_worked_ties(ref):
+    """M = 2^30 is the real multiplier 1/2: acc/2^(1+sh).  Ties: 0.5 -> 1, -0.5 -> -1, 1.5 -> 2,
+    -1.5 -> -2, -2.5 -> -3 (toward +infinity they would be 1, 0, 2, -1, -2)."""
+    A = ref.ROUND_HALF_AWAY
+    for acc, want_away, want_up in ((1, 1, 1), (-1, -1, 0), (3, 2, 2), (-3, -2, -1), (-5, -3, -2), (5, 3, 3),
+                                    (2, 1, 1), (-2, -1, -1), (0, 0, 0), (-4, -2, -2)):
+        assert ref.requantize_one(acc, 2 ** 30, 0, rounding=A) == want_away
+        assert ref.requantize_one(acc, 2 ** 30, 0) == want_up
+    # sh = 2: acc / 8; -12 / 8 = -1.5 -> -2 (away), -1 (upward); -11 / 8 = -1.375 -> -1 under both
+    assert ref.requantize_one(-12, 2 ** 30, 2, rounding=A) == -2 and ref.requantize_one(-12, 2 ** 30, 2) == -1
+    assert ref.requantize_one(-11, 2 ** 30, 2, rounding=A) == -1 and ref.requantize_one(-11, 2 ** 30, 2) == -1
+    # zero point and clip act after the rounding
+    assert ref.requantize_one(-3, 2 ** 30, 0, 10, -128, 127, A) == 8
+    assert ref.requantize_one(-3000, 2 ** 30, 0, 0, -128, 127, A) == -128
+
+
+def test_half_away_fraction_definition_and_where_the_rules_differ(ref):
+    rng = np.random.default_rng(2)
+    A = ref.ROUND_HALF_AWAY
+    diff = 0
+    for M, sh in ((2 ** 30, 0), (2 ** 30, 4), (1717986918, 3), (2 ** 31 - 1, 0), (1288490189, 15), (3 << 29, 1),
+                  (2 ** 31 - 1, 31), (2 ** 30, 31)):
+        accs = np.concatenate([rng.integers(I32_MIN, I32_MAX, 300), rng.integers(-2000, 2000, 300),
+                               [I32_MIN, I32_MAX, 0, -1, 1]])
+        for acc in map(int, accs):
+            want = exact_half_away(acc, M, sh)
+            got = ref.requantize_one(acc, M, sh, rounding=A)
+            assert got == want, (acc, M, sh, got, want)
+            up = ref.requantize_one(acc, M, sh)
+            # the two rules differ exactly on negative ties, and there by one
+            tie = (acc * M) % (2 ** (31 + sh)) == 2 ** (30 + sh)
+            assert (got != up) == (tie and acc * M < 0), (acc, M, sh)
+            if got != up:
+                assert got == up - 1
+                diff += 1
+    assert diff > 20
+
+
+def test_half_away_is_an_odd_function(ref):
+    """round-half-away(-x) = -round-half-away(x): with no zero point and a symmetric clip the
+    operator is odd, which ties toward +infinity are not."""
+    rng = np.random.default_rng(4)
+    A = ref.ROUND_HALF_AWAY
+    for M, sh in ((2 ** 30, 3), (1395864371, 7), (2 ** 31 - 1, 0)):
+        for acc in map(int, rng.integers(-10 ** 6, 10 ** 6, 400)):
+            assert ref.requantize_one(-acc, M, sh, 0, -127, 127, A) == -ref.requantize_one(acc, M, sh, 0, -127, 127, A)
+    assert ref.requantize_one(-1, 2 ** 30, 0) != -ref.requantize_one(1, 2 ** 30, 0)
+
+
+def test_half_away_through_the_tensor_entry_points(ref):
+    """requantize, qdense and qconv2d apply the struct's tie rule: products of small integers with
+    M = 2^30 are full of ties."""
+    rng = np.random.default_rng(8)
+    acc = rng.integers(-40, 40, (2, 3, 50)).astype(np.int32)
+    mult = np.full(3, 2 ** 30, np.int32)
+    shift = np.array([0, 1, 2], np.int32)
+    rq = ref.Requant(mult, shift, rounding=ref.ROUND_HALF_AWAY)
+    got = ref.requantize(acc, rq)
+    want = np.array([[[exact_half_away(int(v), 2 ** 30, int(shift[c])) for v in acc[o, c]] for c in range(3)]
+                     for o in range(2)])
+    assert np.array_equal(got.astype(np.int64), np.clip(want, -128, 127))
+    assert not np.array_equal(got, ref.requantize(acc, ref.Requant(mult, shift)))
+    a = rng.integers(-3, 4, (5, 8)).astype(np.int8)
+    w = rng.integers(-3, 4, (3, 8)).astype(np.int8)
+    raw = ref.qdense(a, 0, w)
+    got = ref.qdense(a, 0, w, None, ref.I32, rq)
+    want = np.array([[exact_half_away(int(raw[m, n]), 2 ** 30, int(shift[n])) for n in range(3)] for m in range(5)])
+    assert np.array_equal(got.astype(np.int64), want)
+    with pytest.raises(Exception):
+        ref.requantize(acc, ref.Requant(mult, shift, rounding=2))
