@@ -66,10 +66,10 @@ def main():
     def to_dev(x):
         return torch.from_numpy(np.ascontiguousarray(x)).to(dev)
 
-    def rq_of(mult, shift, out_u8=False, z_out=0, clip=None):
+    def rq_of(mult, shift, out_u8=False, z_out=0, clip=None, rounding=0):
         q = hago.QType(hago.U8 if out_u8 else hago.I8, 8, not out_u8, z_out)
         lo, hi = clip if clip else (None, None)
-        return hago.Requant(to_dev(mult), to_dev(shift), q, lo, hi)
+        return hago.Requant(to_dev(mult), to_dev(shift), q, lo, hi, rounding=rounding)
 
     def event_time_ms(fn, iters, warmup):
         """Average milliseconds per call of fn over `iters` back-to-back calls (HIP events on
@@ -359,6 +359,26 @@ def extra_ops(torch, hago, datagen, to_dev, rq_of, event_time_ms, only):
                                                prepare=True), nb)
         record("requantize_i32", event_time_ms(f, 60, 6), bytes_=nb, bound="hbm",
                note="i32 [32,144,3136] -> i8, 5 B/elem")
+        del f
+
+    # ---- the second tie rule (halves away from zero) runs through the general code paths
+    if want("requantize_i32_half_away"):
+        acc0 = torch.randint(-2 ** 20, 2 ** 20, (32, 144, 3136), dtype=torch.int32, device=dev)
+        rq = rq_of(c4["mult_dw"], c4["shift_dw"], rounding=hago.ROUND_HALF_AWAY)
+        nb = acc0.numel() * 5
+        f = rotating(lambda i: hago.requantize(acc0.clone(), rq,
+                                               out=torch.empty(acc0.shape, dtype=torch.int8, device=dev),
+                                               prepare=True), nb)
+        record("requantize_i32_half_away", event_time_ms(f, 60, 6), bytes_=nb, bound="hbm",
+               note="i32 [32,144,3136] -> i8, 5 B/elem, ties away from zero")
+        del f
+    if want("dense_c5_ffn1_half_away"):
+        c = datagen.config5_layer(2, 4096)
+        rq = rq_of(c["mult"], c["shift"], rounding=hago.ROUND_HALF_AWAY)
+        f = hago.qdense(to_dev(c["a"]), hago.QType(hago.U8, 8, False, c["z_a"]), to_dev(c["w"]),
+                        hago.QType(hago.I8), to_dev(c["bias"]), hago.I32, rq, prepare=True)
+        record("dense_c5_ffn1_half_away", event_time_ms(f, 100, 10), ops=2.0 * 4096 * 3072 * 768,
+               bound="mfma", note="config 5 layer 768 -> 3072 with ties away from zero (general epilogue)")
         del f
 
     # ---- config 1 (as specified and scaled)

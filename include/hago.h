@@ -96,14 +96,22 @@ typedef struct {
  *     r   = floor(acc * multiplier[c] / 2^(31 + shift[c]) + 1/2)
  *     out = clip(r + out.zero_point, clip_lo, clip_hi)  cast to out.dtype
  * evaluated exactly in 64-bit integers (single rounding, ties toward
- * +infinity).  ReLU / ReLU6 are expressed through clip_lo / clip_hi in the
- * output's quantized domain (Sec. 6.1). */
+ * +infinity).  With rounding == HAGO_ROUND_HALF_AWAY, r is instead the nearest
+ * integer to acc * multiplier[c] / 2^(31 + shift[c]) with halves away from
+ * zero (the two tie rules of the compiler stack the paper generates code
+ * with; the results differ, by one, exactly on negative ties).  The kernels
+ * tuned for speed implement the first rule; the second runs through each
+ * operator's general code path.  ReLU / ReLU6 are expressed through clip_lo /
+ * clip_hi in the output's quantized domain (Sec. 6.1). */
+typedef enum { HAGO_ROUND_UPWARD = 0, HAGO_ROUND_HALF_AWAY = 1 } hago_rounding;
+
 typedef struct {
   const int32_t* multiplier; /* device, [channels] or [1]; Q31                  */
   const int32_t* shift;      /* device, [channels] or [1]; 0..31                */
   int32_t per_channel;       /* 0: entry 0 serves every channel; 1: one each    */
   hago_qtype out;            /* dtype HAGO_I8 or HAGO_U8; bits; zero_point      */
   int32_t clip_lo, clip_hi;  /* inclusive; within out's effective-bit range     */
+  int32_t rounding;          /* HAGO_ROUND_UPWARD or HAGO_ROUND_HALF_AWAY       */
 } hago_requant;
 
 /*

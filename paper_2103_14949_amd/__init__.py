@@ -8,5 +8,5 @@ streams.
 from .binding import (  # noqa: F401
     HagoError, QType, Requant, Prepared, lib, library_path,
     simquant, simquant_batched, requantize, qdense, qconv2d, absmax, quantize, dequantize, simquant_codes,
-    U8, I8, I16, I32, F32, NCHW, NHWC, STRICT_ACC16,
+    U8, I8, I16, I32, F32, NCHW, NHWC, STRICT_ACC16, ROUND_UPWARD, ROUND_HALF_AWAY,
 )

@@ -12,6 +12,7 @@ import os
 U8, I8, I16, I32, F32 = 0, 1, 2, 3, 4
 NCHW, NHWC = 0, 1
 STRICT_ACC16 = 1
+ROUND_UPWARD, ROUND_HALF_AWAY = 0, 1   # hago_rounding
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libhago.so")
@@ -26,7 +27,7 @@ class _QType(C.Structure):
 
 class _Requant(C.Structure):
     _fields_ = [("multiplier", C.c_void_p), ("shift", C.c_void_p), ("per_channel", C.c_int32),
-                ("out", _QType), ("clip_lo", C.c_int32), ("clip_hi", C.c_int32)]
+                ("out", _QType), ("clip_lo", C.c_int32), ("clip_hi", C.c_int32), ("rounding", C.c_int32)]
 
 
 class HagoError(RuntimeError):
@@ -100,7 +101,8 @@ class QType:
 class Requant:
     """Requantize parameters; multiplier/shift are int32 device tensors."""
 
-    def __init__(self, multiplier, shift, out: QType, clip_lo=None, clip_hi=None, per_channel=None):
+    def __init__(self, multiplier, shift, out: QType, clip_lo=None, clip_hi=None, per_channel=None,
+                 rounding=0):
         self.multiplier = multiplier
         self.shift = shift
         self.out = out
@@ -109,10 +111,11 @@ class Requant:
         self.clip_lo = lo if clip_lo is None else int(clip_lo)
         self.clip_hi = hi if clip_hi is None else int(clip_hi)
         self.per_channel = int(multiplier.numel() > 1) if per_channel is None else int(per_channel)
+        self.rounding = int(rounding)   # ROUND_UPWARD or ROUND_HALF_AWAY
 
     def c(self):
         return _Requant(self.multiplier.data_ptr(), self.shift.data_ptr(), self.per_channel,
-                        self.out.c(), self.clip_lo, self.clip_hi)
+                        self.out.c(), self.clip_lo, self.clip_hi, self.rounding)
 
 
 def _torch():

@@ -58,6 +58,7 @@ hago_status check_requant(const hago_requant* rq, RequantArgs* out) {
   if (!rq->multiplier || !rq->shift) return HAGO_ERR_NULL;
   if (rq->out.dtype != HAGO_I8 && rq->out.dtype != HAGO_U8) return HAGO_ERR_DTYPE;
   if (rq->per_channel != 0 && rq->per_channel != 1) return HAGO_ERR_PARAM;
+  if (rq->rounding != HAGO_ROUND_UPWARD && rq->rounding != HAGO_ROUND_HALF_AWAY) return HAGO_ERR_PARAM;
   hago_status s = check_qtype(rq->out, true);
   if (s != HAGO_OK) return s;
   int64_t blo, bhi;
@@ -70,6 +71,7 @@ hago_status check_requant(const hago_requant* rq, RequantArgs* out) {
   out->z_out = rq->out.zero_point;
   out->clip_lo = rq->clip_lo;
   out->clip_hi = rq->clip_hi;
+  out->half_away = rq->rounding == HAGO_ROUND_HALF_AWAY;
   return HAGO_OK;
 }
 

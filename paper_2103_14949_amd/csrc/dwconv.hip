@@ -54,7 +54,7 @@ __device__ __forceinline__ int32_t wrap_acc(int32_t acc, int acc16) {
 __device__ __forceinline__ void store_one(const DwArgs& p, int64_t idx, int32_t acc, int32_t m,
                                           int32_t sh) {
   if (p.out_mode == 0)
-    static_cast<uint8_t*>(p.out)[idx] = (uint8_t)requant_one(acc, m, sh, p.rs);
+    static_cast<uint8_t*>(p.out)[idx] = (uint8_t)requant_general(acc, m, sh, p.rs);
   else if (p.out_mode == 1)
     static_cast<int32_t*>(p.out)[idx] = acc;
   else
@@ -182,8 +182,8 @@ __global__ __launch_bounds__(kThreads) void dw_plane3x3_kernel(DwArgs p, int32_t
     if (vec_io) {
       if (p.out_mode == 0) {
         reinterpret_cast<uint32_t*>(p.out)[o >> 2] =
-            pack4(requant_one(acc[0], m, sh, p.rs), requant_one(acc[1], m, sh, p.rs),
-                  requant_one(acc[2], m, sh, p.rs), requant_one(acc[3], m, sh, p.rs));
+            pack4(requant_general(acc[0], m, sh, p.rs), requant_general(acc[1], m, sh, p.rs),
+                  requant_general(acc[2], m, sh, p.rs), requant_general(acc[3], m, sh, p.rs));
       } else if (p.out_mode == 1) {
         reinterpret_cast<int4*>(p.out)[o >> 2] = make_int4(acc[0], acc[1], acc[2], acc[3]);
       } else {
@@ -545,7 +545,7 @@ hipError_t launch_qconv_depthwise(const GemmArgs& a, const ConvGeom& cg, hipStre
   p.mult = a.rq.multiplier;
   p.shift = a.rq.shift;
   p.per_channel = a.rq.per_channel;
-  p.rs = RequantScalars{a.rq.z_out, a.rq.clip_lo - a.rq.z_out, a.rq.clip_hi - a.rq.z_out};
+  p.rs = RequantScalars{a.rq.z_out, a.rq.clip_lo - a.rq.z_out, a.rq.clip_hi - a.rq.z_out, a.rq.half_away};
 
   const int64_t total = (int64_t)cg.B * cg.O * cg.OH * cg.OW;
   if (total == 0) return hipSuccess;
@@ -564,7 +564,9 @@ hipError_t launch_qconv_depthwise(const GemmArgs& a, const ConvGeom& cg, hipStre
   // the register kernel: bands of 4 * rpc rows, one wavefront each
   const int32_t rpc = (cg.H + 3) / 4 < 16 ? (cg.H + 3) / 4 : 16;
   const int64_t nband_r = (cg.H + 4 * rpc - 1) / (4 * rpc);
-  if (plane_ok && cg.W <= 64 && vec_io && (reinterpret_cast<uintptr_t>(a.wgt) & 3u) == 0 &&
+  // (the register kernel and the wavefront-per-plane kernel round ties toward +infinity only)
+  const bool upward = !(a.has_rq && a.rq.half_away);
+  if (upward && plane_ok && cg.W <= 64 && vec_io && (reinterpret_cast<uintptr_t>(a.wgt) & 3u) == 0 &&
       cg.B <= 65535 && nband_r <= 65535 && (int64_t)cg.H * cg.W * 4 < (1ll << 31) &&
       (int64_t)cg.C * 9 < (1ll << 30)) {
     auto kern = p.out_mode == 1 ? dw_rows3x3_kernel<1, false>
@@ -572,7 +574,7 @@ hipError_t launch_qconv_depthwise(const GemmArgs& a, const ConvGeom& cg, hipStre
               : p.acc16 ? dw_rows3x3_kernel<0, true> : dw_rows3x3_kernel<0, false>;
     hipLaunchKernelGGL(kern, dim3((unsigned)((cg.C + 3) / 4), (unsigned)cg.B, (unsigned)nband_r), dim3(kThreads),
                        0, st, p, rpc);
-  } else if (plane_ok && cg.W <= 64 && wave_lds <= (size_t)kMaxLdsBytes && planes < (1ll << 32)) {
+  } else if (upward && plane_ok && cg.W <= 64 && wave_lds <= (size_t)kMaxLdsBytes && planes < (1ll << 32)) {
     const uint32_t w4 = vec_io ? (uint32_t)cg.W / 4 : 1u;
     const uint32_t inv_w4 = w4 > 1 ? (uint32_t)(((1ull << 32) + w4 - 1) / w4) : 0u;  // unused for w4 == 1
     hipLaunchKernelGGL(dw_wave3x3_kernel, dim3((unsigned)((planes + 3) / 4)), dim3(kThreads),

@@ -164,6 +164,13 @@ __global__ __launch_bounds__(kThreads) void simquant_flat_kernel(
   }
 }
 
+// AWAY: the launch's tie rule is halves away from zero (the general form); else the plain one.
+template <bool AWAY>
+__device__ __forceinline__ int32_t requant_pick(int32_t acc, int32_t mult, int32_t sh, const RequantScalars& rs) {
+  if constexpr (AWAY) return requant_general(acc, mult, sh, rs);
+  else return requant_one(acc, mult, sh, rs);
+}
+
 template <typename AccT>
 __device__ __forceinline__ int32_t load_acc(const AccT* p, int64_t i) {
   return (int32_t)p[i];
@@ -171,7 +178,7 @@ __device__ __forceinline__ int32_t load_acc(const AccT* p, int64_t i) {
 
 // rows: 4 accumulators -> 4 output bytes per step, 128-bit loads for int32; U steps per lane
 // and job with all loads issued first, nontemporal as above.
-template <typename AccT, int U>
+template <typename AccT, int U, bool AWAY>
 __global__ __launch_bounds__(kThreads) void requant_rows_kernel(
     const AccT* __restrict__ acc, uint32_t* __restrict__ out, int64_t rows, int32_t channels,
     int64_t inner_vec, int32_t nseg, int32_t seg_len, const int32_t* __restrict__ mult,
@@ -203,8 +210,8 @@ __global__ __launch_bounds__(kThreads) void requant_rows_kernel(
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         if (vb + u * kThreads < v1) {
-          const uint32_t r = pack4(requant_one((int32_t)q[u].x, m, sh, rs), requant_one((int32_t)q[u].y, m, sh, rs),
-                                   requant_one((int32_t)q[u].z, m, sh, rs), requant_one((int32_t)q[u].w, m, sh, rs));
+          const uint32_t r = pack4(requant_pick<AWAY>((int32_t)q[u].x, m, sh, rs), requant_pick<AWAY>((int32_t)q[u].y, m, sh, rs),
+                                   requant_pick<AWAY>((int32_t)q[u].z, m, sh, rs), requant_pick<AWAY>((int32_t)q[u].w, m, sh, rs));
           __builtin_nontemporal_store(r, orow + vb + u * kThreads);
         }
       }
@@ -213,7 +220,7 @@ __global__ __launch_bounds__(kThreads) void requant_rows_kernel(
 }
 
 // channel-last (inner == 1) with channels % 4 == 0: 4 consecutive channels.
-template <typename AccT>
+template <typename AccT, bool AWAY>
 __global__ __launch_bounds__(kThreads) void requant_lastaxis_kernel(
     const AccT* __restrict__ acc, uint32_t* __restrict__ out, int64_t total_vec,
     int32_t channels_vec, const int4* __restrict__ mult, const int4* __restrict__ shift,
@@ -231,12 +238,12 @@ __global__ __launch_bounds__(kThreads) void requant_lastaxis_kernel(
       const short4 q = reinterpret_cast<const short4*>(acc)[v];
       a0 = q.x; a1 = q.y; a2 = q.z; a3 = q.w;
     }
-    out[v] = pack4(requant_one(a0, m.x, sh.x, rs), requant_one(a1, m.y, sh.y, rs),
-                   requant_one(a2, m.z, sh.z, rs), requant_one(a3, m.w, sh.w, rs));
+    out[v] = pack4(requant_pick<AWAY>(a0, m.x, sh.x, rs), requant_pick<AWAY>(a1, m.y, sh.y, rs),
+                   requant_pick<AWAY>(a2, m.z, sh.z, rs), requant_pick<AWAY>(a3, m.w, sh.w, rs));
   }
 }
 
-template <typename AccT>
+template <typename AccT, bool AWAY>
 __global__ __launch_bounds__(kThreads) void requant_flat_kernel(
     const AccT* __restrict__ acc, uint8_t* __restrict__ out, int64_t total, int64_t inner,
     int64_t channels, const int32_t* __restrict__ mult, const int32_t* __restrict__ shift,
@@ -244,7 +251,7 @@ __global__ __launch_bounds__(kThreads) void requant_flat_kernel(
   const int64_t stride = (int64_t)gridDim.x * kThreads;
   for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += stride) {
     const int64_t c = per_channel ? (i / inner) % channels : 0;
-    out[i] = (uint8_t)requant_one(load_acc(acc, i), mult[c], shift[c], rs);
+    out[i] = (uint8_t)requant_pick<AWAY>(load_acc(acc, i), mult[c], shift[c], rs);
   }
 }
 
@@ -617,7 +624,7 @@ static hipError_t launch_requantize_t(const AccT* acc, int64_t outer, int64_t ch
                                       hipStream_t st) {
   const int64_t total = outer * channels * inner;
   if (total == 0) return hipSuccess;
-  const RequantScalars rs{rq.z_out, rq.clip_lo - rq.z_out, rq.clip_hi - rq.z_out};
+  const RequantScalars rs{rq.z_out, rq.clip_lo - rq.z_out, rq.clip_hi - rq.z_out, rq.half_away};
   const int pc = rq.per_channel;
   int64_t rows = pc ? outer * channels : 1;
   int64_t row_len = pc ? inner : total;
@@ -628,20 +635,25 @@ static hipError_t launch_requantize_t(const AccT* acc, int64_t outer, int64_t ch
     const int u = e ? std::atoi(e) : kVecPerLane;
     int32_t nseg, seg_len;
     split_row(inner_vec, u, &nseg, &seg_len);
-    auto kern = u == 1 ? requant_rows_kernel<AccT, 1> : (u == 4 ? requant_rows_kernel<AccT, 4> : requant_rows_kernel<AccT, 2>);
+    auto kern = rq.half_away ? requant_rows_kernel<AccT, kVecPerLane, true>
+              : u == 1 ? requant_rows_kernel<AccT, 1, false>
+              : (u == 4 ? requant_rows_kernel<AccT, 4, false> : requant_rows_kernel<AccT, 2, false>);
+    if (rq.half_away) split_row(inner_vec, kVecPerLane, &nseg, &seg_len);
     hipLaunchKernelGGL(kern, dim3(grid_for(rows * nseg)), dim3(kThreads), 0, st,
                        acc, reinterpret_cast<uint32_t*>(out), rows, (int32_t)(pc ? channels : 1),
                        inner_vec, nseg, seg_len, rq.multiplier, rq.shift, pc, rs);
   } else if (pc && inner == 1 && channels % 4 == 0 && io_aligned && aligned16(rq.multiplier) &&
              aligned16(rq.shift)) {
     const int64_t total_vec = total / 4;
-    hipLaunchKernelGGL(requant_lastaxis_kernel<AccT>,
+    auto kern = rq.half_away ? requant_lastaxis_kernel<AccT, true> : requant_lastaxis_kernel<AccT, false>;
+    hipLaunchKernelGGL(kern,
                        dim3(grid_for((total_vec + kThreads - 1) / kThreads)), dim3(kThreads), 0, st,
                        acc, reinterpret_cast<uint32_t*>(out), total_vec, (int32_t)(channels / 4),
                        reinterpret_cast<const int4*>(rq.multiplier),
                        reinterpret_cast<const int4*>(rq.shift), rs);
   } else {
-    hipLaunchKernelGGL(requant_flat_kernel<AccT>, dim3(grid_for((total + kThreads - 1) / kThreads)),
+    auto kern = rq.half_away ? requant_flat_kernel<AccT, true> : requant_flat_kernel<AccT, false>;
+    hipLaunchKernelGGL(kern, dim3(grid_for((total + kThreads - 1) / kThreads)),
                        dim3(kThreads), 0, st, acc, reinterpret_cast<uint8_t*>(out), total, inner,
                        channels, rq.multiplier, rq.shift, pc, rs);
   }

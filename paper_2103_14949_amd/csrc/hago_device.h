@@ -14,6 +14,7 @@ struct RequantScalars {
   int32_t z_out;
   int32_t lo_rel;  // clip_lo - z_out
   int32_t hi_rel;  // clip_hi - z_out
+  int32_t half_away;  // tie rule: 0 toward +infinity, 1 away from zero (general code paths only)
 };
 
 // r = floor(acc * mult / 2^(31 + sh) + 1/2), exact in 64-bit integers
@@ -34,6 +35,18 @@ __device__ __forceinline__ int32_t med3(int32_t x, int32_t lo, int32_t hi) {
 __device__ __forceinline__ int32_t requant_one(int32_t acc, int32_t mult, int32_t sh,
                                                const RequantScalars& rs) {
   const int32_t r = rounding_mul_shift(acc, mult, sh);
+  return med3(r, rs.lo_rel, rs.hi_rel) + rs.z_out;
+}
+
+// The general form, with the launch's tie rule.  Nearest with halves away from zero differs
+// from ties toward +infinity exactly where the product is negative and lies on a tie (the low
+// 31 + sh bits of product + rounding term are then all zero), and there by one.
+__device__ __forceinline__ int32_t requant_general(int32_t acc, int32_t mult, int32_t sh,
+                                                   const RequantScalars& rs) {
+  const int64_t rnd = (int64_t)1 << (30 + sh);
+  const int64_t p = (int64_t)acc * (int64_t)mult + rnd;
+  int32_t r = (int32_t)(p >> (31 + sh));
+  if (rs.half_away && p < rnd && (p & ((rnd << 1) - 1)) == 0) r -= 1;
   return med3(r, rs.lo_rel, rs.hi_rel) + rs.z_out;
 }
 

@@ -13,6 +13,7 @@ struct RequantArgs {
   int32_t per_channel;
   int32_t out_unsigned;  // 1: uint8 container, 0: int8
   int32_t z_out, clip_lo, clip_hi;
+  int32_t half_away;  // 1: nearest with halves away from zero; 0: ties toward +infinity
 };
 
 // fp32 simulated quantize over [outer, channels, inner].

@@ -355,6 +355,7 @@ hipError_t launch_nt(const PwArgs& p, hipStream_t st) {
 bool try_qconv_pointwise_nchw(const GemmArgs& a, const ConvGeom& cg, hipStream_t st, hipError_t* err) {
   const int64_t HW = (int64_t)cg.H * cg.W;
   const size_t esz = a.has_rq ? 1 : (a.acc16 ? 2 : 4);
+  if (a.has_rq && a.rq.half_away) return false;  // ties toward +infinity only
   if (cg.nhwc || cg.KH != 1 || cg.KW != 1 || cg.stride_h != 1 || cg.stride_w != 1 || cg.pad_h != 0 ||
       cg.pad_w != 0 || cg.C % 16 != 0 || HW % 4 != 0 || cg.O > 128 || (int64_t)cg.C * HW >= (1ll << 31) ||
       (int64_t)cg.O * cg.C >= (1ll << 31) || (reinterpret_cast<uintptr_t>(a.wgt) & 15u) != 0 ||
@@ -374,7 +375,7 @@ bool try_qconv_pointwise_nchw(const GemmArgs& a, const ConvGeom& cg, hipStream_t
   p.act_xor4 = a.act_unsigned ? 0x80808080u : 0u;
   p.corr_coef = (a.act_unsigned ? 128 : 0) - a.act_zero_point;
   p.per_channel = a.rq.per_channel;
-  p.rs = RequantScalars{a.rq.z_out, a.rq.clip_lo - a.rq.z_out, a.rq.clip_hi - a.rq.z_out};
+  p.rs = RequantScalars{a.rq.z_out, a.rq.clip_lo - a.rq.z_out, a.rq.clip_hi - a.rq.z_out, a.rq.half_away};
   if (p.tiles == 0 || p.tiles / 4 >= (1ll << 31)) return false;
   if (a.has_rq) *err = a.acc16 ? launch_nt<0, true>(p, st) : launch_nt<0, false>(p, st);
   else *err = a.acc16 ? launch_nt<2, true>(p, st) : launch_nt<1, false>(p, st);

@@ -66,7 +66,7 @@ inline QgemmParams make_qgemm_params(const GemmArgs& a, const ConvGeom* cg) {
   p.act_xor4 = a.act_unsigned ? 0x80808080u : 0u;
   p.corr_coef = (a.act_unsigned ? 128 : 0) - a.act_zero_point;
   p.pad_byte = ((uint32_t)a.act_zero_point ^ (a.act_unsigned ? 0x80u : 0u)) & 0xffu;
-  p.rs = RequantScalars{a.rq.z_out, a.rq.clip_lo - a.rq.z_out, a.rq.clip_hi - a.rq.z_out};
+  p.rs = RequantScalars{a.rq.z_out, a.rq.clip_lo - a.rq.z_out, a.rq.clip_hi - a.rq.z_out, a.rq.half_away};
   if (cg) p.g = *cg;
 #ifdef HAGO_PHASE_TIMING
   {
@@ -436,7 +436,8 @@ __device__ __forceinline__ void qgemm_epilogue(const QgemmParams& p, v16i (&acc)
   const int P_ext = ACT_ON_P ? p.M : p.N;
   const int Q_ext = ACT_ON_P ? p.N : p.M;
   const int ohw = p.g.OH * p.g.OW;
-  const bool fast = p.vec_out;  // groups of four along the packed axis are aligned stores
+  // groups of four along the packed axis are aligned stores; ties toward +infinity
+  const bool fast = p.vec_out && !p.rs.half_away;
 
   if (fast) {
     // interior tiles (block-uniform) run without the per-store bounds checks
@@ -477,7 +478,7 @@ __device__ __forceinline__ void qgemm_epilogue(const QgemmParams& p, v16i (&acc)
           for (int x = 0; x < TQ; ++x) raw = (x == tj) ? acc[ti][x][g4 * 4 + r] : raw;
           int32_t a = raw + s_corr[ci];
           if (p.acc16) a = (int32_t)(int16_t)a;
-          if (p.has_rq) a = requant_one(a, s_mult[ci], s_shift[ci], p.rs);
+          if (p.has_rq) a = requant_general(a, s_mult[ci], s_shift[ci], p.rs);
           v[r] = a;
         }
         if (j >= Q_ext || i >= P_ext) continue;

@@ -23,16 +23,17 @@ def act_qtype(a, z, bits=8, is_signed=None):
     return hago.QType(dt, bits, (dt == hago.I8) if is_signed is None else is_signed, z)
 
 
-def gpu_requant(mult, shift, out_u8=False, z_out=0, clip=None, bits=8):
+def gpu_requant(mult, shift, out_u8=False, z_out=0, clip=None, bits=8, rounding=0):
     q = hago.QType(hago.U8 if out_u8 else hago.I8, bits, not out_u8, z_out)
     lo, hi = clip if clip is not None else (None, None)
-    return hago.Requant(dev(np.asarray(mult, np.int32)), dev(np.asarray(shift, np.int32)), q, lo, hi)
+    return hago.Requant(dev(np.asarray(mult, np.int32)), dev(np.asarray(shift, np.int32)), q, lo, hi,
+                        rounding=rounding)
 
 
-def ref_requant(mult, shift, out_u8=False, z_out=0, clip=None):
+def ref_requant(mult, shift, out_u8=False, z_out=0, clip=None, rounding=0):
     lo, hi = clip if clip is not None else ((0, 255) if out_u8 else (-128, 127))
     return ref.Requant(mult, shift, out_dtype=ref.U8 if out_u8 else ref.I8, out_zero_point=z_out,
-                       clip_lo=lo, clip_hi=hi)
+                       clip_lo=lo, clip_hi=hi, rounding=rounding)
 
 
 def assert_same(got, want, what=""):

@@ -39,8 +39,8 @@ def test_status_strings(L):
 BAD = 0x1000  # a non-null pointer that is never dereferenced: validation fails first
 
 
-def _rq(out_dtype=hago.I8, bits=8, signed=1, z=0, lo=-128, hi=127, mult=BAD, shift=BAD, pc=1):
-    return binding._Requant(mult, shift, pc, binding._QType(out_dtype, bits, signed, z), lo, hi)
+def _rq(out_dtype=hago.I8, bits=8, signed=1, z=0, lo=-128, hi=127, mult=BAD, shift=BAD, pc=1, rounding=0):
+    return binding._Requant(mult, shift, pc, binding._QType(out_dtype, bits, signed, z), lo, hi, rounding)
 
 
 def _qt(dt, bits=8, signed=None, z=0):
@@ -68,7 +68,8 @@ def test_qdense_argument_errors(L):
     # requantize struct errors
     for rq, code in ((_rq(mult=None), 1), (_rq(out_dtype=hago.I16, bits=16), 3), (_rq(lo=5, hi=4), 4),
                      (_rq(lo=-129), 4), (_rq(out_dtype=hago.U8, signed=0, lo=0, hi=256), 4),
-                     (_rq(bits=4, lo=-8, hi=8), 4), (_rq(pc=2), 5), (_rq(z=200), 4)):
+                     (_rq(bits=4, lo=-8, hi=8), 4), (_rq(pc=2), 5), (_rq(z=200), 4),
+                     (_rq(rounding=2), 5), (_rq(rounding=-1), 5)):
         assert call(BAD, u8, BAD, i8, None, 4, 4, 4, hago.I32, C.byref(rq), BAD, 0, None) == code
     # strict int16 accumulation bound: K * Amax * Wmax <= 32767
     a4, w4 = _qt(hago.I8, 4, 0), _qt(hago.I8, 4, 1)        # 0..15 x -8..7 -> 120 per term
