@@ -349,6 +349,20 @@ def extra_ops(torch, hago, datagen, to_dev, rq_of, event_time_ms, only):
                bytes_=nb, bound="hbm", note="1x1 conv 144->24 on MFMA, 168 B/pixel")
         del f
 
+    # ---- the same depthwise layer at stride 2 (a downsampling layer of the same network)
+    if want("depthwise_c4_s2"):
+        a0 = to_dev(c4["a"])
+        w, rq = to_dev(c4["w_dw"]), rq_of(c4["mult_dw"], c4["shift_dw"])
+        o_shape = (32, 144, 28, 28)
+        nb = a0.numel() + 32 * 144 * 28 * 28
+        f = rotating(lambda i: hago.qconv2d(a0.clone(), hago.QType(hago.I8), w, hago.QType(hago.I8), None, hago.NCHW,
+                                            (2, 2), (1, 1), 144, hago.I32, rq,
+                                            out=torch.empty(o_shape, dtype=torch.int8, device=dev),
+                                            prepare=True), nb)
+        record("depthwise_c4_s2", event_time_ms(f, 100, 10), ops=2.0 * 32 * 144 * 28 * 28 * 9,
+               bytes_=nb, bound="hbm", note="i8 [32,144,56,56] 3x3 stride 2, 1.25 B/input")
+        del f
+
     # ---- standalone requantize
     if want("requantize_i32"):
         acc0 = torch.randint(-2 ** 20, 2 ** 20, (32, 144, 3136), dtype=torch.int32, device=dev)

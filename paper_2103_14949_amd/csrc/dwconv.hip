@@ -527,6 +527,174 @@ __global__ __launch_bounds__(kThreads) void dw_rows3x3_kernel(DwArgs p, int32_t 
     rows.template operator()<false>();
 }
 
+// The same register scheme for stride 2 (NCHW 3x3, pad 1, W <= 64, W % 4 == 0): the MobileNet
+// downsampling layers.  Lane (q, rc) still loads the dword of input columns 4q .. 4q+3 of each
+// input row; it yields the two outputs 2q (columns 4q-1 .. 4q+1: one byte from the left
+// neighbour, by DPP) and 2q+1 (columns 4q+1 .. 4q+3), so no right neighbour is needed.  Output
+// row oy reads input rows 2oy-1 .. 2oy+1; consecutive output rows share one input row, so a
+// lane with rpc output rows loads 2 * rpc + 1 input rows.  The two 8-bit results of a lane are
+// merged with its neighbour's into one dword store when output rows are dword-aligned
+// (W % 8 == 0), else stored as 16 bits.
+// MODE / ACC16 as above.
+template <int MODE, bool ACC16>
+__global__ __launch_bounds__(kThreads) void dw_rows3x3s2_kernel(DwArgs p, int32_t rpc) {
+  // grid: x = groups of four channels, y = image, z = band of 4 * rpc output rows
+  const ConvGeom& g = p.g;
+  const int H = g.H, W = g.W, OH = g.OH, OW = g.OW;
+  const int lane = threadIdx.x & 63;
+  const int c = (int)(blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6));
+  if (c >= g.C) return;  // wavefront-uniform; the kernel has no barrier
+  const int64_t plane = (int64_t)blockIdx.y * g.C + c;
+  const int band = (int)blockIdx.z;
+  constexpr uint32_t kOob = 0x80000000u;
+  constexpr int kEsz = MODE == 0 ? 1 : (MODE == 1 ? 4 : 2);
+  constexpr int kPass = 16;  // most output rows per lane
+
+  const int q = lane & 15;
+  const int rc = lane >> 4;
+  const int oy0 = (band * 4 + rc) * rpc;  // first output row of the lane
+  const int y0 = 2 * oy0 - 1;             // its first input row
+  const bool has_strip = (q << 2) < W;
+  const uint32_t lane_off = has_strip ? (uint32_t)(q << 2) : kOob;
+  const uint32_t x4 = p.act_xor * 0x01010101u;
+  const uint32_t pad4 = (((uint32_t)p.z_a ^ p.act_xor) & 0xffu) * 0x01010101u;
+  const int64_t ibytes = (int64_t)H * W, obytes = (int64_t)OH * OW * kEsz;
+  const __amdgpu_buffer_rsrc_t rin = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint8_t*>(p.act) + plane * ibytes, 0, (int)ibytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rout = __builtin_amdgcn_make_buffer_rsrc(
+      static_cast<uint8_t*>(p.out) + plane * obytes, 0, (int)obytes, 0x00020000);
+
+  // input row j of the lane is image row y0 + j; out-of-image rows and strip-less lanes read 0
+  // through the descriptor's range check and become the zero point's byte under the flip mask
+  uint32_t flip_lane = has_strip ? x4 : pad4;
+  asm volatile("" : "+v"(flip_lane));
+  uint32_t d[2 * kPass + 1];
+  {
+    const uint32_t off0 = lane_off + (uint32_t)(y0 * W);
+#pragma unroll
+    for (int j = 0; j < 2 * kPass + 1; ++j) {
+      uint32_t off = off0 + (uint32_t)(j * W);
+      if (j >= 3) off = (j <= 2 * rpc) ? off : kOob;  // uniform: rows the lane does not need
+      d[j] = __builtin_amdgcn_raw_buffer_load_b32(rin, off, 0, 0);
+    }
+  }
+  const int rows_in = H - y0;  // rows 1 .. rows_in - 1 of the lane lie in the image (y0 >= -1)
+  auto row = [&](int j) {
+    uint32_t flip = (j == 0 ? y0 >= 0 : j < rows_in) ? flip_lane : pad4;
+    asm volatile("" : "+v"(flip));
+    return d[j] ^ flip;
+  };
+
+  // channel constants through scalar loads, as in the stride-1 kernel
+  const uint32_t wb = (uint32_t)c * 9u;
+  const int pc = p.per_channel ? c : 0;
+  const uint32_t* wp = reinterpret_cast<const uint32_t*>(p.wgt + (wb & ~3u));
+  const uint32_t* bp = p.bias ? reinterpret_cast<const uint32_t*>(p.bias + c) : wp;
+  const uint32_t* mp = MODE == 0 ? reinterpret_cast<const uint32_t*>(p.mult + pc) : wp;
+  const uint32_t* sp = MODE == 0 ? reinterpret_cast<const uint32_t*>(p.shift + pc) : wp;
+  uint64_t d01;
+  uint32_t d2, bias_raw, m_raw, sh_raw;
+  asm volatile(
+      "s_load_dwordx2 %0, %5, 0x0\n\t"
+      "s_load_dword %1, %5, 0x8\n\t"
+      "s_load_dword %2, %6, 0x0\n\t"
+      "s_load_dword %3, %7, 0x0\n\t"
+      "s_load_dword %4, %8, 0x0\n\t"
+      "s_waitcnt lgkmcnt(0)"
+      : "=&s"(d01), "=&s"(d2), "=&s"(bias_raw), "=&s"(m_raw), "=&s"(sh_raw)
+      : "s"(wp), "s"(bp), "s"(mp), "s"(sp));
+  const uint32_t d0 = (uint32_t)d01, d1 = (uint32_t)(d01 >> 32);
+  const uint32_t o8 = (wb & 3u) * 8u;
+  const uint32_t w03 = (uint32_t)((((uint64_t)d1 << 32) | d0) >> o8);  // weights 0..3
+  const uint32_t w47 = (uint32_t)((((uint64_t)d2 << 32) | d1) >> o8);  // weights 4..7
+  const uint32_t w8 = (d2 >> o8) & 0xffu;
+  int32_t wrow[3];
+  wrow[0] = (int32_t)(w03 & 0xffffffu);
+  wrow[1] = (int32_t)((w03 >> 24) | ((w47 & 0xffffu) << 8));
+  wrow[2] = (int32_t)((w47 >> 16) | (w8 << 16));
+  int32_t wsum = 0;
+#pragma unroll
+  for (int ky = 0; ky < 3; ++ky)
+#pragma unroll
+    for (int kx = 0; kx < 3; ++kx) wsum += (int32_t)(int8_t)(wrow[ky] >> (8 * kx));
+  const int32_t bias = p.bias ? (int32_t)bias_raw : 0;
+  const int32_t m = MODE == 0 ? (int32_t)m_raw : 0;
+  const int32_t sh = MODE == 0 ? (int32_t)sh_raw : 0;
+  const int32_t corr = bias + (p.act_off - p.z_a) * wsum;
+  const int64_t rnd = (int64_t)1 << (30 + sh);
+  const int32_t z = p.rs.z_out;
+
+  // windows of one input row: A = columns 4q-1 .. 4q+2 (output 2q uses its first three bytes,
+  // the fourth meets the zero byte of the packed weights), B = columns 4q+1 .. 4q+3
+  uint32_t left = pad4;  // keeps the zero point in the lane a shift has no source for
+  auto windows = [&](uint32_t d1, uint32_t (&w)[2]) {
+    left = (uint32_t)__builtin_amdgcn_update_dpp((int)left, (int)d1, 0x111, 0xf, 0xf, false);  // row_shr:1
+    w[0] = __builtin_amdgcn_alignbyte(d1, left, 3);
+    w[1] = d1 >> 8;
+  };
+  auto dot4 = [](uint32_t a, int32_t b, int32_t c) {
+    return __builtin_amdgcn_sdot4((int)a, b, c, false);
+  };
+  const bool merge = (OW & 3) == 0;  // output rows start on dwords: even lanes store four results
+  // outputs 2q, 2q+1 of row oy0 + i; out-of-range rows lie beyond the plane (dropped)
+  const uint32_t so0 = has_strip ? (uint32_t)(2 * q + oy0 * OW) * kEsz : kOob;
+  const uint32_t so0_even = (has_strip && (q & 1) == 0) ? so0 : kOob;
+
+  auto rows = [&]<bool FOLD>() {
+    int32_t lo = p.rs.lo_rel + (FOLD ? z : 0), hi = p.rs.hi_rel + (FOLD ? z : 0);
+    asm volatile("" : "+v"(lo), "+v"(hi));
+    const int64_t k64 = FOLD ? (int64_t)corr * m + rnd + ((int64_t)z << (31 + sh)) : rnd;
+    const int32_t init = FOLD ? 0 : corr;
+    uint32_t w[3][2];  // windows of input rows 2i, 2i+1, 2i+2: slot = row % 3 over the unrolled loop
+    windows(row(0), w[0]);
+#pragma unroll
+    for (int i = 0; i < kPass; ++i) {
+      if (i < rpc) {  // uniform
+        // rows 2i (slot a), 2i+1 (slot b), 2i+2 (slot cc); the last is the next output's first
+        const int a = (2 * i) % 3, b = (2 * i + 1) % 3, cc = (2 * i + 2) % 3;
+        windows(row(2 * i + 1), w[b]);
+        windows(row(2 * i + 2), w[cc]);
+        int32_t acc[2];
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+          int32_t v = dot4(w[a][e], wrow[0], init);
+          v = dot4(w[b][e], wrow[1], v);
+          v = dot4(w[cc][e], wrow[2], v);
+          acc[e] = ACC16 ? (int32_t)(int16_t)v : v;
+        }
+        const uint32_t step = (uint32_t)(i * OW * kEsz);
+        if constexpr (MODE == 0) {
+          int32_t r[2];
+#pragma unroll
+          for (int e = 0; e < 2; ++e) {
+            const int64_t pr = (int64_t)acc[e] * (int64_t)m + k64;
+            r[e] = med3((int32_t)(pr >> (31 + sh)), lo, hi) + (FOLD ? 0 : z);
+          }
+          const uint32_t h16 = ((uint32_t)r[0] & 0xffu) | (((uint32_t)r[1] & 0xffu) << 8);
+          if (merge) {
+            const uint32_t nb = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)h16, 0x101, 0xf, 0xf, true);  // row_shl:1
+            __builtin_amdgcn_raw_buffer_store_b32(h16 | (nb << 16), rout, so0_even + (so0_even != kOob ? step : 0u), 0, 0);
+          } else {
+            __builtin_amdgcn_raw_buffer_store_b16((short)h16, rout, so0 + (so0 != kOob ? step : 0u), 0, 0);
+          }
+        } else if constexpr (MODE == 1) {
+          typedef int32_t v2i32 __attribute__((ext_vector_type(2)));
+          __builtin_amdgcn_raw_buffer_store_b64(v2i32{acc[0], acc[1]}, rout, so0 + (so0 != kOob ? step : 0u), 0, 0);
+        } else {
+          __builtin_amdgcn_raw_buffer_store_b32(((uint32_t)acc[0] & 0xffffu) | ((uint32_t)acc[1] << 16), rout,
+                                                so0 + (so0 != kOob ? step : 0u), 0, 0);
+        }
+      }
+    }
+  };
+  const bool fold = MODE == 0 && !ACC16 && sh >= 0 && sh <= 19 && corr >= -(1 << 30) && corr <= (1 << 30) &&
+                    z >= -256 && z <= 255;
+  if (fold)
+    rows.template operator()<true>();
+  else
+    rows.template operator()<false>();
+}
+
 }  // namespace
 
 hipError_t launch_qconv_depthwise(const GemmArgs& a, const ConvGeom& cg, hipStream_t st) {
@@ -564,8 +732,24 @@ hipError_t launch_qconv_depthwise(const GemmArgs& a, const ConvGeom& cg, hipStre
   // the register kernel: bands of 4 * rpc rows, one wavefront each
   const int32_t rpc = (cg.H + 3) / 4 < 16 ? (cg.H + 3) / 4 : 16;
   const int64_t nband_r = (cg.H + 4 * rpc - 1) / (4 * rpc);
-  // (the register kernel and the wavefront-per-plane kernel round ties toward +infinity only)
+  // (the register kernels and the wavefront-per-plane kernel round ties toward +infinity only)
   const bool upward = !(a.has_rq && a.rq.half_away);
+  // stride 2: the register kernel for the downsampling layers
+  const bool s2_ok = !cg.nhwc && cg.KH == 3 && cg.KW == 3 && cg.stride_h == 2 && cg.stride_w == 2 &&
+                     cg.pad_h == 1 && cg.pad_w == 1;
+  const int32_t rpc2 = (cg.OH + 3) / 4 < 16 ? (cg.OH + 3) / 4 : 16;
+  const int64_t nband2 = (cg.OH + 4 * rpc2 - 1) / (4 * rpc2);
+  if (upward && s2_ok && cg.W <= 64 && cg.W % 4 == 0 && (reinterpret_cast<uintptr_t>(a.act) & 3u) == 0 &&
+      (reinterpret_cast<uintptr_t>(a.out) & 7u) == 0 && (reinterpret_cast<uintptr_t>(a.wgt) & 3u) == 0 &&
+      cg.B <= 65535 && nband2 <= 65535 && (int64_t)cg.H * cg.W * 4 < (1ll << 31) &&
+      (int64_t)cg.C * 9 < (1ll << 30)) {
+    auto kern = p.out_mode == 1 ? dw_rows3x3s2_kernel<1, false>
+              : p.out_mode == 2 ? dw_rows3x3s2_kernel<2, true>
+              : p.acc16 ? dw_rows3x3s2_kernel<0, true> : dw_rows3x3s2_kernel<0, false>;
+    hipLaunchKernelGGL(kern, dim3((unsigned)((cg.C + 3) / 4), (unsigned)cg.B, (unsigned)nband2), dim3(kThreads),
+                       0, st, p, rpc2);
+    return hipGetLastError();
+  }
   if (upward && plane_ok && cg.W <= 64 && vec_io && (reinterpret_cast<uintptr_t>(a.wgt) & 3u) == 0 &&
       cg.B <= 65535 && nband_r <= 65535 && (int64_t)cg.H * cg.W * 4 < (1ll << 31) &&
       (int64_t)cg.C * 9 < (1ll << 30)) {

@@ -325,6 +325,15 @@ DW_CASES = [
     (1, 3, 17, 31, 3, 3, (1, 1), (1, 1)),      # width not a multiple of 4
     (1, 6, 12, 12, 5, 5, (1, 1), (2, 2)),
     (1, 2, 8, 300, 3, 3, (1, 1), (1, 1)),
+    # stride 2, pad 1 (the downsampling layers): dword-merged stores (W % 8 == 0) and 16-bit stores,
+    # odd heights, more output rows than one band, widths the register kernel does not take
+    (2, 6, 56, 56, 3, 3, (2, 2), (1, 1)),
+    (1, 3, 28, 28, 3, 3, (2, 2), (1, 1)),
+    (1, 2, 150, 20, 3, 3, (2, 2), (1, 1)),
+    (2, 5, 9, 16, 3, 3, (2, 2), (1, 1)),
+    (1, 4, 7, 64, 3, 3, (2, 2), (1, 1)),
+    (1, 3, 12, 10, 3, 3, (2, 2), (1, 1)),
+    (1, 2, 6, 72, 3, 3, (2, 2), (1, 1)),
 ]
 
 
