@@ -339,7 +339,7 @@ __global__ __launch_bounds__(kThreads) void dw_wave3x3_kernel(DwArgs p, int32_t 
 }
 
 
-// NCHW 3x3 stride 1 pad 1, W <= 64, W % 4 == 0, 4-byte aligned tensors and weights, planes
+// NCHW 3x3 stride 1 pad 1, W % 4 == 0, 4-byte aligned tensors and weights, planes
 // below 2 GB: no LDS.  One wavefront per (plane, band of 4 * rpc rows), rpc <= 16.  Lane (q, rc):
 // strip of four output columns q, quarter rc of the band's rows.  A lane loads ONE dword per
 // input row (its own strip) and takes the left and right neighbours' dwords by DPP row shifts
@@ -352,16 +352,21 @@ __global__ __launch_bounds__(kThreads) void dw_wave3x3_kernel(DwArgs p, int32_t 
 // weights, bias and multiplier -- comes through scalar loads and scalar arithmetic, and the
 // per-output work is three dot products, one 64-bit multiply-add, one shift and one clamp.
 // MODE 0: requantized 8-bit, 1: raw int32, 2: raw int16; ACC16: accumulator wraps to 16 bits.
-template <int MODE, bool ACC16>
-__global__ __launch_bounds__(kThreads) void dw_rows3x3_kernel(DwArgs p, int32_t rpc) {
-  // grid: x = groups of four channels, y = image, z = band
+// WIDE: images wider than 64 columns are cut into segments of 64 (grid z = band * nsegs + segment);
+// the lanes at the ends of a segment fetch the neighbouring segment's dword with one more load
+// per row, which replaces what the DPP shift cannot deliver.
+template <int MODE, bool ACC16, bool WIDE>
+__global__ __launch_bounds__(kThreads) void dw_rows3x3_kernel(DwArgs p, int32_t rpc, int32_t nsegs) {
+  // grid: x = groups of four channels, y = image, z = band (and column segment)
   const ConvGeom& g = p.g;
   const int H = g.H, W = g.W;
   const int lane = threadIdx.x & 63;
   const int c = (int)(blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6));
   if (c >= g.C) return;  // wavefront-uniform; the kernel has no barrier
   const int64_t plane = (int64_t)blockIdx.y * g.C + c;
-  const int band = (int)blockIdx.z;
+  const int seg = WIDE ? (int)blockIdx.z % nsegs : 0;
+  const int band = WIDE ? (int)blockIdx.z / nsegs : (int)blockIdx.z;
+  const int cb = seg * 64;  // first column of the segment
   constexpr uint32_t kOob = 0x80000000u;
   constexpr int kEsz = MODE == 0 ? 1 : (MODE == 1 ? 4 : 2);
   constexpr int kPass = 16;  // most output rows per lane
@@ -369,8 +374,12 @@ __global__ __launch_bounds__(kThreads) void dw_rows3x3_kernel(DwArgs p, int32_t 
   const int q = lane & 15;
   const int rc = lane >> 4;
   const int y0 = (band * 4 + rc) * rpc;  // first output row of the lane
-  const bool has_strip = (q << 2) < W;
-  const uint32_t lane_off = has_strip ? (uint32_t)(q << 2) : kOob;  // byte column of the strip
+  const bool has_strip = cb + (q << 2) < W;
+  const uint32_t lane_off = has_strip ? (uint32_t)(cb + (q << 2)) : kOob;  // byte column of the strip
+  // the dword beyond the segment's end that this lane stands in for (first lane: left, last: right)
+  const bool left_edge = WIDE && q == 0 && seg > 0;
+  const bool right_edge = WIDE && q == 15 && cb + 64 < W;
+  const uint32_t edge_off = left_edge ? (uint32_t)(cb - 4) : (right_edge ? (uint32_t)(cb + 64) : kOob);
   const uint32_t x4 = p.act_xor * 0x01010101u;
   const uint32_t pad4 = (((uint32_t)p.z_a ^ p.act_xor) & 0xffu) * 0x01010101u;
   const int64_t pbytes = (int64_t)H * W;
@@ -397,11 +406,22 @@ __global__ __launch_bounds__(kThreads) void dw_rows3x3_kernel(DwArgs p, int32_t 
       d[i] = __builtin_amdgcn_raw_buffer_load_b32(rin, off, 0, 0);
     }
   }
+  uint32_t de[WIDE ? kPass + 2 : 1];  // the edge lanes' extra dwords, same rows
+  if constexpr (WIDE) {
+    const uint32_t off0 = edge_off + (uint32_t)((y0 - 1) * W);
+#pragma unroll
+    for (int i = 0; i < kPass + 2; ++i) {
+      uint32_t off = off0 + (uint32_t)(i * W);
+      if (i >= 3) off = (i - 1 <= rpc) ? off : kOob;
+      de[i] = __builtin_amdgcn_raw_buffer_load_b32(rin, off, 0, 0);
+    }
+  }
   const int rows_in = H + 1 - y0;  // rows 1 .. rows_in - 1 of the lane lie in the image
+  struct Row { uint32_t d, edge; };  // a lane's dword of a row and, for an edge lane (which has a strip: same flip), its edge dword
   auto row = [&](int i) {
     uint32_t flip = (i == 0 ? y0 > 0 : i < rows_in) ? flip_lane : pad4;
     asm volatile("" : "+v"(flip));
-    return d[i] ^ flip;
+    return Row{d[i] ^ flip, WIDE ? de[i] ^ flip : 0u};
   };
 
   // The channel's constants, through scalar loads (the addresses are the same for the whole
@@ -454,9 +474,14 @@ __global__ __launch_bounds__(kThreads) void dw_rows3x3_kernel(DwArgs p, int32_t 
   // every lane: a shift never writes the lane at the end of a DPP row it has no source for, so
   // that lane keeps the zero point from one shift to the next and needs no fresh copy.
   uint32_t left = pad4, right = pad4;
-  auto windows = [&](uint32_t d1, uint32_t (&w)[4]) {
+  auto windows = [&](Row r, uint32_t (&w)[4]) {
+    const uint32_t d1 = r.d;
     left = (uint32_t)__builtin_amdgcn_update_dpp((int)left, (int)d1, 0x111, 0xf, 0xf, false);    // row_shr:1
     right = (uint32_t)__builtin_amdgcn_update_dpp((int)right, (int)d1, 0x101, 0xf, 0xf, false);  // row_shl:1
+    if constexpr (WIDE) {
+      left = left_edge ? r.edge : left;
+      right = right_edge ? r.edge : right;
+    }
     w[0] = __builtin_amdgcn_alignbyte(d1, left, 3);
     w[1] = d1;
     w[2] = __builtin_amdgcn_alignbyte(right, d1, 1);
@@ -469,7 +494,7 @@ __global__ __launch_bounds__(kThreads) void dw_rows3x3_kernel(DwArgs p, int32_t 
   };
   // A store beyond the image lies beyond the plane, and a strip-less lane's offset starts at
   // 2^31: both are out of the descriptor's range and dropped.
-  const uint32_t so0 = has_strip ? (uint32_t)((q << 2) + y0 * W) * kEsz : kOob;
+  const uint32_t so0 = has_strip ? (uint32_t)(cb + (q << 2) + y0 * W) * kEsz : kOob;
 
   // FOLD (requantized, 32-bit accumulator, and the channel's constants small enough): the
   // correction term, the rounding term and the output zero point all go into one 64-bit
@@ -527,7 +552,7 @@ __global__ __launch_bounds__(kThreads) void dw_rows3x3_kernel(DwArgs p, int32_t 
     rows.template operator()<false>();
 }
 
-// The same register scheme for stride 2 (NCHW 3x3, pad 1, W <= 64, W % 4 == 0): the MobileNet
+// The same register scheme for stride 2 (NCHW 3x3, pad 1, W % 4 == 0): the MobileNet
 // downsampling layers.  Lane (q, rc) still loads the dword of input columns 4q .. 4q+3 of each
 // input row; it yields the two outputs 2q (columns 4q-1 .. 4q+1: one byte from the left
 // neighbour, by DPP) and 2q+1 (columns 4q+1 .. 4q+3), so no right neighbour is needed.  Output
@@ -536,16 +561,18 @@ __global__ __launch_bounds__(kThreads) void dw_rows3x3_kernel(DwArgs p, int32_t 
 // merged with its neighbour's into one dword store when output rows are dword-aligned
 // (W % 8 == 0), else stored as 16 bits.
 // MODE / ACC16 as above.
-template <int MODE, bool ACC16>
-__global__ __launch_bounds__(kThreads) void dw_rows3x3s2_kernel(DwArgs p, int32_t rpc) {
-  // grid: x = groups of four channels, y = image, z = band of 4 * rpc output rows
+template <int MODE, bool ACC16, bool WIDE>
+__global__ __launch_bounds__(kThreads) void dw_rows3x3s2_kernel(DwArgs p, int32_t rpc, int32_t nsegs) {
+  // grid: x = groups of four channels, y = image, z = band of 4 * rpc output rows (and column segment)
   const ConvGeom& g = p.g;
   const int H = g.H, W = g.W, OH = g.OH, OW = g.OW;
   const int lane = threadIdx.x & 63;
   const int c = (int)(blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6));
   if (c >= g.C) return;  // wavefront-uniform; the kernel has no barrier
   const int64_t plane = (int64_t)blockIdx.y * g.C + c;
-  const int band = (int)blockIdx.z;
+  const int seg = WIDE ? (int)blockIdx.z % nsegs : 0;
+  const int band = WIDE ? (int)blockIdx.z / nsegs : (int)blockIdx.z;
+  const int cb = seg * 64;  // first input column of the segment
   constexpr uint32_t kOob = 0x80000000u;
   constexpr int kEsz = MODE == 0 ? 1 : (MODE == 1 ? 4 : 2);
   constexpr int kPass = 16;  // most output rows per lane
@@ -554,8 +581,10 @@ __global__ __launch_bounds__(kThreads) void dw_rows3x3s2_kernel(DwArgs p, int32_
   const int rc = lane >> 4;
   const int oy0 = (band * 4 + rc) * rpc;  // first output row of the lane
   const int y0 = 2 * oy0 - 1;             // its first input row
-  const bool has_strip = (q << 2) < W;
-  const uint32_t lane_off = has_strip ? (uint32_t)(q << 2) : kOob;
+  const bool has_strip = cb + (q << 2) < W;
+  const uint32_t lane_off = has_strip ? (uint32_t)(cb + (q << 2)) : kOob;
+  const bool left_edge = WIDE && q == 0 && seg > 0;  // this lane's left neighbour is in the previous segment
+  const uint32_t edge_off = left_edge ? (uint32_t)(cb - 4) : kOob;
   const uint32_t x4 = p.act_xor * 0x01010101u;
   const uint32_t pad4 = (((uint32_t)p.z_a ^ p.act_xor) & 0xffu) * 0x01010101u;
   const int64_t ibytes = (int64_t)H * W, obytes = (int64_t)OH * OW * kEsz;
@@ -578,11 +607,22 @@ __global__ __launch_bounds__(kThreads) void dw_rows3x3s2_kernel(DwArgs p, int32_
       d[j] = __builtin_amdgcn_raw_buffer_load_b32(rin, off, 0, 0);
     }
   }
+  uint32_t de[WIDE ? 2 * kPass + 1 : 1];  // the first lane's extra dwords, same rows
+  if constexpr (WIDE) {
+    const uint32_t off0 = edge_off + (uint32_t)(y0 * W);
+#pragma unroll
+    for (int j = 0; j < 2 * kPass + 1; ++j) {
+      uint32_t off = off0 + (uint32_t)(j * W);
+      if (j >= 3) off = (j <= 2 * rpc) ? off : kOob;
+      de[j] = __builtin_amdgcn_raw_buffer_load_b32(rin, off, 0, 0);
+    }
+  }
   const int rows_in = H - y0;  // rows 1 .. rows_in - 1 of the lane lie in the image (y0 >= -1)
+  struct Row { uint32_t d, edge; };  // a lane's dword of a row and (first lane of a later segment) its left neighbour
   auto row = [&](int j) {
     uint32_t flip = (j == 0 ? y0 >= 0 : j < rows_in) ? flip_lane : pad4;
     asm volatile("" : "+v"(flip));
-    return d[j] ^ flip;
+    return Row{d[j] ^ flip, WIDE ? de[j] ^ flip : 0u};
   };
 
   // channel constants through scalar loads, as in the stride-1 kernel
@@ -627,8 +667,10 @@ __global__ __launch_bounds__(kThreads) void dw_rows3x3s2_kernel(DwArgs p, int32_
   // windows of one input row: A = columns 4q-1 .. 4q+2 (output 2q uses its first three bytes,
   // the fourth meets the zero byte of the packed weights), B = columns 4q+1 .. 4q+3
   uint32_t left = pad4;  // keeps the zero point in the lane a shift has no source for
-  auto windows = [&](uint32_t d1, uint32_t (&w)[2]) {
+  auto windows = [&](Row r, uint32_t (&w)[2]) {
+    const uint32_t d1 = r.d;
     left = (uint32_t)__builtin_amdgcn_update_dpp((int)left, (int)d1, 0x111, 0xf, 0xf, false);  // row_shr:1
+    if constexpr (WIDE) left = left_edge ? r.edge : left;
     w[0] = __builtin_amdgcn_alignbyte(d1, left, 3);
     w[1] = d1 >> 8;
   };
@@ -637,7 +679,7 @@ __global__ __launch_bounds__(kThreads) void dw_rows3x3s2_kernel(DwArgs p, int32_
   };
   const bool merge = (OW & 3) == 0;  // output rows start on dwords: even lanes store four results
   // outputs 2q, 2q+1 of row oy0 + i; out-of-range rows lie beyond the plane (dropped)
-  const uint32_t so0 = has_strip ? (uint32_t)(2 * q + oy0 * OW) * kEsz : kOob;
+  const uint32_t so0 = has_strip ? (uint32_t)(cb / 2 + 2 * q + oy0 * OW) * kEsz : kOob;
   const uint32_t so0_even = (has_strip && (q & 1) == 0) ? so0 : kOob;
 
   auto rows = [&]<bool FOLD>() {
@@ -739,25 +781,32 @@ hipError_t launch_qconv_depthwise(const GemmArgs& a, const ConvGeom& cg, hipStre
                      cg.pad_h == 1 && cg.pad_w == 1;
   const int32_t rpc2 = (cg.OH + 3) / 4 < 16 ? (cg.OH + 3) / 4 : 16;
   const int64_t nband2 = (cg.OH + 4 * rpc2 - 1) / (4 * rpc2);
-  if (upward && s2_ok && cg.W <= 64 && cg.W % 4 == 0 && (reinterpret_cast<uintptr_t>(a.act) & 3u) == 0 &&
+  const int32_t nsegs = (cg.W + 63) / 64;  // column segments of the register kernels
+  if (upward && s2_ok && cg.W % 4 == 0 && (reinterpret_cast<uintptr_t>(a.act) & 3u) == 0 &&
       (reinterpret_cast<uintptr_t>(a.out) & 7u) == 0 && (reinterpret_cast<uintptr_t>(a.wgt) & 3u) == 0 &&
-      cg.B <= 65535 && nband2 <= 65535 && (int64_t)cg.H * cg.W * 4 < (1ll << 31) &&
+      cg.B <= 65535 && nband2 * nsegs <= 65535 && (int64_t)cg.H * cg.W * 4 < (1ll << 31) &&
       (int64_t)cg.C * 9 < (1ll << 30)) {
-    auto kern = p.out_mode == 1 ? dw_rows3x3s2_kernel<1, false>
-              : p.out_mode == 2 ? dw_rows3x3s2_kernel<2, true>
-              : p.acc16 ? dw_rows3x3s2_kernel<0, true> : dw_rows3x3s2_kernel<0, false>;
-    hipLaunchKernelGGL(kern, dim3((unsigned)((cg.C + 3) / 4), (unsigned)cg.B, (unsigned)nband2), dim3(kThreads),
-                       0, st, p, rpc2);
+    auto kern = nsegs > 1 ? (p.out_mode == 1 ? dw_rows3x3s2_kernel<1, false, true>
+                             : p.out_mode == 2 ? dw_rows3x3s2_kernel<2, true, true>
+                             : p.acc16 ? dw_rows3x3s2_kernel<0, true, true> : dw_rows3x3s2_kernel<0, false, true>)
+                          : (p.out_mode == 1 ? dw_rows3x3s2_kernel<1, false, false>
+                             : p.out_mode == 2 ? dw_rows3x3s2_kernel<2, true, false>
+                             : p.acc16 ? dw_rows3x3s2_kernel<0, true, false> : dw_rows3x3s2_kernel<0, false, false>);
+    hipLaunchKernelGGL(kern, dim3((unsigned)((cg.C + 3) / 4), (unsigned)cg.B, (unsigned)(nband2 * nsegs)),
+                       dim3(kThreads), 0, st, p, rpc2, nsegs);
     return hipGetLastError();
   }
-  if (upward && plane_ok && cg.W <= 64 && vec_io && (reinterpret_cast<uintptr_t>(a.wgt) & 3u) == 0 &&
-      cg.B <= 65535 && nband_r <= 65535 && (int64_t)cg.H * cg.W * 4 < (1ll << 31) &&
+  if (upward && plane_ok && vec_io && (reinterpret_cast<uintptr_t>(a.wgt) & 3u) == 0 &&
+      cg.B <= 65535 && nband_r * nsegs <= 65535 && (int64_t)cg.H * cg.W * 4 < (1ll << 31) &&
       (int64_t)cg.C * 9 < (1ll << 30)) {
-    auto kern = p.out_mode == 1 ? dw_rows3x3_kernel<1, false>
-              : p.out_mode == 2 ? dw_rows3x3_kernel<2, true>
-              : p.acc16 ? dw_rows3x3_kernel<0, true> : dw_rows3x3_kernel<0, false>;
-    hipLaunchKernelGGL(kern, dim3((unsigned)((cg.C + 3) / 4), (unsigned)cg.B, (unsigned)nband_r), dim3(kThreads),
-                       0, st, p, rpc);
+    auto kern = nsegs > 1 ? (p.out_mode == 1 ? dw_rows3x3_kernel<1, false, true>
+                             : p.out_mode == 2 ? dw_rows3x3_kernel<2, true, true>
+                             : p.acc16 ? dw_rows3x3_kernel<0, true, true> : dw_rows3x3_kernel<0, false, true>)
+                          : (p.out_mode == 1 ? dw_rows3x3_kernel<1, false, false>
+                             : p.out_mode == 2 ? dw_rows3x3_kernel<2, true, false>
+                             : p.acc16 ? dw_rows3x3_kernel<0, true, false> : dw_rows3x3_kernel<0, false, false>);
+    hipLaunchKernelGGL(kern, dim3((unsigned)((cg.C + 3) / 4), (unsigned)cg.B, (unsigned)(nband_r * nsegs)),
+                       dim3(kThreads), 0, st, p, rpc, nsegs);
   } else if (upward && plane_ok && cg.W <= 64 && wave_lds <= (size_t)kMaxLdsBytes && planes < (1ll << 32)) {
     const uint32_t w4 = vec_io ? (uint32_t)cg.W / 4 : 1u;
     const uint32_t inv_w4 = w4 > 1 ? (uint32_t)(((1ull << 32) + w4 - 1) / w4) : 0u;  // unused for w4 == 1

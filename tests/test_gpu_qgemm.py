@@ -334,6 +334,13 @@ DW_CASES = [
     (1, 4, 7, 64, 3, 3, (2, 2), (1, 1)),
     (1, 3, 12, 10, 3, 3, (2, 2), (1, 1)),
     (1, 2, 6, 72, 3, 3, (2, 2), (1, 1)),
+    # wider than 64 columns: column segments, the segment ends fetch their neighbour's dword
+    (1, 3, 10, 112, 3, 3, (1, 1), (1, 1)),
+    (2, 2, 70, 128, 3, 3, (1, 1), (1, 1)),
+    (1, 2, 5, 68, 3, 3, (1, 1), (1, 1)),
+    (1, 3, 20, 112, 3, 3, (2, 2), (1, 1)),
+    (2, 2, 7, 200, 3, 3, (2, 2), (1, 1)),
+    (1, 2, 5, 132, 3, 3, (2, 2), (1, 1)),
 ]
 
 
