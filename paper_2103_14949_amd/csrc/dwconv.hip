@@ -1,12 +1,13 @@
 // Depthwise quantized convolution (groups == C == O) with the fused requantize
 // epilogue.  Bandwidth-bound: each output byte needs one input byte from HBM,
 // so there is no MFMA here; the work is 9 multiply-adds per output on the
-// vector ALUs (4 at a time with v_dot4) out of an LDS copy of the input plane.
+// vector ALUs (4 at a time with v_dot4).
 //
-//   rows3x3  : NCHW, 3x3, stride 1, pad 1, W <= 64, W % 4 == 0, aligned.  One WAVEFRONT
-//              per (image, channel) plane and no LDS: a lane loads one dword per
-//              input row and gets its neighbours' by DPP; see the kernel.
-//   wave3x3  : the same geometry without the alignment conditions.  One WAVEFRONT per (image,
+//   rows3x3  : NCHW, 3x3, stride 1, pad 1, W % 4 == 0, aligned.  One WAVEFRONT per (image,
+//              channel, band of rows, segment of 64 columns) and no LDS: a lane loads one
+//              dword per input row and gets its neighbours' by DPP; see the kernel.
+//   rows3x3s2: the same for stride 2 (two outputs per lane and row).
+//   wave3x3  : stride 1, W <= 64, without the alignment conditions.  One WAVEFRONT per (image,
 //              channel) plane, four planes per workgroup.  A lane owns a strip
 //              of four output columns and a quarter of the rows and slides
 //              down it, so every staged input row is read from LDS once and
