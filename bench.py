@@ -392,7 +392,7 @@ def extra_ops(torch, hago, datagen, to_dev, rq_of, event_time_ms, only):
         f = hago.qdense(to_dev(c["a"]), hago.QType(hago.U8, 8, False, c["z_a"]), to_dev(c["w"]),
                         hago.QType(hago.I8), to_dev(c["bias"]), hago.I32, rq, prepare=True)
         record("dense_c5_ffn1_half_away", event_time_ms(f, 100, 10), ops=2.0 * 4096 * 3072 * 768,
-               bound="mfma", note="config 5 layer 768 -> 3072 with ties away from zero (general epilogue)")
+               bound="mfma", note="config 5 layer 768 -> 3072 with ties away from zero (straight-line epilogue, not the LDS-staged one)")
         del f
 
     # ---- config 1 (as specified and scaled)

@@ -99,9 +99,9 @@ typedef struct {
  * +infinity).  With rounding == HAGO_ROUND_HALF_AWAY, r is instead the nearest
  * integer to acc * multiplier[c] / 2^(31 + shift[c]) with halves away from
  * zero (the two tie rules of the compiler stack the paper generates code
- * with; the results differ, by one, exactly on negative ties).  The kernels
- * tuned for speed implement the first rule; the second runs through each
- * operator's general code path.  ReLU / ReLU6 are expressed through clip_lo /
+ * with; the results differ, by one, exactly on negative ties).  The fastest
+ * kernel variants implement the first rule; the second takes each operator's
+ * more general variant.  ReLU / ReLU6 are expressed through clip_lo /
  * clip_hi in the output's quantized domain (Sec. 6.1). */
 typedef enum { HAGO_ROUND_UPWARD = 0, HAGO_ROUND_HALF_AWAY = 1 } hago_rounding;
 

@@ -167,7 +167,7 @@ __global__ __launch_bounds__(kThreads) void simquant_flat_kernel(
 // AWAY: the launch's tie rule is halves away from zero (the general form); else the plain one.
 template <bool AWAY>
 __device__ __forceinline__ int32_t requant_pick(int32_t acc, int32_t mult, int32_t sh, const RequantScalars& rs) {
-  if constexpr (AWAY) return requant_general(acc, mult, sh, rs);
+  if constexpr (AWAY) return requant_half_away(acc, mult, sh, rs);
   else return requant_one(acc, mult, sh, rs);
 }
 

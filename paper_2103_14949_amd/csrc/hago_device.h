@@ -38,16 +38,21 @@ __device__ __forceinline__ int32_t requant_one(int32_t acc, int32_t mult, int32_
   return med3(r, rs.lo_rel, rs.hi_rel) + rs.z_out;
 }
 
-// The general form, with the launch's tie rule.  Nearest with halves away from zero differs
-// from ties toward +infinity exactly where the product is negative and lies on a tie (the low
-// 31 + sh bits of product + rounding term are then all zero), and there by one.
+// Nearest with halves away from zero: round the magnitude half up and give the sign back,
+// which for a negative product is floor((product + rounding term - 1) / 2^(31 + sh)).  The
+// product has the sign of acc (mult >= 0; a zero product rounds to 0 either way), so the
+// correction is acc's sign bit added to the 64-bit sum.  It differs from ties toward +infinity
+// exactly on negative ties, and there by one.
+__device__ __forceinline__ int32_t requant_half_away(int32_t acc, int32_t mult, int32_t sh,
+                                                     const RequantScalars& rs) {
+  const int64_t p = (int64_t)acc * (int64_t)mult + ((int64_t)1 << (30 + sh)) + (int64_t)(acc >> 31);
+  return med3((int32_t)(p >> (31 + sh)), rs.lo_rel, rs.hi_rel) + rs.z_out;
+}
+
+// The general form, with the launch's tie rule.
 __device__ __forceinline__ int32_t requant_general(int32_t acc, int32_t mult, int32_t sh,
                                                    const RequantScalars& rs) {
-  const int64_t rnd = (int64_t)1 << (30 + sh);
-  const int64_t p = (int64_t)acc * (int64_t)mult + rnd;
-  int32_t r = (int32_t)(p >> (31 + sh));
-  if (rs.half_away && p < rnd && (p & ((rnd << 1) - 1)) == 0) r -= 1;
-  return med3(r, rs.lo_rel, rs.hi_rel) + rs.z_out;
+  return rs.half_away ? requant_half_away(acc, mult, sh, rs) : requant_one(acc, mult, sh, rs);
 }
 
 // Four results -> one little-endian dword of their low bytes.

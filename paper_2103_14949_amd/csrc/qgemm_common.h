@@ -297,11 +297,11 @@ __device__ __forceinline__ void store_group(void* out, size_t off, int32_t v0, i
         make_short4((short)v0, (short)v1, (short)v2, (short)v3);
 }
 
-template <int OM>
+template <int OM, bool AWAY>
 __device__ __forceinline__ int32_t finish_one(int32_t a, int32_t m, int32_t sh, bool acc16,
                                               const RequantScalars& rs) {
   if (acc16) a = (int32_t)(int16_t)a;
-  if constexpr (OM == 0) a = requant_one(a, m, sh, rs);
+  if constexpr (OM == 0) a = AWAY ? requant_half_away(a, m, sh, rs) : requant_one(a, m, sh, rs);
   return a;
 }
 
@@ -312,7 +312,7 @@ __device__ __forceinline__ constexpr int pix_perm(int r) {
   return 16 * ((r >> 2) & 1) + 4 * (r >> 3) + (r & 3);
 }
 
-template <int WP, int WQ, int TP, int TQ, bool ACT_ON_P, int OM, bool PIXPERM, bool RAGGED>
+template <int WP, int WQ, int TP, int TQ, bool ACT_ON_P, int OM, bool PIXPERM, bool RAGGED, bool AWAY>
 __device__ __forceinline__ void qgemm_epilogue_fast(const QgemmParams& p, v16i (&acc)[TP][TQ],
                                                     int p0, int q0, const int32_t* s_corr,
                                                     const int32_t* s_mult,
@@ -339,10 +339,10 @@ __device__ __forceinline__ void qgemm_epilogue_fast(const QgemmParams& p, v16i (
 #pragma unroll
         for (int tj = 0; tj < TQ; ++tj) {
           const int j = q0 + (wq * TQ + tj) * 32 + frow;
-          const int32_t r0 = finish_one<OM>(acc[ti][tj][g4 * 4 + 0] + c4.x, m4.x, s4.x, acc16, rs);
-          const int32_t r1 = finish_one<OM>(acc[ti][tj][g4 * 4 + 1] + c4.y, m4.y, s4.y, acc16, rs);
-          const int32_t r2 = finish_one<OM>(acc[ti][tj][g4 * 4 + 2] + c4.z, m4.z, s4.z, acc16, rs);
-          const int32_t r3 = finish_one<OM>(acc[ti][tj][g4 * 4 + 3] + c4.w, m4.w, s4.w, acc16, rs);
+          const int32_t r0 = finish_one<OM, AWAY>(acc[ti][tj][g4 * 4 + 0] + c4.x, m4.x, s4.x, acc16, rs);
+          const int32_t r1 = finish_one<OM, AWAY>(acc[ti][tj][g4 * 4 + 1] + c4.y, m4.y, s4.y, acc16, rs);
+          const int32_t r2 = finish_one<OM, AWAY>(acc[ti][tj][g4 * 4 + 2] + c4.z, m4.z, s4.z, acc16, rs);
+          const int32_t r3 = finish_one<OM, AWAY>(acc[ti][tj][g4 * 4 + 3] + c4.w, m4.w, s4.w, acc16, rs);
           if (!RAGGED || (j < Q_ext && p0 + i_loc < P_ext))
             store_group<OM>(p.out, (size_t)j * p.N + (p0 + i_loc), r0, r1, r2, r3);
         }
@@ -367,10 +367,10 @@ __device__ __forceinline__ void qgemm_epilogue_fast(const QgemmParams& p, v16i (
             uint32_t dw[4];
 #pragma unroll
             for (int g4 = 0; g4 < 4; ++g4)
-              dw[g4] = pack4(finish_one<OM>(acc[ti][tj][g4 * 4 + 0] + c, m, sh, acc16, rs),
-                             finish_one<OM>(acc[ti][tj][g4 * 4 + 1] + c, m, sh, acc16, rs),
-                             finish_one<OM>(acc[ti][tj][g4 * 4 + 2] + c, m, sh, acc16, rs),
-                             finish_one<OM>(acc[ti][tj][g4 * 4 + 3] + c, m, sh, acc16, rs));
+              dw[g4] = pack4(finish_one<OM, AWAY>(acc[ti][tj][g4 * 4 + 0] + c, m, sh, acc16, rs),
+                             finish_one<OM, AWAY>(acc[ti][tj][g4 * 4 + 1] + c, m, sh, acc16, rs),
+                             finish_one<OM, AWAY>(acc[ti][tj][g4 * 4 + 2] + c, m, sh, acc16, rs),
+                             finish_one<OM, AWAY>(acc[ti][tj][g4 * 4 + 3] + c, m, sh, acc16, rs));
             if (!RAGGED || (j < Q_ext && i < P_ext))
               *reinterpret_cast<uint4*>(static_cast<uint8_t*>(p.out) + ((size_t)b * p.N + j) * ohw + pix) =
                   make_uint4(dw[0], dw[1], dw[2], dw[3]);
@@ -388,8 +388,8 @@ __device__ __forceinline__ void qgemm_epilogue_fast(const QgemmParams& p, v16i (
               uint32_t dw[4];
 #pragma unroll
               for (int x = 0; x < 4; ++x) {
-                const int32_t lo16 = finish_one<OM>(acc[ti][tj][g2 * 8 + 2 * x] + c, m, sh, acc16, rs);
-                const int32_t hi16 = finish_one<OM>(acc[ti][tj][g2 * 8 + 2 * x + 1] + c, m, sh, acc16, rs);
+                const int32_t lo16 = finish_one<OM, AWAY>(acc[ti][tj][g2 * 8 + 2 * x] + c, m, sh, acc16, rs);
+                const int32_t hi16 = finish_one<OM, AWAY>(acc[ti][tj][g2 * 8 + 2 * x + 1] + c, m, sh, acc16, rs);
                 dw[x] = ((uint32_t)lo16 & 0xffffu) | ((uint32_t)hi16 << 16);
               }
               if (!RAGGED || (j < Q_ext && i < P_ext))
@@ -404,10 +404,10 @@ __device__ __forceinline__ void qgemm_epilogue_fast(const QgemmParams& p, v16i (
           const int i = p0 + (wp * TP + ti) * 32 + (PIXPERM ? fhalf * 16 + g4 * 4 : g4 * 8 + fhalf * 4);
           const int b = i / ohw;
           const int pix = i - b * ohw;
-          const int32_t r0 = finish_one<OM>(acc[ti][tj][g4 * 4 + 0] + c, m, sh, acc16, rs);
-          const int32_t r1 = finish_one<OM>(acc[ti][tj][g4 * 4 + 1] + c, m, sh, acc16, rs);
-          const int32_t r2 = finish_one<OM>(acc[ti][tj][g4 * 4 + 2] + c, m, sh, acc16, rs);
-          const int32_t r3 = finish_one<OM>(acc[ti][tj][g4 * 4 + 3] + c, m, sh, acc16, rs);
+          const int32_t r0 = finish_one<OM, AWAY>(acc[ti][tj][g4 * 4 + 0] + c, m, sh, acc16, rs);
+          const int32_t r1 = finish_one<OM, AWAY>(acc[ti][tj][g4 * 4 + 1] + c, m, sh, acc16, rs);
+          const int32_t r2 = finish_one<OM, AWAY>(acc[ti][tj][g4 * 4 + 2] + c, m, sh, acc16, rs);
+          const int32_t r3 = finish_one<OM, AWAY>(acc[ti][tj][g4 * 4 + 3] + c, m, sh, acc16, rs);
           if (!RAGGED || (j < Q_ext && i < P_ext))
             store_group<OM>(p.out, ((size_t)b * p.N + j) * ohw + pix, r0, r1, r2, r3);
         }
@@ -436,23 +436,31 @@ __device__ __forceinline__ void qgemm_epilogue(const QgemmParams& p, v16i (&acc)
   const int P_ext = ACT_ON_P ? p.M : p.N;
   const int Q_ext = ACT_ON_P ? p.N : p.M;
   const int ohw = p.g.OH * p.g.OW;
-  // groups of four along the packed axis are aligned stores; ties toward +infinity
-  const bool fast = p.vec_out && !p.rs.half_away;
+  const bool fast = p.vec_out;  // groups of four along the packed axis are aligned stores
 
   if (fast) {
     // interior tiles (block-uniform) run without the per-store bounds checks
     const bool ragged = p0 + BP > P_ext || q0 + BQ > Q_ext;
-#define HAGO_FAST_EPILOGUE(OM)                                                                          \
-  (ragged ? qgemm_epilogue_fast<WP, WQ, TP, TQ, ACT_ON_P, OM, PIXPERM, true>(p, acc, p0, q0, s_corr,    \
-                                                                             s_mult, s_shift)          \
-          : qgemm_epilogue_fast<WP, WQ, TP, TQ, ACT_ON_P, OM, PIXPERM, false>(p, acc, p0, q0, s_corr,   \
-                                                                              s_mult, s_shift))
-    if (p.out_mode == 0)
-      HAGO_FAST_EPILOGUE(0);
-    else if (p.out_mode == 1)
+#define HAGO_FAST_EPILOGUE_R(OM, AWAY)                                                                  \
+  (ragged ? qgemm_epilogue_fast<WP, WQ, TP, TQ, ACT_ON_P, OM, PIXPERM, true, AWAY>(p, acc, p0, q0,      \
+                                                                                   s_corr, s_mult,      \
+                                                                                   s_shift)             \
+          : qgemm_epilogue_fast<WP, WQ, TP, TQ, ACT_ON_P, OM, PIXPERM, false, AWAY>(p, acc, p0, q0,     \
+                                                                                    s_corr, s_mult,     \
+                                                                                    s_shift))
+    // (the tie rule only matters for requantized output)
+#define HAGO_FAST_EPILOGUE(OM) HAGO_FAST_EPILOGUE_R(OM, false)
+    if (p.out_mode == 0) {
+      if (p.rs.half_away)
+        HAGO_FAST_EPILOGUE_R(0, true);
+      else
+        HAGO_FAST_EPILOGUE(0);
+    } else if (p.out_mode == 1) {
       HAGO_FAST_EPILOGUE(1);
-    else
+    } else {
       HAGO_FAST_EPILOGUE(2);
+    }
+#undef HAGO_FAST_EPILOGUE_R
 #undef HAGO_FAST_EPILOGUE
     return;
   }
