@@ -469,6 +469,7 @@ __global__ __launch_bounds__(kThreads) void dw_rows3x3_kernel(DwArgs p, int32_t 
   const int32_t corr = bias + (p.act_off - p.z_a) * wsum;
   const int64_t rnd = (int64_t)1 << (30 + sh);
   const int32_t z = p.rs.z_out;
+  const int32_t away = p.rs.half_away ? -1 : 0;  // mask of the sign-bit correction
 
   // the four 3-byte windows of a strip: output x = 4q + i reads input columns x-1 .. x+1
   // The shifted copies live in two registers of their own, which start as the zero point in
@@ -529,7 +530,8 @@ __global__ __launch_bounds__(kThreads) void dw_rows3x3_kernel(DwArgs p, int32_t 
           int32_t r[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            const int64_t pr = (int64_t)acc[e] * (int64_t)m + k64;
+            // (general form only: halves away from zero add the accumulator's sign bit)
+            const int64_t pr = (int64_t)acc[e] * (int64_t)m + k64 + (FOLD ? 0 : (int64_t)((acc[e] >> 31) & away));
             r[e] = med3((int32_t)(pr >> (31 + sh)), lo, hi) + (FOLD ? 0 : z);
           }
           __builtin_amdgcn_raw_buffer_store_b32(pack4_perm(r[0], r[1], r[2], r[3]), rout, so, 0, 0);
@@ -546,7 +548,7 @@ __global__ __launch_bounds__(kThreads) void dw_rows3x3_kernel(DwArgs p, int32_t 
     }
   };
   const bool fold = MODE == 0 && !ACC16 && sh >= 0 && sh <= 19 && corr >= -(1 << 30) && corr <= (1 << 30) &&
-                    z >= -256 && z <= 255;
+                    z >= -256 && z <= 255 && !p.rs.half_away;
   if (fold)
     rows.template operator()<true>();
   else
@@ -664,6 +666,7 @@ __global__ __launch_bounds__(kThreads) void dw_rows3x3s2_kernel(DwArgs p, int32_
   const int32_t corr = bias + (p.act_off - p.z_a) * wsum;
   const int64_t rnd = (int64_t)1 << (30 + sh);
   const int32_t z = p.rs.z_out;
+  const int32_t away = p.rs.half_away ? -1 : 0;  // mask of the sign-bit correction
 
   // windows of one input row: A = columns 4q-1 .. 4q+2 (output 2q uses its first three bytes,
   // the fourth meets the zero byte of the packed weights), B = columns 4q+1 .. 4q+3
@@ -710,7 +713,8 @@ __global__ __launch_bounds__(kThreads) void dw_rows3x3s2_kernel(DwArgs p, int32_
           int32_t r[2];
 #pragma unroll
           for (int e = 0; e < 2; ++e) {
-            const int64_t pr = (int64_t)acc[e] * (int64_t)m + k64;
+            // (general form only: halves away from zero add the accumulator's sign bit)
+            const int64_t pr = (int64_t)acc[e] * (int64_t)m + k64 + (FOLD ? 0 : (int64_t)((acc[e] >> 31) & away));
             r[e] = med3((int32_t)(pr >> (31 + sh)), lo, hi) + (FOLD ? 0 : z);
           }
           const uint32_t h16 = ((uint32_t)r[0] & 0xffu) | (((uint32_t)r[1] & 0xffu) << 8);
@@ -731,7 +735,7 @@ __global__ __launch_bounds__(kThreads) void dw_rows3x3s2_kernel(DwArgs p, int32_
     }
   };
   const bool fold = MODE == 0 && !ACC16 && sh >= 0 && sh <= 19 && corr >= -(1 << 30) && corr <= (1 << 30) &&
-                    z >= -256 && z <= 255;
+                    z >= -256 && z <= 255 && !p.rs.half_away;
   if (fold)
     rows.template operator()<true>();
   else
@@ -775,7 +779,7 @@ hipError_t launch_qconv_depthwise(const GemmArgs& a, const ConvGeom& cg, hipStre
   // the register kernel: bands of 4 * rpc rows, one wavefront each
   const int32_t rpc = (cg.H + 3) / 4 < 16 ? (cg.H + 3) / 4 : 16;
   const int64_t nband_r = (cg.H + 4 * rpc - 1) / (4 * rpc);
-  // (the register kernels and the wavefront-per-plane kernel round ties toward +infinity only)
+  // (the wavefront-per-plane kernel rounds ties toward +infinity only)
   const bool upward = !(a.has_rq && a.rq.half_away);
   // stride 2: the register kernel for the downsampling layers
   const bool s2_ok = !cg.nhwc && cg.KH == 3 && cg.KW == 3 && cg.stride_h == 2 && cg.stride_w == 2 &&
@@ -783,7 +787,7 @@ hipError_t launch_qconv_depthwise(const GemmArgs& a, const ConvGeom& cg, hipStre
   const int32_t rpc2 = (cg.OH + 3) / 4 < 16 ? (cg.OH + 3) / 4 : 16;
   const int64_t nband2 = (cg.OH + 4 * rpc2 - 1) / (4 * rpc2);
   const int32_t nsegs = (cg.W + 63) / 64;  // column segments of the register kernels
-  if (upward && s2_ok && cg.W % 4 == 0 && (reinterpret_cast<uintptr_t>(a.act) & 3u) == 0 &&
+  if (s2_ok && cg.W % 4 == 0 && (reinterpret_cast<uintptr_t>(a.act) & 3u) == 0 &&
       (reinterpret_cast<uintptr_t>(a.out) & 7u) == 0 && (reinterpret_cast<uintptr_t>(a.wgt) & 3u) == 0 &&
       cg.B <= 65535 && nband2 * nsegs <= 65535 && (int64_t)cg.H * cg.W * 4 < (1ll << 31) &&
       (int64_t)cg.C * 9 < (1ll << 30)) {
@@ -797,7 +801,7 @@ hipError_t launch_qconv_depthwise(const GemmArgs& a, const ConvGeom& cg, hipStre
                        dim3(kThreads), 0, st, p, rpc2, nsegs);
     return hipGetLastError();
   }
-  if (upward && plane_ok && vec_io && (reinterpret_cast<uintptr_t>(a.wgt) & 3u) == 0 &&
+  if (plane_ok && vec_io && (reinterpret_cast<uintptr_t>(a.wgt) & 3u) == 0 &&
       cg.B <= 65535 && nband_r * nsegs <= 65535 && (int64_t)cg.H * cg.W * 4 < (1ll << 31) &&
       (int64_t)cg.C * 9 < (1ll << 30)) {
     auto kern = nsegs > 1 ? (p.out_mode == 1 ? dw_rows3x3_kernel<1, false, true>

@@ -286,6 +286,7 @@ __global__ __launch_bounds__(64) void pw_nchw_quad_kernel(PwArgs p) {
   // ((acc + corr) * m + rnd) >> s + z == (acc * m + corr * m + rnd + z * 2^s) >> s exactly, and
   // acc + corr cannot wrap when |corr| <= 2^30 and |acc| <= 2^30 (|acc| <= C * 2^15 < 2^30 for
   // C < 2^15).  With sh <= 19 and an 8-bit z nothing leaves 63 bits.
+  const int32_t away = rs.half_away ? -1 : 0;  // mask of the sign-bit correction
   auto store_all = [&]<bool FOLD>() {
     const int32_t lo = rs.lo_rel + (FOLD ? rs.z_out : 0), hi = rs.hi_rel + (FOLD ? rs.z_out : 0);
     const int64_t k64 = FOLD ? (int64_t)corr * mult_r + rnd + ((int64_t)rs.z_out << (31 + shift_r)) : rnd;
@@ -305,7 +306,8 @@ __global__ __launch_bounds__(64) void pw_nchw_quad_kernel(PwArgs p) {
         if constexpr (MODE == 0) {
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
-            const int64_t pr = (int64_t)v[j] * (int64_t)mult_r + k64;
+            // (general form only: halves away from zero add the accumulator's sign bit)
+            const int64_t pr = (int64_t)v[j] * (int64_t)mult_r + k64 + (FOLD ? 0 : (int64_t)((v[j] >> 31) & away));
             v[j] = med3((int32_t)(pr >> (31 + shift_r)), lo, hi) + (FOLD ? 0 : rs.z_out);
           }
           dw[e] = pack4_perm(v[0], v[1], v[2], v[3]);
@@ -327,7 +329,7 @@ __global__ __launch_bounds__(64) void pw_nchw_quad_kernel(PwArgs p) {
   };
   const bool lane_ok = shift_r >= 0 && shift_r <= 19 && corr >= -(1 << 30) && corr <= (1 << 30);
   const bool fold = MODE == 0 && !ACC16 && C < (1 << 15) && rs.z_out >= -256 && rs.z_out <= 255 &&
-                    __builtin_amdgcn_ballot_w64(!lane_ok) == 0;  // wavefront-uniform
+                    !rs.half_away && __builtin_amdgcn_ballot_w64(!lane_ok) == 0;  // wavefront-uniform
   if (fold)
     store_all.template operator()<true>();
   else
@@ -355,7 +357,7 @@ hipError_t launch_nt(const PwArgs& p, hipStream_t st) {
 bool try_qconv_pointwise_nchw(const GemmArgs& a, const ConvGeom& cg, hipStream_t st, hipError_t* err) {
   const int64_t HW = (int64_t)cg.H * cg.W;
   const size_t esz = a.has_rq ? 1 : (a.acc16 ? 2 : 4);
-  if (a.has_rq && a.rq.half_away) return false;  // ties toward +infinity only
+  if (a.has_rq && a.rq.half_away && cg.O > 32) return false;  // the wider kernel: ties toward +infinity only
   if (cg.nhwc || cg.KH != 1 || cg.KW != 1 || cg.stride_h != 1 || cg.stride_w != 1 || cg.pad_h != 0 ||
       cg.pad_w != 0 || cg.C % 16 != 0 || HW % 4 != 0 || cg.O > 128 || (int64_t)cg.C * HW >= (1ll << 31) ||
       (int64_t)cg.O * cg.C >= (1ll << 31) || (reinterpret_cast<uintptr_t>(a.wgt) & 15u) != 0 ||
