@@ -504,19 +504,24 @@ __global__ __launch_bounds__(kThreads) void dw_rows3x3_kernel(DwArgs p, int32_t 
   // absolute bounds: (acc * m + rnd) >> s + z == (acc * m + rnd + z * 2^s) >> s exactly, and
   // acc = dots + corr cannot wrap when |corr| <= 2^30 (|dots| < 2^19).  With sh <= 19 and an
   // 8-bit z nothing here leaves 63 bits.
-  auto rows = [&]<bool FOLD>() {
+  // PLAIN: int8 activations with zero point 0 need no flip at all (the mask is zero everywhere)
+  auto rows = [&]<bool FOLD, bool PLAIN>() {
+    auto rowp = [&](int i) {
+      if constexpr (PLAIN) return Row{d[i], WIDE ? de[i] : 0u};
+      else return row(i);
+    };
     int32_t lo = p.rs.lo_rel + (FOLD ? z : 0), hi = p.rs.hi_rel + (FOLD ? z : 0);
     // vector-register copies: v_med3 takes at most one scalar operand
     asm volatile("" : "+v"(lo), "+v"(hi));
     const int64_t k64 = FOLD ? (int64_t)corr * m + rnd + ((int64_t)z << (31 + sh)) : rnd;
     const int32_t init = FOLD ? 0 : corr;
     uint32_t w[3][4];  // windows of three consecutive rows, slot = row % 3
-    windows(row(0), w[0]);
-    windows(row(1), w[1]);
+    windows(rowp(0), w[0]);
+    windows(rowp(1), w[1]);
 #pragma unroll
     for (int i = 0; i < kPass; ++i) {
       if (i < rpc) {  // uniform
-        windows(row(i + 2), w[(i + 2) % 3]);
+        windows(rowp(i + 2), w[(i + 2) % 3]);
         int32_t acc[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -549,10 +554,12 @@ __global__ __launch_bounds__(kThreads) void dw_rows3x3_kernel(DwArgs p, int32_t 
   };
   const bool fold = MODE == 0 && !ACC16 && sh >= 0 && sh <= 19 && corr >= -(1 << 30) && corr <= (1 << 30) &&
                     z >= -256 && z <= 255 && !p.rs.half_away;
-  if (fold)
-    rows.template operator()<true>();
+  if (fold && x4 == 0 && pad4 == 0)
+    rows.template operator()<true, true>();
+  else if (fold)
+    rows.template operator()<true, false>();
   else
-    rows.template operator()<false>();
+    rows.template operator()<false, false>();
 }
 
 // The same register scheme for stride 2 (NCHW 3x3, pad 1, W % 4 == 0): the MobileNet
@@ -686,20 +693,25 @@ __global__ __launch_bounds__(kThreads) void dw_rows3x3s2_kernel(DwArgs p, int32_
   const uint32_t so0 = has_strip ? (uint32_t)(cb / 2 + 2 * q + oy0 * OW) * kEsz : kOob;
   const uint32_t so0_even = (has_strip && (q & 1) == 0) ? so0 : kOob;
 
-  auto rows = [&]<bool FOLD>() {
+  // PLAIN: int8 activations with zero point 0 need no flip at all (the mask is zero everywhere)
+  auto rows = [&]<bool FOLD, bool PLAIN>() {
+    auto rowp = [&](int i) {
+      if constexpr (PLAIN) return Row{d[i], WIDE ? de[i] : 0u};
+      else return row(i);
+    };
     int32_t lo = p.rs.lo_rel + (FOLD ? z : 0), hi = p.rs.hi_rel + (FOLD ? z : 0);
     asm volatile("" : "+v"(lo), "+v"(hi));
     const int64_t k64 = FOLD ? (int64_t)corr * m + rnd + ((int64_t)z << (31 + sh)) : rnd;
     const int32_t init = FOLD ? 0 : corr;
     uint32_t w[3][2];  // windows of input rows 2i, 2i+1, 2i+2: slot = row % 3 over the unrolled loop
-    windows(row(0), w[0]);
+    windows(rowp(0), w[0]);
 #pragma unroll
     for (int i = 0; i < kPass; ++i) {
       if (i < rpc) {  // uniform
         // rows 2i (slot a), 2i+1 (slot b), 2i+2 (slot cc); the last is the next output's first
         const int a = (2 * i) % 3, b = (2 * i + 1) % 3, cc = (2 * i + 2) % 3;
-        windows(row(2 * i + 1), w[b]);
-        windows(row(2 * i + 2), w[cc]);
+        windows(rowp(2 * i + 1), w[b]);
+        windows(rowp(2 * i + 2), w[cc]);
         int32_t acc[2];
 #pragma unroll
         for (int e = 0; e < 2; ++e) {
@@ -736,10 +748,12 @@ __global__ __launch_bounds__(kThreads) void dw_rows3x3s2_kernel(DwArgs p, int32_
   };
   const bool fold = MODE == 0 && !ACC16 && sh >= 0 && sh <= 19 && corr >= -(1 << 30) && corr <= (1 << 30) &&
                     z >= -256 && z <= 255 && !p.rs.half_away;
-  if (fold)
-    rows.template operator()<true>();
+  if (fold && x4 == 0 && pad4 == 0)
+    rows.template operator()<true, true>();
+  else if (fold)
+    rows.template operator()<true, false>();
   else
-    rows.template operator()<false>();
+    rows.template operator()<false, false>();
 }
 
 }  // namespace
