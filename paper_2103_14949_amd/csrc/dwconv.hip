@@ -7,6 +7,7 @@
 //              channel, band of rows, segment of 64 columns) and no LDS: a lane loads one
 //              dword per input row and gets its neighbours' by DPP; see the kernel.
 //   rows3x3s2: the same for stride 2 (two outputs per lane and row).
+//   small3x3 : stride 1, W <= 16, H <= 64, any alignment: several planes per wavefront.
 //   wave3x3  : stride 1, W <= 64, without the alignment conditions.  One WAVEFRONT per (image,
 //              channel) plane, four planes per workgroup.  A lane owns a strip
 //              of four output columns and a quarter of the rows and slides
@@ -756,6 +757,135 @@ __global__ __launch_bounds__(kThreads) void dw_rows3x3s2_kernel(DwArgs p, int32_
     rows.template operator()<false, false>();
 }
 
+// Small planes (NCHW 3x3 stride 1 pad 1, W <= 16, H <= 64, any alignment): the late layers of the
+// mobile networks (14 x 14, 7 x 7).  With one plane per wavefront three quarters of the lanes
+// would idle, so the 16 lanes of a DPP row are shared by pp = 16 / nstrips planes (nstrips =
+// strips of four columns per image row); the four DPP rows are the row quarters as in the
+// register kernel.  Rows start at any byte, so a lane's dword is cut out of the two aligned
+// dwords around it; bytes beyond the image row and rows outside the image become the zero
+// point under a byte mask; the shifts stop at plane boundaries by a select.  Everything that
+// depends on the channel is per lane here (weights, bias, multiplier, shift), so the requantize
+// is the general form.  Loads and stores go through descriptors of the whole tensors with
+// out-of-range offsets for everything that does not exist.
+template <int MODE, bool ACC16>
+__global__ __launch_bounds__(kThreads) void dw_small3x3_kernel(DwArgs p, int32_t nstrips, int32_t pp, int32_t rpc,
+                                                               int64_t planes, uint32_t in_bytes,
+                                                               uint32_t out_bytes) {
+  const ConvGeom& g = p.g;
+  const int H = g.H, W = g.W;
+  const int lane = threadIdx.x & 63;
+  const int64_t group = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  constexpr uint32_t kOob = 0x80000000u;
+  constexpr int kEsz = MODE == 0 ? 1 : (MODE == 1 ? 4 : 2);
+  constexpr int kPass = 16;  // most output rows per lane
+
+  const int q = lane & 15;
+  const int rc = lane >> 4;
+  const int pl = q / nstrips;        // plane of the group
+  const int sq = q - pl * nstrips;   // strip of the plane
+  const int64_t plane64 = group * pp + pl;
+  const bool active = pl < pp && plane64 < planes;
+  const uint32_t plane = active ? (uint32_t)plane64 : 0u;  // planes * H * W < 2^31
+  const int c = (int)(plane % (uint32_t)g.C);
+  const int x0 = sq << 2;
+  const int y0 = rc * rpc;
+  const uint32_t x4 = p.act_xor * 0x01010101u;
+  const uint32_t pad4 = (((uint32_t)p.z_a ^ p.act_xor) & 0xffu) * 0x01010101u;
+  // (the input's range ends with the aligned dword that holds its last byte: a dword that
+  // reaches past the range would read as zero as a whole, and an aligned dword lies in one page)
+  const __amdgpu_buffer_rsrc_t rin = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint8_t*>(p.act), 0, (int)((in_bytes + 3u) & ~3u), 0x00020000);
+  const __amdgpu_buffer_rsrc_t rout = __builtin_amdgcn_make_buffer_rsrc(p.out, 0, (int)out_bytes, 0x00020000);
+
+  // row i of the lane is image row y0 + i - 1: the two aligned dwords around its strip
+  const uint32_t base = plane * (uint32_t)(H * W) + (uint32_t)x0;
+  uint32_t dlo[kPass + 2], dhi[kPass + 2];
+#pragma unroll
+  for (int i = 0; i < kPass + 2; ++i) {
+    const int y = y0 + i - 1;
+    const bool ok = active && (uint32_t)y < (uint32_t)H && i - 1 <= rpc;
+    const uint32_t a = base + (uint32_t)(y * W);
+    dlo[i] = __builtin_amdgcn_raw_buffer_load_b32(rin, ok ? (a & ~3u) : kOob, 0, 0);
+    dhi[i] = __builtin_amdgcn_raw_buffer_load_b32(rin, ok ? (a & ~3u) + 4u : kOob, 0, 0);
+  }
+  // the bytes of the strip that lie inside the image row
+  const int nv = W - x0;
+  const uint32_t colmask = nv >= 4 ? 0xffffffffu : (nv <= 0 ? 0u : (1u << (8 * nv)) - 1u);
+  auto row = [&](int i) {
+    const int y = y0 + i - 1;
+    const bool ok = active && (uint32_t)y < (uint32_t)H;
+    const uint32_t a = base + (uint32_t)(y * W);
+    const uint32_t v = __builtin_amdgcn_alignbyte(dhi[i], dlo[i], a & 3u) ^ x4;
+    const uint32_t mask = ok ? colmask : 0u;
+    return (v & mask) | (pad4 & ~mask);
+  };
+
+  // per-lane channel constants
+  const int8_t* wc = p.wgt + (int64_t)c * 9;
+  int32_t wrow[3];
+  int32_t wsum = 0;
+#pragma unroll
+  for (int ky = 0; ky < 3; ++ky) {
+    const int32_t w0 = wc[ky * 3 + 0], w1 = wc[ky * 3 + 1], w2 = wc[ky * 3 + 2];
+    wsum += w0 + w1 + w2;
+    wrow[ky] = (w0 & 0xff) | ((w1 & 0xff) << 8) | ((w2 & 0xff) << 16);
+  }
+  const int32_t bias = p.bias ? p.bias[c] : 0;
+  const int pc = p.per_channel ? c : 0;
+  const int32_t m = MODE == 0 ? p.mult[pc] : 0;
+  const int32_t sh = MODE == 0 ? p.shift[pc] : 0;
+  const int32_t corr = bias + (p.act_off - p.z_a) * wsum;
+  const int64_t rnd = (int64_t)1 << (30 + sh);
+  const int32_t z = p.rs.z_out;
+  const int32_t away = p.rs.half_away ? -1 : 0;
+  int32_t lo = p.rs.lo_rel, hi = p.rs.hi_rel;
+  asm volatile("" : "+v"(lo), "+v"(hi));
+
+  const bool first = sq == 0, last = sq == nstrips - 1;  // the plane's ends inside the DPP row
+  auto windows = [&](uint32_t d1, uint32_t (&w)[4]) {
+    uint32_t left = (uint32_t)__builtin_amdgcn_update_dpp((int)pad4, (int)d1, 0x111, 0xf, 0xf, false);   // row_shr:1
+    uint32_t right = (uint32_t)__builtin_amdgcn_update_dpp((int)pad4, (int)d1, 0x101, 0xf, 0xf, false);  // row_shl:1
+    left = first ? pad4 : left;
+    right = last ? pad4 : right;
+    w[0] = __builtin_amdgcn_alignbyte(d1, left, 3);
+    w[1] = d1;
+    w[2] = __builtin_amdgcn_alignbyte(right, d1, 1);
+    w[3] = __builtin_amdgcn_alignbyte(right, d1, 2);
+  };
+  auto dot4 = [](uint32_t a, int32_t b, int32_t c) {
+    return __builtin_amdgcn_sdot4((int)a, b, c, false);
+  };
+  uint32_t w[3][4];
+  windows(row(0), w[0]);
+  windows(row(1), w[1]);
+#pragma unroll
+  for (int i = 0; i < kPass; ++i) {
+    if (i < rpc) {  // uniform
+      windows(row(i + 2), w[(i + 2) % 3]);
+      const int y = y0 + i;
+      const bool rok = active && y < H;
+      const uint32_t o0 = (plane * (uint32_t)(H * W) + (uint32_t)(y * W + x0)) * kEsz;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        int32_t a = dot4(w[i % 3][e], wrow[0], corr);
+        a = dot4(w[(i + 1) % 3][e], wrow[1], a);
+        a = dot4(w[(i + 2) % 3][e], wrow[2], a);
+        if (ACC16) a = (int32_t)(int16_t)a;
+        const uint32_t off = (rok && x0 + e < W) ? o0 + (uint32_t)(e * kEsz) : kOob;
+        if constexpr (MODE == 0) {
+          const int64_t pr = (int64_t)a * (int64_t)m + rnd + (int64_t)((a >> 31) & away);
+          const int32_t r = med3((int32_t)(pr >> (31 + sh)), lo, hi) + z;
+          __builtin_amdgcn_raw_buffer_store_b8((uint8_t)r, rout, off, 0, 0);
+        } else if constexpr (MODE == 1) {
+          __builtin_amdgcn_raw_buffer_store_b32((uint32_t)a, rout, off, 0, 0);
+        } else {
+          __builtin_amdgcn_raw_buffer_store_b16((short)a, rout, off, 0, 0);
+        }
+      }
+    }
+  }
+}
+
 }  // namespace
 
 hipError_t launch_qconv_depthwise(const GemmArgs& a, const ConvGeom& cg, hipStream_t st) {
@@ -800,6 +930,22 @@ hipError_t launch_qconv_depthwise(const GemmArgs& a, const ConvGeom& cg, hipStre
                      cg.pad_h == 1 && cg.pad_w == 1;
   const int32_t rpc2 = (cg.OH + 3) / 4 < 16 ? (cg.OH + 3) / 4 : 16;
   const int64_t nband2 = (cg.OH + 4 * rpc2 - 1) / (4 * rpc2);
+  // small planes: several planes share the 16 lanes of a DPP row
+  if (plane_ok && cg.W <= 16 && cg.H <= 64 && total * (int64_t)esz < (1ll << 31) &&
+      (int64_t)cg.B * cg.C * cg.H * cg.W < (1ll << 31) &&
+      (reinterpret_cast<uintptr_t>(a.act) & 3u) == 0 && (reinterpret_cast<uintptr_t>(a.out) & 3u) == 0) {
+    const int32_t nstrips = (cg.W + 3) / 4, pp = 16 / nstrips;
+    const int64_t groups = (planes + pp - 1) / pp;
+    if ((groups + 3) / 4 < (1ll << 31)) {
+      auto kern = p.out_mode == 1 ? dw_small3x3_kernel<1, false>
+                : p.out_mode == 2 ? dw_small3x3_kernel<2, true>
+                : p.acc16 ? dw_small3x3_kernel<0, true> : dw_small3x3_kernel<0, false>;
+      hipLaunchKernelGGL(kern, dim3((unsigned)((groups + 3) / 4)), dim3(kThreads), 0, st, p, nstrips, pp,
+                         (int32_t)((cg.H + 3) / 4), planes, (uint32_t)((int64_t)cg.B * cg.C * cg.H * cg.W),
+                         (uint32_t)(total * (int64_t)esz));
+      return hipGetLastError();
+    }
+  }
   const int32_t nsegs = (cg.W + 63) / 64;  // column segments of the register kernels
   if (s2_ok && cg.W % 4 == 0 && (reinterpret_cast<uintptr_t>(a.act) & 3u) == 0 &&
       (reinterpret_cast<uintptr_t>(a.out) & 7u) == 0 && (reinterpret_cast<uintptr_t>(a.wgt) & 3u) == 0 &&

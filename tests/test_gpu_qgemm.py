@@ -341,6 +341,15 @@ DW_CASES = [
     (1, 3, 20, 112, 3, 3, (2, 2), (1, 1)),
     (2, 2, 7, 200, 3, 3, (2, 2), (1, 1)),
     (1, 2, 5, 132, 3, 3, (2, 2), (1, 1)),
+    # small planes (W <= 16): several planes share a DPP row; rows start at any byte
+    (2, 6, 14, 14, 3, 3, (1, 1), (1, 1)),
+    (3, 5, 7, 7, 3, 3, (1, 1), (1, 1)),
+    (1, 4, 16, 16, 3, 3, (1, 1), (1, 1)),
+    (2, 3, 9, 10, 3, 3, (1, 1), (1, 1)),
+    (1, 7, 5, 3, 3, 3, (1, 1), (1, 1)),
+    (1, 2, 64, 13, 3, 3, (1, 1), (1, 1)),
+    (1, 37, 4, 8, 3, 3, (1, 1), (1, 1)),
+    (1, 3, 1, 1, 3, 3, (1, 1), (1, 1)),
 ]
 
 
