@@ -865,22 +865,40 @@ __global__ __launch_bounds__(kThreads) void dw_small3x3_kernel(DwArgs p, int32_t
       const int y = y0 + i;
       const bool rok = active && y < H;
       const uint32_t o0 = (plane * (uint32_t)(H * W) + (uint32_t)(y * W + x0)) * kEsz;
+      int32_t v[4];
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         int32_t a = dot4(w[i % 3][e], wrow[0], corr);
         a = dot4(w[(i + 1) % 3][e], wrow[1], a);
         a = dot4(w[(i + 2) % 3][e], wrow[2], a);
         if (ACC16) a = (int32_t)(int16_t)a;
-        const uint32_t off = (rok && x0 + e < W) ? o0 + (uint32_t)(e * kEsz) : kOob;
         if constexpr (MODE == 0) {
           const int64_t pr = (int64_t)a * (int64_t)m + rnd + (int64_t)((a >> 31) & away);
-          const int32_t r = med3((int32_t)(pr >> (31 + sh)), lo, hi) + z;
-          __builtin_amdgcn_raw_buffer_store_b8((uint8_t)r, rout, off, 0, 0);
-        } else if constexpr (MODE == 1) {
-          __builtin_amdgcn_raw_buffer_store_b32((uint32_t)a, rout, off, 0, 0);
-        } else {
-          __builtin_amdgcn_raw_buffer_store_b16((short)a, rout, off, 0, 0);
+          a = med3((int32_t)(pr >> (31 + sh)), lo, hi) + z;
         }
+        v[e] = a;
+      }
+      auto off = [&](int e) { return (rok && x0 + e < W) ? o0 + (uint32_t)(e * kEsz) : kOob; };
+      if constexpr (MODE == 0) {
+        // whole strips as one dword when rows are dword-aligned, pairs when they are 2-byte
+        // aligned (a pair is inside the row or outside), else single bytes
+        if ((W & 3) == 0) {
+          __builtin_amdgcn_raw_buffer_store_b32(pack4_perm(v[0], v[1], v[2], v[3]), rout, off(0), 0, 0);
+        } else if ((W & 1) == 0) {
+          __builtin_amdgcn_raw_buffer_store_b16((short)(((uint32_t)v[0] & 0xffu) | (((uint32_t)v[1] & 0xffu) << 8)),
+                                                rout, off(0), 0, 0);
+          __builtin_amdgcn_raw_buffer_store_b16((short)(((uint32_t)v[2] & 0xffu) | (((uint32_t)v[3] & 0xffu) << 8)),
+                                                rout, off(2), 0, 0);
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) __builtin_amdgcn_raw_buffer_store_b8((uint8_t)v[e], rout, off(e), 0, 0);
+        }
+      } else if constexpr (MODE == 1) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) __builtin_amdgcn_raw_buffer_store_b32((uint32_t)v[e], rout, off(e), 0, 0);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) __builtin_amdgcn_raw_buffer_store_b16((short)v[e], rout, off(e), 0, 0);
       }
     }
   }
