@@ -196,6 +196,9 @@ __global__ __launch_bounds__(64) void pw_nchw_quad_kernel(PwArgs p) {
   const int pix0 = (int)(tile - (int64_t)b * p.tiles_per_img) * 128;
   const int i = lane & 31, h = lane >> 5;
   const int C = p.C, HW = p.HW, N = p.N;
+  // grid y: block of 32 output channels (few input channels, many output channels: the input is
+  // re-read per block, from the cache)
+  const int n = (int)blockIdx.y * 32 + i;  // the lane's output channel
 
   const __amdgpu_buffer_rsrc_t rin = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<uint8_t*>(p.act) + (int64_t)b * C * HW, 0, C * HW, 0x00020000);
@@ -203,15 +206,15 @@ __global__ __launch_bounds__(64) void pw_nchw_quad_kernel(PwArgs p) {
       const_cast<int8_t*>(p.wgt), 0, N * C, 0x00020000);
   // the lane's four pixels (H * W % 4 == 0: all inside the image or all outside); + channel * HW
   const uint32_t a_lane = (pix0 + 4 * i < HW) ? (uint32_t)(pix0 + 4 * i) : kOob;
-  const uint32_t w_lane = (i < N) ? (uint32_t)(i * C) : kOob;  // + k
+  const uint32_t w_lane = (n < N) ? (uint32_t)(n * C) : kOob;  // + k
 
   // the lane's output channel: requantize parameters (used at the very end)
   int32_t bias_r = 0, mult_r = 0, shift_r = 0;
-  if (i < N) {
-    if (p.bias) bias_r = p.bias[i];
+  if (n < N) {
+    if (p.bias) bias_r = p.bias[n];
     if (MODE == 0) {
-      mult_r = p.mult[p.per_channel ? i : 0];
-      shift_r = p.shift[p.per_channel ? i : 0];
+      mult_r = p.mult[p.per_channel ? n : 0];
+      shift_r = p.shift[p.per_channel ? n : 0];
     }
   }
 
@@ -231,12 +234,13 @@ __global__ __launch_bounds__(64) void pw_nchw_quad_kernel(PwArgs p) {
 #pragma unroll
     for (int u = 0; u < kChunk; ++u) {
       if (FULL || s0 + u < ksteps) {  // uniform
-        const int k = (s0 + u) * 32 + 16 * h;  // first channel of this lane's 16 (C % 16 == 0)
+        const int k = (s0 + u) * 32 + 16 * h;  // first channel of this lane's 16 (C % 4 == 0)
         const bool kok = k < C;
         const uint32_t a0 = (kok && a_lane != kOob) ? a_lane + (uint32_t)(k * HW) : kOob;
 #pragma unroll
-        for (int d = 0; d < 16; ++d)  // channel k + d, four pixels (an out-of-range base stays out of range)
-          ab[u][d] = __builtin_amdgcn_raw_buffer_load_b32(rin, a0 + (a0 != kOob ? (uint32_t)(d * HW) : 0u), 0, 0);
+        for (int d = 0; d < 16; ++d)  // channel k + d, four pixels; channels beyond C are not fetched
+          ab[u][d] = __builtin_amdgcn_raw_buffer_load_b32(
+              rin, (a0 != kOob && k + d < C) ? a0 + (uint32_t)(d * HW) : kOob, 0, 0);
         wb[u] = __builtin_amdgcn_raw_buffer_load_b128(
             rw, (kok && w_lane != kOob) ? w_lane + (uint32_t)k : kOob, 0, 0);
       }
@@ -245,18 +249,24 @@ __global__ __launch_bounds__(64) void pw_nchw_quad_kernel(PwArgs p) {
     for (int u = 0; u < kChunk; ++u) {
       if (FULL || s0 + u < ksteps) {  // uniform
         v4i af[4];
+        const int kc = (s0 + u) * 32 + 16 * h;
 #pragma unroll
         for (int m = 0; m < 4; ++m) {
+          // channels 4m .. 4m+3 of this group exist or not as a whole (C % 4 == 0): the ones that
+          // do not must be exactly zero on both sides (the flip would make them -128, and the
+          // 16-byte weight load runs into the next row)
+          const uint32_t live = kc + 4 * m < C ? 0xffffffffu : 0u;
+          wb[u][m] &= (int)live;
           // rows a..d = channels 4m .. 4m+3, bytes = pixels 0..3  ->  rows = pixels, bytes = channels
           const uint32_t a = ab[u][4 * m], bq = ab[u][4 * m + 1], c = ab[u][4 * m + 2], d = ab[u][4 * m + 3];
           const uint32_t t0 = __builtin_amdgcn_perm(bq, a, 0x05010400u);  // a0 b0 a1 b1
           const uint32_t t1 = __builtin_amdgcn_perm(bq, a, 0x07030602u);  // a2 b2 a3 b3
           const uint32_t t2 = __builtin_amdgcn_perm(d, c, 0x05010400u);   // c0 d0 c1 d1
           const uint32_t t3 = __builtin_amdgcn_perm(d, c, 0x07030602u);   // c2 d2 c3 d3
-          af[0][m] = (int)(__builtin_amdgcn_perm(t2, t0, 0x05040100u) ^ p.act_xor4);
-          af[1][m] = (int)(__builtin_amdgcn_perm(t2, t0, 0x07060302u) ^ p.act_xor4);
-          af[2][m] = (int)(__builtin_amdgcn_perm(t3, t1, 0x05040100u) ^ p.act_xor4);
-          af[3][m] = (int)(__builtin_amdgcn_perm(t3, t1, 0x07060302u) ^ p.act_xor4);
+          af[0][m] = (int)((__builtin_amdgcn_perm(t2, t0, 0x05040100u) ^ p.act_xor4) & live);
+          af[1][m] = (int)((__builtin_amdgcn_perm(t2, t0, 0x07060302u) ^ p.act_xor4) & live);
+          af[2][m] = (int)((__builtin_amdgcn_perm(t3, t1, 0x05040100u) ^ p.act_xor4) & live);
+          af[3][m] = (int)((__builtin_amdgcn_perm(t3, t1, 0x07060302u) ^ p.act_xor4) & live);
         }
 #pragma unroll
         for (int d = 0; d < 4; ++d) wsum = __builtin_amdgcn_sdot4(wb[u][d], 0x01010101, wsum, false);
@@ -274,7 +284,6 @@ __global__ __launch_bounds__(64) void pw_nchw_quad_kernel(PwArgs p) {
 
   const RequantScalars rs = p.rs;
   constexpr int kEsz = MODE == 0 ? 1 : (MODE == 1 ? 4 : 2);
-  const int n = i;
   const int32_t ws = wsum + __shfl_xor(wsum, 32);  // the two k-halves of the row sums
   const int32_t corr = bias_r + p.corr_coef * ws;
   const int64_t rnd = (int64_t)1 << (30 + shift_r);
@@ -338,11 +347,14 @@ __global__ __launch_bounds__(64) void pw_nchw_quad_kernel(PwArgs p) {
 
 template <int MODE, bool ACC16>
 hipError_t launch_nt(const PwArgs& p, hipStream_t st) {
-  if (p.N <= 32) {  // 128 pixels per wavefront, one wavefront per workgroup
+  // 128 pixels per wavefront, one wavefront per workgroup, 32 output channels per workgroup row:
+  // for up to 32 output channels, and for few input channels (the input is then cheap to re-read)
+  if (p.N <= 32 || (p.C <= 64 && (p.N + 31) / 32 <= 65535)) {
     PwArgs q = p;
     q.tiles_per_img = (p.HW + 127) / 128;
     q.tiles = (int64_t)p.B * q.tiles_per_img;  // < 2^31: B and H*W are 32-bit and B * H*W fits the tensor
-    hipLaunchKernelGGL((pw_nchw_quad_kernel<MODE, ACC16>), dim3((unsigned)q.tiles), dim3(64), 0, st, q);
+    hipLaunchKernelGGL((pw_nchw_quad_kernel<MODE, ACC16>), dim3((unsigned)q.tiles, (unsigned)((p.N + 31) / 32)),
+                       dim3(64), 0, st, q);
     return hipGetLastError();
   }
   const unsigned grid = (unsigned)((p.tiles + 3) / 4);
@@ -357,9 +369,11 @@ hipError_t launch_nt(const PwArgs& p, hipStream_t st) {
 bool try_qconv_pointwise_nchw(const GemmArgs& a, const ConvGeom& cg, hipStream_t st, hipError_t* err) {
   const int64_t HW = (int64_t)cg.H * cg.W;
   const size_t esz = a.has_rq ? 1 : (a.acc16 ? 2 : 4);
-  if (a.has_rq && a.rq.half_away && cg.O > 32) return false;  // the wider kernel: ties toward +infinity only
+  const bool quad = cg.O <= 32 || cg.C <= 64;  // the 128-pixel kernel (any O when C is small)
+  if (a.has_rq && a.rq.half_away && !quad) return false;  // the wider kernel: ties toward +infinity only
   if (cg.nhwc || cg.KH != 1 || cg.KW != 1 || cg.stride_h != 1 || cg.stride_w != 1 || cg.pad_h != 0 ||
-      cg.pad_w != 0 || cg.C % 16 != 0 || HW % 4 != 0 || cg.O > 128 || (int64_t)cg.C * HW >= (1ll << 31) ||
+      cg.pad_w != 0 || (quad ? cg.C % 4 != 0 : cg.C % 16 != 0) || HW % 4 != 0 || (!quad && cg.O > 128) ||
+      (int64_t)cg.C * HW >= (1ll << 31) ||
       (int64_t)cg.O * cg.C >= (1ll << 31) || (reinterpret_cast<uintptr_t>(a.wgt) & 15u) != 0 ||
       (reinterpret_cast<uintptr_t>(a.act) & 3u) != 0 ||
       (reinterpret_cast<uintptr_t>(a.out) & (4 * esz - 1)) != 0)

@@ -185,6 +185,10 @@ POINTWISE_CASES = [
     (2, 16, 6, 6, 5), (1, 48, 5, 8, 33), (3, 32, 10, 10, 70), (1, 160, 4, 7, 128), (2, 208, 16, 12, 24),
     # up to 32 output channels: 128 pixels per wavefront, 16-byte stores when H*W % 16 == 0
     (1, 144, 28, 28, 24), (2, 32, 9, 16, 32), (1, 16, 2, 2, 1), (1, 336, 13, 12, 17),
+    # few input channels, many output channels (the expansion layers): blocks of 32 output
+    # channels per workgroup row; channel counts that are multiples of 4 but not of 16
+    (2, 24, 12, 12, 144), (1, 16, 8, 8, 96), (1, 36, 6, 6, 40), (2, 64, 4, 4, 384), (1, 8, 6, 6, 5),
+    (1, 4, 2, 2, 70), (1, 20, 14, 14, 33),
 ]
 
 

@@ -61,6 +61,7 @@ CONV = [
     (1, 3, 9, 7, 5, 3, 3, (2, 2), (1, 1), 1, "nchw"),
     (2, 48, 8, 8, 24, 1, 1, (1, 1), (0, 0), 1, "nchw"),       # the pointwise geometry
     (2, 144, 28, 28, 24, 1, 1, (1, 1), (0, 0), 1, "nchw"),
+    (2, 24, 28, 28, 144, 1, 1, (1, 1), (0, 0), 1, "nchw"),    # few input, many output channels
     (2, 24, 56, 56, 24, 3, 3, (1, 1), (1, 1), 24, "nchw"),    # depthwise: the register kernel's geometry
     (1, 5, 17, 31, 5, 3, 3, (1, 1), (1, 1), 5, "nchw"),       # depthwise, width not a multiple of 4
     (1, 4, 9, 9, 4, 3, 3, (2, 2), (0, 0), 4, "nchw"),         # depthwise, strided
