@@ -465,6 +465,45 @@ __device__ __forceinline__ void qgemm_epilogue(const QgemmParams& p, v16i (&acc)
     return;
   }
 
+  // ---- NCHW output whose image size is not a multiple of 4 (7 x 7 feature maps): a lane's 16
+  // consecutive pixels are stored one by one, walking (image, pixel) without a division per element
+  if constexpr (ACT_ON_P && PIXPERM) {
+    const bool acc16 = p.acc16 != 0;
+#pragma unroll 1
+    for (int tj = 0; tj < TQ; ++tj) {
+      const int j_loc = (wq * TQ + tj) * 32 + frow;
+      const int j = q0 + j_loc;
+      const int32_t c = s_corr[j_loc], m = s_mult[j_loc], sh = s_shift[j_loc];
+#pragma unroll
+      for (int ti = 0; ti < TP; ++ti) {
+        const int i0 = p0 + (wp * TP + ti) * 32 + fhalf * 16;
+        int b = i0 / ohw;
+        int pix = i0 - b * ohw;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          // acc[..][tj] with a runtime tj would need dynamic register indexing; select instead
+          int32_t raw = 0;
+#pragma unroll
+          for (int x = 0; x < TQ; ++x) raw = (x == tj) ? acc[ti][x][r] : raw;
+          int32_t a = raw + c;
+          if (acc16) a = (int32_t)(int16_t)a;
+          if (p.has_rq) a = requant_general(a, m, sh, p.rs);
+          if (j < Q_ext && i0 + r < P_ext) {
+            const int64_t o = ((int64_t)b * p.N + j) * ohw + pix;
+            if (p.out_mode == 0)
+              static_cast<uint8_t*>(p.out)[o] = (uint8_t)a;
+            else if (p.out_mode == 1)
+              static_cast<int32_t*>(p.out)[o] = a;
+            else
+              static_cast<int16_t*>(p.out)[o] = (int16_t)a;
+          }
+          if (++pix == ohw) { pix = 0; ++b; }
+        }
+      }
+    }
+    return;
+  }
+
   // ---- generic path: any output mode, partial tiles, unaligned outputs
 #pragma unroll 1
   for (int tj = 0; tj < TQ; ++tj) {
