@@ -505,7 +505,7 @@ hipError_t launch_qdense(const GemmArgs& a, hipStream_t st) {
     // Tile shape: the one whose busiest CU has the least to do (rounds of tiles over the 256
     // CUs x tile area), with larger tiles discounted for their better operand reuse.
     struct Cand { int id, bp, bq; double eff; };
-    static const Cand cands[] = {{0, 256, 256, 1.0}, {1, 192, 256, 0.95}, {2, 128, 128, 0.75}};
+    static const Cand cands[] = {{0, 256, 256, 1.0}, {1, 192, 256, 0.95}, {2, 128, 128, 0.75}, {4, 64, 64, 0.5}};
     int best = 0;
     double best_cost = 0;
     for (const Cand& c : cands) {

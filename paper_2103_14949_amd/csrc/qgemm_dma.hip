@@ -583,6 +583,7 @@ hipError_t launch_qdense_dma(const QgemmParams& p, int shape, hipStream_t st) {
     case 1: return launch_dma_cfg<2, 4, 3, 2, 4, 1, false, false>(p, st);   // 192 x 256
     case 2: return launch_dma_cfg<2, 4, 2, 1, 4, 1, false, false, 128>(p, st);   // 128 x 128, 128-byte stages
     case 3: return launch_dma_cfg<2, 4, 2, 1, 4, 1, false, false>(p, st);   // 128 x 128, 64-byte stages
+    case 4: return launch_dma_cfg<2, 2, 1, 1, 4, 2, false, false>(p, st);   // 64 x 64: few rows
     default: return launch_dma_cfg<2, 4, 4, 2, 4, 1, false, false>(p, st);  // 256 x 256
   }
 }

@@ -60,7 +60,7 @@ def test_qdense_requant_and_acc16(M, N, K):
     assert_same(host(got), want, "acc16 requant")
 
 
-@pytest.mark.parametrize("tile", [0, 1, 2, 3])  # 256 x 256, 192 x 256, 128 x 128 with 128- and with 64-byte stages
+@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4])  # 256 x 256, 192 x 256, 128 x 128 with 128- and with 64-byte stages, 64 x 64
 @pytest.mark.parametrize("K", [448, 400, 64, 16])  # whole 64-byte stages / a 16-byte tail / one stage
 @pytest.mark.parametrize("adt,za", [(np.uint8, 121), (np.uint8, 128), (np.int8, -4)])
 def test_qdense_every_tile_shape(tile, K, adt, za, monkeypatch):
