@@ -596,8 +596,11 @@ hipError_t launch_qconv_dma(const QgemmParams& p, bool nchw_out, hipStream_t st)
   if (nchw_out) {  // P = pixels, Q = channels
     if (p.N <= 32) return small_m ? launch_dma_cfg<4, 1, 1, 1, 4, 2, true, true>(p, st)    // 128 x 32
                                   : launch_dma_cfg<4, 1, 2, 1, 4, 2, true, true>(p, st);   // 256 x 32
-    if (p.N <= 64) return small_m ? launch_dma_cfg<4, 1, 1, 2, 4, 2, true, true>(p, st)    // 128 x 64
-                                  : launch_dma_cfg<4, 1, 2, 2, 4, 2, true, true>(p, st);   // 256 x 64
+    if (p.N <= 64) {
+      if (p.M <= 64 * 128) return launch_dma_cfg<2, 2, 1, 1, 4, 2, true, true>(p, st);  // 64 x 64: few pixels
+      return small_m ? launch_dma_cfg<4, 1, 1, 2, 4, 2, true, true>(p, st)    // 128 x 64
+                     : launch_dma_cfg<4, 1, 2, 2, 4, 2, true, true>(p, st);   // 256 x 64
+    }
     // few pixels: 64 x 64 tiles when 128 x 128 ones would leave most of the chip idle
     const int64_t tiles128 = (int64_t)((p.M + 127) / 128) * ((p.N + 127) / 128);
     if (small_m && p.N > 64 && tiles128 < 256) return launch_dma_cfg<2, 2, 1, 1, 4, 2, true, true>(p, st);  // 64 x 64
