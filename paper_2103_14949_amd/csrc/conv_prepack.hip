@@ -24,6 +24,7 @@ struct PrepackArgs {
   uint8_t* act_out;
   int8_t* wgt_out;
   int32_t B, C, H, W, O, KH, KW, ph, pw, Hp, Wp, Cp, nhwc;
+  int32_t nhwc_vec;   // channel-last input whose 16-channel chunks are aligned 16-byte loads
   uint32_t act_xor;   // 0x80 for uint8 inputs
   uint32_t pad_byte;  // (zero point XOR act_xor) & 0xff
   int64_t act_chunks, wgt_chunks;  // 16-byte chunks to produce
@@ -75,6 +76,13 @@ __global__ __launch_bounds__(256) void conv_prepack_kernel(PrepackArgs p) {
     uint32_t v[16];
     if (p.nhwc) {
       const int64_t base = (((int64_t)b * p.H + (inside ? iy : 0)) * p.W + (inside ? ix : 0)) * p.C;
+      if (p.nhwc_vec) {  // C % 16 == 0 and a 16-byte aligned tensor: the chunk is one aligned load
+        const uint4 q = *reinterpret_cast<const uint4*>(p.act + base + c0);
+        const uint32_t x4 = p.act_xor * 0x01010101u, pad4 = p.pad_byte * 0x01010101u;
+        const uint4 r = inside ? make_uint4(q.x ^ x4, q.y ^ x4, q.z ^ x4, q.w ^ x4) : make_uint4(pad4, pad4, pad4, pad4);
+        *reinterpret_cast<uint4*>(p.act_out + ((((int64_t)b * p.Hp + py) * p.Wp + px) * p.Cp) + c0) = r;
+        return;
+      }
 #pragma unroll
       for (int j = 0; j < 16; ++j) v[j] = p.act[base + (c0 + j < p.C ? c0 + j : p.C - 1)];
     } else {
@@ -224,6 +232,7 @@ hipError_t launch_conv_prepack(const GemmArgs& a, const ConvGeom& cg, int32_t Cp
   p.ph = cg.pad_h; p.pw = cg.pad_w;
   p.Hp = cg.H + 2 * cg.pad_h; p.Wp = cg.W + 2 * cg.pad_w; p.Cp = Cp;
   p.nhwc = cg.nhwc;
+  p.nhwc_vec = cg.nhwc && cg.C % 16 == 0 && (reinterpret_cast<uintptr_t>(a.act) & 15u) == 0;
   p.act_xor = a.act_unsigned ? 0x80u : 0u;
   p.pad_byte = ((uint32_t)a.act_zero_point ^ p.act_xor) & 0xffu;
   p.act_chunks = (int64_t)p.B * p.Hp * p.Wp * (Cp / 16);
