@@ -8,6 +8,7 @@
 //              dword per input row and gets its neighbours' by DPP; see the kernel.
 //   rows3x3s2: the same for stride 2 (two outputs per lane and row).
 //   small3x3 : stride 1, W <= 16, H <= 64, any alignment: several planes per wavefront.
+//   nhwc3x3  : channel-last, stride 1, pad 1, C % 4 == 0: four channels and a run of pixels per thread.
 //   wave3x3  : stride 1, W <= 64, without the alignment conditions.  One WAVEFRONT per (image,
 //              channel) plane, four planes per workgroup.  A lane owns a strip
 //              of four output columns and a quarter of the rows and slides
@@ -904,6 +905,115 @@ __global__ __launch_bounds__(kThreads) void dw_small3x3_kernel(DwArgs p, int32_t
   }
 }
 
+// Channel-last 3x3, stride 1, pad 1, C % 4 == 0, 4-byte aligned tensors.  A thread owns four
+// consecutive channels (one dword per pixel) and a run of kRun output pixels along a row;
+// consecutive threads own consecutive channel quads, so a wavefront's loads and stores are
+// contiguous.  Per new output column the thread loads three dwords (the column's three rows),
+// splits them into bytes once and keeps the last three columns in registers; the channel's
+// weights, their sum, bias, multiplier and shift are fetched once per thread.  Taps outside
+// the image read as the zero point.  There is no dot product across channels here, so the
+// arithmetic is 36 multiply-adds per output dword.
+constexpr int kNhwcRun = 8;
+
+template <int MODE, bool ACC16>
+__global__ __launch_bounds__(kThreads) void dw_nhwc3x3_kernel(DwArgs p, int32_t c4, int32_t xruns, int64_t threads,
+                                                              uint32_t in_bytes) {
+  const ConvGeom& g = p.g;
+  const int H = g.H, W = g.W, C = g.C;
+  const int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (t >= threads) return;
+  const int cq = (int)(t % c4);
+  int64_t r = t / c4;
+  const int xr = (int)(r % xruns); r /= xruns;
+  const int y = (int)(r % H);
+  const int b = (int)(r / H);
+  const int c = cq << 2;
+  const int x0 = xr * kNhwcRun;
+  constexpr uint32_t kOob = 0x80000000u;
+  constexpr int kEsz = MODE == 0 ? 1 : (MODE == 1 ? 4 : 2);
+  const __amdgpu_buffer_rsrc_t rin = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint8_t*>(p.act), 0, (int)in_bytes, 0x00020000);
+  const uint32_t x4 = p.act_xor * 0x01010101u;
+  const uint32_t pad4 = (((uint32_t)p.z_a ^ p.act_xor) & 0xffu) * 0x01010101u;
+
+  // the four channels' weights: 36 consecutive bytes from byte 9c (c % 4 == 0: dword-aligned)
+  const uint32_t* wp = reinterpret_cast<const uint32_t*>(p.wgt + (int64_t)c * 9);
+  uint32_t wd[9];
+#pragma unroll
+  for (int i = 0; i < 9; ++i) wd[i] = wp[i];
+  int32_t wt[4][9];  // [channel][tap]
+  int32_t wsum[4] = {0, 0, 0, 0};
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int k = 0; k < 9; ++k) {
+      const int byte = j * 9 + k;
+      wt[j][k] = (int32_t)(int8_t)(wd[byte >> 2] >> (8 * (byte & 3)));
+      wsum[j] += wt[j][k];
+    }
+  int32_t corr[4], m[4], sh[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int pc = p.per_channel ? c + j : 0;
+    corr[j] = (p.bias ? p.bias[c + j] : 0) + (p.act_off - p.z_a) * wsum[j];
+    m[j] = MODE == 0 ? p.mult[pc] : 0;
+    sh[j] = MODE == 0 ? p.shift[pc] : 0;
+  }
+  const int32_t away = p.rs.half_away ? -1 : 0;
+
+  // column x of the three rows y-1 .. y+1 as signed bytes per channel
+  const uint32_t pix_stride = (uint32_t)C;
+  const uint32_t row0 = ((uint32_t)b * (uint32_t)H) * (uint32_t)W;  // in pixels
+  auto load_col = [&](int x, int32_t (&col)[3][4]) {
+    uint32_t d[3];
+#pragma unroll
+    for (int ky = 0; ky < 3; ++ky) {
+      const int iy = y + ky - 1;
+      const bool ok = (uint32_t)iy < (uint32_t)H && (uint32_t)x < (uint32_t)W;
+      const uint32_t off = ok ? (row0 + (uint32_t)(iy * W + x)) * pix_stride + (uint32_t)c : kOob;
+      const uint32_t v = __builtin_amdgcn_raw_buffer_load_b32(rin, off, 0, 0);
+      d[ky] = ok ? (v ^ x4) : pad4;
+    }
+#pragma unroll
+    for (int ky = 0; ky < 3; ++ky)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) col[ky][j] = (int32_t)(int8_t)(d[ky] >> (8 * j));
+  };
+  int32_t cols[3][3][4];  // ring of the last three columns, slot = (x + 1) % 3 over the unrolled loop
+  load_col(x0 - 1, cols[0]);
+  load_col(x0, cols[1]);
+  uint8_t* out = static_cast<uint8_t*>(p.out);
+#pragma unroll
+  for (int i = 0; i < kNhwcRun; ++i) {
+    const int x = x0 + i;
+    load_col(x + 1, cols[(i + 2) % 3]);
+    if (x < W) {
+      int32_t v[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        int32_t a = corr[j];
+#pragma unroll
+        for (int ky = 0; ky < 3; ++ky)
+#pragma unroll
+          for (int kx = 0; kx < 3; ++kx) a += cols[(i + kx) % 3][ky][j] * wt[j][ky * 3 + kx];
+        if (ACC16) a = (int32_t)(int16_t)a;
+        if constexpr (MODE == 0) {
+          const int64_t pr = (int64_t)a * (int64_t)m[j] + ((int64_t)1 << (30 + sh[j])) + (int64_t)((a >> 31) & away);
+          a = med3((int32_t)(pr >> (31 + sh[j])), p.rs.lo_rel, p.rs.hi_rel) + p.rs.z_out;
+        }
+        v[j] = a;
+      }
+      const int64_t o = ((((int64_t)b * H + y) * W + x) * C + c) * kEsz;
+      if constexpr (MODE == 0)
+        *reinterpret_cast<uint32_t*>(out + o) = pack4_perm(v[0], v[1], v[2], v[3]);
+      else if constexpr (MODE == 1)
+        *reinterpret_cast<int4*>(out + o) = make_int4(v[0], v[1], v[2], v[3]);
+      else
+        *reinterpret_cast<short4*>(out + o) = make_short4((short)v[0], (short)v[1], (short)v[2], (short)v[3]);
+    }
+  }
+}
+
 }  // namespace
 
 hipError_t launch_qconv_depthwise(const GemmArgs& a, const ConvGeom& cg, hipStream_t st) {
@@ -948,6 +1058,22 @@ hipError_t launch_qconv_depthwise(const GemmArgs& a, const ConvGeom& cg, hipStre
                      cg.pad_h == 1 && cg.pad_w == 1;
   const int32_t rpc2 = (cg.OH + 3) / 4 < 16 ? (cg.OH + 3) / 4 : 16;
   const int64_t nband2 = (cg.OH + 4 * rpc2 - 1) / (4 * rpc2);
+  // channel-last 3x3 stride 1 pad 1
+  if (cg.nhwc && cg.KH == 3 && cg.KW == 3 && cg.stride_h == 1 && cg.stride_w == 1 && cg.pad_h == 1 &&
+      cg.pad_w == 1 && cg.C % 4 == 0 && (reinterpret_cast<uintptr_t>(a.act) & 3u) == 0 &&
+      (reinterpret_cast<uintptr_t>(a.wgt) & 3u) == 0 && (reinterpret_cast<uintptr_t>(a.out) & (4 * esz - 1)) == 0 &&
+      (int64_t)cg.B * cg.C * cg.H * cg.W < (1ll << 31)) {
+    const int32_t c4 = cg.C / 4, xruns = (cg.W + kNhwcRun - 1) / kNhwcRun;
+    const int64_t threads = (int64_t)cg.B * cg.H * xruns * c4;
+    if ((threads + kThreads - 1) / kThreads < (1ll << 31)) {
+      auto kern = p.out_mode == 1 ? dw_nhwc3x3_kernel<1, false>
+                : p.out_mode == 2 ? dw_nhwc3x3_kernel<2, true>
+                : p.acc16 ? dw_nhwc3x3_kernel<0, true> : dw_nhwc3x3_kernel<0, false>;
+      hipLaunchKernelGGL(kern, dim3((unsigned)((threads + kThreads - 1) / kThreads)), dim3(kThreads), 0, st, p, c4,
+                         xruns, threads, (uint32_t)((int64_t)cg.B * cg.C * cg.H * cg.W));
+      return hipGetLastError();
+    }
+  }
   // small planes: several planes share the 16 lanes of a DPP row
   if (plane_ok && cg.W <= 16 && cg.H <= 64 && total * (int64_t)esz < (1ll << 31) &&
       (int64_t)cg.B * cg.C * cg.H * cg.W < (1ll << 31) &&

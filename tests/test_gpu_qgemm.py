@@ -354,6 +354,12 @@ DW_CASES = [
     (1, 2, 64, 13, 3, 3, (1, 1), (1, 1)),
     (1, 37, 4, 8, 3, 3, (1, 1), (1, 1)),
     (1, 3, 1, 1, 3, 3, (1, 1), (1, 1)),
+    # channel counts that are multiples of 4: the channel-last kernel (its NCHW twins take other paths)
+    (2, 8, 9, 11, 3, 3, (1, 1), (1, 1)),
+    (1, 12, 20, 7, 3, 3, (1, 1), (1, 1)),
+    (1, 144, 14, 14, 3, 3, (1, 1), (1, 1)),
+    (2, 4, 5, 37, 3, 3, (1, 1), (1, 1)),
+    (1, 32, 3, 8, 3, 3, (1, 1), (1, 1)),
 ]
 
 

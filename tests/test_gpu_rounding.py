@@ -67,6 +67,7 @@ CONV = [
     (1, 4, 9, 9, 4, 3, 3, (2, 2), (0, 0), 4, "nchw"),         # depthwise, strided
     (1, 6, 150, 20, 6, 3, 3, (1, 1), (1, 1), 6, "nhwc"),
     (2, 40, 14, 14, 40, 3, 3, (1, 1), (1, 1), 40, "nchw"),    # depthwise, small planes
+    (2, 40, 14, 14, 40, 3, 3, (1, 1), (1, 1), 40, "nhwc"),    # depthwise, channel-last kernel
 ]
 
 
