@@ -18,11 +18,10 @@
  *   - Pointers marked "device" are GPU addresses valid on the current HIP
  *     device; "host" are ordinary pointers.  The caller owns every buffer it
  *     passes: the library never frees or keeps such a pointer after returning.
- *   - hago_qconv2d with groups == 1 first rewrites its operands into a scratch
- *     buffer that the library owns, one per device, allocated on first use and
- *     reallocated when a larger one is needed (that call waits for the device
- *     to go idle).  Calls that use it must not run concurrently on one device.
- *     No other entry point allocates.
+ *   - No entry point allocates, frees or keeps device memory, and none waits
+ *     for the device.  The one operator that wants scratch memory, the
+ *     groups == 1 convolution (it rewrites its operands before the matrix
+ *     cores read them), takes it from the caller: hago_qconv2d_ws.
  *   - Tensors are dense and contiguous in the stated order.  `out` must not
  *     overlap any input.  A tensor with zero elements may be passed as NULL.
  *   - `stream` is the caller's hipStream_t (NULL = the default stream).  Calls
@@ -78,6 +77,10 @@ typedef enum {
 /* flags */
 #define HAGO_STRICT_ACC16 1u /* refuse int16 accumulation unless the declared
                                 operand ranges prove it cannot overflow */
+#define HAGO_WS_WEIGHTS_READY 2u /* hago_qconv2d_ws only: the workspace still
+                                holds this layer's rewritten weights from an
+                                earlier call with the same w, geometry and
+                                workspace; only the activations are rewritten */
 
 /* A quantized tensor type: container, effective bit count, signedness of the
  * effective range, zero point.  `bits` is a CONTRACT on the value range
@@ -166,6 +169,10 @@ hago_status hago_qdense(const void* a, hago_qtype a_t, const void* w,
  * requantize (channel = o) and raw output as for hago_qdense.
  * Errors as for hago_qdense; additionally SHAPE for any other `groups`, a
  * kernel larger than the padded image, stride < 1, pad < 0.
+ * This entry point uses no scratch memory: depthwise, 1x1 and channel-last
+ * 1x1 geometries have kernels that read the caller's tensors directly; every
+ * other groups == 1 geometry runs a general kernel that gathers its operands
+ * from the caller's layout and is several times slower than hago_qconv2d_ws.
  */
 hago_status hago_qconv2d(const void* a, hago_qtype a_t, const void* w,
                          hago_qtype w_t, const int32_t* bias,
@@ -175,6 +182,45 @@ hago_status hago_qconv2d(const void* a, hago_qtype a_t, const void* w,
                          int32_t pad_w, int32_t groups, hago_dtype acc_dtype,
                          const hago_requant* rq, void* out, uint32_t flags,
                          void* stream);
+
+/*
+ * The same operator with caller-owned scratch memory (Sec. 6.2: conv2d on the
+ * fast integer instruction).  The matrix cores read 16 consecutive reduction
+ * elements per lane, so a groups == 1 convolution first rewrites, in one
+ * launch, the activations into a padded channel-last int8 copy and the
+ * weights into [O][KH*KW][C rounded up to 16] inside `workspace`, then runs
+ * the implicit GEMM over the copies.
+ *   hago_qconv2d_workspace_bytes  (host only, launches nothing): bytes this
+ *     geometry wants; 0 when it runs without scratch (depthwise, or shapes
+ *     only the general kernel indexes); -1 for arguments hago_qconv2d would
+ *     refuse with SHAPE.  The weight copy comes first and its size does not
+ *     depend on B.
+ *   hago_qconv2d_ws: `workspace` is device memory, 256-byte aligned, of
+ *     `workspace_bytes` >= that count (NULL / 0 allowed when the count is 0).
+ *     Its contents need not be initialised and are overwritten; the library
+ *     keeps no pointer to it after the call's work has run.  Calls that share
+ *     one workspace must be ordered on one stream; calls with distinct
+ *     workspaces may overlap freely.  With HAGO_WS_WEIGHTS_READY the weight
+ *     part is taken as written by an earlier call (weights are constants of a
+ *     layer) and only the activations are rewritten.
+ * Results are identical to hago_qconv2d's.  Errors as for hago_qconv2d;
+ * additionally NULL (workspace needed but NULL) and PARAM (workspace too
+ * small, misaligned, or negative size).
+ */
+int64_t hago_qconv2d_workspace_bytes(hago_layout layout, int64_t B, int64_t C,
+                                     int64_t H, int64_t W, int64_t O,
+                                     int32_t KH, int32_t KW, int32_t stride_h,
+                                     int32_t stride_w, int32_t pad_h,
+                                     int32_t pad_w, int32_t groups);
+hago_status hago_qconv2d_ws(const void* a, hago_qtype a_t, const void* w,
+                            hago_qtype w_t, const int32_t* bias,
+                            hago_layout layout, int64_t B, int64_t C, int64_t H,
+                            int64_t W, int64_t O, int32_t KH, int32_t KW,
+                            int32_t stride_h, int32_t stride_w, int32_t pad_h,
+                            int32_t pad_w, int32_t groups, hago_dtype acc_dtype,
+                            const hago_requant* rq, void* out, void* workspace,
+                            int64_t workspace_bytes, uint32_t flags,
+                            void* stream);
 
 /*
  * Batched candidate evaluation of simulated_quantize (Sec. 6.3 "Batched GPU
@@ -266,6 +312,33 @@ hago_status hago_requantize(const void* acc, hago_dtype acc_dtype,
 
 /* Static, NUL-terminated description of a status code. */
 const char* hago_status_string(hago_status s);
+
+/*
+ * The inclusive range of integer codes that `bits` effective bits hold
+ * (Sec. 2: a b-bit data type has 2^b bins; Sec. 5.3: fewer effective bits than
+ * the container): signed [-2^(bits-1), 2^(bits-1)-1], unsigned [0, 2^bits-1].
+ * These are the widest clip limits a call accepts for that bit count and the
+ * defaults a binding should pass.  lo, hi: host pointers.  Errors: NULL, BITS
+ * (bits < 1, > 32, or 32 unsigned, which int32 cannot hold).
+ */
+hago_status hago_bit_range(int32_t bits, int32_t is_signed, int32_t* lo,
+                           int32_t* hi);
+
+/*
+ * Test hook, not part of the operator set: forces which GEMM kernel family
+ * and tile shape serve the following hago_qdense / hago_qconv2d* calls of
+ * this process, so that tests can compare every variant with the oracle on
+ * one shape.  Results never depend on it.  Keys:
+ *   HAGO_HOOK_GEMM_PATH     0 automatic; 1 the general register-staged kernel;
+ *                           2 the streaming kernel, skipping the 1x1 special cases
+ *   HAGO_HOOK_STREAM_TILE   -1 automatic; 0..4 a tile of the streaming dense kernel
+ *   HAGO_HOOK_GENERAL_TILE  -1 automatic; 0..6 a tile of the general kernel
+ * Unknown keys are ignored.
+ */
+#define HAGO_HOOK_GEMM_PATH 0
+#define HAGO_HOOK_STREAM_TILE 1
+#define HAGO_HOOK_GENERAL_TILE 2
+void hago_set_test_hook(int32_t key, int32_t value);
 
 #ifdef __cplusplus
 }

@@ -12,12 +12,15 @@ import os
 U8, I8, I16, I32, F32 = 0, 1, 2, 3, 4
 NCHW, NHWC = 0, 1
 STRICT_ACC16 = 1
+WS_WEIGHTS_READY = 2
+HOOK_GEMM_PATH, HOOK_STREAM_TILE, HOOK_GENERAL_TILE = 0, 1, 2   # hago_set_test_hook keys
 ROUND_UPWARD, ROUND_HALF_AWAY = 0, 1   # hago_rounding
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libhago.so")
 
-EXPORTS = ("hago_simquant", "hago_simquant_batched", "hago_absmax", "hago_quantize", "hago_dequantize", "hago_simquant_codes", "hago_qdense", "hago_qconv2d", "hago_requantize", "hago_status_string")
+EXPORTS = ("hago_simquant", "hago_simquant_batched", "hago_absmax", "hago_quantize", "hago_dequantize", "hago_simquant_codes", "hago_qdense", "hago_qconv2d", "hago_qconv2d_ws", "hago_qconv2d_workspace_bytes", "hago_requantize",
+           "hago_status_string", "hago_bit_range", "hago_set_test_hook")
 
 
 class _QType(C.Structure):
@@ -76,8 +79,30 @@ def lib():
         L.hago_qconv2d.argtypes = [vp, _QType, vp, _QType, vp, i32, i64, i64, i64, i64, i64,
                                    i32, i32, i32, i32, i32, i32, i32, i32,
                                    C.POINTER(_Requant), vp, u32, vp]
+        L.hago_qconv2d_ws.restype = i32
+        L.hago_qconv2d_ws.argtypes = [vp, _QType, vp, _QType, vp, i32, i64, i64, i64, i64, i64,
+                                      i32, i32, i32, i32, i32, i32, i32, i32,
+                                      C.POINTER(_Requant), vp, vp, i64, u32, vp]
+        L.hago_qconv2d_workspace_bytes.restype = i64
+        L.hago_qconv2d_workspace_bytes.argtypes = [i32, i64, i64, i64, i64, i64, i32, i32, i32, i32, i32, i32, i32]
+        L.hago_bit_range.restype = i32
+        L.hago_bit_range.argtypes = [i32, i32, C.POINTER(i32), C.POINTER(i32)]
+        L.hago_set_test_hook.restype = None
+        L.hago_set_test_hook.argtypes = [i32, i32]
         _lib = L
     return _lib
+
+
+def bit_range(bits, is_signed):
+    """hago_bit_range: the inclusive code range of `bits` effective bits."""
+    lo, hi = C.c_int32(), C.c_int32()
+    _check(lib().hago_bit_range(int(bits), int(bool(is_signed)), C.byref(lo), C.byref(hi)))
+    return lo.value, hi.value
+
+
+def set_test_hook(key, value):
+    """hago_set_test_hook: force a GEMM kernel family / tile for the following calls (tests)."""
+    lib().hago_set_test_hook(int(key), int(value))
 
 
 def _check(code):
@@ -106,8 +131,7 @@ class Requant:
         self.multiplier = multiplier
         self.shift = shift
         self.out = out
-        lo, hi = ((-(1 << (out.bits - 1)), (1 << (out.bits - 1)) - 1) if out.is_signed
-                  else (0, (1 << out.bits) - 1))
+        lo, hi = bit_range(out.bits, out.is_signed)
         self.clip_lo = lo if clip_lo is None else int(clip_lo)
         self.clip_hi = hi if clip_hi is None else int(clip_hi)
         self.per_channel = int(multiplier.numel() > 1) if per_channel is None else int(per_channel)
@@ -162,7 +186,7 @@ def simquant(x, scale, zero_point, q: QType, clip_lo=None, clip_hi=None, per_cha
     """hago_simquant over x[outer, channels, inner] (fp32, contiguous)."""
     assert x.dim() == 3 and x.is_contiguous()
     outer, channels, inner = x.shape
-    lo, hi = ((-(1 << (q.bits - 1)), (1 << (q.bits - 1)) - 1) if q.is_signed else (0, (1 << q.bits) - 1))
+    lo, hi = bit_range(q.bits, q.is_signed)
     clip_lo = lo if clip_lo is None else clip_lo
     clip_hi = hi if clip_hi is None else clip_hi
     pc = int(scale.numel() > 1) if per_channel is None else int(per_channel)
@@ -203,7 +227,7 @@ def quantize(x, scale, zero_point, q: QType, clip_lo=None, clip_hi=None, per_cha
     """hago_quantize over x[outer, channels, inner] (fp32): integer codes in q's container."""
     assert x.dim() == 3 and x.is_contiguous()
     outer, channels, inner = x.shape
-    lo, hi = ((-(1 << (q.bits - 1)), (1 << (q.bits - 1)) - 1) if q.is_signed else (0, (1 << q.bits) - 1))
+    lo, hi = bit_range(q.bits, q.is_signed)
     clip_lo = lo if clip_lo is None else clip_lo
     clip_hi = hi if clip_hi is None else clip_hi
     pc = int(scale.numel() > 1) if per_channel is None else int(per_channel)
@@ -222,7 +246,7 @@ def simquant_codes(x, scale, zero_point, q: QType, clip_lo=None, clip_hi=None, p
     """hago_simquant_codes over x[outer, channels, inner] (fp32): (simulated-quantized fp32, integer codes)."""
     assert x.dim() == 3 and x.is_contiguous()
     outer, channels, inner = x.shape
-    lo, hi = ((-(1 << (q.bits - 1)), (1 << (q.bits - 1)) - 1) if q.is_signed else (0, (1 << q.bits) - 1))
+    lo, hi = bit_range(q.bits, q.is_signed)
     clip_lo = lo if clip_lo is None else clip_lo
     clip_hi = hi if clip_hi is None else clip_hi
     pc = int(scale.numel() > 1) if per_channel is None else int(per_channel)
@@ -301,16 +325,35 @@ def qdense(a, a_t: QType, w, w_t: QType, bias=None, acc_dtype=I32, rq: Requant |
     return out
 
 
-def qconv2d(a, a_t: QType, w, w_t: QType, bias=None, layout=NCHW, stride=(1, 1), pad=(0, 0),
-            groups=1, acc_dtype=I32, rq: Requant | None = None, flags=0, out=None, prepare=False):
-    """hago_qconv2d: NCHW a [B,C,H,W], w [O,C/g,KH,KW]; NHWC a [B,H,W,C], w [O,KH,KW,C/g]."""
-    assert a.dim() == 4 and w.dim() == 4 and a.is_contiguous() and w.is_contiguous()
+def _conv_dims(a, w, layout):
     if layout == NCHW:
         B, Cc, H, W = a.shape
         O, _, KH, KW = w.shape
     else:
         B, H, W, Cc = a.shape
         O, KH, KW, _ = w.shape
+    return B, Cc, H, W, O, KH, KW
+
+
+def qconv2d_workspace_bytes(a_shape, w_shape, layout=NCHW, stride=(1, 1), pad=(0, 0), groups=1):
+    """hago_qconv2d_workspace_bytes for tensors of these shapes."""
+    class _S:
+        def __init__(self, shape):
+            self.shape = tuple(shape)
+    B, Cc, H, W, O, KH, KW = _conv_dims(_S(a_shape), _S(w_shape), layout)
+    return int(lib().hago_qconv2d_workspace_bytes(layout, B, Cc, H, W, O, KH, KW, stride[0], stride[1],
+                                                  pad[0], pad[1], groups))
+
+
+def qconv2d(a, a_t: QType, w, w_t: QType, bias=None, layout=NCHW, stride=(1, 1), pad=(0, 0),
+            groups=1, acc_dtype=I32, rq: Requant | None = None, flags=0, out=None, prepare=False,
+            workspace=None):
+    """hago_qconv2d: NCHW a [B,C,H,W], w [O,C/g,KH,KW]; NHWC a [B,H,W,C], w [O,KH,KW,C/g].
+
+    With `workspace` (a uint8 device tensor of at least qconv2d_workspace_bytes(...) bytes, or an
+    empty one when that is 0) the call goes to hago_qconv2d_ws."""
+    assert a.dim() == 4 and w.dim() == 4 and a.is_contiguous() and w.is_contiguous()
+    B, Cc, H, W, O, KH, KW = _conv_dims(a, w, layout)
     OH = (H + 2 * pad[0] - KH) // stride[0] + 1
     OW = (W + 2 * pad[1] - KW) // stride[1] + 1
     if out is None:
@@ -320,8 +363,15 @@ def qconv2d(a, a_t: QType, w, w_t: QType, bias=None, layout=NCHW, stride=(1, 1),
     st = rq.c() if rq is not None else None
     args = (_ptr(a), a_t.c(), _ptr(w), w_t.c(), _ptr(bias), layout, B, Cc, H, W, O,
             KH, KW, stride[0], stride[1], pad[0], pad[1], groups, acc_dtype,
-            C.byref(st) if st is not None else None, _ptr(out), flags, _stream())
+            C.byref(st) if st is not None else None, _ptr(out))
+    if workspace is not None:
+        fn = lib().hago_qconv2d_ws
+        args += (_ptr(workspace) if workspace.numel() else None, workspace.numel() * workspace.element_size(),
+                 flags, _stream())
+    else:
+        fn = lib().hago_qconv2d
+        args += (flags, _stream())
     if prepare:
-        return Prepared(lib().hago_qconv2d, args, (a, w, bias, rq, st, out), out)
-    _check(lib().hago_qconv2d(*args))
+        return Prepared(fn, args, (a, w, bias, rq, st, out, workspace), out)
+    _check(fn(*args))
     return out

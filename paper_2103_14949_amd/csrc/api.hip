@@ -304,26 +304,31 @@ hago_status hago_qdense(const void* a, hago_qtype a_t, const void* w, hago_qtype
   return from_hip(hago::launch_qdense(g, static_cast<hipStream_t>(stream)));
 }
 
-hago_status hago_qconv2d(const void* a, hago_qtype a_t, const void* w, hago_qtype w_t,
-                         const int32_t* bias, hago_layout layout, int64_t B, int64_t C, int64_t H,
-                         int64_t W, int64_t O, int32_t KH, int32_t KW, int32_t stride_h,
-                         int32_t stride_w, int32_t pad_h, int32_t pad_w, int32_t groups,
-                         hago_dtype acc_dtype, const hago_requant* rq, void* out, uint32_t flags,
-                         void* stream) {
-  GemmArgs g{};
+}  // extern "C"
+
+namespace {
+
+// Geometry checks shared by the convolution entry points, in two steps (the operand checks come
+// between them): the scalars, then the 32-bit index limits; the second fills cg.
+hago_status check_conv_scalars(hago_layout layout, int64_t B, int64_t C, int64_t H, int64_t W, int64_t O,
+                               int32_t KH, int32_t KW, int32_t stride_h, int32_t stride_w, int32_t pad_h,
+                               int32_t pad_w, int32_t groups, int64_t* kred, bool* depthwise) {
   if (B < 0 || C < 1 || H < 1 || W < 1 || O < 1 || KH < 1 || KW < 1 || stride_h < 1 ||
       stride_w < 1 || pad_h < 0 || pad_w < 0)
     return HAGO_ERR_SHAPE;
   if (layout != HAGO_NCHW && layout != HAGO_NHWC) return HAGO_ERR_SHAPE;
-  const bool depthwise = (groups != 1) && (groups == C) && (groups == O);
-  if (groups != 1 && !depthwise) return HAGO_ERR_SHAPE;
+  *depthwise = (groups != 1) && (groups == C) && (groups == O);
+  if (groups != 1 && !*depthwise) return HAGO_ERR_SHAPE;
   if (H + 2 * (int64_t)pad_h < KH || W + 2 * (int64_t)pad_w < KW) return HAGO_ERR_SHAPE;
+  *kred = *depthwise ? (int64_t)KH * KW : C * (int64_t)KH * KW;
+  return HAGO_OK;
+}
+
+hago_status check_conv_limits(hago_layout layout, int64_t B, int64_t C, int64_t H, int64_t W, int64_t O,
+                              int32_t KH, int32_t KW, int32_t stride_h, int32_t stride_w, int32_t pad_h,
+                              int32_t pad_w, int64_t kred, ConvGeom* cg) {
   const int64_t OH = (H + 2 * (int64_t)pad_h - KH) / stride_h + 1;
   const int64_t OW = (W + 2 * (int64_t)pad_w - KW) / stride_w + 1;
-  const int64_t Kred = depthwise ? (int64_t)KH * KW : C * (int64_t)KH * KW;
-  hago_status s = check_operands(a, a_t, w, w_t, acc_dtype, rq, out, flags, Kred, B == 0, false,
-                                 B == 0, &g);
-  if (s != HAGO_OK) return s;
   // every flat offset into the input, weights and (per image) output fits 31 bits
   const int64_t lim = kI32Max - 512;
   if (KH > 4096 || KW > 4096 || pad_h > 4096 || pad_w > 4096 || stride_h > 4096 ||
@@ -333,19 +338,109 @@ hago_status hago_qconv2d(const void* a, hago_qtype a_t, const void* w, hago_qtyp
   if ((B ? B : 1) * C > lim / H / W) return HAGO_ERR_SHAPE;         // input elements
   if ((B ? B : 1) * OH * OW > lim) return HAGO_ERR_SHAPE;            // GEMM rows
   if ((B ? B : 1) * O > lim / OH / OW) return HAGO_ERR_SHAPE;        // output elements
-  if (O * Kred > lim) return HAGO_ERR_SHAPE;                          // weight elements
+  if (O * kred > lim) return HAGO_ERR_SHAPE;                          // weight elements
+  cg->B = (int32_t)B; cg->C = (int32_t)C; cg->H = (int32_t)H; cg->W = (int32_t)W; cg->O = (int32_t)O;
+  cg->OH = (int32_t)OH; cg->OW = (int32_t)OW; cg->KH = KH; cg->KW = KW;
+  cg->stride_h = stride_h; cg->stride_w = stride_w; cg->pad_h = pad_h; cg->pad_w = pad_w;
+  cg->nhwc = layout == HAGO_NHWC;
+  return HAGO_OK;
+}
+
+// Scratch the convolution asks for: 0 for depthwise and for geometries only the generic kernel serves.
+int64_t conv_scratch_need(const ConvGeom& cg, bool depthwise) {
+  if (depthwise || cg.B == 0) return 0;
+  const int64_t n = hago::qconv_workspace_bytes(cg);
+  return n < 0 ? 0 : n;
+}
+
+enum class Scratch { kNone, kCaller };
+
+hago_status qconv2d_impl(const void* a, hago_qtype a_t, const void* w, hago_qtype w_t,
+                         const int32_t* bias, hago_layout layout, int64_t B, int64_t C, int64_t H,
+                         int64_t W, int64_t O, int32_t KH, int32_t KW, int32_t stride_h,
+                         int32_t stride_w, int32_t pad_h, int32_t pad_w, int32_t groups,
+                         hago_dtype acc_dtype, const hago_requant* rq, void* out, uint32_t flags,
+                         void* stream, Scratch mode, void* workspace, int64_t workspace_bytes) {
+  GemmArgs g{};
   ConvGeom cg{};
-  cg.B = (int32_t)B; cg.C = (int32_t)C; cg.H = (int32_t)H; cg.W = (int32_t)W; cg.O = (int32_t)O;
-  cg.OH = (int32_t)OH; cg.OW = (int32_t)OW; cg.KH = KH; cg.KW = KW;
-  cg.stride_h = stride_h; cg.stride_w = stride_w; cg.pad_h = pad_h; cg.pad_w = pad_w;
-  cg.nhwc = layout == HAGO_NHWC;
+  int64_t Kred = 0;
+  bool depthwise = false;
+  hago_status s = check_conv_scalars(layout, B, C, H, W, O, KH, KW, stride_h, stride_w, pad_h, pad_w,
+                                     groups, &Kred, &depthwise);
+  if (s != HAGO_OK) return s;
+  const uint32_t ws_flags = mode == Scratch::kCaller ? HAGO_WS_WEIGHTS_READY : 0u;
+  s = check_operands(a, a_t, w, w_t, acc_dtype, rq, out, flags & ~ws_flags, Kred, B == 0, false,
+                     B == 0, &g);
+  if (s != HAGO_OK) return s;
+  s = check_conv_limits(layout, B, C, H, W, O, KH, KW, stride_h, stride_w, pad_h, pad_w, Kred, &cg);
+  if (s != HAGO_OK) return s;
   g.bias = bias;
-  g.M = (int32_t)(B * OH * OW);
+  g.M = (int32_t)(B * cg.OH * cg.OW);
   g.N = (int32_t)O;
   g.K = (int32_t)Kred;
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (depthwise) return from_hip(hago::launch_qconv_depthwise(g, cg, st));
-  return from_hip(hago::launch_qconv_gemm(g, cg, st));
+  void* ws = nullptr;
+  if (mode == Scratch::kCaller) {
+    const int64_t need = conv_scratch_need(cg, false);
+    if (need > 0) {
+      if (!workspace) return HAGO_ERR_NULL;
+      if (workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return HAGO_ERR_PARAM;
+      ws = workspace;
+    }
+  }
+  return from_hip(hago::launch_qconv_gemm(g, cg, ws, (flags & HAGO_WS_WEIGHTS_READY) != 0, st));
+}
+
+}  // namespace
+
+extern "C" {
+
+hago_status hago_qconv2d(const void* a, hago_qtype a_t, const void* w, hago_qtype w_t,
+                         const int32_t* bias, hago_layout layout, int64_t B, int64_t C, int64_t H,
+                         int64_t W, int64_t O, int32_t KH, int32_t KW, int32_t stride_h,
+                         int32_t stride_w, int32_t pad_h, int32_t pad_w, int32_t groups,
+                         hago_dtype acc_dtype, const hago_requant* rq, void* out, uint32_t flags,
+                         void* stream) {
+  return qconv2d_impl(a, a_t, w, w_t, bias, layout, B, C, H, W, O, KH, KW, stride_h, stride_w, pad_h,
+                      pad_w, groups, acc_dtype, rq, out, flags, stream, Scratch::kNone, nullptr, 0);
+}
+
+int64_t hago_qconv2d_workspace_bytes(hago_layout layout, int64_t B, int64_t C, int64_t H, int64_t W,
+                                     int64_t O, int32_t KH, int32_t KW, int32_t stride_h,
+                                     int32_t stride_w, int32_t pad_h, int32_t pad_w, int32_t groups) {
+  ConvGeom cg{};
+  int64_t Kred = 0;
+  bool depthwise = false;
+  if (check_conv_scalars(layout, B, C, H, W, O, KH, KW, stride_h, stride_w, pad_h, pad_w, groups, &Kred,
+                         &depthwise) != HAGO_OK ||
+      check_conv_limits(layout, B, C, H, W, O, KH, KW, stride_h, stride_w, pad_h, pad_w, Kred, &cg) != HAGO_OK)
+    return -1;
+  return conv_scratch_need(cg, depthwise);
+}
+
+hago_status hago_qconv2d_ws(const void* a, hago_qtype a_t, const void* w, hago_qtype w_t,
+                            const int32_t* bias, hago_layout layout, int64_t B, int64_t C, int64_t H,
+                            int64_t W, int64_t O, int32_t KH, int32_t KW, int32_t stride_h,
+                            int32_t stride_w, int32_t pad_h, int32_t pad_w, int32_t groups,
+                            hago_dtype acc_dtype, const hago_requant* rq, void* out,
+                            void* workspace, int64_t workspace_bytes, uint32_t flags, void* stream) {
+  if (workspace_bytes < 0) return HAGO_ERR_PARAM;
+  return qconv2d_impl(a, a_t, w, w_t, bias, layout, B, C, H, W, O, KH, KW, stride_h, stride_w, pad_h,
+                      pad_w, groups, acc_dtype, rq, out, flags, stream, Scratch::kCaller, workspace,
+                      workspace_bytes);
+}
+
+void hago_set_test_hook(int32_t key, int32_t value) { hago::set_test_hook(key, value); }
+
+hago_status hago_bit_range(int32_t bits, int32_t is_signed, int32_t* lo, int32_t* hi) {
+  if (!lo || !hi) return HAGO_ERR_NULL;
+  if (bits < 1 || bits > 32 || (bits == 32 && !is_signed)) return HAGO_ERR_BITS;
+  int64_t l, h;
+  bit_range(bits, is_signed != 0, &l, &h);
+  *lo = (int32_t)l;
+  *hi = (int32_t)h;
+  return HAGO_OK;
 }
 
 }  // extern "C"

@@ -1,5 +1,5 @@
-// Operand preparation for the implicit-GEMM convolution and the library's
-// per-device scratch buffer that holds the prepared copies.
+// Operand preparation for the implicit-GEMM convolution: the rewrite of both
+// operands into the caller's workspace.
 //
 // The int8 matrix cores want 16 consecutive reduction elements per lane.  In
 // NCHW the reduction index (input channel) is the slowest-varying one, so the
@@ -188,41 +188,12 @@ __global__ __launch_bounds__(256) void conv_prepack_nchw_kernel(PrepackArgs p, i
   if (k < p.wgt_chunks) prepack_weight_chunk(p, k);
 }
 
-struct DeviceScratch {
-  void* ptr = nullptr;
-  size_t cap = 0;
-};
-DeviceScratch g_scratch[64];
-
 }  // namespace
 
-// One scratch allocation per device, owned by the library and grown on demand.  Growing
-// frees the old buffer, which waits for the device to go idle.  Not safe for calls that run
-// concurrently on one device.
-hipError_t scratch_reserve(size_t bytes, void** out) {
-  int dev = 0;
-  hipError_t e = hipGetDevice(&dev);
-  if (e != hipSuccess) return e;
-  if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
-  DeviceScratch& s = g_scratch[dev];
-  if (s.cap < bytes) {
-    if (s.ptr) {
-      e = hipFree(s.ptr);
-      s.ptr = nullptr;
-      s.cap = 0;
-      if (e != hipSuccess) return e;
-    }
-    const size_t want = bytes + bytes / 4 + (1u << 20);
-    e = hipMalloc(&s.ptr, want);
-    if (e != hipSuccess) { s.ptr = nullptr; return e; }
-    s.cap = want;
-  }
-  *out = s.ptr;
-  return hipSuccess;
-}
-
+// skip_weights: the weight copy is already in place (a previous call with the same weights
+// wrote it); only the activations and their padding ring are rewritten.
 hipError_t launch_conv_prepack(const GemmArgs& a, const ConvGeom& cg, int32_t Cp, uint8_t* act_out,
-                               int8_t* wgt_out, hipStream_t st) {
+                               int8_t* wgt_out, bool skip_weights, hipStream_t st) {
   PrepackArgs p{};
   p.act = static_cast<const uint8_t*>(a.act);
   p.wgt = a.wgt;
@@ -236,7 +207,7 @@ hipError_t launch_conv_prepack(const GemmArgs& a, const ConvGeom& cg, int32_t Cp
   p.act_xor = a.act_unsigned ? 0x80u : 0u;
   p.pad_byte = ((uint32_t)a.act_zero_point ^ p.act_xor) & 0xffu;
   p.act_chunks = (int64_t)p.B * p.Hp * p.Wp * (Cp / 16);
-  p.wgt_chunks = (int64_t)p.O * p.KH * p.KW * (Cp / 16);
+  p.wgt_chunks = skip_weights ? 0 : (int64_t)p.O * p.KH * p.KW * (Cp / 16);
   const int64_t hw = (int64_t)cg.H * cg.W;
   if (!cg.nhwc && cg.W % 4 == 0 && (reinterpret_cast<uintptr_t>(a.act) & 3u) == 0 &&
       (int64_t)cg.C * hw < (1ll << 31)) {

@@ -478,12 +478,9 @@ hipError_t launch_simquant(const float* x, float* y, int64_t outer, int64_t chan
   int64_t row_len = per_channel ? inner : total;
   if (row_len % 4 == 0 && row_len >= 512 && aligned16(x) && aligned16(y)) {
     const int64_t inner_vec = row_len / 4;
-    const char* e = std::getenv("HAGO_EW_U");  // tuning override
-    const int u = e ? std::atoi(e) : kVecPerLane;
     int32_t nseg, seg_len;
-    split_row(inner_vec, u, &nseg, &seg_len);
-    auto kern = u == 1 ? simquant_rows_kernel<1> : (u == 4 ? simquant_rows_kernel<4> : simquant_rows_kernel<2>);
-    hipLaunchKernelGGL(kern, dim3(grid_for(rows * nseg)), dim3(kThreads), 0, st,
+    split_row(inner_vec, kVecPerLane, &nseg, &seg_len);
+    hipLaunchKernelGGL(simquant_rows_kernel<kVecPerLane>, dim3(grid_for(rows * nseg)), dim3(kThreads), 0, st,
                        reinterpret_cast<const v4f*>(x), reinterpret_cast<v4f*>(y), rows,
                        (int32_t)(per_channel ? channels : 1), inner_vec, nseg, seg_len, scale, zp,
                        per_channel, lo, hi);
@@ -631,14 +628,10 @@ static hipError_t launch_requantize_t(const AccT* acc, int64_t outer, int64_t ch
   const bool io_aligned = aligned16(acc) && aligned16(out);
   if (row_len % 4 == 0 && row_len >= 512 && io_aligned) {
     const int64_t inner_vec = row_len / 4;
-    const char* e = std::getenv("HAGO_EW_U");  // tuning override
-    const int u = e ? std::atoi(e) : kVecPerLane;
     int32_t nseg, seg_len;
-    split_row(inner_vec, u, &nseg, &seg_len);
+    split_row(inner_vec, kVecPerLane, &nseg, &seg_len);
     auto kern = rq.half_away ? requant_rows_kernel<AccT, kVecPerLane, true>
-              : u == 1 ? requant_rows_kernel<AccT, 1, false>
-              : (u == 4 ? requant_rows_kernel<AccT, 4, false> : requant_rows_kernel<AccT, 2, false>);
-    if (rq.half_away) split_row(inner_vec, kVecPerLane, &nseg, &seg_len);
+                             : requant_rows_kernel<AccT, kVecPerLane, false>;
     hipLaunchKernelGGL(kern, dim3(grid_for(rows * nseg)), dim3(kThreads), 0, st,
                        acc, reinterpret_cast<uint32_t*>(out), rows, (int32_t)(pc ? channels : 1),
                        inner_vec, nseg, seg_len, rq.multiplier, rq.shift, pc, rs);

@@ -63,13 +63,25 @@ struct GemmArgs {
 
 // C[M,N] = act[M,K] x wgt[N,K]^T on int8 MFMA; out row-major [M,N].
 hipError_t launch_qdense(const GemmArgs& g, hipStream_t st);
-// implicit-GEMM convolution, groups == 1.
-hipError_t launch_qconv_gemm(const GemmArgs& g, const ConvGeom& cg, hipStream_t st);
-// Library-owned per-device scratch (grown on demand) and the operand rewrite that the
-// implicit-GEMM convolution runs first (padded NHWC activations, [O][KH*KW][Cp] weights).
-hipError_t scratch_reserve(size_t bytes, void** out);
+
+// Scratch of the fast implicit-GEMM convolution (groups == 1): the operand rewrite writes
+// [weights as [O][KH*KW][Cp], rounded up to 256 bytes][padded NHWC activations, same rounding]
+// into it and the GEMM streams both from there.  Returns the byte count for a geometry, or -1
+// when the geometry is outside what that path indexes with 32 bits (the generic kernel, which
+// needs no scratch, serves it).
+int64_t qconv_workspace_bytes(const ConvGeom& cg);
+// Implicit-GEMM convolution, groups == 1.  ws: device scratch of at least
+// qconv_workspace_bytes(cg) bytes, 256-byte aligned, or nullptr (then, unless one of the
+// scratch-free special kernels takes the geometry, the generic register-staged kernel runs).
+// weights_ready: the weight part of ws already holds this call's weights (same tensor, same
+// geometry), so only the activations are rewritten.
+hipError_t launch_qconv_gemm(const GemmArgs& g, const ConvGeom& cg, void* ws, bool weights_ready,
+                             hipStream_t st);
 hipError_t launch_conv_prepack(const GemmArgs& g, const ConvGeom& cg, int32_t Cp, uint8_t* act_out,
-                               int8_t* wgt_out, hipStream_t st);
+                               int8_t* wgt_out, bool skip_weights, hipStream_t st);
+// Test hooks (see hago_set_test_hook): which GEMM kernel family and tile serve the next calls.
+enum { kHookGemmPath = 0, kHookDmaTile = 1, kHookGenericTile = 2, kNumHooks = 3 };
+void set_test_hook(int key, int value);
 // 1x1 stride-1 unpadded NCHW convolution straight from the caller's buffers; false when the
 // geometry is not that kernel's (nothing is launched then).
 bool try_qconv_pointwise_nchw(const GemmArgs& g, const ConvGeom& cg, hipStream_t st, hipError_t* err);

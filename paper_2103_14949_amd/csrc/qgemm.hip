@@ -38,7 +38,6 @@
 // so that fragment reads and staging writes spread over all banks.
 #include "qgemm_common.h"
 
-#include <cstdlib>
 
 namespace hago {
 
@@ -415,13 +414,9 @@ hipError_t launch_cfg(const QgemmParams& p, hipStream_t st) {
   const int Q_ext = (MODE == MODE_CONV_NCHW) ? p.N : p.M;
   const int64_t tiles = (int64_t)((P_ext + BP - 1) / BP) * ((Q_ext + BQ - 1) / BQ);
   auto kern = qgemm_kernel<WP, WQ, TP, TQ, MODE, VEC>;
-  static bool attr_set = false;  // raising the dynamic-LDS limit is needed once per kernel
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static std::atomic<uint64_t> attr_set{0};  // per kernel: the devices whose dynamic-LDS limit is raised
+  hipError_t e = raise_lds_limit(reinterpret_cast<const void*>(kern), (int)lds, attr_set);
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3((unsigned)tiles), dim3(64 * WP * WQ), lds, st, p);
   return hipGetLastError();
 }
@@ -469,14 +464,13 @@ double shape_cost(const TileShape& s, int64_t P_ext, int64_t Q_ext, int64_t K) {
   return rounds * (main + epi + 1500.0);
 }
 
+// Test hooks: -1 / 0 mean "choose automatically".  Plain atomics: a test sets them between calls.
+std::atomic<int> g_hook[kNumHooks] = {0, -1, -1};
+
 int pick_shape(int mode, int64_t P_ext, int64_t Q_ext, int64_t K) {
-  const char* env = std::getenv("HAGO_QGEMM_SHAPE");  // tuning override
-  if (env && *env) {
-    const int v = std::atoi(env);
-    if (v >= 0 && v < kNumShapes &&
-        shape_ok(mode, kShapes[v].wp, kShapes[v].wq, kShapes[v].tp, kShapes[v].tq))
-      return v;
-  }
+  const int v = g_hook[kHookGenericTile].load(std::memory_order_relaxed);  // forced tile (tests)
+  if (v >= 0 && v < kNumShapes && shape_ok(mode, kShapes[v].wp, kShapes[v].wq, kShapes[v].tp, kShapes[v].tq))
+    return v;
   int best = 2;
   double best_cost = 1e300;
   for (int i = 0; i < kNumShapes; ++i) {
@@ -491,6 +485,10 @@ int pick_shape(int mode, int64_t P_ext, int64_t Q_ext, int64_t K) {
 
 hipError_t launch_qdense_dma(const QgemmParams& p, int shape, hipStream_t st);
 
+void set_test_hook(int key, int value) {
+  if (key >= 0 && key < kNumHooks) g_hook[key].store(value, std::memory_order_relaxed);
+}
+
 hipError_t launch_qdense(const GemmArgs& a, hipStream_t st) {
   if (a.M == 0 || a.N == 0) return hipSuccess;
   QgemmParams p = make_qgemm_params(a, nullptr);
@@ -498,10 +496,10 @@ hipError_t launch_qdense(const GemmArgs& a, hipStream_t st) {
   p.vec_out = (a.N % 4 == 0) && ptr_aligned(a.out, 4 * qgemm_out_elem_size(a));
   p.vec16_out = (a.N % 16 == 0) && ptr_aligned(a.out, 16);
   if (!p.vec_k || a.K < 16) return launch_cfg<2, 2, 2, 2, MODE_DENSE, false>(p, st);
-  const char* env = std::getenv("HAGO_QGEMM_PATH");  // tuning override: "reg" forces the generic kernel
+  const bool generic = g_hook[kHookGemmPath].load(std::memory_order_relaxed) == 1;
   const bool fits32 = (int64_t)a.N * a.K < (1ll << 31) && (int64_t)a.M * a.K < (1ll << 31);
-  if (fits32 && !(env && env[0] == 'r')) {
-    const char* sh = std::getenv("HAGO_DMA_SHAPE");  // tuning override
+  if (fits32 && !generic) {
+    const int forced = g_hook[kHookDmaTile].load(std::memory_order_relaxed);
     // Tile shape: the one whose busiest CU has the least to do (rounds of tiles over the 256
     // CUs x tile area), with larger tiles discounted for their better operand reuse.
     struct Cand { int id, bp, bq; double eff; };
@@ -513,34 +511,45 @@ hipError_t launch_qdense(const GemmArgs& a, hipStream_t st) {
       const double cost = (double)((tiles + 255) / 256) * c.bp * c.bq / c.eff;
       if (c.id == 0 || cost < best_cost) { best = c.id; best_cost = cost; }
     }
-    return launch_qdense_dma(p, sh ? std::atoi(sh) : best, st);
+    return launch_qdense_dma(p, forced >= 0 ? forced : best, st);
   }
   return launch_shape<MODE_DENSE>(pick_shape(MODE_DENSE, a.N, a.M, a.K), p, st);
 }
 
 hipError_t launch_qconv_dma(const QgemmParams& p, bool nchw_out, hipStream_t st);
 
-// Fast path: rewrite both operands into the scratch buffer (one launch), then run the
-// implicit GEMM that streams them into LDS.  Returns false when the shape is outside what
-// that path indexes with 32 bits.
-static bool try_conv_dma(const GemmArgs& a, const ConvGeom& cg, hipStream_t st, hipError_t* err) {
-  const char* env = std::getenv("HAGO_QGEMM_PATH");  // tuning override: "reg" forces the generic kernel
-  if (env && env[0] == 'r') return false;
+namespace {
+inline int64_t round256(int64_t v) { return (v + 255) & ~(int64_t)255; }
+}  // namespace
+
+int64_t qconv_workspace_bytes(const ConvGeom& cg) {
   const int64_t Cp = (cg.C + 15) / 16 * 16;
   const int64_t Hp = cg.H + 2 * (int64_t)cg.pad_h, Wp = cg.W + 2 * (int64_t)cg.pad_w;
   const int64_t act_bytes = (int64_t)cg.B * Hp * Wp * Cp;
   const int64_t Kp = (int64_t)cg.KH * cg.KW * Cp;
   const int64_t wgt_bytes = (int64_t)cg.O * Kp;
-  if (act_bytes >= (1ll << 31) || wgt_bytes >= (1ll << 31) || Kp * Cp >= (1ll << 32)) return false;
-  if (!ptr_aligned(a.out, 4 * qgemm_out_elem_size(a)) && false) return false;
-  const size_t act_sz = ((size_t)act_bytes + 255) & ~(size_t)255;
-  void* scratch = nullptr;
-  *err = scratch_reserve(act_sz + (size_t)wgt_bytes + 256, &scratch);
-  if (*err != hipSuccess) return true;
-  uint8_t* act_p = static_cast<uint8_t*>(scratch);
-  int8_t* wgt_p = reinterpret_cast<int8_t*>(act_p + act_sz);
-  *err = launch_conv_prepack(a, cg, (int32_t)Cp, act_p, wgt_p, st);
-  if (*err != hipSuccess) return true;
+  // 32-bit offsets into both copies; k -> (tap, channel) and tap -> (ky, kx) by multiplication
+  // with ceil(2^32 / C) and ceil(2^32 / KW), which is exact while k * Cp and tap * KW stay
+  // below 2^32
+  if (act_bytes >= (1ll << 31) || wgt_bytes >= (1ll << 31) || Kp * Cp >= (1ll << 32) ||
+      (int64_t)cg.KH * cg.KW * cg.KW >= (1ll << 32))
+    return -1;
+  return round256(wgt_bytes) + round256(act_bytes);
+}
+
+// Fast path: rewrite both operands into the workspace (one launch), then run the implicit GEMM
+// that streams them into LDS.
+static hipError_t conv_dma(const GemmArgs& a, const ConvGeom& cg, void* ws, bool weights_ready,
+                           hipStream_t st) {
+  const int64_t Cp = (cg.C + 15) / 16 * 16;
+  const int64_t Hp = cg.H + 2 * (int64_t)cg.pad_h, Wp = cg.W + 2 * (int64_t)cg.pad_w;
+  const int64_t act_bytes = (int64_t)cg.B * Hp * Wp * Cp;
+  const int64_t Kp = (int64_t)cg.KH * cg.KW * Cp;
+  const int64_t wgt_bytes = (int64_t)cg.O * Kp;
+  int8_t* wgt_p = static_cast<int8_t*>(ws);
+  uint8_t* act_p = static_cast<uint8_t*>(ws) + round256(wgt_bytes);
+  hipError_t err = launch_conv_prepack(a, cg, (int32_t)Cp, act_p, wgt_p, weights_ready, st);
+  if (err != hipSuccess) return err;
 
   ConvGeom pg = cg;  // geometry of the padded copy
   pg.H = (int32_t)Hp; pg.W = (int32_t)Wp; pg.C = (int32_t)Cp; pg.pad_h = 0; pg.pad_w = 0;
@@ -560,22 +569,22 @@ static bool try_conv_dma(const GemmArgs& a, const ConvGeom& cg, hipStream_t st, 
   } else {
     p.vec_out = ((cg.OH * cg.OW) % 4 == 0) && ptr_aligned(a.out, 4 * qgemm_out_elem_size(a));
   }
-  *err = launch_qconv_dma(p, !cg.nhwc, st);
-  return true;
+  return launch_qconv_dma(p, !cg.nhwc, st);
 }
 
-hipError_t launch_qconv_gemm(const GemmArgs& a, const ConvGeom& cg, hipStream_t st) {
+hipError_t launch_qconv_gemm(const GemmArgs& a, const ConvGeom& cg, void* ws, bool weights_ready,
+                             hipStream_t st) {
   if (a.M == 0 || a.N == 0) return hipSuccess;
   hipError_t err = hipSuccess;
-  const char* env = std::getenv("HAGO_QGEMM_PATH");  // tuning override: "reg" / "dma" skip the special cases
-  if (!env) {
+  const int path = g_hook[kHookGemmPath].load(std::memory_order_relaxed);  // 1 / 2: skip the special cases
+  if (path == 0) {
     if (try_qconv_pointwise_nchw(a, cg, st, &err)) return err;
     // channel-last 1x1 stride-1 unpadded convolution is a dense layer over the pixels
     if (cg.nhwc && cg.KH == 1 && cg.KW == 1 && cg.stride_h == 1 && cg.stride_w == 1 && cg.pad_h == 0 &&
         cg.pad_w == 0)
       return launch_qdense(a, st);
   }
-  if (try_conv_dma(a, cg, st, &err)) return err;
+  if (ws && path != 1 && qconv_workspace_bytes(cg) >= 0) return conv_dma(a, cg, ws, weights_ready, st);
   QgemmParams p = make_qgemm_params(a, &cg);
   if (cg.nhwc) {
     p.vec_k = (cg.C % 16 == 0) && ptr_aligned(a.act, 16) && ptr_aligned(a.wgt, 16);

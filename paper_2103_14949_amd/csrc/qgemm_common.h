@@ -6,6 +6,7 @@
 #include "hago_device.h"
 #include "launch.h"
 
+#include <atomic>
 #include <cstdlib>
 
 namespace hago {
@@ -23,6 +24,12 @@ namespace hago {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
+
+#ifdef HAGO_PHASE_TIMING
+// development builds only: where the kernels write their phase timestamps (set by the timing driver)
+inline long long* g_stamp_buffer = nullptr;
+inline int g_stamp_skip = 0;
+#endif
 
 struct QgemmParams {
   const uint8_t* act;
@@ -69,14 +76,24 @@ inline QgemmParams make_qgemm_params(const GemmArgs& a, const ConvGeom* cg) {
   p.rs = RequantScalars{a.rq.z_out, a.rq.clip_lo - a.rq.z_out, a.rq.clip_hi - a.rq.z_out, a.rq.half_away};
   if (cg) p.g = *cg;
 #ifdef HAGO_PHASE_TIMING
-  {
-    const char* e = std::getenv("HAGO_DBG_PTR");
-    p.dbg = e ? reinterpret_cast<long long*>(std::strtoull(e, nullptr, 0)) : nullptr;
-    const char* k = std::getenv("HAGO_DBG_SKIP");
-    p.dbg_skip = k ? std::atoi(k) : 0;
-  }
+  p.dbg = g_stamp_buffer;
+  p.dbg_skip = g_stamp_skip;
 #endif
   return p;
+}
+
+// The dynamic-LDS limit of a kernel is a per-device attribute.  `done` holds one bit per device
+// (ids modulo 64) on which it has been raised; concurrent first calls may both set it, which is
+// harmless.
+inline hipError_t raise_lds_limit(const void* kern, int lds_bytes, std::atomic<uint64_t>& done) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const uint64_t bit = 1ull << (dev & 63);
+  if (done.load(std::memory_order_acquire) & bit) return hipSuccess;
+  e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+  if (e == hipSuccess) done.fetch_or(bit, std::memory_order_release);
+  return e;
 }
 
 inline bool ptr_aligned(const void* ptr, size_t n) {

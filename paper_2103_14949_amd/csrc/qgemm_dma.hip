@@ -71,7 +71,7 @@ __device__ __forceinline__ void dma16(v4i rsrc, uint32_t lds_addr, uint32_t voff
   asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
                :
                : "s"(lds_addr), "v"(voff), "s"(rsrc)
-               : "memory");
+               : "memory", "m0");
 }
 
 // Same with a scalar byte offset added to every lane's address (not range checked).
@@ -79,7 +79,7 @@ __device__ __forceinline__ void dma16s(v4i rsrc, uint32_t lds_addr, uint32_t vof
   asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                :
                : "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff)
-               : "memory");
+               : "memory", "m0");
 }
 
 __device__ __forceinline__ v4i make_rsrc(const void* base, uint32_t bytes) {
@@ -548,13 +548,9 @@ hipError_t launch_dma_kernel(const QgemmParams& p, hipStream_t st) {
   const int Q_ext = ACT_ON_P ? p.N : p.M;
   const int64_t tiles = (int64_t)((P_ext + BP - 1) / BP) * ((Q_ext + BQ - 1) / BQ);
   auto kern = qgemm_dma_kernel<WP, WQ, TP, TQ, kStages, OCC, CONV, ACT_ON_P, FLIP, UNIFORM, BK>;
-  static bool attr_set = false;  // raising the dynamic-LDS limit is needed once per kernel
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static std::atomic<uint64_t> attr_set{0};  // per kernel: the devices whose dynamic-LDS limit is raised
+  hipError_t e = raise_lds_limit(reinterpret_cast<const void*>(kern), (int)lds, attr_set);
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3((unsigned)tiles), dim3(64 * WP * WQ), lds, st, p);
   return hipGetLastError();
 }

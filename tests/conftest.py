@@ -31,3 +31,29 @@ def ref():
     hago_ref.build()
     hago_ref.lib()
     return hago_ref
+
+
+@pytest.fixture(params=["plain", "ws"])
+def conv_entry(request):
+    """Runs a convolution parity test once per entry point (see gpu_util.qconv2d)."""
+    import gpu_util
+    gpu_util.CONV_ENTRY["name"] = request.param
+    yield request.param
+    gpu_util.CONV_ENTRY["name"] = "plain"
+
+
+@pytest.fixture
+def stream_tile():
+    """Forces a tile shape of the streaming dense kernel for the rest of a test."""
+    import paper_2103_14949_amd as hago
+    yield lambda tile: hago.set_test_hook(hago.HOOK_STREAM_TILE, tile)
+    hago.set_test_hook(hago.HOOK_STREAM_TILE, -1)
+
+
+@pytest.fixture
+def gemm_path():
+    """Forces the GEMM kernel family (1: general register-staged, 2: streaming without the 1x1
+    special cases) for the rest of a test."""
+    import paper_2103_14949_amd as hago
+    yield lambda path: hago.set_test_hook(hago.HOOK_GEMM_PATH, path)
+    hago.set_test_hook(hago.HOOK_GEMM_PATH, 0)

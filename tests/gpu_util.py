@@ -54,3 +54,23 @@ def assert_same_bits(got, want, what=""):
     g[both_nan] = 0
     w[both_nan] = 0
     assert_same(g, w, what)
+
+
+# Which convolution entry point the parity tests call (set by the `conv_entry` fixture):
+#   "plain"  hago_qconv2d (no scratch memory)
+#   "ws"     hago_qconv2d_ws with a workspace of exactly the queried size, filled with garbage
+CONV_ENTRY = {"name": "plain"}
+
+
+def qconv2d(a, a_t, w, w_t, bias=None, layout=None, stride=(1, 1), pad=(0, 0), groups=1, acc_dtype=None,
+            rq=None, flags=0):
+    """hago.qconv2d through the entry point under test."""
+    layout = hago.NCHW if layout is None else layout
+    acc_dtype = hago.I32 if acc_dtype is None else acc_dtype
+    if CONV_ENTRY["name"] == "plain":
+        return hago.qconv2d(a, a_t, w, w_t, bias, layout, stride, pad, groups, acc_dtype, rq, flags)
+    need = hago.qconv2d_workspace_bytes(a.shape, w.shape, layout, stride, pad, groups)
+    assert need >= 0
+    ws = torch.full((need,), 0xA5, dtype=torch.uint8, device=DEV)
+    assert need == 0 or ws.data_ptr() % 256 == 0
+    return hago.qconv2d(a, a_t, w, w_t, bias, layout, stride, pad, groups, acc_dtype, rq, flags, workspace=ws)

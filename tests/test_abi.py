@@ -92,6 +92,49 @@ def test_qconv2d_argument_errors(L):
     assert call(B=2 ** 20, Cc=2 ** 10, H=64, W=64) == 2   # beyond the 31-bit index range
 
 
+def test_qconv2d_workspace_queries_and_errors(L):
+    """hago_qconv2d_workspace_bytes is host-only arithmetic; hago_qconv2d_ws refuses a workspace that
+    is missing, too small or misaligned before anything is launched."""
+    wsb = lambda **k: L.hago_qconv2d_workspace_bytes(*[k.get(n, d) for n, d in (  # noqa: E731
+        ("layout", 0), ("B", 1), ("C", 64), ("H", 56), ("W", 56), ("O", 64), ("KH", 3), ("KW", 3),
+        ("sh", 1), ("sw", 1), ("ph", 1), ("pw", 1), ("groups", 1))])
+    r256 = lambda v: (v + 255) // 256 * 256  # noqa: E731
+    # config 2: weights [64][9][64], activations [1][58][58][64]
+    assert wsb() == r256(64 * 9 * 64) + r256(58 * 58 * 64)
+    # the weight part does not depend on the batch; channels are rounded up to 16
+    assert wsb(B=8) - wsb(B=7) == 58 * 58 * 64     # a multiple of 256
+    assert wsb(C=3, O=4, H=5, W=6) == r256(4 * 9 * 16) + r256(7 * 8 * 16)
+    assert wsb(groups=64) == 0                      # depthwise needs none
+    assert wsb(B=0) == 0
+    assert wsb(groups=3) == -1 and wsb(KH=70, ph=0) == -1 and wsb(layout=5) == -1
+    # 32-bit limits of the rewritten copies: the general kernel serves those shapes without scratch
+    assert wsb(B=640, C=1024, H=56, W=56, O=8) == 0
+    u8, i8 = _qt(hago.U8, z=128), _qt(hago.I8)
+
+    def call(ws, nbytes, flags=0, groups=1, O=64):
+        return L.hago_qconv2d_ws(BAD, u8, BAD, i8, None, 0, 1, 64, 56, 56, O, 3, 3, 1, 1, 1, 1, groups,
+                                 hago.I32, None, BAD, ws, nbytes, flags, None)
+
+    need = wsb()
+    assert call(None, need) == 1                    # needed but NULL
+    assert call(0x100000, need - 1) == 5            # too small
+    assert call(0x100010, need) == 5                # not 256-byte aligned
+    assert call(0x100000, -1) == 5
+    assert call(0x100000, need, flags=8) == 5       # unknown flag
+    assert L.hago_qconv2d(BAD, u8, BAD, i8, None, 0, 1, 64, 56, 56, 64, 3, 3, 1, 1, 1, 1, 1, hago.I32, None, BAD,
+                          hago.WS_WEIGHTS_READY, None) == 5   # a workspace flag without a workspace
+
+
+def test_bit_range(L):
+    assert hago.bit_range(8, True) == (-128, 127) and hago.bit_range(8, False) == (0, 255)
+    assert hago.bit_range(4, True) == (-8, 7) and hago.bit_range(1, False) == (0, 1)
+    assert hago.bit_range(32, True) == (-2 ** 31, 2 ** 31 - 1)
+    lo, hi = C.c_int32(), C.c_int32()
+    assert L.hago_bit_range(0, 1, C.byref(lo), C.byref(hi)) == 4
+    assert L.hago_bit_range(32, 0, C.byref(lo), C.byref(hi)) == 4
+    assert L.hago_bit_range(8, 1, None, C.byref(hi)) == 1
+
+
 def test_simquant_and_requantize_argument_errors(L):
     q = _qt(hago.I8)
     sq = lambda *a: L.hago_simquant(*a)  # noqa: E731

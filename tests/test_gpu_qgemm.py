@@ -63,10 +63,10 @@ def test_qdense_requant_and_acc16(M, N, K):
 @pytest.mark.parametrize("tile", [0, 1, 2, 3, 4])  # 256 x 256, 192 x 256, 128 x 128 with 128- and with 64-byte stages, 64 x 64
 @pytest.mark.parametrize("K", [448, 400, 64, 16])  # whole 64-byte stages / a 16-byte tail / one stage
 @pytest.mark.parametrize("adt,za", [(np.uint8, 121), (np.uint8, 128), (np.int8, -4)])
-def test_qdense_every_tile_shape(tile, K, adt, za, monkeypatch):
+def test_qdense_every_tile_shape(tile, K, adt, za, stream_tile):
     """Each dense tile shape of the LDS-DMA kernel on a shape with several tiles and ragged edges
     in both directions, requantized (staged and plain epilogues) and raw."""
-    monkeypatch.setenv("HAGO_DMA_SHAPE", str(tile))
+    stream_tile(tile)
     M, N = 600, 528
     rng = np.random.default_rng(tile * 1000 + K + za)
     a, w = rnd_act(rng, (M, K), adt), rnd_w(rng, (N, K))
@@ -136,7 +136,7 @@ CONV_CASES = [
 @pytest.mark.parametrize("case", CONV_CASES)
 @pytest.mark.parametrize("adt,za", [(np.uint8, 128), (np.uint8, 3), (np.int8, 0), (np.int8, -5)])
 @pytest.mark.parametrize("layout", ["nchw", "nhwc"])
-def test_qconv2d_raw(case, adt, za, layout):
+def test_qconv2d_raw(case, adt, za, layout, conv_entry):
     B, C, H, W, O, KH, KW, stride, pad = case
     rng = np.random.default_rng(abs(hash((case, za))) % 2 ** 31)
     a = rnd_act(rng, (B, C, H, W), adt)
@@ -144,15 +144,15 @@ def test_qconv2d_raw(case, adt, za, layout):
     bias = rng.integers(-5000, 5000, O).astype(np.int32)
     want = ref.qconv2d(a, za, w, bias, ref.NCHW, stride, pad, 1)
     if layout == "nchw":
-        got = host(hago.qconv2d(dev(a), act_qtype(a, za), dev(w), hago.QType(hago.I8), dev(bias), hago.NCHW, stride, pad))
+        got = host(qconv2d(dev(a), act_qtype(a, za), dev(w), hago.QType(hago.I8), dev(bias), hago.NCHW, stride, pad))
     else:
-        got = host(hago.qconv2d(dev(a.transpose(0, 2, 3, 1)), act_qtype(a, za), dev(w.transpose(0, 2, 3, 1)),
+        got = host(qconv2d(dev(a.transpose(0, 2, 3, 1)), act_qtype(a, za), dev(w.transpose(0, 2, 3, 1)),
                                 hago.QType(hago.I8), dev(bias), hago.NHWC, stride, pad)).transpose(0, 3, 1, 2)
     assert_same(np.ascontiguousarray(got), want, f"qconv2d {layout} {case}")
 
 
 @pytest.mark.parametrize("case", [c for c in CONV_CASES if c[1] % 32 == 0 and c[7] == (1, 1) and c[5] * c[6] > 1])
-def test_qconv2d_output_modes(case):
+def test_qconv2d_output_modes(case, conv_entry):
     """Requantized (int8 and uint8 with a zero point), raw int16 and requantized int16-accumulation
     outputs of the implicit-GEMM convolution on multi-tile shapes."""
     B, C, H, W, O, KH, KW, stride, pad = case
@@ -164,17 +164,17 @@ def test_qconv2d_output_modes(case):
     for out_u8, z_out, clip in ((False, 0, (-128, 127)), (True, 7, (7, 255))):
         want = ref.qconv2d(a, 99, w, bias, ref.NCHW, stride, pad, 1, ref.I32,
                            ref_requant(mult, shift, out_u8, z_out, clip))
-        got = hago.qconv2d(dev(a), act_qtype(a, 99), dev(w), hago.QType(hago.I8), dev(bias), hago.NCHW,
+        got = qconv2d(dev(a), act_qtype(a, 99), dev(w), hago.QType(hago.I8), dev(bias), hago.NCHW,
                            stride, pad, 1, hago.I32, gpu_requant(mult, shift, out_u8, z_out, clip))
         assert_same(host(got), want, f"conv requantized u8={out_u8}")
         assert np.mean((want == clip[0]) | (want == clip[1])) < 0.6
     want = ref.qconv2d(a, 99, w, bias, ref.NCHW, stride, pad, 1, ref.I16)
-    got = hago.qconv2d(dev(a), act_qtype(a, 99), dev(w), hago.QType(hago.I8), dev(bias), hago.NCHW, stride,
+    got = qconv2d(dev(a), act_qtype(a, 99), dev(w), hago.QType(hago.I8), dev(bias), hago.NCHW, stride,
                        pad, 1, hago.I16)
     assert_same(host(got), want, "conv raw int16")
     m16, s16 = datagen.requant_params(rng, np.full(O, 19000.0), 40.0)
     want = ref.qconv2d(a, 99, w, bias, ref.NCHW, stride, pad, 1, ref.I16, ref_requant(m16, s16))
-    got = hago.qconv2d(dev(a), act_qtype(a, 99), dev(w), hago.QType(hago.I8), dev(bias), hago.NCHW, stride,
+    got = qconv2d(dev(a), act_qtype(a, 99), dev(w), hago.QType(hago.I8), dev(bias), hago.NCHW, stride,
                        pad, 1, hago.I16, gpu_requant(m16, s16))
     assert_same(host(got), want, "conv int16 accumulation requantized")
 
@@ -194,7 +194,7 @@ POINTWISE_CASES = [
 
 @pytest.mark.parametrize("case", POINTWISE_CASES)
 @pytest.mark.parametrize("adt,za", [(np.uint8, 7), (np.int8, -3)])
-def test_pointwise_nchw_all_output_modes(case, adt, za):
+def test_pointwise_nchw_all_output_modes(case, adt, za, conv_entry):
     B, C, H, W, O = case
     rng = np.random.default_rng(abs(hash((case, za))) % 2 ** 31)
     a = rnd_act(rng, (B, C, H, W), adt)
@@ -204,19 +204,19 @@ def test_pointwise_nchw_all_output_modes(case, adt, za):
     rargs = (ref.NCHW, (1, 1), (0, 0), 1)
     a_t, w_t = act_qtype(a, za), hago.QType(hago.I8)
     want = ref.qconv2d(a, za, w, bias, *rargs)
-    assert_same(host(hago.qconv2d(dev(a), a_t, dev(w), w_t, dev(bias), *args)), want, f"pointwise raw {case}")
+    assert_same(host(qconv2d(dev(a), a_t, dev(w), w_t, dev(bias), *args)), want, f"pointwise raw {case}")
     mult, shift = datagen.requant_params(rng, np.full(O, 74.0 * 73.0 * np.sqrt(C)), 40.0)
     for out_u8, z_out, clip in ((False, 0, (-128, 127)), (True, 9, (9, 255))):
         want = ref.qconv2d(a, za, w, bias, *rargs, ref.I32, ref_requant(mult, shift, out_u8, z_out, clip))
-        got = hago.qconv2d(dev(a), a_t, dev(w), w_t, dev(bias), *args, hago.I32,
+        got = qconv2d(dev(a), a_t, dev(w), w_t, dev(bias), *args, hago.I32,
                            gpu_requant(mult, shift, out_u8, z_out, clip))
         assert_same(host(got), want, f"pointwise rq {case} u8={out_u8}")
         assert np.mean((want == clip[0]) | (want == clip[1])) < 0.9
     want = ref.qconv2d(a, za, w, bias, *rargs, ref.I16)
-    assert_same(host(hago.qconv2d(dev(a), a_t, dev(w), w_t, dev(bias), *args, hago.I16)), want, f"pointwise acc16 {case}")
+    assert_same(host(qconv2d(dev(a), a_t, dev(w), w_t, dev(bias), *args, hago.I16)), want, f"pointwise acc16 {case}")
     m16, s16 = datagen.requant_params(rng, np.full(O, 19000.0), 40.0)
     want = ref.qconv2d(a, za, w, bias, *rargs, ref.I16, ref_requant(m16[:1], s16[:1]))
-    got = hago.qconv2d(dev(a), a_t, dev(w), w_t, dev(bias), *args, hago.I16, gpu_requant(m16[:1], s16[:1]))
+    got = qconv2d(dev(a), a_t, dev(w), w_t, dev(bias), *args, hago.I16, gpu_requant(m16[:1], s16[:1]))
     assert_same(host(got), want, f"pointwise acc16 requant per-tensor {case}")
 
 
@@ -241,31 +241,31 @@ def test_pointwise_requant_constant_ranges(big, out_u8, z_out):
     mult = rng.integers(2 ** 30, 2 ** 31, size=O).astype(np.int32)
     a_t, w_t = act_qtype(a, 121), hago.QType(hago.I8)
     want = ref.qconv2d(a, 121, w, bias, ref.NCHW, (1, 1), (0, 0), 1, ref.I32, ref_requant(mult, shift, out_u8, z_out))
-    got = hago.qconv2d(dev(a), a_t, dev(w), w_t, dev(bias), hago.NCHW, (1, 1), (0, 0), 1, hago.I32,
+    got = qconv2d(dev(a), a_t, dev(w), w_t, dev(bias), hago.NCHW, (1, 1), (0, 0), 1, hago.I32,
                        gpu_requant(mult, shift, out_u8, z_out))
     assert_same(host(got), want, "pointwise requant ranges")
     assert len(np.unique(want)) > 50
 
 
-def test_qconv2d_config2_full_size():
+def test_qconv2d_config2_full_size(conv_entry):
     for z_a in (0, 128):
         c = datagen.config2(z_a=z_a)
         rq = ref_requant(c["mult"], c["shift"], True, 0, (0, 255))
         want = ref.qconv2d(c["a"], z_a, c["w"], None, ref.NCHW, (1, 1), (1, 1), 1, ref.I32, rq)
-        got = hago.qconv2d(dev(c["a"]), act_qtype(c["a"], z_a), dev(c["w"]), hago.QType(hago.I8), None, hago.NCHW,
+        got = qconv2d(dev(c["a"]), act_qtype(c["a"], z_a), dev(c["w"]), hago.QType(hago.I8), None, hago.NCHW,
                            (1, 1), (1, 1), 1, hago.I32, gpu_requant(c["mult"], c["shift"], True, 0, (0, 255)))
         assert_same(host(got), want, f"config 2 z_a={z_a}")
         assert 0.2 < np.mean(want == 0) < 0.8       # the ReLU clip removes about half
         assert np.mean(want == 255) < 0.05
 
 
-def test_qconv2d_config3_int16_accumulation_full_size():
+def test_qconv2d_config3_int16_accumulation_full_size(conv_entry):
     for adversarial in (False, True):
         c = datagen.config3(adversarial=adversarial)
         want = ref.qconv2d(c["a"], 0, c["w"], None, ref.NCHW, (1, 1), (1, 1), 1, ref.I16)
         a_t = hago.QType(hago.I8, 4, False, 0)
         w_t = hago.QType(hago.I8, 4, True, 0)
-        got = hago.qconv2d(dev(c["a"]), a_t, dev(c["w"]), w_t, None, hago.NCHW, (1, 1), (1, 1), 1, hago.I16)
+        got = qconv2d(dev(c["a"]), a_t, dev(c["w"]), w_t, None, hago.NCHW, (1, 1), (1, 1), 1, hago.I16)
         assert_same(host(got), want, f"config 3 adversarial={adversarial}")
         if adversarial:
             assert want[0, 0, 5, 5] == -10112      # 1152 * 15 * 7 = 120960 wraps
@@ -274,13 +274,13 @@ def test_qconv2d_config3_int16_accumulation_full_size():
             assert np.array_equal(w32, want[:1].astype(np.int32))  # random data does not reach the wrap
         # the declared 4-bit ranges do not prove safety for K = 1152
         with pytest.raises(hago.HagoError) as e:
-            hago.qconv2d(dev(c["a"]), a_t, dev(c["w"]), w_t, None, hago.NCHW, (1, 1), (1, 1), 1, hago.I16,
+            qconv2d(dev(c["a"]), a_t, dev(c["w"]), w_t, None, hago.NCHW, (1, 1), (1, 1), 1, hago.I16,
                          flags=hago.STRICT_ACC16)
         assert e.value.code == 6
 
 
 @pytest.mark.parametrize("O", [128, 100])
-def test_qconv2d_many_pixels_128_channels(O):
+def test_qconv2d_many_pixels_128_channels(O, conv_entry):
     """3x3 convolution with 128 input channels over more than 2^15 output pixels (the 256-pixel
     implicit-GEMM tiles, full and ragged in the channels), all three output modes."""
     B, C, H, W = 44, 128, 28, 28
@@ -292,29 +292,29 @@ def test_qconv2d_many_pixels_128_channels(O):
     args = (hago.NCHW, (1, 1), (1, 1), 1)
     rargs = (ref.NCHW, (1, 1), (1, 1), 1)
     want = ref.qconv2d(a, 119, w, bias, *rargs)
-    assert_same(host(hago.qconv2d(dev(a), a_t, dev(w), w_t, dev(bias), *args)), want, "raw int32")
+    assert_same(host(qconv2d(dev(a), a_t, dev(w), w_t, dev(bias), *args)), want, "raw int32")
     mult, shift = datagen.requant_params(rng, np.full(O, 74.0 * 73.0 * np.sqrt(9 * C)), 40.0)
     want = ref.qconv2d(a, 119, w, bias, *rargs, ref.I32, ref_requant(mult, shift))
-    got = hago.qconv2d(dev(a), a_t, dev(w), w_t, dev(bias), *args, hago.I32, gpu_requant(mult, shift))
+    got = qconv2d(dev(a), a_t, dev(w), w_t, dev(bias), *args, hago.I32, gpu_requant(mult, shift))
     assert_same(host(got), want, "requantized")
     assert len(np.unique(want)) > 100
     want = ref.qconv2d(a, 119, w, bias, *rargs, ref.I16)
-    assert_same(host(hago.qconv2d(dev(a), a_t, dev(w), w_t, dev(bias), *args, hago.I16)), want, "raw int16")
+    assert_same(host(qconv2d(dev(a), a_t, dev(w), w_t, dev(bias), *args, hago.I16)), want, "raw int16")
 
 
-def test_config4_mobilenet_block_full_size():
+def test_config4_mobilenet_block_full_size(conv_entry):
     c = datagen.config4()
     a_t = hago.QType(hago.I8, 8, True, 0)
     w_t = hago.QType(hago.I8)
     rq_dw = ref_requant(c["mult_dw"], c["shift_dw"])
     want_dw = ref.qconv2d(c["a"], 0, c["w_dw"], None, ref.NCHW, (1, 1), (1, 1), 144, ref.I32, rq_dw)
-    got_dw = hago.qconv2d(dev(c["a"]), a_t, dev(c["w_dw"]), w_t, None, hago.NCHW, (1, 1), (1, 1), 144, hago.I32,
+    got_dw = qconv2d(dev(c["a"]), a_t, dev(c["w_dw"]), w_t, None, hago.NCHW, (1, 1), (1, 1), 144, hago.I32,
                           gpu_requant(c["mult_dw"], c["shift_dw"]))
     assert_same(host(got_dw), want_dw, "config 4 depthwise")
     assert np.mean(np.abs(want_dw.astype(np.int32)) >= 127) < 0.05
     rq_pw = ref_requant(c["mult_pw"], c["shift_pw"])
     want_pw = ref.qconv2d(want_dw, 0, c["w_pw"], None, ref.NCHW, (1, 1), (0, 0), 1, ref.I32, rq_pw)
-    got_pw = hago.qconv2d(got_dw, a_t, dev(c["w_pw"]), w_t, None, hago.NCHW, (1, 1), (0, 0), 1, hago.I32,
+    got_pw = qconv2d(got_dw, a_t, dev(c["w_pw"]), w_t, None, hago.NCHW, (1, 1), (0, 0), 1, hago.I32,
                           gpu_requant(c["mult_pw"], c["shift_pw"]))
     assert_same(host(got_pw), want_pw, "config 4 pointwise")
     assert np.mean(np.abs(want_pw.astype(np.int32)) >= 127) < 0.05
@@ -375,14 +375,14 @@ def test_depthwise(case, adt, za):
     a_t, w_t = act_qtype(a, za), hago.QType(hago.I8)
     for acc_dt_r, acc_dt_g in ((ref.I32, hago.I32), (ref.I16, hago.I16)):
         want = ref.qconv2d(a, za, w, bias, ref.NCHW, stride, pad, C, acc_dt_r)
-        got = hago.qconv2d(dev(a), a_t, dev(w), w_t, dev(bias), hago.NCHW, stride, pad, C, acc_dt_g)
+        got = qconv2d(dev(a), a_t, dev(w), w_t, dev(bias), hago.NCHW, stride, pad, C, acc_dt_g)
         assert_same(host(got), want, f"depthwise raw {case}")
     want = ref.qconv2d(a, za, w, bias, ref.NCHW, stride, pad, C, ref.I32, ref_requant(mult, shift))
-    got = hago.qconv2d(dev(a), a_t, dev(w), w_t, dev(bias), hago.NCHW, stride, pad, C, hago.I32, gpu_requant(mult, shift))
+    got = qconv2d(dev(a), a_t, dev(w), w_t, dev(bias), hago.NCHW, stride, pad, C, hago.I32, gpu_requant(mult, shift))
     assert_same(host(got), want, f"depthwise rq {case}")
     want = ref.qconv2d(a.transpose(0, 2, 3, 1), za, w.transpose(0, 2, 3, 1), bias, ref.NHWC, stride, pad, C, ref.I32,
                        ref_requant(mult, shift))
-    got = hago.qconv2d(dev(a.transpose(0, 2, 3, 1)), a_t, dev(w.transpose(0, 2, 3, 1)), w_t, dev(bias), hago.NHWC,
+    got = qconv2d(dev(a.transpose(0, 2, 3, 1)), a_t, dev(w.transpose(0, 2, 3, 1)), w_t, dev(bias), hago.NHWC,
                        stride, pad, C, hago.I32, gpu_requant(mult, shift))
     assert_same(host(got), want, f"depthwise nhwc {case}")
 
@@ -406,14 +406,14 @@ def test_depthwise_requant_constant_ranges(out_u8, z_out, with_bias):
     a_t, w_t = act_qtype(a, 128), hago.QType(hago.I8)
     b_ref, b_gpu = (bias, dev(bias)) if with_bias else (None, None)
     want = ref.qconv2d(a, 128, w, b_ref, ref.NCHW, (1, 1), (1, 1), C, ref.I32, ref_requant(mult, shift, out_u8, z_out))
-    got = hago.qconv2d(dev(a), a_t, dev(w), w_t, b_gpu, hago.NCHW, (1, 1), (1, 1), C, hago.I32,
+    got = qconv2d(dev(a), a_t, dev(w), w_t, b_gpu, hago.NCHW, (1, 1), (1, 1), C, hago.I32,
                        gpu_requant(mult, shift, out_u8, z_out))
     assert_same(host(got), want, "depthwise per-channel")
     assert len(np.unique(want)) > 50
     # one multiplier and shift for the whole tensor
     want = ref.qconv2d(a, 128, w, b_ref, ref.NCHW, (1, 1), (1, 1), C, ref.I32,
                        ref_requant(mult[:1], np.array([9], np.int32), out_u8, z_out))
-    got = hago.qconv2d(dev(a), a_t, dev(w), w_t, b_gpu, hago.NCHW, (1, 1), (1, 1), C, hago.I32,
+    got = qconv2d(dev(a), a_t, dev(w), w_t, b_gpu, hago.NCHW, (1, 1), (1, 1), C, hago.I32,
                        gpu_requant(mult[:1], np.array([9], np.int32), out_u8, z_out))
     assert_same(host(got), want, "depthwise per-tensor")
 
@@ -428,7 +428,7 @@ def test_empty_inputs_are_a_no_op():
     assert y.numel() == 0
     a4 = torch.empty((0, 4, 5, 5), dtype=torch.int8, device=DEV)
     w4 = torch.zeros((4, 4, 3, 3), dtype=torch.int8, device=DEV)
-    out = hago.qconv2d(a4, hago.QType(hago.I8), w4, hago.QType(hago.I8), pad=(1, 1))
+    out = qconv2d(a4, hago.QType(hago.I8), w4, hago.QType(hago.I8), pad=(1, 1))
     assert out.shape == (0, 4, 5, 5)
     torch.cuda.synchronize()
 
