@@ -56,7 +56,9 @@ typedef enum {
                              or clip range outside the container / bit range    */
   HAGO_ERR_PARAM = 5,     /* other invalid scalar parameter (flags, per_channel) */
   HAGO_ERR_ACC_BOUND = 6, /* HAGO_STRICT_ACC16 set and K*Amax*Wmax > 32767       */
-  HAGO_ERR_DEVICE = 7     /* the HIP runtime refused the launch                  */
+  HAGO_ERR_DEVICE = 7,    /* the HIP runtime refused the launch                  */
+  HAGO_ERR_SCRATCH = 8    /* hago_qconv2d_static: the rewritten operands exceed
+                             HAGO_STATIC_SCRATCH_BYTES                          */
 } hago_status;
 
 /* Container data types.  "Effective bits" (Sec. 2, Sec. 5.3) may be fewer
@@ -221,6 +223,31 @@ hago_status hago_qconv2d_ws(const void* a, hago_qtype a_t, const void* w,
                             const hago_requant* rq, void* out, void* workspace,
                             int64_t workspace_bytes, uint32_t flags,
                             void* stream);
+
+/*
+ * hago_qconv2d for callers that cannot allocate device memory and have no
+ * workspace to hand over: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments and results as
+ * hago_qconv2d_ws, but the scratch is a fixed array of
+ * HAGO_STATIC_SCRATCH_BYTES of static device memory inside the library (each
+ * GPU the library runs on holds its own copy until the process ends).  The
+ * call allocates and frees nothing and does not wait for the device.
+ * A geometry whose hago_qconv2d_workspace_bytes exceeds the array is refused
+ * with HAGO_ERR_SCRATCH before anything is launched (use hago_qconv2d_ws).
+ * Every call on a GPU uses that GPU's one array, which is overwritten by each
+ * call: calls that may run at the same time on one GPU (different streams,
+ * different host threads) race and must be ordered by the caller; calls on
+ * one stream are safe.
+ */
+#define HAGO_STATIC_SCRATCH_BYTES (64ll << 20)
+hago_status hago_qconv2d_static(const void* a, hago_qtype a_t, const void* w,
+                                hago_qtype w_t, const int32_t* bias,
+                                hago_layout layout, int64_t B, int64_t C,
+                                int64_t H, int64_t W, int64_t O, int32_t KH,
+                                int32_t KW, int32_t stride_h, int32_t stride_w,
+                                int32_t pad_h, int32_t pad_w, int32_t groups,
+                                hago_dtype acc_dtype, const hago_requant* rq,
+                                void* out, uint32_t flags, void* stream);
 
 /*
  * Batched candidate evaluation of simulated_quantize (Sec. 6.3 "Batched GPU

@@ -13,13 +13,14 @@ U8, I8, I16, I32, F32 = 0, 1, 2, 3, 4
 NCHW, NHWC = 0, 1
 STRICT_ACC16 = 1
 WS_WEIGHTS_READY = 2
+STATIC_SCRATCH_BYTES = 64 << 20   # HAGO_STATIC_SCRATCH_BYTES
 HOOK_GEMM_PATH, HOOK_STREAM_TILE, HOOK_GENERAL_TILE = 0, 1, 2   # hago_set_test_hook keys
 ROUND_UPWARD, ROUND_HALF_AWAY = 0, 1   # hago_rounding
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libhago.so")
 
-EXPORTS = ("hago_simquant", "hago_simquant_batched", "hago_absmax", "hago_quantize", "hago_dequantize", "hago_simquant_codes", "hago_qdense", "hago_qconv2d", "hago_qconv2d_ws", "hago_qconv2d_workspace_bytes", "hago_requantize",
+EXPORTS = ("hago_simquant", "hago_simquant_batched", "hago_absmax", "hago_quantize", "hago_dequantize", "hago_simquant_codes", "hago_qdense", "hago_qconv2d", "hago_qconv2d_ws", "hago_qconv2d_workspace_bytes", "hago_qconv2d_static", "hago_requantize",
            "hago_status_string", "hago_bit_range", "hago_set_test_hook")
 
 
@@ -79,6 +80,8 @@ def lib():
         L.hago_qconv2d.argtypes = [vp, _QType, vp, _QType, vp, i32, i64, i64, i64, i64, i64,
                                    i32, i32, i32, i32, i32, i32, i32, i32,
                                    C.POINTER(_Requant), vp, u32, vp]
+        L.hago_qconv2d_static.restype = i32
+        L.hago_qconv2d_static.argtypes = L.hago_qconv2d.argtypes
         L.hago_qconv2d_ws.restype = i32
         L.hago_qconv2d_ws.argtypes = [vp, _QType, vp, _QType, vp, i32, i64, i64, i64, i64, i64,
                                       i32, i32, i32, i32, i32, i32, i32, i32,
@@ -347,11 +350,12 @@ def qconv2d_workspace_bytes(a_shape, w_shape, layout=NCHW, stride=(1, 1), pad=(0
 
 def qconv2d(a, a_t: QType, w, w_t: QType, bias=None, layout=NCHW, stride=(1, 1), pad=(0, 0),
             groups=1, acc_dtype=I32, rq: Requant | None = None, flags=0, out=None, prepare=False,
-            workspace=None):
+            workspace=None, static_scratch=False):
     """hago_qconv2d: NCHW a [B,C,H,W], w [O,C/g,KH,KW]; NHWC a [B,H,W,C], w [O,KH,KW,C/g].
 
     With `workspace` (a uint8 device tensor of at least qconv2d_workspace_bytes(...) bytes, or an
-    empty one when that is 0) the call goes to hago_qconv2d_ws."""
+    empty one when that is 0) the call goes to hago_qconv2d_ws; with static_scratch=True to
+    hago_qconv2d_static."""
     assert a.dim() == 4 and w.dim() == 4 and a.is_contiguous() and w.is_contiguous()
     B, Cc, H, W, O, KH, KW = _conv_dims(a, w, layout)
     OH = (H + 2 * pad[0] - KH) // stride[0] + 1
@@ -369,7 +373,7 @@ def qconv2d(a, a_t: QType, w, w_t: QType, bias=None, layout=NCHW, stride=(1, 1),
         args += (_ptr(workspace) if workspace.numel() else None, workspace.numel() * workspace.element_size(),
                  flags, _stream())
     else:
-        fn = lib().hago_qconv2d
+        fn = lib().hago_qconv2d_static if static_scratch else lib().hago_qconv2d
         args += (flags, _stream())
     if prepare:
         return Prepared(fn, args, (a, w, bias, rq, st, out, workspace), out)

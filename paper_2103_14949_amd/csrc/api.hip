@@ -137,6 +137,7 @@ const char* hago_status_string(hago_status s) {
     case HAGO_ERR_PARAM: return "invalid parameter";
     case HAGO_ERR_ACC_BOUND: return "int16 accumulation may overflow for the declared bit widths";
     case HAGO_ERR_DEVICE: return "HIP runtime error";
+    case HAGO_ERR_SCRATCH: return "the operands do not fit the library's fixed scratch array";
   }
   return "unknown status";
 }
@@ -353,7 +354,7 @@ int64_t conv_scratch_need(const ConvGeom& cg, bool depthwise) {
   return n < 0 ? 0 : n;
 }
 
-enum class Scratch { kNone, kCaller };
+enum class Scratch { kNone, kCaller, kStatic };
 
 hago_status qconv2d_impl(const void* a, hago_qtype a_t, const void* w, hago_qtype w_t,
                          const int32_t* bias, hago_layout layout, int64_t B, int64_t C, int64_t H,
@@ -387,6 +388,13 @@ hago_status qconv2d_impl(const void* a, hago_qtype a_t, const void* w, hago_qtyp
       if (!workspace) return HAGO_ERR_NULL;
       if (workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return HAGO_ERR_PARAM;
       ws = workspace;
+    }
+  } else if (mode == Scratch::kStatic) {
+    const int64_t need = conv_scratch_need(cg, false);
+    if (need > (int64_t)HAGO_STATIC_SCRATCH_BYTES) return HAGO_ERR_SCRATCH;
+    if (need > 0) {
+      int64_t cap = 0;
+      if (hago::static_scratch(&ws, &cap) != hipSuccess) return HAGO_ERR_DEVICE;
     }
   }
   return from_hip(hago::launch_qconv_gemm(g, cg, ws, (flags & HAGO_WS_WEIGHTS_READY) != 0, st));
@@ -429,6 +437,16 @@ hago_status hago_qconv2d_ws(const void* a, hago_qtype a_t, const void* w, hago_q
   return qconv2d_impl(a, a_t, w, w_t, bias, layout, B, C, H, W, O, KH, KW, stride_h, stride_w, pad_h,
                       pad_w, groups, acc_dtype, rq, out, flags, stream, Scratch::kCaller, workspace,
                       workspace_bytes);
+}
+
+hago_status hago_qconv2d_static(const void* a, hago_qtype a_t, const void* w, hago_qtype w_t,
+                                const int32_t* bias, hago_layout layout, int64_t B, int64_t C,
+                                int64_t H, int64_t W, int64_t O, int32_t KH, int32_t KW,
+                                int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w,
+                                int32_t groups, hago_dtype acc_dtype, const hago_requant* rq,
+                                void* out, uint32_t flags, void* stream) {
+  return qconv2d_impl(a, a_t, w, w_t, bias, layout, B, C, H, W, O, KH, KW, stride_h, stride_w, pad_h,
+                      pad_w, groups, acc_dtype, rq, out, flags, stream, Scratch::kStatic, nullptr, 0);
 }
 
 void hago_set_test_hook(int32_t key, int32_t value) { hago::set_test_hook(key, value); }

@@ -11,8 +11,17 @@
 //   weights     -> [O][KH * KW][Cp], channels beyond C zero.
 // After that a tap of an output pixel is 16-byte chunks of contiguous memory
 // and the GEMM kernel can stream both operands straight into LDS.
+#include "../../include/hago.h"
 #include "hago_device.h"
 #include "launch.h"
+
+#include <atomic>
+
+// Fixed scratch of the entry point that must not allocate (hago_qconv2d_static): static device
+// memory, one copy per GPU at that GPU's own address, held until the process ends.  Host code
+// never uses this name as an address; static_scratch() below asks the runtime for the device
+// address once per device and hands that out.
+static __device__ __align__(256) unsigned char scratch[HAGO_STATIC_SCRATCH_BYTES];
 
 namespace hago {
 
@@ -189,6 +198,25 @@ __global__ __launch_bounds__(256) void conv_prepack_nchw_kernel(PrepackArgs p, i
 }
 
 }  // namespace
+
+hipError_t static_scratch(void** ptr, int64_t* capacity) {
+  static std::atomic<void*> addr[64];  // per device; zero-initialised
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+  void* p = addr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    // the current device's copy of the array (two threads may both ask; they get the same answer)
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    addr[dev].store(p, std::memory_order_release);
+  }
+  *ptr = p;
+  *capacity = (int64_t)HAGO_STATIC_SCRATCH_BYTES;
+  return hipSuccess;
+}
 
 // skip_weights: the weight copy is already in place (a previous call with the same weights
 // wrote it); only the activations and their padding ring are rewritten.

@@ -77,6 +77,9 @@ int64_t qconv_workspace_bytes(const ConvGeom& cg);
 // geometry), so only the activations are rewritten.
 hipError_t launch_qconv_gemm(const GemmArgs& g, const ConvGeom& cg, void* ws, bool weights_ready,
                              hipStream_t st);
+// The library's fixed scratch array on the current device (static device memory: nothing is
+// allocated or freed, the address never changes) and its capacity in bytes.
+hipError_t static_scratch(void** ptr, int64_t* capacity);
 hipError_t launch_conv_prepack(const GemmArgs& g, const ConvGeom& cg, int32_t Cp, uint8_t* act_out,
                                int8_t* wgt_out, bool skip_weights, hipStream_t st);
 // Test hooks (see hago_set_test_hook): which GEMM kernel family and tile serve the next calls.

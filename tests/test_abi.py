@@ -32,8 +32,8 @@ def test_every_declared_symbol_is_exported(L):
 
 
 def test_status_strings(L):
-    seen = {L.hago_status_string(i) for i in range(8)}
-    assert len(seen) == 8 and all(seen)
+    seen = {L.hago_status_string(i) for i in range(9)}
+    assert len(seen) == 9 and all(seen)
 
 
 BAD = 0x1000  # a non-null pointer that is never dereferenced: validation fails first
