@@ -485,6 +485,14 @@ int pick_shape(int mode, int64_t P_ext, int64_t Q_ext, int64_t K) {
 
 hipError_t launch_qdense_dma(const QgemmParams& p, int shape, hipStream_t st);
 
+#ifdef HAGO_PHASE_TIMING
+// development builds only: the timing driver hands over the buffer for the kernels' phase stamps
+extern "C" void hago_debug_set_stamp_buffer(long long* buf, int skip) {
+  g_stamp_buffer = buf;
+  g_stamp_skip = skip;
+}
+#endif
+
 void set_test_hook(int key, int value) {
   if (key >= 0 && key < kNumHooks) g_hook[key].store(value, std::memory_order_relaxed);
 }

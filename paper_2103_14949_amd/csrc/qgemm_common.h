@@ -295,7 +295,9 @@ __device__ __forceinline__ void qgemm_epilogue_dense_staged(const QgemmParams& p
     const v4i v = *reinterpret_cast<const v4i*>(s_out + row * RS + c * 16);
     // ragged tiles: rows beyond M and 16-channel chunks beyond N (N % 16 == 0) stay in LDS
     if (!ragged || (q0 + row < p.M && p0 + c * 16 < p.N))
-      *reinterpret_cast<v4i*>(out8 + (size_t)(q0 + row) * p.N + p0 + c * 16) = v;
+      // streaming store: the tile is complete and nothing in this launch reads it again, so it
+      // need not stay in L2 until the end-of-kernel write-back (large outputs: 1 us per launch)
+      __builtin_nontemporal_store(v, reinterpret_cast<v4i*>(out8 + (size_t)(q0 + row) * p.N + p0 + c * 16));
   }
   HAGO_STAMP(p, 6);
 }

@@ -291,6 +291,16 @@ __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParam
   using ICL = std::integral_constant<int, L>;
 
   HAGO_STAMP(p, 0);
+  // prologue: stages 0 .. kStages-2 go out before anything else is set up (stages beyond K are
+  // all-zero fills, which keeps the number of outstanding loads uniform)
+  [&]<int... S>(std::integer_sequence<int, S...>) {
+    ([&] {
+      const StageArgs a = stage_args(S);
+      issue_range(S, a.dp, a.dq, a.soff_w, a.soff_a, std::integral_constant<int, S>{}, IC0{}, ICL{});
+    }(), ...);
+  }(std::make_integer_sequence<int, kStages - 1>{});
+  HAGO_STAMP(p, 1);
+  __builtin_amdgcn_sched_barrier(0);
   ChannelRegs<NT, CH> chregs;
   load_channel_regs<NT, CH>(p, w0, chregs);
 
@@ -312,15 +322,6 @@ __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParam
 #pragma unroll
   for (int i = 0; i < NSB; ++i) wsum[i] = 0;
 
-  // prologue: stages 0 .. kStages-2 (stages beyond K are all-zero fills, which keeps the
-  // number of outstanding loads uniform)
-  [&]<int... S>(std::integer_sequence<int, S...>) {
-    ([&] {
-      const StageArgs a = stage_args(S);
-      issue_range(S, a.dp, a.dq, a.soff_w, a.soff_a, std::integral_constant<int, S>{}, IC0{}, ICL{});
-    }(), ...);
-  }(std::make_integer_sequence<int, kStages - 1>{});
-  HAGO_STAMP(p, 1);
 
   const int frow = lane & 31;
   const int fhalf = lane >> 5;
