@@ -191,7 +191,16 @@ __global__ __launch_bounds__(256) void pw_nchw_kernel(PwArgs p) {
 template <int MODE, bool ACC16>
 __global__ __launch_bounds__(64) void pw_nchw_quad_kernel(PwArgs p) {
   const int lane = threadIdx.x;
-  const int64_t tile = blockIdx.x;
+  // Workgroups go to the eight XCDs round-robin.  A channel plane is not a multiple of the
+  // 128-byte line in general, so neighbouring tiles share lines; numbering the tiles so that
+  // an XCD gets a run of consecutive ones lets that XCD's L2 serve the shared lines (with the
+  // plain order every such line was fetched from memory by two XCDs: 1.5 times the bytes).
+  int64_t tile = blockIdx.x;
+  if (gridDim.y == 1) {
+    const int64_t nt = gridDim.x, x = tile & 7, slot = tile >> 3;
+    const int64_t qn = nt >> 3, rn = nt & 7;
+    tile = x * qn + (x < rn ? x : rn) + slot;
+  }
   const int b = (int)(tile / p.tiles_per_img);
   const int pix0 = (int)(tile - (int64_t)b * p.tiles_per_img) * 128;
   const int i = lane & 31, h = lane >> 5;

@@ -94,17 +94,154 @@ def test_qdense_config1_both_variants():
 
 
 @pytest.mark.parametrize("idx", [0, 1, 2, 3])
-def test_qdense_config5_full_size_sampled_rows(idx):
+def test_qdense_config5_full_size(idx):
+    """Every element of every layer of the benchmark stack, in the launch configuration bench.py times."""
+    import os
     c = datagen.config5_layer(idx)
     got = host(hago.qdense(dev(c["a"]), act_qtype(c["a"], c["z_a"]), dev(c["w"]), hago.QType(hago.I8),
                            dev(c["bias"]), hago.I32, gpu_requant(c["mult"], c["shift"])))
-    rng = np.random.default_rng(50 + idx)
-    rows = np.unique(np.concatenate([rng.integers(0, 4096, 160), [0, 1, 127, 128, 4095]]))
-    want = ref.qdense(c["a"][rows], c["z_a"], c["w"], c["bias"], ref.I32, ref_requant(c["mult"], c["shift"]))
-    assert_same(got[rows], want, f"config 5 layer {idx}")
+    want = ref.qdense_threaded(c["a"], c["z_a"], c["w"], c["bias"], ref.I32, ref_requant(c["mult"], c["shift"]),
+                               threads=min(16, os.cpu_count() or 1))
+    assert_same(got, want, f"config 5 layer {idx}")
     sat = np.mean(np.abs(want.astype(np.int32)) >= 127)
     assert sat < 0.05, sat
     assert want.std() > 10
+
+
+def _extreme_terms(rng, N):
+    """Bias and shift vectors that put channels on both sides of every switch of the fused epilogue:
+    |bias| around 2^30 (where the folded 64-bit constant stops being usable), INT32 extremes (the
+    accumulator wraps), shifts 0 and 31 next to ordinary ones."""
+    bias = rng.integers(-10 ** 5, 10 ** 5, N).astype(np.int64)
+    shift = rng.integers(6, 14, N).astype(np.int32)
+    special = [2 ** 30 - 7, 2 ** 30 + 7, -(2 ** 30) + 7, -(2 ** 30) - 7, 2 ** 31 - 1, -(2 ** 31), 2 ** 30, -(2 ** 30)]
+    for k, b in enumerate(special):
+        for base in (3, 70, 200, 333, N - 40):      # spread over every 32-channel block a tile may hold
+            if 0 <= base + 5 * k < N:
+                bias[base + 5 * k] = b
+    for base in (1, 64, 129, 250, 300, N - 9):
+        if 0 <= base < N - 2:
+            shift[base], shift[base + 2] = 0, 31
+    return bias.astype(np.int32), shift
+
+
+@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4])
+@pytest.mark.parametrize("out_u8,z_out", [(False, 0), (True, 131), (False, -9)])
+def test_qdense_epilogue_switches_every_tile(tile, out_u8, z_out, stream_tile):
+    """The streaming kernel's fused epilogue picks, per tile, between the folded arithmetic and the
+    general one (a shift of 0, a bias term near 2^30); both kinds of channel inside one staged tile,
+    for every tile shape, multi-tile and ragged, against the oracle's wrapping arithmetic."""
+    stream_tile(tile)
+    M, N, K = 520, 400, 448
+    rng = np.random.default_rng(4000 + tile * 10 + z_out)
+    a, w = rnd_act(rng, (M, K), np.uint8), rnd_w(rng, (N, K))
+    bias, shift = _extreme_terms(rng, N)
+    mult = rng.integers(2 ** 30, 2 ** 31, N).astype(np.int32)
+    want = ref.qdense(a, 121, w, bias, ref.I32, ref_requant(mult, shift, out_u8, z_out))
+    got = hago.qdense(dev(a), act_qtype(a, 121), dev(w), hago.QType(hago.I8), dev(bias), hago.I32,
+                      gpu_requant(mult, shift, out_u8, z_out))
+    assert_same(host(got), want, f"tile {tile} extreme terms")
+    assert len(np.unique(want)) > 100
+    # a tile whose channels are all ordinary next to tiles that are not: ordinary terms only in the first 256
+    bias2, shift2 = bias.copy(), shift.copy()
+    bias2[:256] = rng.integers(-10 ** 5, 10 ** 5, 256)
+    shift2[:256] = rng.integers(6, 14, 256)
+    want = ref.qdense(a, 121, w, bias2, ref.I32, ref_requant(mult, shift2, out_u8, z_out))
+    got = hago.qdense(dev(a), act_qtype(a, 121), dev(w), hago.QType(hago.I8), dev(bias2), hago.I32,
+                      gpu_requant(mult, shift2, out_u8, z_out))
+    assert_same(host(got), want, f"tile {tile} mixed tiles")
+    # raw accumulators with the same biases: the int32 wrap of acc + bias
+    want = ref.qdense(a, 121, w, bias)
+    assert_same(host(hago.qdense(dev(a), act_qtype(a, 121), dev(w), hago.QType(hago.I8), dev(bias))), want, "raw wrap")
+
+
+@pytest.mark.parametrize("layout", ["nchw", "nhwc"])
+@pytest.mark.parametrize("O", [72, 200])
+def test_qconv2d_epilogue_switches(layout, O):
+    """The same switches through the 3x3 implicit GEMM on the workspace path (several tiles, ragged)."""
+    B, C, H, W = 2, 32, 19, 24
+    rng = np.random.default_rng(5100 + O)
+    a, w = rnd_act(rng, (B, C, H, W), np.uint8), rnd_w(rng, (O, C, 3, 3))
+    bias, shift = _extreme_terms(rng, O)
+    mult = rng.integers(2 ** 30, 2 ** 31, O).astype(np.int32)
+    lay_g, lay_r = (hago.NCHW, ref.NCHW) if layout == "nchw" else (hago.NHWC, ref.NHWC)
+    ah = a if layout == "nchw" else np.ascontiguousarray(a.transpose(0, 2, 3, 1))
+    wh = w if layout == "nchw" else np.ascontiguousarray(w.transpose(0, 2, 3, 1))
+    need = hago.qconv2d_workspace_bytes(ah.shape, wh.shape, lay_g, (1, 1), (1, 1))
+    ws = torch.empty(need, dtype=torch.uint8, device=DEV)
+    for out_u8, z_out in ((False, 0), (True, 131)):
+        want = ref.qconv2d(ah, 128, wh, bias, lay_r, (1, 1), (1, 1), 1, ref.I32, ref_requant(mult, shift, out_u8, z_out))
+        got = hago.qconv2d(dev(ah), act_qtype(ah, 128), dev(wh), hago.QType(hago.I8), dev(bias), lay_g, (1, 1), (1, 1), 1,
+                           hago.I32, gpu_requant(mult, shift, out_u8, z_out), workspace=ws)
+        assert_same(host(got), want, f"conv extreme terms {layout} u8={out_u8}")
+    # the weights part of the workspace is still valid: skip its rewrite
+    want = ref.qconv2d(ah, 128, wh, bias, lay_r, (1, 1), (1, 1), 1)
+    got = hago.qconv2d(dev(ah), act_qtype(ah, 128), dev(wh), hago.QType(hago.I8), dev(bias), lay_g, (1, 1), (1, 1), 1,
+                       hago.I32, None, flags=hago.WS_WEIGHTS_READY, workspace=ws)
+    assert_same(host(got), want, f"conv raw, weights kept {layout}")
+
+
+def test_qdense_long_reduction_takes_the_general_epilogue():
+    """K > 65536: |acc| may exceed 2^30, so the folded constant is not used; int8 activations at their
+    extremes make the accumulator wrap."""
+    M, N, K = 40, 48, 66048
+    rng = np.random.default_rng(66)
+    a = np.where(rng.random((M, K)) < 0.9, 127, -128).astype(np.int8)
+    w = np.where(rng.random((N, K)) < 0.9, 127, -127).astype(np.int8)
+    bias = rng.integers(-10 ** 6, 10 ** 6, N).astype(np.int32)
+    mult = rng.integers(2 ** 30, 2 ** 31, N).astype(np.int32)
+    shift = rng.integers(18, 24, N).astype(np.int32)
+    want = ref.qdense(a, -3, w, bias, ref.I32, ref_requant(mult, shift))
+    got = hago.qdense(dev(a), act_qtype(a, -3), dev(w), hago.QType(hago.I8), dev(bias), hago.I32, gpu_requant(mult, shift))
+    assert_same(host(got), want, "K = 66048")
+    assert np.abs(ref.qdense(a, -3, w, bias).astype(np.int64)).max() > 2 ** 29
+
+
+@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4, 5, 6])
+def test_general_kernel_every_tile_dense(tile, gemm_path):
+    """The register-staged kernel (what unaligned or oversized operands get) forced on an aligned
+    shape, one tile shape at a time."""
+    gemm_path(1)
+    hago.set_test_hook(hago.HOOK_GENERAL_TILE, tile)
+    try:
+        M, N, K = 300, 272, 208
+        rng = np.random.default_rng(900 + tile)
+        a, w = rnd_act(rng, (M, K), np.uint8), rnd_w(rng, (N, K))
+        bias = rng.integers(-10 ** 5, 10 ** 5, N).astype(np.int32)
+        mult, shift = datagen.requant_params(rng, np.full(N, 74.0 * 73.0 * np.sqrt(K)), 40.0)
+        want = ref.qdense(a, 119, w, bias, ref.I32, ref_requant(mult, shift))
+        got = hago.qdense(dev(a), act_qtype(a, 119), dev(w), hago.QType(hago.I8), dev(bias), hago.I32, gpu_requant(mult, shift))
+        assert_same(host(got), want, f"general kernel tile {tile}")
+    finally:
+        hago.set_test_hook(hago.HOOK_GENERAL_TILE, -1)
+
+
+@pytest.mark.parametrize("tile", [-1, 0, 1, 2, 3, 4, 5, 6])
+@pytest.mark.parametrize("layout", ["nchw", "nhwc"])
+def test_general_kernel_every_tile_conv(tile, layout, gemm_path):
+    """The general kernel's implicit-GEMM loaders for both layouts, one tile shape at a time (shapes a
+    layout cannot instantiate fall back to 128 x 128), with a workspace present that must stay unused."""
+    gemm_path(1)
+    hago.set_test_hook(hago.HOOK_GENERAL_TILE, tile)
+    try:
+        B, C, H, W, O = 2, 48, 13, 20, 136
+        rng = np.random.default_rng(950 + tile)
+        a, w = rnd_act(rng, (B, C, H, W), np.uint8), rnd_w(rng, (O, C, 3, 3))
+        bias = rng.integers(-10 ** 5, 10 ** 5, O).astype(np.int32)
+        mult, shift = datagen.requant_params(rng, np.full(O, 74.0 * 73.0 * np.sqrt(9 * C)), 40.0)
+        lay_g, lay_r = (hago.NCHW, ref.NCHW) if layout == "nchw" else (hago.NHWC, ref.NHWC)
+        ah = a if layout == "nchw" else np.ascontiguousarray(a.transpose(0, 2, 3, 1))
+        wh = w if layout == "nchw" else np.ascontiguousarray(w.transpose(0, 2, 3, 1))
+        ws = torch.full((hago.qconv2d_workspace_bytes(ah.shape, wh.shape, lay_g, (1, 1), (1, 1)),), 0x77,
+                        dtype=torch.uint8, device=DEV)
+        for acc_g, acc_r, rq in ((hago.I32, ref.I32, True), (hago.I32, ref.I32, False), (hago.I16, ref.I16, False)):
+            want = ref.qconv2d(ah, 125, wh, bias, lay_r, (1, 1), (1, 1), 1, acc_r, ref_requant(mult, shift) if rq else None)
+            got = hago.qconv2d(dev(ah), act_qtype(ah, 125), dev(wh), hago.QType(hago.I8), dev(bias), lay_g, (1, 1), (1, 1), 1,
+                               acc_g, gpu_requant(mult, shift) if rq else None, workspace=ws)
+            assert_same(host(got), want, f"general conv tile {tile} {layout} rq={rq}")
+        assert bool((ws == 0x77).all())
+    finally:
+        hago.set_test_hook(hago.HOOK_GENERAL_TILE, -1)
 
 
 CONV_CASES = [
@@ -385,6 +522,16 @@ def test_depthwise(case, adt, za):
     got = qconv2d(dev(a.transpose(0, 2, 3, 1)), a_t, dev(w.transpose(0, 2, 3, 1)), w_t, dev(bias), hago.NHWC,
                        stride, pad, C, hago.I32, gpu_requant(mult, shift))
     assert_same(host(got), want, f"depthwise nhwc {case}")
+    # channel-last: raw int32, raw int16 and int16 accumulation with requantize
+    an, wn = np.ascontiguousarray(a.transpose(0, 2, 3, 1)), np.ascontiguousarray(w.transpose(0, 2, 3, 1))
+    for acc_dt_r, acc_dt_g in ((ref.I32, hago.I32), (ref.I16, hago.I16)):
+        want = ref.qconv2d(an, za, wn, bias, ref.NHWC, stride, pad, C, acc_dt_r)
+        got = qconv2d(dev(an), a_t, dev(wn), w_t, dev(bias), hago.NHWC, stride, pad, C, acc_dt_g)
+        assert_same(host(got), want, f"depthwise nhwc raw {case}")
+    m16, s16 = datagen.requant_params(rng, np.full(C, 19000.0), 40.0)
+    want = ref.qconv2d(an, za, wn, bias, ref.NHWC, stride, pad, C, ref.I16, ref_requant(m16, s16))
+    got = qconv2d(dev(an), a_t, dev(wn), w_t, dev(bias), hago.NHWC, stride, pad, C, hago.I16, gpu_requant(m16, s16))
+    assert_same(host(got), want, f"depthwise nhwc int16 accumulation, requantized {case}")
 
 
 @pytest.mark.parametrize("out_u8,z_out", [(False, 0), (False, -7), (True, 131)])

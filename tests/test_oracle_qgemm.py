@@ -250,3 +250,21 @@ def test_bad_arguments(ref):
         ref.qconv2d(a, 0, w, None, ref.NCHW, (1, 1), (1, 1), 3)     # groups does not divide
     with pytest.raises(ref.RefError):
         ref.qconv2d(a, 0, np.zeros((4, 4, 7, 7), np.int8), None, ref.NCHW, (1, 1), (0, 0), 1)  # kernel > image
+
+
+def test_threaded_helper_equals_the_plain_oracle(ref):
+    """qdense_threaded (the timing helper of the benchmark's CPU baseline and of the full-size parity
+    test) only slices rows: its result is the plain oracle's, for every thread count, ragged splits
+    included."""
+    rng = np.random.default_rng(31)
+    a = rng.integers(0, 256, (37, 50)).astype(np.uint8)
+    w = rng.integers(-127, 128, (19, 50)).astype(np.int8)
+    bias = rng.integers(-1000, 1000, 19).astype(np.int32)
+    mult = rng.integers(2 ** 30, 2 ** 31, 19).astype(np.int32)
+    shift = rng.integers(5, 12, 19).astype(np.int32)
+    for rq in (None, ref.Requant(mult, shift)):
+        for acc in (ref.I32, ref.I16):
+            want = ref.qdense(a, 128, w, bias, acc, rq)
+            for threads in (1, 2, 5, 16, 64):
+                got = ref.qdense_threaded(a, 128, w, bias, acc, rq, threads=threads)
+                assert got.dtype == want.dtype and np.array_equal(got, want), (threads, acc)

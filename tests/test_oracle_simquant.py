@@ -169,3 +169,19 @@ def test_batched_candidates_on_the_worked_vectors(ref):
     x = np.array([[[0.375], [0.375]]], np.float32)          # [1, 2, 1]
     y = ref.simquant_batched(x, [[0.25, 0.125], [0.5, 0.25]], [[0, 0], [0, 0]], [-128, -128], [127, 127])
     assert y[:, 0, :, 0].tolist() == [[0.5, 0.375], [0.5, 0.5]]   # 1.5->2, 3->3 | 0.75->1, 1.5->2
+
+
+def test_absmax_ignores_nan_and_handles_infinities(ref):
+    """Reading taken where Eq. 2 is silent: a NaN element never wins the comparison `|v| > t`, so
+    the threshold is the maximum over the other elements (numpy's nanmax); an infinity wins; the
+    result is never -0; an all-NaN or empty reduction gives 0."""
+    x = np.array([[[1.5, np.nan, -3.25, 0.0], [np.nan, np.nan, np.nan, np.nan], [-0.0, 0.0, -0.0, 0.0],
+                   [2.0, -np.inf, 7.0, np.nan]]], np.float32)
+    thr = ref.absmax(x, True)
+    assert thr.tolist() == [3.25, 0.0, 0.0, np.inf]
+    assert not np.signbit(thr).any()
+    want = np.abs(np.where(np.isnan(x), np.float32(0), x)).max(axis=(0, 2))   # the maximum over the non-NaN elements
+    assert np.array_equal(thr, want.astype(np.float32))
+    assert ref.absmax(x, False).tolist() == [np.inf]
+    assert ref.absmax(x[:, :3], False).tolist() == [3.25]
+    assert ref.absmax(np.zeros((0, 3, 4), np.float32), True).tolist() == [0.0, 0.0, 0.0]
