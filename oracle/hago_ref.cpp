@@ -17,25 +17,33 @@ namespace {
 
 inline int32_t load_operand(const void* p, int32_t dtype, int64_t i) {
   if (dtype == REF_U8) return (int32_t) static_cast<const uint8_t*>(p)[i];
+  if (dtype == REF_I16) return (int32_t) static_cast<const int16_t*>(p)[i];
   return (int32_t) static_cast<const int8_t*>(p)[i];
 }
 
-inline bool operand_dtype_ok(int32_t dtype) {
-  return dtype == REF_U8 || dtype == REF_I8;
+/* Operand triples: (u8 | i8) x i8, or i16 x i16 (Sec. 1, Sec. 4.1). */
+inline bool operand_pair_ok(int32_t a_dtype, int32_t w_dtype, int32_t acc_dtype) {
+  if (w_dtype == REF_I8) return a_dtype == REF_U8 || a_dtype == REF_I8;
+  if (w_dtype == REF_I16) return a_dtype == REF_I16 && acc_dtype != REF_I16;
+  return false;
 }
 
 inline bool acc_dtype_ok(int32_t dtype) {
-  return dtype == REF_I32 || dtype == REF_I16;
+  return dtype == REF_I32 || dtype == REF_I16 || dtype == REF_I24;
 }
 
 /* Reduce a 32-bit wrapped sum to the accumulator type and sign-extend. */
 inline int32_t finish_acc(uint32_t sum, int32_t acc_dtype) {
   if (acc_dtype == REF_I16) return (int32_t)(int16_t)(uint16_t)(sum & 0xFFFFu);
+  if (acc_dtype == REF_I24) {
+    const uint32_t low = sum & 0xFFFFFFu;
+    return (low & 0x800000u) ? (int32_t)low - (int32_t)0x1000000 : (int32_t)low;
+  }
   return (int32_t)sum;
 }
 
 bool requant_ok(const ref_requant* rq, int64_t channels) {
-  if (!rq->multiplier || !rq->shift) return false;
+  if (!rq->shift) return false;
   if (rq->out_dtype != REF_I8 && rq->out_dtype != REF_U8) return false;
   if (rq->clip_lo > rq->clip_hi) return false;
   if (rq->rounding != REF_ROUND_UPWARD && rq->rounding != REF_ROUND_HALF_AWAY) return false;
@@ -51,15 +59,18 @@ inline void emit(void* out, int64_t i, int64_t c, int32_t acc,
   if (!rq) {
     if (acc_dtype == REF_I16)
       static_cast<int16_t*>(out)[i] = (int16_t)acc;
-    else
+    else /* int32, and 24 bits sign-extended into an int32 */
       static_cast<int32_t*>(out)[i] = acc;
     return;
   }
   const int64_t pc = rq->per_channel ? c : 0;
   const int64_t v =
-      hago_ref_requantize_one_mode(acc, rq->multiplier[pc], rq->shift[pc],
-                                   rq->out_zero_point, rq->clip_lo, rq->clip_hi,
-                                   rq->rounding);
+      rq->multiplier
+          ? hago_ref_requantize_one_mode(acc, rq->multiplier[pc], rq->shift[pc],
+                                         rq->out_zero_point, rq->clip_lo,
+                                         rq->clip_hi, rq->rounding)
+          : hago_ref_requantize_shift_one(acc, rq->shift[pc], rq->out_zero_point,
+                                          rq->clip_lo, rq->clip_hi, rq->rounding);
   if (rq->out_dtype == REF_U8)
     static_cast<uint8_t*>(out)[i] = (uint8_t)v;
   else
@@ -219,12 +230,33 @@ int64_t hago_ref_requantize_one_mode(int32_t acc, int32_t multiplier,
   return o;
 }
 
+int64_t hago_ref_requantize_shift_one(int32_t acc, int32_t shift, int32_t z_out,
+                                      int32_t lo, int32_t hi, int32_t rounding) {
+  const int64_t p = (int64_t)acc;
+  int64_t r;
+  if (shift <= 0) {
+    r = p; /* scale 1: nothing to round */
+  } else {
+    const int64_t half = (int64_t)1 << (shift - 1);
+    if (rounding == REF_ROUND_HALF_AWAY) {
+      const int64_t mag = ((p < 0 ? -p : p) + half) >> shift;
+      r = p < 0 ? -mag : mag;
+    } else {
+      r = (p + half) >> shift; /* floor(acc / 2^sh + 1/2) */
+    }
+  }
+  int64_t o = r + (int64_t)z_out;
+  if (o < (int64_t)lo) o = lo;
+  if (o > (int64_t)hi) o = hi;
+  return o;
+}
+
 int hago_ref_requantize(const void* acc, int32_t acc_dtype, int64_t outer,
                         int64_t channels, int64_t inner, const ref_requant* rq,
                         void* out) {
   if (!acc || !rq || !out) return REF_ERR_NULL;
   if (outer < 0 || channels < 0 || inner < 0) return REF_ERR_SHAPE;
-  if (!acc_dtype_ok(acc_dtype)) return REF_ERR_DTYPE;
+  if (acc_dtype != REF_I32 && acc_dtype != REF_I16) return REF_ERR_DTYPE;
   if (!requant_ok(rq, channels)) return REF_ERR_PARAM;
   for (int64_t o = 0; o < outer; ++o)
     for (int64_t c = 0; c < channels; ++c)
@@ -246,22 +278,79 @@ int hago_ref_acc16_safe(int64_t K, int64_t a_absmax, int64_t w_absmax) {
   return (K * a_absmax * w_absmax <= 32767) ? 1 : 0;
 }
 
+int hago_ref_acc_safe(int64_t K, int64_t a_absmax, int64_t w_absmax,
+                      int32_t acc_bits) {
+  if (acc_bits != 16 && acc_bits != 24 && acc_bits != 32) return 0;
+  const int64_t limit = ((int64_t)1 << (acc_bits - 1)) - 1;
+  if (K < 0 || a_absmax < 0 || w_absmax < 0) return 0;
+  if (K == 0 || a_absmax == 0 || w_absmax == 0) return 1;
+  if (a_absmax > limit || w_absmax > limit || K > limit) return 0;
+  if (a_absmax > limit / w_absmax) return 0; /* the product alone is too large */
+  if (K > limit / (a_absmax * w_absmax)) return 0;
+  return 1;
+}
+
+int hago_ref_simquant_wrap(const float* x, float* y, int64_t outer,
+                           int64_t channels, int64_t inner, const float* scale,
+                           const int32_t* zero_point, int32_t per_channel,
+                           int32_t wrap_bits, int32_t wrap_signed,
+                           int32_t clip_lo, int32_t clip_hi) {
+  if (!x || !y || !scale || !zero_point) return REF_ERR_NULL;
+  if (outer < 0 || channels < 0 || inner < 0) return REF_ERR_SHAPE;
+  if (clip_lo > clip_hi || wrap_bits < 2 || wrap_bits > 32) return REF_ERR_BITS;
+  const float lo = (float)clip_lo;
+  const float hi = (float)clip_hi;
+  const int64_t modulus = (int64_t)1 << wrap_bits;
+  const int64_t top = (int64_t)1 << (wrap_bits - 1);
+  for (int64_t o = 0; o < outer; ++o)
+    for (int64_t c = 0; c < channels; ++c) {
+      const float s = scale[per_channel ? c : 0];
+      const float zf = (float)zero_point[per_channel ? c : 0];
+      for (int64_t i = 0; i < inner; ++i) {
+        const int64_t idx = (o * channels + c) * inner + i;
+        const float t = x[idx] / s;          /* Eq. 3: r / s        */
+        const float u = std::nearbyintf(t);  /* round, ties to even */
+        float v = u + zf;                    /* integer code        */
+        if (v == v) {                        /* not NaN: overflow   */
+          int64_t code = 0;                  /* huge and infinite codes: 0 */
+          if (v > -4.0e18f && v < 4.0e18f) {
+            code = (int64_t)v;               /* v holds an integer  */
+            code = ((code % modulus) + modulus) % modulus; /* 0 .. 2^b - 1 */
+            if (wrap_signed && code >= top) code -= modulus; /* two's complement */
+          }
+          v = (float)code;
+        }
+        v = (v < lo) ? lo : ((v > hi) ? hi : v); /* saturation      */
+        y[idx] = (v - zf) * s;               /* r ~= q * s          */
+      }
+    }
+  return REF_OK;
+}
+
 int hago_ref_qdense(const void* a, int32_t a_dtype, int32_t a_zero_point,
                     const int8_t* w, const int32_t* bias, int64_t M, int64_t N,
                     int64_t K, int32_t acc_dtype, const ref_requant* rq,
                     void* out) {
+  return hago_ref_qdense_x(a, a_dtype, a_zero_point, w, REF_I8, bias, M, N, K,
+                           acc_dtype, rq, out);
+}
+
+int hago_ref_qdense_x(const void* a, int32_t a_dtype, int32_t a_zero_point,
+                      const void* w, int32_t w_dtype, const int32_t* bias,
+                      int64_t M, int64_t N, int64_t K, int32_t acc_dtype,
+                      const ref_requant* rq, void* out) {
   if (!a || !w || !out) return REF_ERR_NULL;
   if (M < 0 || N < 0 || K < 0) return REF_ERR_SHAPE;
-  if (!operand_dtype_ok(a_dtype) || !acc_dtype_ok(acc_dtype))
+  if (!acc_dtype_ok(acc_dtype) || !operand_pair_ok(a_dtype, w_dtype, acc_dtype))
     return REF_ERR_DTYPE;
   if (rq && !requant_ok(rq, N)) return REF_ERR_PARAM;
   for (int64_t m = 0; m < M; ++m)
     for (int64_t n = 0; n < N; ++n) {
       uint32_t sum = bias ? (uint32_t)bias[n] : 0u;
       for (int64_t k = 0; k < K; ++k) {
-        const int32_t av = load_operand(a, a_dtype, m * K + k) - a_zero_point;
-        const int32_t wv = (int32_t)w[n * K + k];
-        sum += (uint32_t)(av * wv); /* |av*wv| <= 510*128, no overflow */
+        const int64_t av = load_operand(a, a_dtype, m * K + k) - a_zero_point;
+        const int64_t wv = load_operand(w, w_dtype, n * K + k);
+        sum += (uint32_t)(uint64_t)(av * wv); /* exact product, sum mod 2^32 */
       }
       emit(out, m * N + n, n, finish_acc(sum, acc_dtype), acc_dtype, rq);
     }
@@ -274,6 +363,18 @@ int hago_ref_qconv2d(const void* a, int32_t a_dtype, int32_t a_zero_point,
                      int32_t KH, int32_t KW, int32_t stride_h, int32_t stride_w,
                      int32_t pad_h, int32_t pad_w, int32_t groups,
                      int32_t acc_dtype, const ref_requant* rq, void* out) {
+  return hago_ref_qconv2d_x(a, a_dtype, a_zero_point, w, REF_I8, bias, layout, B,
+                            C, H, W, O, KH, KW, stride_h, stride_w, pad_h, pad_w,
+                            groups, acc_dtype, rq, out);
+}
+
+int hago_ref_qconv2d_x(const void* a, int32_t a_dtype, int32_t a_zero_point,
+                       const void* w, int32_t w_dtype, const int32_t* bias,
+                       int32_t layout, int64_t B, int64_t C, int64_t H, int64_t W,
+                       int64_t O, int32_t KH, int32_t KW, int32_t stride_h,
+                       int32_t stride_w, int32_t pad_h, int32_t pad_w,
+                       int32_t groups, int32_t acc_dtype, const ref_requant* rq,
+                       void* out) {
   if (!a || !w || !out) return REF_ERR_NULL;
   if (B < 0 || C < 1 || H < 1 || W < 1 || O < 1 || KH < 1 || KW < 1 ||
       stride_h < 1 || stride_w < 1 || pad_h < 0 || pad_w < 0)
@@ -282,7 +383,7 @@ int hago_ref_qconv2d(const void* a, int32_t a_dtype, int32_t a_zero_point,
   if (layout != REF_NCHW && layout != REF_NHWC) return REF_ERR_SHAPE;
   if (H + 2 * (int64_t)pad_h < KH || W + 2 * (int64_t)pad_w < KW)
     return REF_ERR_SHAPE;
-  if (!operand_dtype_ok(a_dtype) || !acc_dtype_ok(acc_dtype))
+  if (!acc_dtype_ok(acc_dtype) || !operand_pair_ok(a_dtype, w_dtype, acc_dtype))
     return REF_ERR_DTYPE;
   if (rq && !requant_ok(rq, O)) return REF_ERR_PARAM;
 
@@ -310,8 +411,9 @@ int hago_ref_qconv2d(const void* a, int32_t a_dtype, int32_t a_zero_point,
                                         : ((b * H + iy) * W + ix) * C + c;
                 const int64_t wi = nchw ? ((o * Cg + ci) * KH + ky) * KW + kx
                                         : ((o * KH + ky) * KW + kx) * Cg + ci;
-                const int32_t av = load_operand(a, a_dtype, ai) - a_zero_point;
-                sum += (uint32_t)(av * (int32_t)w[wi]);
+                const int64_t av = load_operand(a, a_dtype, ai) - a_zero_point;
+                const int64_t wv = load_operand(w, w_dtype, wi);
+                sum += (uint32_t)(uint64_t)(av * wv); /* exact product, sum mod 2^32 */
               }
             }
           }

@@ -27,7 +27,10 @@ extern "C" {
 #endif
 
 /* container dtypes (values chosen by this file alone) */
-enum { REF_U8 = 0, REF_I8 = 1, REF_I16 = 2, REF_I32 = 3, REF_F32 = 4 };
+enum { REF_U8 = 0, REF_I8 = 1, REF_I16 = 2, REF_I32 = 3, REF_F32 = 4,
+       REF_I24 = 5 /* accumulator only: 24-bit two's complement, stored
+                      sign-extended in an int32 (Sec. 4.1: accelerators with
+                      24-bit accumulation) */ };
 enum { REF_NCHW = 0, REF_NHWC = 1 }; /* weights OIHW / OHWI respectively */
 
 enum {
@@ -42,7 +45,10 @@ enum {
 /* Requantize parameters.  multiplier/shift have `channels` entries when
  * per_channel != 0, else one entry.  out_dtype is REF_I8 or REF_U8. */
 typedef struct {
-  const int32_t* multiplier; /* Q31 fixed point, value = multiplier / 2^31 */
+  const int32_t* multiplier; /* Q31 fixed point, value = multiplier / 2^31;
+                                NULL: power-of-two scales (Sec. 5.1), the
+                                requantize is the rounding right shift alone,
+                                r = round(acc / 2^shift) */
   const int32_t* shift;      /* extra right shift, 0..31 */
   int32_t per_channel;
   int32_t out_dtype;
@@ -108,6 +114,13 @@ int64_t hago_ref_requantize_one_mode(int32_t acc, int32_t multiplier,
                                      int32_t shift, int32_t z_out, int32_t lo,
                                      int32_t hi, int32_t rounding);
 
+/* Requantize for power-of-two scales (Sec. 5.1: thresholds rounded to powers
+ * of two so that shifting replaces the multiplication): r = round(acc / 2^sh),
+ * sh in 0..31, same tie rules as above (sh == 0: r = acc);
+ * out = clip(r + z_out, lo, hi).  No multiplication anywhere. */
+int64_t hago_ref_requantize_shift_one(int32_t acc, int32_t shift, int32_t z_out,
+                                      int32_t lo, int32_t hi, int32_t rounding);
+
 /* Standalone requantize over acc[outer, channels, inner] (REF_I32 or REF_I16;
  * int16 is sign-extended) -> out (REF_I8 / REF_U8). */
 int hago_ref_requantize(const void* acc, int32_t acc_dtype, int64_t outer,
@@ -117,6 +130,28 @@ int hago_ref_requantize(const void* acc, int32_t acc_dtype, int64_t outer,
 /* Largest |sum| the declared operand ranges allow: K * Amax * Wmax, and
  * whether it fits int16 (<= 32767).  Returns 1 if safe, 0 if not. */
 int hago_ref_acc16_safe(int64_t K, int64_t a_absmax, int64_t w_absmax);
+
+/* The same bound for an accumulator of acc_bits bits (16, 24 or 32):
+ * K * Amax * Wmax <= 2^(acc_bits-1) - 1. */
+int hago_ref_acc_safe(int64_t K, int64_t a_absmax, int64_t w_absmax,
+                      int32_t acc_bits);
+
+/* simulated_quantize with the overflow of the simulated integer type (Sec. 5.2
+ * names three error sources: rounding, saturation, and overflow "when the
+ * output of quantized operator is beyond the limit of output data type").
+ * The code u = rint(x / s) + z is first reduced modulo 2^wrap_bits into
+ * [-2^(wrap_bits-1), 2^(wrap_bits-1)) (wrap_signed != 0, two's complement) or
+ * [0, 2^wrap_bits) (unsigned), wrap_bits in 2..32 being the width of the
+ * simulated accumulator / container, then clipped and dequantized as in
+ * simulated_quantize.  Codes of magnitude >= 2^62 and
+ * infinities reduce to 0 (every float that large is a multiple of 2^32); NaN
+ * stays NaN.  The wrapped code is converted back to binary32 (exact for
+ * wrap_bits <= 25). */
+int hago_ref_simquant_wrap(const float* x, float* y, int64_t outer,
+                           int64_t channels, int64_t inner, const float* scale,
+                           const int32_t* zero_point, int32_t per_channel,
+                           int32_t wrap_bits, int32_t wrap_signed,
+                           int32_t clip_lo, int32_t clip_hi);
 
 /* Quantized dense (Sec. 1 / Sec. 6.2: low-precision operands, integer
  * accumulation): acc[m,n] = bias[n] + sum_k (a[m,k] - z_a) * w[n,k], reduced
@@ -139,6 +174,22 @@ int hago_ref_qconv2d(const void* a, int32_t a_dtype, int32_t a_zero_point,
                      int32_t KH, int32_t KW, int32_t stride_h, int32_t stride_w,
                      int32_t pad_h, int32_t pad_w, int32_t groups,
                      int32_t acc_dtype, const ref_requant* rq, void* out);
+
+/* The same two operators with the weight container named: REF_I8 as above, or
+ * the second operand triple of Sec. 1 / Sec. 4.1, int16 x int16 with int32
+ * accumulation (a_dtype == w_dtype == REF_I16, acc_dtype REF_I32 or REF_I24).
+ * Products are formed exactly and the sum wraps modulo 2^32 as before. */
+int hago_ref_qdense_x(const void* a, int32_t a_dtype, int32_t a_zero_point,
+                      const void* w, int32_t w_dtype, const int32_t* bias,
+                      int64_t M, int64_t N, int64_t K, int32_t acc_dtype,
+                      const ref_requant* rq, void* out);
+int hago_ref_qconv2d_x(const void* a, int32_t a_dtype, int32_t a_zero_point,
+                       const void* w, int32_t w_dtype, const int32_t* bias,
+                       int32_t layout, int64_t B, int64_t C, int64_t H, int64_t W,
+                       int64_t O, int32_t KH, int32_t KW, int32_t stride_h,
+                       int32_t stride_w, int32_t pad_h, int32_t pad_w,
+                       int32_t groups, int32_t acc_dtype, const ref_requant* rq,
+                       void* out);
 
 #ifdef __cplusplus
 }

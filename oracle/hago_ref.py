@@ -18,10 +18,10 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "hago_ref.cpp")
 _LIB = os.path.join(_HERE, "libhago_ref.so")
 
-U8, I8, I16, I32, F32 = 0, 1, 2, 3, 4
+U8, I8, I16, I32, F32, I24 = 0, 1, 2, 3, 4, 5   # I24: accumulator only, stored sign-extended in int32
 NCHW, NHWC = 0, 1
 
-_NP_OF = {U8: np.uint8, I8: np.int8, I16: np.int16, I32: np.int32}
+_NP_OF = {U8: np.uint8, I8: np.int8, I16: np.int16, I32: np.int32, I24: np.int32}
 _CODE_OF = {np.dtype(np.uint8): U8, np.dtype(np.int8): I8,
             np.dtype(np.int16): I16, np.dtype(np.int32): I32}
 
@@ -72,6 +72,12 @@ def lib(path: str | None = None):
             L.hago_ref_requantize_one_mode.argtypes = [i32] * 7
             L.hago_ref_requantize.argtypes = [vp, i32, i64, i64, i64, vp, vp]
             L.hago_ref_acc16_safe.argtypes = [i64, i64, i64]
+            L.hago_ref_acc_safe.argtypes = [i64, i64, i64, i32]
+            L.hago_ref_requantize_shift_one.restype = i64
+            L.hago_ref_requantize_shift_one.argtypes = [i32] * 6
+            L.hago_ref_simquant_wrap.argtypes = [vp, vp, i64, i64, i64, vp, vp, i32, i32, i32, i32, i32]
+            L.hago_ref_qdense_x.argtypes = [vp, i32, i32, vp, i32, vp, i64, i64, i64, i32, vp, vp]
+            L.hago_ref_qconv2d_x.argtypes = [vp, i32, i32, vp, i32, vp, i32] + [i64] * 5 + [i32] * 7 + [i32, vp, vp]
             L.hago_ref_qdense.argtypes = [vp, i32, i32, vp, vp, i64, i64, i64, i32, vp, vp]
             L.hago_ref_qconv2d.argtypes = [vp, i32, i32, vp, vp, i32] + [i64] * 5 + [i32] * 7 + [i32, vp, vp]
             if path is not None:
@@ -96,13 +102,15 @@ def _p(a):
 
 
 class Requant:
-    """Requantize parameters (host arrays)."""
+    """Requantize parameters (host arrays).  multiplier=None: power-of-two scales, the rounding
+    right shift alone (Sec. 5.1)."""
 
     def __init__(self, multiplier, shift, out_dtype=I8, out_zero_point=0,
                  clip_lo=-128, clip_hi=127, per_channel=None, rounding=0):
-        self.multiplier = np.ascontiguousarray(multiplier, dtype=np.int32).reshape(-1)
+        self.multiplier = (None if multiplier is None
+                           else np.ascontiguousarray(multiplier, dtype=np.int32).reshape(-1))
         self.shift = np.ascontiguousarray(shift, dtype=np.int32).reshape(-1)
-        self.per_channel = int(self.multiplier.size > 1) if per_channel is None else int(per_channel)
+        self.per_channel = int(self.shift.size > 1) if per_channel is None else int(per_channel)
         self.out_dtype = out_dtype
         self.out_zero_point = int(out_zero_point)
         self.clip_lo = int(clip_lo)
@@ -110,7 +118,7 @@ class Requant:
         self.rounding = int(rounding)   # ROUND_UPWARD or ROUND_HALF_AWAY
 
     def c_struct(self):
-        return _Requant(self.multiplier.ctypes.data, self.shift.ctypes.data,
+        return _Requant(None if self.multiplier is None else self.multiplier.ctypes.data, self.shift.ctypes.data,
                         self.per_channel, self.out_dtype, self.out_zero_point,
                         self.clip_lo, self.clip_hi, self.rounding)
 
@@ -144,6 +152,19 @@ def simquant(x, scale, zero_point, clip_lo, clip_hi, per_channel=None):
     y = np.empty_like(x)
     _chk(lib().hago_ref_simquant(_p(x), _p(y), o, c, i, _p(s), _p(z), pc,
                                  int(clip_lo), int(clip_hi)))
+    return y
+
+
+def simquant_wrap(x, scale, zero_point, wrap_bits, wrap_signed, clip_lo, clip_hi, per_channel=None):
+    """simulated_quantize with the overflow of a wrap_bits-wide (un)signed integer type (Sec. 5.2)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    o, c, i = x.shape
+    s = np.ascontiguousarray(scale, dtype=np.float32).reshape(-1)
+    z = np.ascontiguousarray(zero_point, dtype=np.int32).reshape(-1)
+    pc = int(s.size > 1) if per_channel is None else int(per_channel)
+    y = np.empty_like(x)
+    _chk(lib().hago_ref_simquant_wrap(_p(x), _p(y), o, c, i, _p(s), _p(z), pc, int(wrap_bits),
+                                      int(bool(wrap_signed)), int(clip_lo), int(clip_hi)))
     return y
 
 
@@ -207,6 +228,10 @@ def requantize_one(acc, multiplier, shift, z_out=0, lo=-(2 ** 31), hi=2 ** 31 - 
                                               int(z_out), int(lo), int(hi), int(rounding))
 
 
+def requantize_shift_one(acc, shift, z_out=0, lo=-(2 ** 31), hi=2 ** 31 - 1, rounding=ROUND_UPWARD):
+    return lib().hago_ref_requantize_shift_one(int(acc), int(shift), int(z_out), int(lo), int(hi), int(rounding))
+
+
 def requantize(acc, rq: Requant):
     """acc: int32 or int16 [outer, channels, inner]."""
     acc = np.ascontiguousarray(acc)
@@ -222,13 +247,23 @@ def acc16_safe(K, a_absmax, w_absmax):
     return bool(lib().hago_ref_acc16_safe(int(K), int(a_absmax), int(w_absmax)))
 
 
+def acc_safe(K, a_absmax, w_absmax, acc_bits):
+    return bool(lib().hago_ref_acc_safe(int(K), int(a_absmax), int(w_absmax), int(acc_bits)))
+
+
+def _weights(w):
+    """int8 weights, or int16 ones for the int16 x int16 operand triple."""
+    w = np.ascontiguousarray(w)
+    return w if w.dtype == np.int16 else np.ascontiguousarray(w, dtype=np.int8)
+
+
 def _out_dtype(acc_dtype, rq):
     return _NP_OF[rq.out_dtype] if rq is not None else _NP_OF[acc_dtype]
 
 
 def qdense(a, a_zero_point, w, bias=None, acc_dtype=I32, rq: Requant | None = None, out=None):
     a = np.ascontiguousarray(a)
-    w = np.ascontiguousarray(w, dtype=np.int8)
+    w = _weights(w)
     M, K = a.shape
     N = w.shape[0]
     assert w.shape[1] == K
@@ -237,9 +272,9 @@ def qdense(a, a_zero_point, w, bias=None, acc_dtype=I32, rq: Requant | None = No
     if out is None:
         out = np.empty((M, N), _out_dtype(acc_dtype, rq))
     st = rq.c_struct() if rq is not None else None
-    _chk(lib().hago_ref_qdense(_p(a), _CODE_OF[a.dtype], int(a_zero_point), _p(w), _p(bias),
-                               M, N, K, acc_dtype,
-                               C.addressof(st) if st is not None else None, _p(out)))
+    _chk(lib().hago_ref_qdense_x(_p(a), _CODE_OF[a.dtype], int(a_zero_point), _p(w), _CODE_OF[w.dtype], _p(bias),
+                                 M, N, K, acc_dtype,
+                                 C.addressof(st) if st is not None else None, _p(out)))
     return out
 
 
@@ -251,7 +286,7 @@ def conv_out_hw(H, W, KH, KW, stride, pad):
 def qconv2d(a, a_zero_point, w, bias=None, layout=NCHW, stride=(1, 1), pad=(0, 0),
             groups=1, acc_dtype=I32, rq: Requant | None = None):
     a = np.ascontiguousarray(a)
-    w = np.ascontiguousarray(w, dtype=np.int8)
+    w = _weights(w)
     if layout == NCHW:
         B, Cc, H, W = a.shape
         O, _, KH, KW = w.shape
@@ -265,10 +300,10 @@ def qconv2d(a, a_zero_point, w, bias=None, layout=NCHW, stride=(1, 1), pad=(0, 0
     shape = (B, O, OHa, OWa) if layout == NCHW else (B, OHa, OWa, O)
     out = np.empty(shape, _out_dtype(acc_dtype, rq))
     st = rq.c_struct() if rq is not None else None
-    _chk(lib().hago_ref_qconv2d(_p(a), _CODE_OF[a.dtype], int(a_zero_point), _p(w), _p(bias),
-                                layout, B, Cc, H, W, O, KH, KW, stride[0], stride[1],
-                                pad[0], pad[1], groups, acc_dtype,
-                                C.addressof(st) if st is not None else None, _p(out)))
+    _chk(lib().hago_ref_qconv2d_x(_p(a), _CODE_OF[a.dtype], int(a_zero_point), _p(w), _CODE_OF[w.dtype], _p(bias),
+                                  layout, B, Cc, H, W, O, KH, KW, stride[0], stride[1],
+                                  pad[0], pad[1], groups, acc_dtype,
+                                  C.addressof(st) if st is not None else None, _p(out)))
     return out
 
 
