@@ -13,6 +13,11 @@
  *   hago_absmax     -- max-abs calibration thresholds (Eq. 2)
  *   hago_quantize, hago_dequantize -- fp32 <-> integer codes (Sec. 6.1; Eq. 3)
  *   hago_simquant_codes -- simulated_quantize plus its integer codes, one pass
+ *   hago_simquant_wrap  -- simulated_quantize with the overflow of the simulated
+ *                          integer type (Sec. 5.2)
+ * and the operand / accumulator variants the paper names: int16 x int16
+ * operands, 24-bit accumulators (Sec. 4.1), shift-only requantize for
+ * power-of-two scales (Sec. 5.1).
  *
  * Conventions common to every call
  *   - Pointers marked "device" are GPU addresses valid on the current HIP
@@ -68,7 +73,10 @@ typedef enum {
   HAGO_I8 = 1,
   HAGO_I16 = 2,
   HAGO_I32 = 3,
-  HAGO_F32 = 4
+  HAGO_F32 = 4,
+  HAGO_I24 = 5  /* accumulator type only (Sec. 4.1: accelerators with 24-bit
+                   accumulation): 24-bit two's complement, held sign-extended
+                   in an int32; also a simulated type of hago_simquant_wrap */
 } hago_dtype;
 
 typedef enum {
@@ -77,8 +85,9 @@ typedef enum {
 } hago_layout;
 
 /* flags */
-#define HAGO_STRICT_ACC16 1u /* refuse int16 accumulation unless the declared
-                                operand ranges prove it cannot overflow */
+#define HAGO_STRICT_ACC16 1u /* refuse 16-bit (and 24-bit) accumulation unless
+                                the declared operand ranges prove that it
+                                cannot overflow */
 #define HAGO_WS_WEIGHTS_READY 2u /* hago_qconv2d_ws only: the workspace still
                                 holds this layer's rewritten weights from an
                                 earlier call with the same w, geometry and
@@ -107,11 +116,17 @@ typedef struct {
  * with; the results differ, by one, exactly on negative ties).  The fastest
  * kernel variants implement the first rule; the second takes each operator's
  * more general variant.  ReLU / ReLU6 are expressed through clip_lo /
- * clip_hi in the output's quantized domain (Sec. 6.1). */
+ * clip_hi in the output's quantized domain (Sec. 6.1).
+ * multiplier == NULL selects the form for power-of-two scales (Sec. 5.1:
+ * thresholds rounded to powers of two "make it possible to use shifting to
+ * replace multiplication"): r is acc / 2^shift[c] rounded by the same tie
+ * rule, shift 0..31 (0: r = acc).  The standalone operator then runs a kernel
+ * without a multiplication; the fused epilogues use the identity
+ * acc / 2^s = acc * 2^30 / 2^(31 + s - 1). */
 typedef enum { HAGO_ROUND_UPWARD = 0, HAGO_ROUND_HALF_AWAY = 1 } hago_rounding;
 
 typedef struct {
-  const int32_t* multiplier; /* device, [channels] or [1]; Q31                  */
+  const int32_t* multiplier; /* device, [channels] or [1]; Q31; NULL: shift only */
   const int32_t* shift;      /* device, [channels] or [1]; 0..31                */
   int32_t per_channel;       /* 0: entry 0 serves every channel; 1: one each    */
   hago_qtype out;            /* dtype HAGO_I8 or HAGO_U8; bits; zero_point      */
@@ -139,19 +154,24 @@ hago_status hago_simquant(const float* x, float* y, int64_t outer,
                           void* stream);
 
 /*
- * Quantized dense (Introduction: u8 x i8 -> i32 and i8 x i8 -> i16 operand
- * triples; Sec. 6.2: dense on the fast integer instruction):
+ * Quantized dense (Introduction: u8 x i8 -> i32, i8 x i8 -> i16 and
+ * i16 x i16 -> i32 operand triples; Sec. 6.2: dense on the fast integer
+ * instruction):
  *     acc[m,n] = bias[n] + sum_k (a[m,k] - a_t.zero_point) * w[n,k]
- * reduced modulo 2^32 (acc_dtype HAGO_I32) or modulo 2^16 and sign-extended
- * (HAGO_I16, the int16-accumulation mode of Sec. 8.4).  With rq != NULL (host
+ * reduced modulo 2^32 (acc_dtype HAGO_I32), modulo 2^16 and sign-extended
+ * (HAGO_I16, the int16-accumulation mode of Sec. 8.4) or modulo 2^24 and
+ * sign-extended (HAGO_I24, Sec. 4.1; raw results are int32).  With rq != NULL (host
  * pointer to the struct) each accumulator is requantized with channel = n and
  * out is [M,N] of rq->out.dtype; with rq == NULL the raw accumulators are
  * stored as [M,N] int32 / int16.
  * a: device [M,K], HAGO_U8 or HAGO_I8.  w: device [N,K] HAGO_I8, symmetric
  * (w_t.zero_point must be 0).  bias: device [N] int32 or NULL.
+ * Or both operands HAGO_I16 (int16 data, acc_dtype HAGO_I32 or HAGO_I24): there
+ * is no 16-bit matrix instruction, so this triple runs on the vector ALUs.
  * Errors: NULL, SHAPE (negative dims, > 2^31-1), DTYPE, BITS, PARAM,
- * ACC_BOUND (flags & HAGO_STRICT_ACC16 and acc_dtype I16 and
- * K * max|a - z_a| * max|w| over the declared bit ranges > 32767), DEVICE.
+ * ACC_BOUND (flags & HAGO_STRICT_ACC16 and acc_dtype I16 / I24 and
+ * K * max|a - z_a| * max|w| over the declared bit ranges > 2^15 - 1 /
+ * 2^23 - 1), DEVICE.
  * M == 0 or N == 0 is a no-op; K == 0 yields the bias.
  */
 hago_status hago_qdense(const void* a, hago_qtype a_t, const void* w,
@@ -170,7 +190,8 @@ hago_status hago_qdense(const void* a, hago_qtype a_t, const void* w,
  * OW.  groups must be 1, or equal C and O (depthwise).  Accumulator width,
  * requantize (channel = o) and raw output as for hago_qdense.
  * Errors as for hago_qdense; additionally SHAPE for any other `groups`, a
- * kernel larger than the padded image, stride < 1, pad < 0.
+ * kernel larger than the padded image, stride < 1, pad < 0; DTYPE for int16
+ * operands with groups != 1.
  * This entry point uses no scratch memory: depthwise, 1x1 and channel-last
  * 1x1 geometries have kernels that read the caller's tensors directly; every
  * other groups == 1 geometry runs a general kernel that gathers its operands
@@ -248,6 +269,26 @@ hago_status hago_qconv2d_static(const void* a, hago_qtype a_t, const void* w,
                                 int32_t pad_h, int32_t pad_w, int32_t groups,
                                 hago_dtype acc_dtype, const hago_requant* rq,
                                 void* out, uint32_t flags, void* stream);
+
+/*
+ * simulated_quantize with the overflow of the simulated integer type (Sec. 5.2
+ * "Model Simulation": besides the rounding and the saturation error there is
+ * "the overflow error, possible when the output of quantized operator is beyond
+ * the limit of output data type can represent").  As hago_simquant, but the
+ * code rint(x / s) + z is first reduced modulo 2^w into the range of q.dtype's
+ * container: w = 8 (HAGO_I8 two's complement, HAGO_U8 0..255), 16 (HAGO_I16),
+ * 24 (HAGO_I24) or 32 (HAGO_I32); then clipped to clip_lo..clip_hi (within
+ * q's effective bits and +-2^24) and dequantized.  With q the accumulator
+ * type of a quantized operator this reproduces, in the simulated graph, what
+ * hago_qdense / hago_qconv2d with that acc_dtype do to a sum that does not fit.
+ * A code of magnitude >= 4e18 or an infinite one reduces to 0; NaN stays NaN.
+ * Errors as for hago_simquant.
+ */
+hago_status hago_simquant_wrap(const float* x, float* y, int64_t outer,
+                               int64_t channels, int64_t inner,
+                               const float* scale, const int32_t* zero_point,
+                               int32_t per_channel, hago_qtype q,
+                               int32_t clip_lo, int32_t clip_hi, void* stream);
 
 /*
  * Batched candidate evaluation of simulated_quantize (Sec. 6.3 "Batched GPU

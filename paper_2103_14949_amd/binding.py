@@ -9,7 +9,7 @@ from __future__ import annotations
 import ctypes as C
 import os
 
-U8, I8, I16, I32, F32 = 0, 1, 2, 3, 4
+U8, I8, I16, I32, F32, I24 = 0, 1, 2, 3, 4, 5   # I24: accumulator / simulated type only
 NCHW, NHWC = 0, 1
 STRICT_ACC16 = 1
 WS_WEIGHTS_READY = 2
@@ -20,7 +20,7 @@ ROUND_UPWARD, ROUND_HALF_AWAY = 0, 1   # hago_rounding
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libhago.so")
 
-EXPORTS = ("hago_simquant", "hago_simquant_batched", "hago_absmax", "hago_quantize", "hago_dequantize", "hago_simquant_codes", "hago_qdense", "hago_qconv2d", "hago_qconv2d_ws", "hago_qconv2d_workspace_bytes", "hago_qconv2d_static", "hago_requantize",
+EXPORTS = ("hago_simquant", "hago_simquant_batched", "hago_absmax", "hago_simquant_wrap", "hago_quantize", "hago_dequantize", "hago_simquant_codes", "hago_qdense", "hago_qconv2d", "hago_qconv2d_ws", "hago_qconv2d_workspace_bytes", "hago_qconv2d_static", "hago_requantize",
            "hago_status_string", "hago_bit_range", "hago_set_test_hook")
 
 
@@ -61,6 +61,8 @@ def lib():
         L.hago_status_string.argtypes = [i32]
         L.hago_simquant.restype = i32
         L.hago_simquant.argtypes = [vp, vp, i64, i64, i64, vp, vp, i32, _QType, i32, i32, vp]
+        L.hago_simquant_wrap.restype = i32
+        L.hago_simquant_wrap.argtypes = L.hago_simquant.argtypes
         L.hago_simquant_batched.restype = i32
         L.hago_simquant_batched.argtypes = [vp, vp, i64, i64, i64, i32, vp, vp, i32, _QType, vp, vp, vp]
         L.hago_quantize.restype = i32
@@ -118,7 +120,7 @@ class QType:
 
     def __init__(self, dtype, bits=None, is_signed=None, zero_point=0):
         self.dtype = dtype
-        self.bits = {U8: 8, I8: 8, I16: 16, I32: 32}.get(dtype, 0) if bits is None else bits
+        self.bits = {U8: 8, I8: 8, I16: 16, I32: 32, I24: 24}.get(dtype, 0) if bits is None else bits
         self.is_signed = (dtype != U8) if is_signed is None else bool(is_signed)
         self.zero_point = int(zero_point)
 
@@ -127,7 +129,8 @@ class QType:
 
 
 class Requant:
-    """Requantize parameters; multiplier/shift are int32 device tensors."""
+    """Requantize parameters; multiplier/shift are int32 device tensors (multiplier None: the
+    shift-only form for power-of-two scales)."""
 
     def __init__(self, multiplier, shift, out: QType, clip_lo=None, clip_hi=None, per_channel=None,
                  rounding=0):
@@ -137,11 +140,11 @@ class Requant:
         lo, hi = bit_range(out.bits, out.is_signed)
         self.clip_lo = lo if clip_lo is None else int(clip_lo)
         self.clip_hi = hi if clip_hi is None else int(clip_hi)
-        self.per_channel = int(multiplier.numel() > 1) if per_channel is None else int(per_channel)
+        self.per_channel = int(shift.numel() > 1) if per_channel is None else int(per_channel)
         self.rounding = int(rounding)   # ROUND_UPWARD or ROUND_HALF_AWAY
 
     def c(self):
-        return _Requant(self.multiplier.data_ptr(), self.shift.data_ptr(), self.per_channel,
+        return _Requant(None if self.multiplier is None else self.multiplier.data_ptr(), self.shift.data_ptr(), self.per_channel,
                         self.out.c(), self.clip_lo, self.clip_hi, self.rounding)
 
 
@@ -156,7 +159,7 @@ def _stream():
 
 def _tdtype(code):
     t = _torch()
-    return {U8: t.uint8, I8: t.int8, I16: t.int16, I32: t.int32, F32: t.float32}[code]
+    return {U8: t.uint8, I8: t.int8, I16: t.int16, I32: t.int32, F32: t.float32, I24: t.int32}[code]
 
 
 def _code(tensor):
@@ -199,6 +202,24 @@ def simquant(x, scale, zero_point, q: QType, clip_lo=None, clip_hi=None, per_cha
     if prepare:
         return Prepared(lib().hago_simquant, args, (x, y, scale, zero_point), y)
     _check(lib().hago_simquant(*args))
+    return y
+
+
+def simquant_wrap(x, scale, zero_point, q: QType, clip_lo=None, clip_hi=None, per_channel=None, out=None,
+                  prepare=False):
+    """hago_simquant_wrap over x[outer, channels, inner]: simulated quantize with the overflow of q's container."""
+    assert x.dim() == 3 and x.is_contiguous()
+    outer, channels, inner = x.shape
+    lo, hi = bit_range(min(q.bits, 25), q.is_signed)
+    clip_lo = lo if clip_lo is None else clip_lo
+    clip_hi = hi if clip_hi is None else clip_hi
+    pc = int(scale.numel() > 1) if per_channel is None else int(per_channel)
+    y = _torch().empty_like(x) if out is None else out
+    args = (_ptr(x), _ptr(y), outer, channels, inner, _ptr(scale), _ptr(zero_point), pc, q.c(),
+            int(clip_lo), int(clip_hi), _stream())
+    if prepare:
+        return Prepared(lib().hago_simquant_wrap, args, (x, y, scale, zero_point), y)
+    _check(lib().hago_simquant_wrap(*args))
     return y
 
 

@@ -55,7 +55,7 @@ hago_status check_qtype(const hago_qtype& q, bool zero_point_in_container) {
 }
 
 hago_status check_requant(const hago_requant* rq, RequantArgs* out) {
-  if (!rq->multiplier || !rq->shift) return HAGO_ERR_NULL;
+  if (!rq->shift) return HAGO_ERR_NULL;  // (no multiplier array: power-of-two scales, shift only)
   if (rq->out.dtype != HAGO_I8 && rq->out.dtype != HAGO_U8) return HAGO_ERR_DTYPE;
   if (rq->per_channel != 0 && rq->per_channel != 1) return HAGO_ERR_PARAM;
   if (rq->rounding != HAGO_ROUND_UPWARD && rq->rounding != HAGO_ROUND_HALF_AWAY) return HAGO_ERR_PARAM;
@@ -82,10 +82,13 @@ hago_status check_operands(const void* a, const hago_qtype& a_t, const void* w,
                            bool w_empty, bool out_empty, GemmArgs* g) {
   // an empty tensor may come with a NULL pointer
   if ((!a && !a_empty) || (!w && !w_empty) || (!out && !out_empty)) return HAGO_ERR_NULL;
-  if (a_t.dtype != HAGO_U8 && a_t.dtype != HAGO_I8) return HAGO_ERR_DTYPE;
-  if (w_t.dtype != HAGO_I8) return HAGO_ERR_DTYPE;
+  // operand triples (Introduction; Sec. 4.1): (u8 | i8) x i8 with 32-, 24- or 16-bit accumulation,
+  // or i16 x i16 with 32- or 24-bit accumulation
+  const bool op16 = a_t.dtype == HAGO_I16 && w_t.dtype == HAGO_I16;
+  if (!op16 && ((a_t.dtype != HAGO_U8 && a_t.dtype != HAGO_I8) || w_t.dtype != HAGO_I8)) return HAGO_ERR_DTYPE;
+  if (op16 && acc_dtype == HAGO_I16) return HAGO_ERR_DTYPE;
   if (w_t.zero_point != 0) return HAGO_ERR_DTYPE;  // weights are symmetric
-  if (acc_dtype != HAGO_I32 && acc_dtype != HAGO_I16) return HAGO_ERR_DTYPE;
+  if (acc_dtype != HAGO_I32 && acc_dtype != HAGO_I16 && acc_dtype != HAGO_I24) return HAGO_ERR_DTYPE;
   if (flags & ~HAGO_STRICT_ACC16) return HAGO_ERR_PARAM;
   hago_status s = check_qtype(a_t, true);
   if (s != HAGO_OK) return s;
@@ -98,7 +101,8 @@ hago_status check_operands(const void* a, const hago_qtype& a_t, const void* w,
     if (s != HAGO_OK) return s;
     g->has_rq = 1;
   }
-  if ((flags & HAGO_STRICT_ACC16) && acc_dtype == HAGO_I16) {
+  if ((flags & HAGO_STRICT_ACC16) && acc_dtype != HAGO_I32) {
+    const int64_t acc_max = acc_dtype == HAGO_I16 ? 32767 : 8388607;  // 2^15 - 1, 2^23 - 1
     // Worst case of |sum_k (a - z_a) w| over the declared ranges (Sec. 5.3:
     // effective bits are what keeps a 16-bit accumulator from overflowing).
     int64_t alo, ahi, wlo, whi;
@@ -108,16 +112,19 @@ hago_status check_operands(const void* a, const hago_qtype& a_t, const void* w,
                                                                        : a_t.zero_point - alo;
     const int64_t wmax = (whi > -wlo) ? whi : -wlo;
     if (amax > 0 && wmax > 0 && K > 0) {
-      if (amax > 32767 || wmax > 32767 || K > 32767 || K * amax * wmax > 32767)
+      if (amax > acc_max || wmax > acc_max || K > acc_max || amax * wmax > acc_max ||
+          K > acc_max / (amax * wmax))
         return HAGO_ERR_ACC_BOUND;
     }
   }
   g->act = a;
   g->wgt = static_cast<const int8_t*>(w);
   g->out = const_cast<void*>(out);
+  g->operand16 = op16;
   g->act_unsigned = a_t.dtype == HAGO_U8;
   g->act_zero_point = a_t.zero_point;
   g->acc16 = acc_dtype == HAGO_I16;
+  g->acc_wrap_shift = acc_dtype == HAGO_I16 ? 16 : (acc_dtype == HAGO_I24 ? 8 : 0);
   return HAGO_OK;
 }
 
@@ -163,6 +170,37 @@ hago_status hago_simquant(const float* x, float* y, int64_t outer, int64_t chann
   return from_hip(hago::launch_simquant(x, y, outer, channels, inner, scale, zero_point,
                                         per_channel, clip_lo, clip_hi,
                                         static_cast<hipStream_t>(stream)));
+}
+
+hago_status hago_simquant_wrap(const float* x, float* y, int64_t outer, int64_t channels, int64_t inner,
+                               const float* scale, const int32_t* zero_point, int32_t per_channel,
+                               hago_qtype q, int32_t clip_lo, int32_t clip_hi, void* stream) {
+  if (outer < 0 || channels < 0 || inner < 0) return HAGO_ERR_SHAPE;
+  const bool empty = outer == 0 || channels == 0 || inner == 0;
+  if (((!x || !y) && !empty) || !scale || !zero_point) return HAGO_ERR_NULL;
+  if (per_channel != 0 && per_channel != 1) return HAGO_ERR_PARAM;
+  // the simulated type: its container decides the width and signedness of the overflow
+  int wrap_bits = 0;
+  switch (q.dtype) {
+    case HAGO_U8: case HAGO_I8: wrap_bits = 8; break;
+    case HAGO_I16: wrap_bits = 16; break;
+    case HAGO_I24: wrap_bits = 24; break;
+    case HAGO_I32: wrap_bits = 32; break;
+    default: return HAGO_ERR_DTYPE;
+  }
+  if (q.bits < 1 || q.bits > wrap_bits) return HAGO_ERR_BITS;
+  if (q.dtype == HAGO_U8 && q.is_signed) return HAGO_ERR_BITS;
+  int64_t blo, bhi;
+  bit_range(q.bits, q.is_signed != 0, &blo, &bhi);
+  if (q.dtype != HAGO_U8 && !q.is_signed && bhi >= ((int64_t)1 << (wrap_bits - 1))) return HAGO_ERR_BITS;
+  if (clip_lo > clip_hi || clip_lo < blo || clip_hi > bhi) return HAGO_ERR_BITS;
+  if (clip_lo < -(1 << 24) || clip_hi > (1 << 24)) return HAGO_ERR_BITS;
+  if (!empty) {
+    if (outer > INT64_MAX / channels || outer * channels > INT64_MAX / inner) return HAGO_ERR_SHAPE;
+  }
+  return from_hip(hago::launch_simquant_wrap(x, y, outer, channels, inner, scale, zero_point, per_channel,
+                                             wrap_bits, q.dtype != HAGO_U8, clip_lo, clip_hi,
+                                             static_cast<hipStream_t>(stream)));
 }
 
 hago_status hago_simquant_batched(const float* x, float* y, int64_t outer, int64_t channels,
@@ -380,6 +418,7 @@ hago_status qconv2d_impl(const void* a, hago_qtype a_t, const void* w, hago_qtyp
   g.N = (int32_t)O;
   g.K = (int32_t)Kred;
   hipStream_t st = static_cast<hipStream_t>(stream);
+  if (depthwise && g.operand16) return HAGO_ERR_DTYPE;  // int16 operands: groups == 1 only
   if (depthwise) return from_hip(hago::launch_qconv_depthwise(g, cg, st));
   void* ws = nullptr;
   if (mode == Scratch::kCaller) {

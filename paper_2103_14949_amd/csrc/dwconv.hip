@@ -42,6 +42,7 @@ struct DwArgs {
   int32_t act_off;     // 128 for uint8, 0 for int8
   int32_t z_a;
   int32_t acc16;
+  int32_t acc_wrap_shift;  // 32 - accumulator bits (0, 16 or 8); the register kernels know 0 and 16 only
   int32_t has_rq;
   int32_t out_mode;    // 0: requantized 8-bit, 1: raw int32, 2: raw int16
   const int32_t* mult;
@@ -50,8 +51,8 @@ struct DwArgs {
   RequantScalars rs;
 };
 
-__device__ __forceinline__ int32_t wrap_acc(int32_t acc, int acc16) {
-  return acc16 ? (int32_t)(int16_t)acc : acc;
+__device__ __forceinline__ int32_t wrap_acc(int32_t acc, int wrap_shift) {
+  return wrap_shift ? wrap_acc_bits(acc, wrap_shift) : acc;
 }
 
 __device__ __forceinline__ void store_one(const DwArgs& p, int64_t idx, int32_t acc, int32_t m,
@@ -95,9 +96,9 @@ __global__ __launch_bounds__(kThreads) void dw_direct_kernel(DwArgs p) {
         acc += av * (int32_t)p.wgt[wi];
       }
     }
-    acc = wrap_acc(acc, p.acc16);
+    acc = wrap_acc(acc, p.acc_wrap_shift);
     const int pc = p.per_channel ? c : 0;
-    store_one(p, i, acc, p.has_rq ? p.mult[pc] : 0, p.has_rq ? p.shift[pc] : 0);
+    store_one(p, i, acc, p.has_rq ? rq_mult(p.mult, pc) : 0, p.has_rq ? rq_shift(p.mult, p.shift, pc) : 0);
   }
 }
 
@@ -155,8 +156,8 @@ __global__ __launch_bounds__(kThreads) void dw_plane3x3_kernel(DwArgs p, int32_t
   // sum (a - z) w = sum (a' + off - z) w = sum a' w + (off - z) * sum w, a' = staged byte
   const int32_t corr = (p.bias ? p.bias[c] : 0) + (p.act_off - p.z_a) * wsum;
   const int pc = p.per_channel ? c : 0;
-  const int32_t m = p.has_rq ? p.mult[pc] : 0;
-  const int32_t sh = p.has_rq ? p.shift[pc] : 0;
+  const int32_t m = p.has_rq ? rq_mult(p.mult, pc) : 0;
+  const int32_t sh = p.has_rq ? rq_shift(p.mult, p.shift, pc) : 0;
   __syncthreads();
 
   const int gx = (W + 3) >> 2;  // groups of 4 outputs per row
@@ -179,7 +180,7 @@ __global__ __launch_bounds__(kThreads) void dw_plane3x3_kernel(DwArgs p, int32_t
       acc[3] = __builtin_amdgcn_sdot4((int)w3, (int)wrow[ky], acc[3], false);
     }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) acc[i] = wrap_acc(acc[i], p.acc16);
+    for (int i = 0; i < 4; ++i) acc[i] = wrap_acc(acc[i], p.acc_wrap_shift);
     const int x0 = q << 2;
     const int64_t o = obase + (int64_t)(y0 + ry) * W + x0;
     if (vec_io) {
@@ -205,7 +206,7 @@ __global__ __launch_bounds__(kThreads) void dw_plane3x3_kernel(DwArgs p, int32_t
 // r = floor((a * m + 2^(30+sh)) / 2^(31+sh)); sh is wavefront-uniform here.
 __device__ __forceinline__ int32_t dw_mul_shift(int32_t a, int32_t m, int64_t rnd, int32_t sh) {
   const int64_t pr = (int64_t)a * (int64_t)m + rnd;
-  return sh >= 1 ? ((int32_t)(pr >> 32) >> (sh - 1)) : (int32_t)(pr >> 31);
+  return sh >= 1 ? ((int32_t)(pr >> 32) >> (sh - 1)) : (int32_t)(pr >> (31 + sh));
 }
 
 // NCHW 3x3 stride 1 pad 1, W <= 64.  Dynamic LDS: 4 planes x (H + 2) * rs bytes,
@@ -277,8 +278,8 @@ __global__ __launch_bounds__(kThreads) void dw_wave3x3_kernel(DwArgs p, int32_t 
   }
   const int32_t corr = (p.bias ? p.bias[c] : 0) + (p.act_off - p.z_a) * wsum;
   const int pc = p.per_channel ? c : 0;
-  const int32_t m = p.has_rq ? p.mult[pc] : 0;
-  const int32_t sh = p.has_rq ? p.shift[pc] : 0;
+  const int32_t m = p.has_rq ? rq_mult(p.mult, pc) : 0;
+  const int32_t sh = p.has_rq ? rq_shift(p.mult, p.shift, pc) : 0;
   const int64_t rnd = (int64_t)1 << (30 + sh);
   const int32_t lo = p.rs.lo_rel, hi = p.rs.hi_rel, z = p.rs.z_out;
 
@@ -311,7 +312,7 @@ __global__ __launch_bounds__(kThreads) void dw_wave3x3_kernel(DwArgs p, int32_t 
       int32_t a = __builtin_amdgcn_sdot4((int)wa[i], (int)wrow[0], corr, false);
       a = __builtin_amdgcn_sdot4((int)wb[i], (int)wrow[1], a, false);
       a = __builtin_amdgcn_sdot4((int)wcur[i], (int)wrow[2], a, false);
-      acc[i] = wrap_acc(a, p.acc16);
+      acc[i] = wrap_acc(a, p.acc_wrap_shift);
       wa[i] = wb[i];
       wb[i] = wcur[i];
     }
@@ -437,7 +438,7 @@ __global__ __launch_bounds__(kThreads) void dw_rows3x3_kernel(DwArgs p, int32_t 
   const int pc = p.per_channel ? c : 0;
   const uint32_t* wp = reinterpret_cast<const uint32_t*>(p.wgt + (wb & ~3u));
   const uint32_t* bp = p.bias ? reinterpret_cast<const uint32_t*>(p.bias + c) : wp;
-  const uint32_t* mp = MODE == 0 ? reinterpret_cast<const uint32_t*>(p.mult + pc) : wp;
+  const uint32_t* mp = (MODE == 0 && p.mult) ? reinterpret_cast<const uint32_t*>(p.mult + pc) : wp;
   const uint32_t* sp = MODE == 0 ? reinterpret_cast<const uint32_t*>(p.shift + pc) : wp;
   uint64_t d01;
   uint32_t d2, bias_raw, m_raw, sh_raw;
@@ -465,8 +466,9 @@ __global__ __launch_bounds__(kThreads) void dw_rows3x3_kernel(DwArgs p, int32_t 
 #pragma unroll
     for (int kx = 0; kx < 3; ++kx) wsum += (int32_t)(int8_t)(wrow[ky] >> (8 * kx));
   const int32_t bias = p.bias ? (int32_t)bias_raw : 0;
-  const int32_t m = MODE == 0 ? (int32_t)m_raw : 0;
-  const int32_t sh = MODE == 0 ? (int32_t)sh_raw : 0;
+  // (no multiplier array: power-of-two scales, i.e. multiplier one half and the shift one less)
+  const int32_t m = MODE == 0 ? (p.mult ? (int32_t)m_raw : (1 << 30)) : 0;
+  const int32_t sh = MODE == 0 ? (int32_t)sh_raw - (p.mult ? 0 : 1) : 0;
   // sum (a - z) w = sum (a' + off - z) w = sum a' w + (off - z) * sum w, a' = flipped byte
   const int32_t corr = bias + (p.act_off - p.z_a) * wsum;
   const int64_t rnd = (int64_t)1 << (30 + sh);
@@ -642,7 +644,7 @@ __global__ __launch_bounds__(kThreads) void dw_rows3x3s2_kernel(DwArgs p, int32_
   const int pc = p.per_channel ? c : 0;
   const uint32_t* wp = reinterpret_cast<const uint32_t*>(p.wgt + (wb & ~3u));
   const uint32_t* bp = p.bias ? reinterpret_cast<const uint32_t*>(p.bias + c) : wp;
-  const uint32_t* mp = MODE == 0 ? reinterpret_cast<const uint32_t*>(p.mult + pc) : wp;
+  const uint32_t* mp = (MODE == 0 && p.mult) ? reinterpret_cast<const uint32_t*>(p.mult + pc) : wp;
   const uint32_t* sp = MODE == 0 ? reinterpret_cast<const uint32_t*>(p.shift + pc) : wp;
   uint64_t d01;
   uint32_t d2, bias_raw, m_raw, sh_raw;
@@ -670,8 +672,9 @@ __global__ __launch_bounds__(kThreads) void dw_rows3x3s2_kernel(DwArgs p, int32_
 #pragma unroll
     for (int kx = 0; kx < 3; ++kx) wsum += (int32_t)(int8_t)(wrow[ky] >> (8 * kx));
   const int32_t bias = p.bias ? (int32_t)bias_raw : 0;
-  const int32_t m = MODE == 0 ? (int32_t)m_raw : 0;
-  const int32_t sh = MODE == 0 ? (int32_t)sh_raw : 0;
+  // (no multiplier array: power-of-two scales, i.e. multiplier one half and the shift one less)
+  const int32_t m = MODE == 0 ? (p.mult ? (int32_t)m_raw : (1 << 30)) : 0;
+  const int32_t sh = MODE == 0 ? (int32_t)sh_raw - (p.mult ? 0 : 1) : 0;
   const int32_t corr = bias + (p.act_off - p.z_a) * wsum;
   const int64_t rnd = (int64_t)1 << (30 + sh);
   const int32_t z = p.rs.z_out;
@@ -833,8 +836,8 @@ __global__ __launch_bounds__(kThreads) void dw_small3x3_kernel(DwArgs p, int32_t
   }
   const int32_t bias = p.bias ? p.bias[c] : 0;
   const int pc = p.per_channel ? c : 0;
-  const int32_t m = MODE == 0 ? p.mult[pc] : 0;
-  const int32_t sh = MODE == 0 ? p.shift[pc] : 0;
+  const int32_t m = MODE == 0 ? rq_mult(p.mult, pc) : 0;
+  const int32_t sh = MODE == 0 ? rq_shift(p.mult, p.shift, pc) : 0;
   const int32_t corr = bias + (p.act_off - p.z_a) * wsum;
   const int64_t rnd = (int64_t)1 << (30 + sh);
   const int32_t z = p.rs.z_out;
@@ -956,8 +959,8 @@ __global__ __launch_bounds__(kThreads) void dw_nhwc3x3_kernel(DwArgs p, int32_t 
   for (int j = 0; j < 4; ++j) {
     const int pc = p.per_channel ? c + j : 0;
     corr[j] = (p.bias ? p.bias[c + j] : 0) + (p.act_off - p.z_a) * wsum[j];
-    m[j] = MODE == 0 ? p.mult[pc] : 0;
-    sh[j] = MODE == 0 ? p.shift[pc] : 0;
+    m[j] = MODE == 0 ? rq_mult(p.mult, pc) : 0;
+    sh[j] = MODE == 0 ? rq_shift(p.mult, p.shift, pc) : 0;
   }
   const int32_t away = p.rs.half_away ? -1 : 0;
 
@@ -1027,6 +1030,7 @@ hipError_t launch_qconv_depthwise(const GemmArgs& a, const ConvGeom& cg, hipStre
   p.act_off = a.act_unsigned ? 128 : 0;
   p.z_a = a.act_zero_point;
   p.acc16 = a.acc16;
+  p.acc_wrap_shift = a.acc_wrap_shift;
   p.has_rq = a.has_rq;
   p.out_mode = a.has_rq ? 0 : (a.acc16 ? 2 : 1);
   p.mult = a.rq.multiplier;
@@ -1058,8 +1062,11 @@ hipError_t launch_qconv_depthwise(const GemmArgs& a, const ConvGeom& cg, hipStre
                      cg.pad_h == 1 && cg.pad_w == 1;
   const int32_t rpc2 = (cg.OH + 3) / 4 < 16 ? (cg.OH + 3) / 4 : 16;
   const int64_t nband2 = (cg.OH + 4 * rpc2 - 1) / (4 * rpc2);
+  // (the register kernels are compiled for 32- and 16-bit accumulators; 24-bit ones take the
+  // kernels that wrap by a run-time width)
+  const bool regs_ok = a.acc_wrap_shift == 0 || a.acc_wrap_shift == 16;
   // channel-last 3x3 stride 1 pad 1
-  if (cg.nhwc && cg.KH == 3 && cg.KW == 3 && cg.stride_h == 1 && cg.stride_w == 1 && cg.pad_h == 1 &&
+  if (regs_ok && cg.nhwc && cg.KH == 3 && cg.KW == 3 && cg.stride_h == 1 && cg.stride_w == 1 && cg.pad_h == 1 &&
       cg.pad_w == 1 && cg.C % 4 == 0 && (reinterpret_cast<uintptr_t>(a.act) & 3u) == 0 &&
       (reinterpret_cast<uintptr_t>(a.wgt) & 3u) == 0 && (reinterpret_cast<uintptr_t>(a.out) & (4 * esz - 1)) == 0 &&
       (int64_t)cg.B * cg.C * cg.H * cg.W < (1ll << 31)) {
@@ -1075,7 +1082,7 @@ hipError_t launch_qconv_depthwise(const GemmArgs& a, const ConvGeom& cg, hipStre
     }
   }
   // small planes: several planes share the 16 lanes of a DPP row
-  if (plane_ok && cg.W <= 16 && cg.H <= 64 && total * (int64_t)esz < (1ll << 31) &&
+  if (regs_ok && plane_ok && cg.W <= 16 && cg.H <= 64 && total * (int64_t)esz < (1ll << 31) &&
       (int64_t)cg.B * cg.C * cg.H * cg.W < (1ll << 31) &&
       (reinterpret_cast<uintptr_t>(a.act) & 3u) == 0 && (reinterpret_cast<uintptr_t>(a.out) & 3u) == 0) {
     const int32_t nstrips = (cg.W + 3) / 4, pp = 16 / nstrips;
@@ -1091,7 +1098,7 @@ hipError_t launch_qconv_depthwise(const GemmArgs& a, const ConvGeom& cg, hipStre
     }
   }
   const int32_t nsegs = (cg.W + 63) / 64;  // column segments of the register kernels
-  if (s2_ok && cg.W % 4 == 0 && (reinterpret_cast<uintptr_t>(a.act) & 3u) == 0 &&
+  if (regs_ok && s2_ok && cg.W % 4 == 0 && (reinterpret_cast<uintptr_t>(a.act) & 3u) == 0 &&
       (reinterpret_cast<uintptr_t>(a.out) & 7u) == 0 && (reinterpret_cast<uintptr_t>(a.wgt) & 3u) == 0 &&
       cg.B <= 65535 && nband2 * nsegs <= 65535 && (int64_t)cg.H * cg.W * 4 < (1ll << 31) &&
       (int64_t)cg.C * 9 < (1ll << 30)) {
@@ -1105,7 +1112,7 @@ hipError_t launch_qconv_depthwise(const GemmArgs& a, const ConvGeom& cg, hipStre
                        dim3(kThreads), 0, st, p, rpc2, nsegs);
     return hipGetLastError();
   }
-  if (plane_ok && vec_io && (reinterpret_cast<uintptr_t>(a.wgt) & 3u) == 0 &&
+  if (regs_ok && plane_ok && vec_io && (reinterpret_cast<uintptr_t>(a.wgt) & 3u) == 0 &&
       cg.B <= 65535 && nband_r * nsegs <= 65535 && (int64_t)cg.H * cg.W * 4 < (1ll << 31) &&
       (int64_t)cg.C * 9 < (1ll << 30)) {
     auto kern = nsegs > 1 ? (p.out_mode == 1 ? dw_rows3x3_kernel<1, false, true>

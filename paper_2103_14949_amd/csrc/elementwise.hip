@@ -44,14 +44,43 @@ __device__ __forceinline__ float simquant_one(float x, float s, float zf, float 
   return (v - zf) * s;
 }
 
+// The same with the overflow of the simulated integer type (Sec. 5.2 of the paper: the third error
+// source): the code is reduced modulo 2^wrap_bits before the clip, into the two's-complement range
+// (wrap_signed) or into 0 .. 2^wrap_bits - 1.  A code of magnitude 4e18 or more, or an infinite one,
+// reduces to 0 (every binary32 number that large is a multiple of 2^32); NaN stays NaN.
+__device__ __forceinline__ float simquant_wrap_one(float x, float s, float zf, float lo, float hi,
+                                                   int wrap_bits, int wrap_signed) {
+  const float t = x / s;
+  const float u = rintf(t);
+  float v = u + zf;
+  if (v == v) {
+    long long code = 0;
+    if (v > -4.0e18f && v < 4.0e18f) {
+      code = (long long)v;  // v holds an integer below 2^62
+      const int sh = 64 - wrap_bits;
+      const unsigned long long low = (unsigned long long)code << sh;
+      code = wrap_signed ? ((long long)low >> sh) : (long long)(low >> sh);
+    }
+    v = (float)code;  // exact up to 25 bits, round to nearest beyond
+  }
+  v = (v < lo) ? lo : ((v > hi) ? hi : v);
+  return (v - zf) * s;
+}
+
 // U: 128-bit vectors per lane and job; all of a job's loads are issued before the first
 // result is computed.  Loads and stores carry the nontemporal hint: the tensors are streamed
 // once, and without the hint the copy rate of this chip is about 10 % lower.
-template <int U>
+// WRAP: the overflow-simulating form (wrap_bits, wrap_signed).
+template <int U, bool WRAP = false>
 __global__ __launch_bounds__(kThreads) void simquant_rows_kernel(
     const v4f* __restrict__ x, v4f* __restrict__ y, int64_t rows, int32_t channels,
     int64_t inner_vec, int32_t nseg, int32_t seg_len, const float* __restrict__ scale,
-    const int32_t* __restrict__ zp, int per_channel, float lo, float hi) {
+    const int32_t* __restrict__ zp, int per_channel, float lo, float hi, int wrap_bits = 0,
+    int wrap_signed = 0) {
+  auto one = [&](float v, float s, float zf) {
+    if constexpr (WRAP) return simquant_wrap_one(v, s, zf, lo, hi, wrap_bits, wrap_signed);
+    else return simquant_one(v, s, zf, lo, hi);
+  };
   for (int64_t job = blockIdx.x; job < rows * nseg; job += gridDim.x) {
     int64_t row;
     int32_t c;
@@ -79,10 +108,10 @@ __global__ __launch_bounds__(kThreads) void simquant_rows_kernel(
       for (int u = 0; u < U; ++u) {
         if (vb + u * kThreads < v1) {
           v4f r;
-          r.x = simquant_one(a[u].x, s, zf, lo, hi);
-          r.y = simquant_one(a[u].y, s, zf, lo, hi);
-          r.z = simquant_one(a[u].z, s, zf, lo, hi);
-          r.w = simquant_one(a[u].w, s, zf, lo, hi);
+          r.x = one(a[u].x, s, zf);
+          r.y = one(a[u].y, s, zf);
+          r.z = one(a[u].z, s, zf);
+          r.w = one(a[u].w, s, zf);
           __builtin_nontemporal_store(r, yr + vb + u * kThreads);
         }
       }
@@ -153,14 +182,16 @@ __global__ __launch_bounds__(kThreads) void simquant_batched_flat_kernel(
   }
 }
 
+template <bool WRAP = false>
 __global__ __launch_bounds__(kThreads) void simquant_flat_kernel(
     const float* __restrict__ x, float* __restrict__ y, int64_t total, int64_t inner,
     int64_t channels, const float* __restrict__ scale, const int32_t* __restrict__ zp,
-    int per_channel, float lo, float hi) {
+    int per_channel, float lo, float hi, int wrap_bits = 0, int wrap_signed = 0) {
   const int64_t stride = (int64_t)gridDim.x * kThreads;
   for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += stride) {
     const int64_t c = per_channel ? (i / inner) % channels : 0;
-    y[i] = simquant_one(x[i], scale[c], (float)zp[c], lo, hi);
+    if constexpr (WRAP) y[i] = simquant_wrap_one(x[i], scale[c], (float)zp[c], lo, hi, wrap_bits, wrap_signed);
+    else y[i] = simquant_one(x[i], scale[c], (float)zp[c], lo, hi);
   }
 }
 
@@ -178,7 +209,8 @@ __device__ __forceinline__ int32_t load_acc(const AccT* p, int64_t i) {
 
 // rows: 4 accumulators -> 4 output bytes per step, 128-bit loads for int32; U steps per lane
 // and job with all loads issued first, nontemporal as above.
-template <typename AccT, int U, bool AWAY>
+// POW2: no multiplier array (power-of-two scales): the rounding shift alone, no multiplication.
+template <typename AccT, int U, bool AWAY, bool POW2 = false>
 __global__ __launch_bounds__(kThreads) void requant_rows_kernel(
     const AccT* __restrict__ acc, uint32_t* __restrict__ out, int64_t rows, int32_t channels,
     int64_t inner_vec, int32_t nseg, int32_t seg_len, const int32_t* __restrict__ mult,
@@ -196,8 +228,12 @@ __global__ __launch_bounds__(kThreads) void requant_rows_kernel(
       c = per_channel ? (int32_t)(row % channels) : 0;
     }
     const int32_t seg = (int32_t)(job - row * nseg);
-    const int32_t m = mult[c];
-    const int32_t sh = shift[c];
+    const int32_t m = POW2 ? 0 : rq_mult(mult, c);
+    const int32_t sh = POW2 ? shift[c] : rq_shift(mult, shift, c);
+    auto one = [&](int32_t a) {
+      if constexpr (POW2) return med3(shift_round(a, sh), rs.lo_rel, rs.hi_rel) + rs.z_out;
+      else return requant_pick<AWAY>(a, m, sh, rs);
+    };
     const int64_t v0 = (int64_t)seg * seg_len;
     const int64_t v1 = (v0 + seg_len < inner_vec) ? v0 + seg_len : inner_vec;
     const VecT* ar = reinterpret_cast<const VecT*>(acc) + row * inner_vec;
@@ -210,8 +246,7 @@ __global__ __launch_bounds__(kThreads) void requant_rows_kernel(
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         if (vb + u * kThreads < v1) {
-          const uint32_t r = pack4(requant_pick<AWAY>((int32_t)q[u].x, m, sh, rs), requant_pick<AWAY>((int32_t)q[u].y, m, sh, rs),
-                                   requant_pick<AWAY>((int32_t)q[u].z, m, sh, rs), requant_pick<AWAY>((int32_t)q[u].w, m, sh, rs));
+          const uint32_t r = pack4(one((int32_t)q[u].x), one((int32_t)q[u].y), one((int32_t)q[u].z), one((int32_t)q[u].w));
           __builtin_nontemporal_store(r, orow + vb + u * kThreads);
         }
       }
@@ -251,7 +286,7 @@ __global__ __launch_bounds__(kThreads) void requant_flat_kernel(
   const int64_t stride = (int64_t)gridDim.x * kThreads;
   for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += stride) {
     const int64_t c = per_channel ? (i / inner) % channels : 0;
-    out[i] = (uint8_t)requant_pick<AWAY>(load_acc(acc, i), mult[c], shift[c], rs);
+    out[i] = (uint8_t)requant_pick<AWAY>(load_acc(acc, i), rq_mult(mult, c), rq_shift(mult, shift, c), rs);
   }
 }
 
@@ -480,14 +515,38 @@ hipError_t launch_simquant(const float* x, float* y, int64_t outer, int64_t chan
     const int64_t inner_vec = row_len / 4;
     int32_t nseg, seg_len;
     split_row(inner_vec, kVecPerLane, &nseg, &seg_len);
-    hipLaunchKernelGGL(simquant_rows_kernel<kVecPerLane>, dim3(grid_for(rows * nseg)), dim3(kThreads), 0, st,
+    hipLaunchKernelGGL((simquant_rows_kernel<kVecPerLane, false>), dim3(grid_for(rows * nseg)), dim3(kThreads), 0, st,
                        reinterpret_cast<const v4f*>(x), reinterpret_cast<v4f*>(y), rows,
                        (int32_t)(per_channel ? channels : 1), inner_vec, nseg, seg_len, scale, zp,
-                       per_channel, lo, hi);
+                       per_channel, lo, hi, 0, 0);
   } else {
-    hipLaunchKernelGGL(simquant_flat_kernel, dim3(grid_for((total + kThreads - 1) / kThreads)),
+    hipLaunchKernelGGL(simquant_flat_kernel<false>, dim3(grid_for((total + kThreads - 1) / kThreads)),
                        dim3(kThreads), 0, st, x, y, total, inner, channels, scale, zp, per_channel,
-                       lo, hi);
+                       lo, hi, 0, 0);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_simquant_wrap(const float* x, float* y, int64_t outer, int64_t channels, int64_t inner,
+                                const float* scale, const int32_t* zp, int per_channel, int32_t wrap_bits,
+                                int32_t wrap_signed, int32_t clip_lo, int32_t clip_hi, hipStream_t st) {
+  const int64_t total = outer * channels * inner;
+  if (total == 0) return hipSuccess;
+  const float lo = (float)clip_lo, hi = (float)clip_hi;
+  int64_t rows = per_channel ? outer * channels : 1;
+  int64_t row_len = per_channel ? inner : total;
+  if (row_len % 4 == 0 && row_len >= 512 && aligned16(x) && aligned16(y)) {
+    const int64_t inner_vec = row_len / 4;
+    int32_t nseg, seg_len;
+    split_row(inner_vec, kVecPerLane, &nseg, &seg_len);
+    hipLaunchKernelGGL((simquant_rows_kernel<kVecPerLane, true>), dim3(grid_for(rows * nseg)), dim3(kThreads), 0, st,
+                       reinterpret_cast<const v4f*>(x), reinterpret_cast<v4f*>(y), rows,
+                       (int32_t)(per_channel ? channels : 1), inner_vec, nseg, seg_len, scale, zp,
+                       per_channel, lo, hi, wrap_bits, wrap_signed);
+  } else {
+    hipLaunchKernelGGL(simquant_flat_kernel<true>, dim3(grid_for((total + kThreads - 1) / kThreads)),
+                       dim3(kThreads), 0, st, x, y, total, inner, channels, scale, zp, per_channel,
+                       lo, hi, wrap_bits, wrap_signed);
   }
   return hipGetLastError();
 }
@@ -631,11 +690,12 @@ static hipError_t launch_requantize_t(const AccT* acc, int64_t outer, int64_t ch
     int32_t nseg, seg_len;
     split_row(inner_vec, kVecPerLane, &nseg, &seg_len);
     auto kern = rq.half_away ? requant_rows_kernel<AccT, kVecPerLane, true>
-                             : requant_rows_kernel<AccT, kVecPerLane, false>;
+                : (rq.multiplier ? requant_rows_kernel<AccT, kVecPerLane, false>
+                                 : requant_rows_kernel<AccT, kVecPerLane, false, true>);
     hipLaunchKernelGGL(kern, dim3(grid_for(rows * nseg)), dim3(kThreads), 0, st,
                        acc, reinterpret_cast<uint32_t*>(out), rows, (int32_t)(pc ? channels : 1),
                        inner_vec, nseg, seg_len, rq.multiplier, rq.shift, pc, rs);
-  } else if (pc && inner == 1 && channels % 4 == 0 && io_aligned && aligned16(rq.multiplier) &&
+  } else if (pc && inner == 1 && channels % 4 == 0 && io_aligned && rq.multiplier && aligned16(rq.multiplier) &&
              aligned16(rq.shift)) {
     const int64_t total_vec = total / 4;
     auto kern = rq.half_away ? requant_lastaxis_kernel<AccT, true> : requant_lastaxis_kernel<AccT, false>;

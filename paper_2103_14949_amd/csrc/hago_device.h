@@ -25,6 +25,30 @@ __device__ __forceinline__ int32_t rounding_mul_shift(int32_t acc, int32_t mult,
   return (int32_t)(p >> (31 + sh));
 }
 
+// Power-of-two scales (Sec. 5.1 of the paper: shifting replaces the multiplication): the
+// multiplier array is absent and the requantize is round(acc / 2^s).  That is the general form
+// with multiplier 2^30 (one half) and shift s - 1; the 64-bit forms below accept the resulting
+// shift of -1 for s == 0 (rounding term 2^29, shift distance 30), the folded fast paths of the
+// kernels exclude it like they exclude shift 0.
+__device__ __forceinline__ int32_t rq_mult(const int32_t* mult, int64_t i) {
+  return mult ? mult[i] : (1 << 30);
+}
+__device__ __forceinline__ int32_t rq_shift(const int32_t* mult, const int32_t* shift, int64_t i) {
+  return shift[i] - (mult ? 0 : 1);
+}
+// The shift-only form itself, without a multiplication: floor(acc / 2^s + 1/2) is the floored
+// quotient plus the first bit shifted out (no rounding term is added, so nothing can wrap).
+__device__ __forceinline__ int32_t shift_round(int32_t acc, int32_t s) {
+  return s > 0 ? (acc >> s) + ((acc >> (s - 1)) & 1) : acc;
+}
+
+// Accumulators narrower than 32 bits (int16 accumulation; 24-bit accumulators): the 32-bit sum
+// reduced modulo 2^bits and sign-extended, which equals accumulating in that width all along
+// (the reduction is a ring homomorphism).  wrap_shift = 32 - bits, 0 for a full int32.
+__device__ __forceinline__ int32_t wrap_acc_bits(int32_t acc, int32_t wrap_shift) {
+  return (int32_t)((uint32_t)acc << wrap_shift) >> wrap_shift;
+}
+
 // median of three = clamp when lo <= hi; one instruction instead of two compare/select pairs
 __device__ __forceinline__ int32_t med3(int32_t x, int32_t lo, int32_t hi) {
   int32_t r;

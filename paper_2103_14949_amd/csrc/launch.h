@@ -21,6 +21,11 @@ hipError_t launch_simquant(const float* x, float* y, int64_t outer, int64_t chan
                            const float* scale, const int32_t* zp, int per_channel, int32_t clip_lo,
                            int32_t clip_hi, hipStream_t st);
 
+// simulated quantize with the overflow of a wrap_bits-wide integer type (signed: two's complement).
+hipError_t launch_simquant_wrap(const float* x, float* y, int64_t outer, int64_t channels, int64_t inner,
+                                const float* scale, const int32_t* zp, int per_channel, int32_t wrap_bits,
+                                int32_t wrap_signed, int32_t clip_lo, int32_t clip_hi, hipStream_t st);
+
 // nbatch (<= 16) candidate parameter sets over one tensor: y[nbatch][outer][channels][inner];
 // scale / zp: [nbatch][channels] (or [nbatch]); clip_lo / clip_hi: host arrays [nbatch].
 hipError_t launch_simquant_batched(const float* x, float* y, int64_t outer, int64_t channels,
@@ -54,13 +59,17 @@ struct GemmArgs {
   const int32_t* bias;
   void* out;
   int32_t M, N, K;
+  int32_t operand16;     // 1: both operands are int16 (act and wgt point to int16 data)
   int32_t act_unsigned;  // 1: uint8 container
   int32_t act_zero_point;
-  int32_t acc16;           // reduce accumulator modulo 2^16
+  int32_t acc16;           // reduce accumulator modulo 2^16 (raw results are int16)
+  int32_t acc_wrap_shift;  // 32 - accumulator bits: 0 (int32), 16 (int16) or 8 (24 bits, kept in an int32)
   int32_t has_rq;          // 0: store raw accumulators
   RequantArgs rq;
 };
 
+// int16 x int16 operands (dense, or a groups == 1 convolution when cg != nullptr) on the vector ALUs.
+hipError_t launch_qgemm16(const GemmArgs& g, const ConvGeom* cg, hipStream_t st);
 // C[M,N] = act[M,K] x wgt[N,K]^T on int8 MFMA; out row-major [M,N].
 hipError_t launch_qdense(const GemmArgs& g, hipStream_t st);
 

@@ -82,8 +82,8 @@ __global__ __launch_bounds__(256) void pw_nchw_kernel(PwArgs p) {
     if (n < N) {
       if (p.bias) bias_r[t] = p.bias[n];
       if (MODE == 0) {
-        mult_r[t] = p.mult[p.per_channel ? n : 0];
-        shift_r[t] = p.shift[p.per_channel ? n : 0];
+        mult_r[t] = rq_mult(p.mult, p.per_channel ? n : 0);
+        shift_r[t] = rq_shift(p.mult, p.shift, p.per_channel ? n : 0);
       }
     }
   }
@@ -222,8 +222,8 @@ __global__ __launch_bounds__(64) void pw_nchw_quad_kernel(PwArgs p) {
   if (n < N) {
     if (p.bias) bias_r = p.bias[n];
     if (MODE == 0) {
-      mult_r = p.mult[p.per_channel ? n : 0];
-      shift_r = p.shift[p.per_channel ? n : 0];
+      mult_r = rq_mult(p.mult, p.per_channel ? n : 0);
+      shift_r = rq_shift(p.mult, p.shift, p.per_channel ? n : 0);
     }
   }
 
@@ -379,6 +379,7 @@ bool try_qconv_pointwise_nchw(const GemmArgs& a, const ConvGeom& cg, hipStream_t
   const int64_t HW = (int64_t)cg.H * cg.W;
   const size_t esz = a.has_rq ? 1 : (a.acc16 ? 2 : 4);
   const bool quad = cg.O <= 32 || cg.C <= 64;  // the 128-pixel kernel (any O when C is small)
+  if (a.acc_wrap_shift != 0 && a.acc_wrap_shift != 16) return false;  // 24-bit accumulators: the general path
   if (a.has_rq && a.rq.half_away && !quad) return false;  // the wider kernel: ties toward +infinity only
   if (cg.nhwc || cg.KH != 1 || cg.KW != 1 || cg.stride_h != 1 || cg.stride_w != 1 || cg.pad_h != 0 ||
       cg.pad_w != 0 || (quad ? cg.C % 4 != 0 : cg.C % 16 != 0) || HW % 4 != 0 || (!quad && cg.O > 128) ||

@@ -499,6 +499,7 @@ void set_test_hook(int key, int value) {
 
 hipError_t launch_qdense(const GemmArgs& a, hipStream_t st) {
   if (a.M == 0 || a.N == 0) return hipSuccess;
+  if (a.operand16) return launch_qgemm16(a, nullptr, st);
   QgemmParams p = make_qgemm_params(a, nullptr);
   p.vec_k = (a.K % 16 == 0) && ptr_aligned(a.act, 16) && ptr_aligned(a.wgt, 16);
   p.vec_out = (a.N % 4 == 0) && ptr_aligned(a.out, 4 * qgemm_out_elem_size(a));
@@ -583,6 +584,7 @@ static hipError_t conv_dma(const GemmArgs& a, const ConvGeom& cg, void* ws, bool
 hipError_t launch_qconv_gemm(const GemmArgs& a, const ConvGeom& cg, void* ws, bool weights_ready,
                              hipStream_t st) {
   if (a.M == 0 || a.N == 0) return hipSuccess;
+  if (a.operand16) return launch_qgemm16(a, &cg, st);
   hipError_t err = hipSuccess;
   const int path = g_hook[kHookGemmPath].load(std::memory_order_relaxed);  // 1 / 2: skip the special cases
   if (path == 0) {

@@ -40,6 +40,7 @@ struct QgemmParams {
   const int32_t* shift;
   int32_t M, N, K;
   int32_t per_channel, has_rq, acc16;
+  int32_t acc_wrap_shift;  // 32 - accumulator bits (0, 16 or 8)
   int32_t out_mode;    // 0: requantized 8-bit, 1: raw int32, 2: raw int16
   uint32_t act_xor4;   // 0x80808080 for uint8 activations, else 0
   int32_t corr_coef;   // off - z_a
@@ -69,6 +70,7 @@ inline QgemmParams make_qgemm_params(const GemmArgs& a, const ConvGeom* cg) {
   p.per_channel = a.rq.per_channel;
   p.has_rq = a.has_rq;
   p.acc16 = a.acc16;
+  p.acc_wrap_shift = a.acc_wrap_shift;
   p.out_mode = a.has_rq ? 0 : (a.acc16 ? 2 : 1);
   p.act_xor4 = a.act_unsigned ? 0x80808080u : 0u;
   p.corr_coef = (a.act_unsigned ? 128 : 0) - a.act_zero_point;
@@ -122,8 +124,8 @@ __device__ __forceinline__ void stage_channel_terms(const QgemmParams& p, int w0
     if (n < p.N) {
       corr = (p.bias ? p.bias[n] : 0) + p.corr_coef * s_corr[ci];
       if (p.has_rq) {
-        mu = p.mult[p.per_channel ? n : 0];
-        sh = p.shift[p.per_channel ? n : 0];
+        mu = rq_mult(p.mult, p.per_channel ? n : 0);
+        sh = rq_shift(p.mult, p.shift, p.per_channel ? n : 0);
       }
     }
     s_corr[ci] = corr;
@@ -151,8 +153,8 @@ __device__ __forceinline__ void load_channel_regs(const QgemmParams& p, int w0, 
     if (ci < CH && n < p.N) {
       if (p.bias) r.bias[s] = p.bias[n];
       if (p.has_rq) {
-        r.mult[s] = p.mult[p.per_channel ? n : 0];
-        r.shift[s] = p.shift[p.per_channel ? n : 0];
+        r.mult[s] = rq_mult(p.mult, p.per_channel ? n : 0);
+        r.shift[s] = rq_shift(p.mult, p.shift, p.per_channel ? n : 0);
       }
     }
   }
@@ -184,7 +186,7 @@ __device__ __forceinline__ bool finish_channel_terms(const QgemmParams& p, const
       s_shift[ci] = r.shift[s];
       if (s_shm1) s_shm1[ci] = r.shift[s] - 1;  // the folded form shifts the high dword by this
       s_c64[ci] = (int64_t)corr * (int64_t)r.mult[s] + ((int64_t)1 << (30 + (r.shift[s] & 31)));
-      general |= (r.shift[s] == 0) | (corr >= (1 << 30)) | (corr <= -(1 << 30));
+      general |= (r.shift[s] <= 0) | (corr >= (1 << 30)) | (corr <= -(1 << 30));
     }
   }
   return __syncthreads_or(general) != 0;
@@ -317,9 +319,9 @@ __device__ __forceinline__ void store_group(void* out, size_t off, int32_t v0, i
 }
 
 template <int OM, bool AWAY>
-__device__ __forceinline__ int32_t finish_one(int32_t a, int32_t m, int32_t sh, bool acc16,
+__device__ __forceinline__ int32_t finish_one(int32_t a, int32_t m, int32_t sh, int32_t acc16,
                                               const RequantScalars& rs) {
-  if (acc16) a = (int32_t)(int16_t)a;
+  if (acc16) a = wrap_acc_bits(a, acc16);  // (the wrap shift of a narrow accumulator, 0 for int32)
   if constexpr (OM == 0) a = AWAY ? requant_half_away(a, m, sh, rs) : requant_one(a, m, sh, rs);
   return a;
 }
@@ -341,7 +343,7 @@ __device__ __forceinline__ void qgemm_epilogue_fast(const QgemmParams& p, v16i (
   const int wp = wave % WP, wq = wave / WP;
   const int frow = lane & 31, fhalf = lane >> 5;
   const RequantScalars rs = p.rs;
-  const bool acc16 = p.acc16 != 0;
+  const int32_t acc16 = p.acc_wrap_shift;
   // ragged tiles: a group of four results along the packed axis is inside the tensor or outside
   // (the packed extent is a multiple of 4, of 16 where 16-byte stores are used)
   const int P_ext = ACT_ON_P ? p.M : p.N;
@@ -487,7 +489,7 @@ __device__ __forceinline__ void qgemm_epilogue(const QgemmParams& p, v16i (&acc)
   // ---- NCHW output whose image size is not a multiple of 4 (7 x 7 feature maps): a lane's 16
   // consecutive pixels are stored one by one, walking (image, pixel) without a division per element
   if constexpr (ACT_ON_P && PIXPERM) {
-    const bool acc16 = p.acc16 != 0;
+    const int32_t acc16 = p.acc_wrap_shift;
 #pragma unroll 1
     for (int tj = 0; tj < TQ; ++tj) {
       const int j_loc = (wq * TQ + tj) * 32 + frow;
@@ -505,7 +507,7 @@ __device__ __forceinline__ void qgemm_epilogue(const QgemmParams& p, v16i (&acc)
 #pragma unroll
           for (int x = 0; x < TQ; ++x) raw = (x == tj) ? acc[ti][x][r] : raw;
           int32_t a = raw + c;
-          if (acc16) a = (int32_t)(int16_t)a;
+          if (acc16) a = wrap_acc_bits(a, acc16);
           if (p.has_rq) a = requant_general(a, m, sh, p.rs);
           if (j < Q_ext && i0 + r < P_ext) {
             const int64_t o = ((int64_t)b * p.N + j) * ohw + pix;
@@ -543,7 +545,7 @@ __device__ __forceinline__ void qgemm_epilogue(const QgemmParams& p, v16i (&acc)
 #pragma unroll
           for (int x = 0; x < TQ; ++x) raw = (x == tj) ? acc[ti][x][g4 * 4 + r] : raw;
           int32_t a = raw + s_corr[ci];
-          if (p.acc16) a = (int32_t)(int16_t)a;
+          if (p.acc_wrap_shift) a = wrap_acc_bits(a, p.acc_wrap_shift);
           if (p.has_rq) a = requant_general(a, s_mult[ci], s_shift[ci], p.rs);
           v[r] = a;
         }

@@ -525,7 +525,7 @@ __global__ __launch_bounds__(64 * WP * WQ, OCC) void qgemm_dma_kernel(QgemmParam
   if constexpr (!ACT_ON_P) {
     constexpr bool kCanStage = BQ * (BP + 16) <= kStages * STAGE && (BQ * BP / 16) % NT == 0;
     if constexpr (kCanStage) {
-      if (p.out_mode == 0 && !p.acc16 && p.vec16_out && !p.rs.half_away) {
+      if (p.out_mode == 0 && !p.acc_wrap_shift && p.vec16_out && !p.rs.half_away) {
         if (general)
           qgemm_epilogue_dense_staged<WP, WQ, TP, TQ, false>(p, acc, p0, q0, s_corr, s_mult, s_shift,
                                                              s_c64, s_shm1, smem);

@@ -66,11 +66,21 @@ def test_qdense_argument_errors(L):
     assert call(BAD, _qt(hago.I8, bits=8, signed=0), BAD, i8, None, 4, 4, 4, *ok_tail) == 4   # 0..255 in an int8
     assert call(BAD, u8, BAD, i8, None, 4, 4, 4, hago.I32, None, BAD, 2, None) == 5
     # requantize struct errors
-    for rq, code in ((_rq(mult=None), 1), (_rq(out_dtype=hago.I16, bits=16), 3), (_rq(lo=5, hi=4), 4),
+    for rq, code in ((_rq(shift=None), 1), (_rq(out_dtype=hago.I16, bits=16), 3), (_rq(lo=5, hi=4), 4),
                      (_rq(lo=-129), 4), (_rq(out_dtype=hago.U8, signed=0, lo=0, hi=256), 4),
                      (_rq(bits=4, lo=-8, hi=8), 4), (_rq(pc=2), 5), (_rq(z=200), 4),
                      (_rq(rounding=2), 5), (_rq(rounding=-1), 5)):
         assert call(BAD, u8, BAD, i8, None, 4, 4, 4, hago.I32, C.byref(rq), BAD, 0, None) == code
+    # operand triples: int16 operands come in pairs and do not accumulate in 16 bits
+    i16 = _qt(hago.I16, 16)
+    assert call(BAD, i16, BAD, i8, None, 4, 4, 4, *ok_tail) == 3
+    assert call(BAD, u8, BAD, i16, None, 4, 4, 4, *ok_tail) == 3
+    assert call(BAD, i16, BAD, i16, None, 4, 4, 4, hago.I16, None, BAD, 0, None) == 3
+    assert call(BAD, i16, BAD, _qt(hago.I16, 16, z=3), None, 4, 4, 4, *ok_tail) == 3
+    # strict 24-bit accumulation bound: K * Amax * Wmax <= 2^23 - 1
+    strict24 = (hago.I24, None, BAD, hago.STRICT_ACC16, None)
+    assert call(BAD, _qt(hago.I8, 8, 1), BAD, i8, None, 4, 4, 512, *strict24) == 6     # 512 * 128 * 128 = 2^23
+    assert call(BAD, i16, BAD, i16, None, 4, 4, 1, *strict24) == 6                     # 2^15 * 2^15
     # strict int16 accumulation bound: K * Amax * Wmax <= 32767
     a4, w4 = _qt(hago.I8, 4, 0), _qt(hago.I8, 4, 1)        # 0..15 x -8..7 -> 120 per term
     strict = (hago.I16, None, BAD, hago.STRICT_ACC16, None)
