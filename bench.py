@@ -71,20 +71,27 @@ def main():
         lo, hi = clip if clip else (None, None)
         return hago.Requant(to_dev(mult), to_dev(shift), q, lo, hi, rounding=rounding)
 
-    def event_time_ms(fn, iters, warmup):
-        """Average milliseconds per call of fn over `iters` back-to-back calls (HIP events on
-        the launch stream, so launch latency is amortised as in steady-state inference)."""
+    def event_times_ms(fn, iters, warmup, reps=5):
+        """Milliseconds per call of fn over `iters` back-to-back calls (HIP events on the launch
+        stream, so launch latency is amortised as in steady-state inference), `reps` repetitions."""
         for _ in range(warmup):
             fn()
         torch.cuda.synchronize()
-        e0 = torch.cuda.Event(enable_timing=True)
-        e1 = torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(iters):
-            fn()
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / iters
+        out = []
+        for _ in range(reps):
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(iters):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            out.append(e0.elapsed_time(e1) / iters)
+        return out
+
+    def event_time_ms(fn, iters, warmup):
+        """Median of five repetitions."""
+        return float(np.median(event_times_ms(fn, iters, warmup)))
 
     if args.gemm:
         Mg, Ng, Kg = (int(v) for v in args.gemm.split(","))
@@ -155,13 +162,19 @@ def main():
     # dominant kernel: the int8 MFMA GEMM; four launches per step
     avg_launch_ms = ev_ms / (args.steps * len(layers))
     achieved = total_ops * args.steps / (ev_ms * 1e-3) / 1e12
+    step_reps = [ev_ms / args.steps] + event_times_ms(step, args.steps, 0, reps=4)
     per_layer = []
     for l in layers:
-        ms = event_time_ms(lambda: run_layer(l), args.steps, 5)
-        per_layer.append({"K": l["K"], "N": l["N"], "us": round(ms * 1e3, 3),
+        reps = event_times_ms(lambda: run_layer(l), args.steps, 5)
+        ms = float(np.median(reps))
+        per_layer.append({"K": l["K"], "N": l["N"], "us": round(ms * 1e3, 3), "us_min": round(min(reps) * 1e3, 3),
                           "tops": round(l["ops"] / (ms * 1e-3) / 1e12, 1),
                           "frac": round(l["ops"] / (ms * 1e-3) / 1e12 / PEAK_INT8_TOPS, 4)})
     log("config 5 layers:", per_layer)
+
+    # measured ceilings of this machine, same run: the matrix pipe alone on real data, and a streaming copy
+    ceilings = measured_ceilings(torch, hago, event_times_ms, dev)
+    log("measured ceilings:", ceilings)
 
     # HBM bytes per launch cannot be counted from inside this process: the figure is the one the
     # committed rocprofv3 --pmc summary of this same command ends with (null if it is absent).
@@ -169,26 +182,37 @@ def main():
     prof = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles",
                         "qgemm_dma_config5_hbm_traffic.md")
     if os.path.exists(prof):
+        meta = {}
         for line in open(prof):
-            if line.startswith("traffic_bytes_per_launch:"):
-                traffic = int(line.split(":")[1])
-                traffic_src = "profiles/qgemm_dma_config5_hbm_traffic.md (FETCH_SIZE x2 + WRITE_SIZE, KiB)"
+            for key in ("traffic_bytes_per_launch", "kernel", "commit"):
+                if line.startswith(key + ":"):
+                    meta[key] = line.split(":", 1)[1].strip()
+        if "traffic_bytes_per_launch" in meta:
+            traffic = int(meta["traffic_bytes_per_launch"])
+            traffic_src = {"file": "profiles/qgemm_dma_config5_hbm_traffic.md (FETCH_SIZE x2 + WRITE_SIZE, KiB)",
+                           "kernel": meta.get("kernel"), "commit": meta.get("commit")}
     roofline = {"bound": "mfma", "traffic_source": traffic_src, "kernel": "qgemm_dma_kernel (int8 MFMA 32x32x32, fused requantize)",
                 "achieved": round(achieved, 2), "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
                 "frac": round(achieved / PEAK_INT8_TOPS, 4), "traffic": traffic,
                 "avg_launch_us": round(avg_launch_ms * 1e3, 3), "launches_per_step": len(layers),
-                "ops_per_step": total_ops, "per_layer": per_layer}
+                "ops_per_step": total_ops,
+                "step_us_median_of_5": round(float(np.median(step_reps)) * 1e3, 3),
+                "step_us_min_of_5": round(min(step_reps) * 1e3, 3),
+                "measured_peak": ceilings.get("mfma_int8_tops"),
+                "frac_of_measured_peak": (round(achieved / ceilings["mfma_int8_tops"], 4)
+                                          if ceilings.get("mfma_int8_tops") else None),
+                "per_layer": per_layer}
 
     # ------------------------------------------------------------------ other operators
     ops = {}
     if not args.no_extra_ops:
         only = set(filter(None, args.only.split(",")))
-        ops = extra_ops(torch, hago, datagen, to_dev, rq_of, event_time_ms, only)
+        ops = extra_ops(torch, hago, datagen, to_dev, rq_of, event_times_ms, only, ceilings)
 
     # ------------------------------------------------------------------ CPU oracle baseline
-    cpu = None
+    cpu, parity = None, None
     if not args.no_cpu_baseline:
-        cpu = cpu_baseline(datagen, layers)
+        cpu, parity = cpu_baseline(datagen, layers, torch)
 
     out = {
         "metric": "int8 TOPS (qdense + fused requantize, BERT-base dense stack)",
@@ -198,34 +222,79 @@ def main():
         "config": {"workload": "config5: BERT-base dense stack, M=4096 (batch 32 x seq 128), "
                                "u8 x i8 -> i32, per-channel requantize to i8; 4 launches/step",
                    "M": M, "layers_KN": [list(x) for x in datagen.BERT_LAYERS]},
-        "roofline": roofline, "cpu_baseline": cpu, "ops": ops,
+        "roofline": roofline, "cpu_baseline": cpu, "parity_checked": parity, "ceilings": ceilings, "ops": ops,
     }
     print(json.dumps(out), flush=True)
 
 
-def cpu_baseline(datagen, layers):
-    """The oracle as it stands on a bounded sample: one whole step (all 4096 rows of the four
-    layers, 58 GOP: about a second on 16 cores, i.e. some 16 s of CPU work)."""
+def measured_ceilings(torch, hago, event_times_ms, dev):
+    """The chip's own ceilings in this run: matrix instructions only (random operands: the clock under
+    matrix-core load depends on the data), and streaming copies of the sizes the HBM-bound lines move,
+    over rotating buffers larger than the last-level cache."""
+    res = {}
+    operands = torch.randint(-128, 128, (8192,), dtype=torch.int8, device=dev)
+    sink = torch.zeros(4, dtype=torch.int32, device=dev)
+    wgs, iters = 256 * 2, 2000      # two workgroups of four wavefronts per CU
+    ms = float(np.median(event_times_ms(lambda: hago.probe_mfma_i8(operands, sink, wgs, iters), 5, 2)))
+    res["mfma_int8_tops"] = round(2.0 * 32 ** 3 * 16 * iters * wgs / (ms * 1e-3) / 1e12, 1)
+    res["mfma_note"] = "v_mfma_i32_32x32x32_i8 only, random operands, 8 wavefronts per CU, %.2f ms" % ms
+    for name, nbytes in (("copy_58MB_gbs", 32 * 144 * 3136 * 4), ("copy_14MB_gbs", 32 * 144 * 3136)):
+        n = max(2, int(np.ceil(640e6 / (2 * nbytes))))
+        srcs = [torch.empty(nbytes, dtype=torch.uint8, device=dev).random_(0, 255) for _ in range(n)]
+        dsts = [torch.empty(nbytes, dtype=torch.uint8, device=dev) for _ in range(n)]
+        state = {"i": 0}
+
+        def run():
+            i = state["i"] % n
+            hago.probe_copy(srcs[i], dsts[i])
+            state["i"] += 1
+        ms = float(np.median(event_times_ms(run, 40, 4)))
+        res[name] = round(2.0 * nbytes / (ms * 1e-3) / 1e9, 1)
+        del srcs, dsts
+    res["copy_note"] = "hago_probe_copy (128-bit nontemporal loads/stores), read + written bytes, rotating buffers"
+    return res
+
+
+def cpu_baseline(datagen, layers, torch):
+    """The oracle as it stands on a bounded sample: one whole step on every core (all 4096 rows of the
+    four layers, 58 GOP: about a second on 16 cores), and 256 rows of each layer on one thread.  The
+    all-core results are also compared with what the GPU left in the layers' output buffers."""
     from oracle import hago_ref as ref
     ref.build()
     threads = int(os.environ.get("OMP_NUM_THREADS", "0")) or (os.cpu_count() or 1)
     threads = max(1, min(threads, os.cpu_count() or 1))
     rows = 4096
     ops = 0.0
+    parity = True
+    t0 = time.perf_counter()
+    results = []
+    for l in layers:
+        c = l["host"]
+        rq = ref.Requant(c["mult"], c["shift"], out_dtype=ref.I8)
+        results.append(ref.qdense_threaded(c["a"][:rows], c["z_a"], c["w"], c["bias"], ref.I32, rq, threads=threads))
+        ops += 2.0 * rows * l["N"] * l["K"]
+    dt = time.perf_counter() - t0
+    torch.cuda.synchronize()
+    for l, want in zip(layers, results):
+        parity = parity and bool(np.array_equal(l["out"].cpu().numpy(), want))
+    log(f"cpu oracle: {ops / 1e9:.2f} GOP in {dt:.2f} s on {threads} threads; GPU outputs equal: {parity}")
+    rows1, ops1 = 256, 0.0
     t0 = time.perf_counter()
     for l in layers:
         c = l["host"]
         rq = ref.Requant(c["mult"], c["shift"], out_dtype=ref.I8)
-        ref.qdense_threaded(c["a"][:rows], c["z_a"], c["w"], c["bias"], ref.I32, rq, threads=threads)
-        ops += 2.0 * rows * l["N"] * l["K"]
-    dt = time.perf_counter() - t0
-    log(f"cpu oracle: {ops / 1e9:.2f} GOP in {dt:.2f} s on {threads} threads")
+        ref.qdense(c["a"][:rows1], c["z_a"], c["w"], c["bias"], ref.I32, rq)
+        ops1 += 2.0 * rows1 * l["N"] * l["K"]
+    dt1 = time.perf_counter() - t0
+    log(f"cpu oracle, one thread: {ops1 / 1e9:.2f} GOP in {dt1:.2f} s")
     return {"value": round(ops / dt / 1e12, 5), "unit": "TOP/s", "cores": threads, "kind": "oracle",
             "sample": f"all {rows} rows of each of the 4 layers, one step ({ops / 1e9:.1f} GOP), "
-                      f"row slices on {threads} threads, {dt:.2f} s wall"}
+                      f"row slices on {threads} threads, {dt:.2f} s wall",
+            "single_thread": {"value": round(ops1 / dt1 / 1e12, 5), "unit": "TOP/s", "cores": 1,
+                              "sample": f"the first {rows1} rows of each layer ({ops1 / 1e9:.2f} GOP), {dt1:.2f} s wall"}}, parity
 
 
-def extra_ops(torch, hago, datagen, to_dev, rq_of, event_time_ms, only):
+def extra_ops(torch, hago, datagen, to_dev, rq_of, event_times_ms, only, ceilings):
     """Timings of the remaining operators.  HBM-bound operators rotate over buffer sets that
     together exceed the 256 MB last-level cache, so the figure is an HBM rate."""
     dev = "cuda:0"
@@ -234,14 +303,25 @@ def extra_ops(torch, hago, datagen, to_dev, rq_of, event_time_ms, only):
     def want(name):
         return not only or name in only
 
-    def record(name, ms, ops=None, bytes_=None, bound=None, note=None):
-        r = {"us": round(ms * 1e3, 3)}
+    def event_time_ms(fn, iters, warmup):
+        """All five repetitions (record() reports their median and minimum)."""
+        return event_times_ms(fn, iters, warmup)
+
+    def record(name, reps, ops=None, bytes_=None, bound=None, note=None, warm=None):
+        ms = float(np.median(reps))
+        r = {"us": round(ms * 1e3, 3), "us_min": round(min(reps) * 1e3, 3)}
         if ops is not None:
             r["tops"] = round(ops / (ms * 1e-3) / 1e12, 3)
             r["frac_mfma"] = round(r["tops"] / PEAK_INT8_TOPS, 4)
         if bytes_ is not None:
             r["gbs"] = round(bytes_ / (ms * 1e-3) / 1e9, 1)
             r["frac_hbm"] = round(r["gbs"] / PEAK_HBM_GBS, 4)
+            ref_copy = ceilings.get("copy_58MB_gbs" if bytes_ > 50e6 else "copy_14MB_gbs")
+            if ref_copy:
+                r["frac_of_measured_copy"] = round(r["gbs"] / ref_copy, 4)
+        if warm is not None:   # the same call on ONE buffer set (served from the last-level cache where it fits)
+            wms = float(np.median(event_times_ms(warm, 40, 4)))
+            r["us_cache_warm"] = round(wms * 1e3, 3)
         r["bound"] = bound
         if note:
             r["note"] = note
@@ -257,6 +337,7 @@ def extra_ops(torch, hago, datagen, to_dev, rq_of, event_time_ms, only):
         def run():
             calls[state["i"] % n]()
             state["i"] += 1
+        run.warm = calls[0]
         return run
 
     # ---- simquant, config 4 tensor
@@ -268,7 +349,7 @@ def extra_ops(torch, hago, datagen, to_dev, rq_of, event_time_ms, only):
         nb = x0.numel() * 8
         f = rotating(lambda i: hago.simquant(x0.clone(), scale, zp, q, out=torch.empty_like(x0),
                                              prepare=True), nb)
-        record("simquant_c4", event_time_ms(f, 60, 6), bytes_=nb, bound="hbm",
+        record("simquant_c4", event_time_ms(f, 60, 6), warm=f.warm, bytes_=nb, bound="hbm",
                note="fp32 [32,144,56,56], per-channel, 8 B/elem")
         del f
 
@@ -284,7 +365,7 @@ def extra_ops(torch, hago, datagen, to_dev, rq_of, event_time_ms, only):
         nb = x0.numel() * 4 * 9
         f = rotating(lambda i: hago.simquant_batched(x0.clone(), scales, zps, hago.QType(hago.I8), lo, hi,
                                                      prepare=True), nb)
-        record("simquant_batched8_c4", event_time_ms(f, 30, 4), bytes_=nb, bound="hbm",
+        record("simquant_batched8_c4", event_time_ms(f, 30, 4), warm=f.warm, bytes_=nb, bound="hbm",
                note="fp32 [32,144,56,56], 8 candidates in one launch, 4 + 32 B/elem "
                     "(8 separate simquant launches move 64 B/elem)")
         del f
@@ -298,18 +379,18 @@ def extra_ops(torch, hago, datagen, to_dev, rq_of, event_time_ms, only):
         nb = x0.numel() * 5
         if want("quantize_c4"):
             f = rotating(lambda i: hago.quantize(x0.clone(), scale, zp, q, prepare=True), nb)
-            record("quantize_c4", event_time_ms(f, 60, 6), bytes_=nb, bound="hbm",
+            record("quantize_c4", event_time_ms(f, 60, 6), warm=f.warm, bytes_=nb, bound="hbm",
                    note="fp32 [32,144,56,56] -> int8 codes, 5 B/elem")
             del f
         if want("simquant_codes_c4"):
             f = rotating(lambda i: hago.simquant_codes(x0.clone(), scale, zp, q, prepare=True), x0.numel() * 9)
-            record("simquant_codes_c4", event_time_ms(f, 60, 6), bytes_=x0.numel() * 9, bound="hbm",
+            record("simquant_codes_c4", event_time_ms(f, 60, 6), warm=f.warm, bytes_=x0.numel() * 9, bound="hbm",
                    note="fp32 [32,144,56,56] -> fp32 + int8 codes in one pass, 9 B/elem")
             del f
         if want("dequantize_c4"):
             codes0 = hago.quantize(x0, scale, zp, q)
             f = rotating(lambda i: hago.dequantize(codes0.clone(), q, scale, zp, prepare=True), nb)
-            record("dequantize_c4", event_time_ms(f, 60, 6), bytes_=nb, bound="hbm",
+            record("dequantize_c4", event_time_ms(f, 60, 6), warm=f.warm, bytes_=nb, bound="hbm",
                    note="int8 codes [32,144,56,56] -> fp32, 5 B/elem")
             del f
 
@@ -319,7 +400,7 @@ def extra_ops(torch, hago, datagen, to_dev, rq_of, event_time_ms, only):
         x0 = to_dev(c["x"].reshape(32, 144, -1))
         nb = x0.numel() * 4
         f = rotating(lambda i: hago.absmax(x0.clone(), True, prepare=True), nb)
-        record("absmax_c4", event_time_ms(f, 60, 6), bytes_=nb, bound="hbm",
+        record("absmax_c4", event_time_ms(f, 60, 6), warm=f.warm, bytes_=nb, bound="hbm",
                note="fp32 [32,144,56,56] -> 144 thresholds, 4 B/elem (zero fill + reduction, two launches)")
         del f
 
@@ -333,7 +414,7 @@ def extra_ops(torch, hago, datagen, to_dev, rq_of, event_time_ms, only):
         f = rotating(lambda i: hago.qconv2d(a0.clone(), a_t, w, w_t, None, hago.NCHW, (1, 1), (1, 1),
                                             144, hago.I32, rq, out=torch.empty_like(a0),
                                             prepare=True), nb)
-        record("depthwise_c4", event_time_ms(f, 100, 10), ops=2.0 * a0.numel() * 9, bytes_=nb,
+        record("depthwise_c4", event_time_ms(f, 100, 10), warm=f.warm, ops=2.0 * a0.numel() * 9, bytes_=nb,
                bound="hbm", note="i8 [32,144,56,56] 3x3, 2 B/output")
         del f
     if want("pointwise_c4"):
@@ -345,7 +426,7 @@ def extra_ops(torch, hago, datagen, to_dev, rq_of, event_time_ms, only):
                                             1, hago.I32, rq,
                                             out=torch.empty(o_shape, dtype=torch.int8, device=dev),
                                             prepare=True), nb)
-        record("pointwise_c4", event_time_ms(f, 100, 10), ops=2.0 * 32 * 56 * 56 * 24 * 144,
+        record("pointwise_c4", event_time_ms(f, 100, 10), warm=f.warm, ops=2.0 * 32 * 56 * 56 * 24 * 144,
                bytes_=nb, bound="hbm", note="1x1 conv 144->24 on MFMA, 168 B/pixel")
         del f
 
@@ -359,7 +440,7 @@ def extra_ops(torch, hago, datagen, to_dev, rq_of, event_time_ms, only):
                                             (2, 2), (1, 1), 144, hago.I32, rq,
                                             out=torch.empty(o_shape, dtype=torch.int8, device=dev),
                                             prepare=True), nb)
-        record("depthwise_c4_s2", event_time_ms(f, 100, 10), ops=2.0 * 32 * 144 * 28 * 28 * 9,
+        record("depthwise_c4_s2", event_time_ms(f, 100, 10), warm=f.warm, ops=2.0 * 32 * 144 * 28 * 28 * 9,
                bytes_=nb, bound="hbm", note="i8 [32,144,56,56] 3x3 stride 2, 1.25 B/input")
         del f
 
@@ -371,7 +452,7 @@ def extra_ops(torch, hago, datagen, to_dev, rq_of, event_time_ms, only):
         f = rotating(lambda i: hago.requantize(acc0.clone(), rq,
                                                out=torch.empty(acc0.shape, dtype=torch.int8, device=dev),
                                                prepare=True), nb)
-        record("requantize_i32", event_time_ms(f, 60, 6), bytes_=nb, bound="hbm",
+        record("requantize_i32", event_time_ms(f, 60, 6), warm=f.warm, bytes_=nb, bound="hbm",
                note="i32 [32,144,3136] -> i8, 5 B/elem")
         del f
 
@@ -383,7 +464,7 @@ def extra_ops(torch, hago, datagen, to_dev, rq_of, event_time_ms, only):
         f = rotating(lambda i: hago.requantize(acc0.clone(), rq,
                                                out=torch.empty(acc0.shape, dtype=torch.int8, device=dev),
                                                prepare=True), nb)
-        record("requantize_i32_half_away", event_time_ms(f, 60, 6), bytes_=nb, bound="hbm",
+        record("requantize_i32_half_away", event_time_ms(f, 60, 6), warm=f.warm, bytes_=nb, bound="hbm",
                note="i32 [32,144,3136] -> i8, 5 B/elem, ties away from zero")
         del f
     if want("dense_c5_ffn1_half_away"):

@@ -393,6 +393,25 @@ hago_status hago_bit_range(int32_t bits, int32_t is_signed, int32_t* lo,
                            int32_t* hi);
 
 /*
+ * Measurement probes, not part of the operator set: what this chip delivers
+ * when a kernel does nothing but the bounding operation, printed by the
+ * benchmark beside the published peaks.
+ *   hago_probe_mfma_i8: `workgroups` workgroups of four wavefronts each issue
+ *     16 * iters int8 matrix instructions (32x32x32) back to back on the operands
+ *     at `operands` (device, 8192 bytes, read once; real data matters, the clock
+ *     under matrix-core load depends on it); 2 * 32*32*32 * 16 * iters *
+ *     workgroups operations in all.  sink: device, 4 bytes, practically never
+ *     written.
+ *   hago_probe_copy: streaming copy of `bytes` (a multiple of 16, 16-byte aligned
+ *     device pointers) with the elementwise kernels' access pattern.
+ * Errors: NULL, SHAPE, PARAM (alignment), DEVICE.
+ */
+hago_status hago_probe_mfma_i8(const void* operands, void* sink,
+                               int32_t workgroups, int32_t iters, void* stream);
+hago_status hago_probe_copy(const void* src, void* dst, int64_t bytes,
+                            void* stream);
+
+/*
  * Test hook, not part of the operator set: forces which GEMM kernel family
  * and tile shape serve the following hago_qdense / hago_qconv2d* calls of
  * this process, so that tests can compare every variant with the oracle on

@@ -21,7 +21,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libhago.so")
 
 EXPORTS = ("hago_simquant", "hago_simquant_batched", "hago_absmax", "hago_simquant_wrap", "hago_quantize", "hago_dequantize", "hago_simquant_codes", "hago_qdense", "hago_qconv2d", "hago_qconv2d_ws", "hago_qconv2d_workspace_bytes", "hago_qconv2d_static", "hago_requantize",
-           "hago_status_string", "hago_bit_range", "hago_set_test_hook")
+           "hago_status_string", "hago_bit_range", "hago_set_test_hook", "hago_probe_mfma_i8", "hago_probe_copy")
 
 
 class _QType(C.Structure):
@@ -92,6 +92,10 @@ def lib():
         L.hago_qconv2d_workspace_bytes.argtypes = [i32, i64, i64, i64, i64, i64, i32, i32, i32, i32, i32, i32, i32]
         L.hago_bit_range.restype = i32
         L.hago_bit_range.argtypes = [i32, i32, C.POINTER(i32), C.POINTER(i32)]
+        L.hago_probe_mfma_i8.restype = i32
+        L.hago_probe_mfma_i8.argtypes = [vp, vp, i32, i32, vp]
+        L.hago_probe_copy.restype = i32
+        L.hago_probe_copy.argtypes = [vp, vp, i64, vp]
         L.hago_set_test_hook.restype = None
         L.hago_set_test_hook.argtypes = [i32, i32]
         _lib = L
@@ -103,6 +107,19 @@ def bit_range(bits, is_signed):
     lo, hi = C.c_int32(), C.c_int32()
     _check(lib().hago_bit_range(int(bits), int(bool(is_signed)), C.byref(lo), C.byref(hi)))
     return lo.value, hi.value
+
+
+def probe_mfma_i8(operands, sink, workgroups, iters):
+    """hago_probe_mfma_i8: operands 8192 bytes, sink 4 bytes (device tensors)."""
+    assert operands.numel() * operands.element_size() >= 8192 and sink.numel() * sink.element_size() >= 4
+    _check(lib().hago_probe_mfma_i8(_ptr(operands), _ptr(sink), int(workgroups), int(iters), _stream()))
+
+
+def probe_copy(src, dst):
+    """hago_probe_copy between two device tensors of the same byte size."""
+    n = src.numel() * src.element_size()
+    assert n == dst.numel() * dst.element_size()
+    _check(lib().hago_probe_copy(_ptr(src), _ptr(dst), n, _stream()))
 
 
 def set_test_hook(key, value):
