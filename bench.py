@@ -501,13 +501,22 @@ def extra_ops(torch, hago, datagen, to_dev, rq_of, event_times_ms, only, ceiling
         out = torch.empty((B, 64, 56, 56), dtype=torch.uint8, device=dev)
         at = hago.QType(hago.U8, 8, False, 0)
 
+        # hago_qconv2d, no scratch memory: one launch straight from the NCHW tensor
+        f = hago.qconv2d(a, at, w, w_t, None, hago.NCHW, (1, 1), (1, 1), 1, hago.I32, rq, out=out, prepare=True)
+        record(name, event_time_ms(f, 100, 10), ops=2.0 * B * 3136 * 64 * 576,
+               bound="latency" if B == 1 else "mfma",
+               note="3x3 conv 64->64 @56x56 NCHW, one launch" + (" (scaled batch)" if B != 1 else ""))
+        # beside it: both operands rewritten into a workspace, then the streaming implicit GEMM
         ws = torch.empty(hago.qconv2d_workspace_bytes(a.shape, w.shape, hago.NCHW, (1, 1), (1, 1)),
                          dtype=torch.uint8, device=dev)
         f = hago.qconv2d(a, at, w, w_t, None, hago.NCHW, (1, 1), (1, 1), 1, hago.I32, rq, out=out,
                          prepare=True, workspace=ws)
-        record(name, event_time_ms(f, 100, 10), ops=2.0 * B * 3136 * 64 * 576,
-               bound="latency" if B == 1 else "mfma",
-               note="3x3 conv 64->64 @56x56 NCHW" + (" (scaled batch)" if B != 1 else ""))
+        hago.set_test_hook(hago.HOOK_GEMM_PATH, 2)
+        try:
+            record(name + "_via_workspace", event_time_ms(f, 100, 10), ops=2.0 * B * 3136 * 64 * 576,
+                   bound="latency" if B == 1 else "mfma", note="the same through hago_qconv2d_ws's two-launch path")
+        finally:
+            hago.set_test_hook(hago.HOOK_GEMM_PATH, 0)
 
     # ---- config 3 (int16 accumulation; as specified and scaled)
     for name, B in (("conv_c3_acc16", 8), ("conv_c3_acc16_B64", 64)):
@@ -518,12 +527,19 @@ def extra_ops(torch, hago, datagen, to_dev, rq_of, event_times_ms, only, ceiling
         out = torch.empty((B, 128, 28, 28), dtype=torch.int16, device=dev)
         at, wt = hago.QType(hago.I8, 4, False, 0), hago.QType(hago.I8, 4, True, 0)
 
+        f = hago.qconv2d(a, at, w, wt, None, hago.NCHW, (1, 1), (1, 1), 1, hago.I16, None, out=out, prepare=True)
+        record(name, event_time_ms(f, 100, 10), ops=2.0 * B * 784 * 128 * 1152, bound="mfma",
+               note="3x3 conv 128->128 @28x28, raw int16 out, one launch" + (" (scaled batch)" if B != 8 else ""))
         ws = torch.empty(hago.qconv2d_workspace_bytes(a.shape, w.shape, hago.NCHW, (1, 1), (1, 1)),
                          dtype=torch.uint8, device=dev)
         f = hago.qconv2d(a, at, w, wt, None, hago.NCHW, (1, 1), (1, 1), 1, hago.I16, None, out=out,
                          prepare=True, workspace=ws)
-        record(name, event_time_ms(f, 100, 10), ops=2.0 * B * 784 * 128 * 1152, bound="mfma",
-               note="3x3 conv 128->128 @28x28, raw int16 out" + (" (scaled batch)" if B != 8 else ""))
+        hago.set_test_hook(hago.HOOK_GEMM_PATH, 2)
+        try:
+            record(name + "_via_workspace", event_time_ms(f, 100, 10), ops=2.0 * B * 784 * 128 * 1152, bound="mfma",
+                   note="the same through hago_qconv2d_ws's two-launch path")
+        finally:
+            hago.set_test_hook(hago.HOOK_GEMM_PATH, 0)
     return res
 
 

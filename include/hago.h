@@ -192,10 +192,13 @@ hago_status hago_qdense(const void* a, hago_qtype a_t, const void* w,
  * Errors as for hago_qdense; additionally SHAPE for any other `groups`, a
  * kernel larger than the padded image, stride < 1, pad < 0; DTYPE for int16
  * operands with groups != 1.
- * This entry point uses no scratch memory: depthwise, 1x1 and channel-last
- * 1x1 geometries have kernels that read the caller's tensors directly; every
- * other groups == 1 geometry runs a general kernel that gathers its operands
- * from the caller's layout and is several times slower than hago_qconv2d_ws.
+ * This entry point uses no scratch memory.  Depthwise, 1x1 (either layout) and
+ * NCHW 3x3 stride-1 pad-1 convolutions with C a multiple of 32 up to 128 and
+ * W a multiple of 4 up to 128 (configs 2 and 3) run one kernel that reads
+ * the caller's tensors directly, as fast as or faster than hago_qconv2d_ws;
+ * every other groups == 1 geometry runs a general kernel that gathers its
+ * operands from the caller's layout and is several times slower than
+ * hago_qconv2d_ws.
  */
 hago_status hago_qconv2d(const void* a, hago_qtype a_t, const void* w,
                          hago_qtype w_t, const int32_t* bias,
@@ -212,7 +215,9 @@ hago_status hago_qconv2d(const void* a, hago_qtype a_t, const void* w,
  * elements per lane, so a groups == 1 convolution first rewrites, in one
  * launch, the activations into a padded channel-last int8 copy and the
  * weights into [O][KH*KW][C rounded up to 16] inside `workspace`, then runs
- * the implicit GEMM over the copies.
+ * the implicit GEMM over the copies.  (Geometries for which hago_qconv2d has
+ * a kernel of its own that is at least as fast run that kernel here too and
+ * leave the workspace untouched.)
  *   hago_qconv2d_workspace_bytes  (host only, launches nothing): bytes this
  *     geometry wants; 0 when it runs without scratch (depthwise, or shapes
  *     only the general kernel indexes); -1 for arguments hago_qconv2d would
@@ -417,7 +422,8 @@ hago_status hago_probe_copy(const void* src, void* dst, int64_t bytes,
  * this process, so that tests can compare every variant with the oracle on
  * one shape.  Results never depend on it.  Keys:
  *   HAGO_HOOK_GEMM_PATH     0 automatic; 1 the general register-staged kernel;
- *                           2 the streaming kernel, skipping the 1x1 special cases
+ *                           2 the streaming kernel, skipping the kernels
+ *                           specialised for 1x1 and 3x3 convolutions
  *   HAGO_HOOK_STREAM_TILE   -1 automatic; 0..4 a tile of the streaming dense kernel
  *   HAGO_HOOK_GENERAL_TILE  -1 automatic; 0..6 a tile of the general kernel
  * Unknown keys are ignored.

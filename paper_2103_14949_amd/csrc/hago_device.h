@@ -79,6 +79,38 @@ __device__ __forceinline__ int32_t requant_general(int32_t acc, int32_t mult, in
   return rs.half_away ? requant_half_away(acc, mult, sh, rs) : requant_one(acc, mult, sh, rs);
 }
 
+// Byte B of dst <- low byte of (src >> sh) (arithmetic); B == 0 clears the other bytes, the
+// later ones keep them: four of these in a row shift and pack four results with no separate
+// pack instructions (the destination-byte select of the sub-dword addressing forms).
+template <int B>
+__device__ __forceinline__ void ashr_into_byte(uint32_t& dst, int32_t src, int32_t sh) {
+  static_assert(B >= 0 && B < 4, "byte index");
+  if constexpr (B == 0)
+    asm("v_ashrrev_i32_sdwa %0, %1, %2 dst_sel:BYTE_0 dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:DWORD"
+        : "=v"(dst) : "v"(sh), "v"(src));
+  else if constexpr (B == 1)
+    asm("v_ashrrev_i32_sdwa %0, %1, %2 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD"
+        : "+v"(dst) : "v"(sh), "v"(src));
+  else if constexpr (B == 2)
+    asm("v_ashrrev_i32_sdwa %0, %1, %2 dst_sel:BYTE_2 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD"
+        : "+v"(dst) : "v"(sh), "v"(src));
+  else
+    asm("v_ashrrev_i32_sdwa %0, %1, %2 dst_sel:BYTE_3 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD"
+        : "+v"(dst) : "v"(sh), "v"(src));
+}
+
+// Clip limits moved in front of a right shift by s: clip(y >> s, lo, hi) == clip(y, lo * 2^s,
+// (hi + 1) * 2^s - 1) >> s for the flooring shift; a limit that leaves int32 saturates there
+// (no y lies beyond it, so it is inactive, as it should be).
+__device__ __forceinline__ int32_t clip_lo_before_shift(int32_t lo, int32_t s) {
+  const int64_t v = (int64_t)lo * ((int64_t)1 << s);
+  return v < INT32_MIN ? INT32_MIN : (v > INT32_MAX ? INT32_MAX : (int32_t)v);
+}
+__device__ __forceinline__ int32_t clip_hi_before_shift(int32_t hi, int32_t s) {
+  const int64_t v = ((int64_t)hi + 1) * ((int64_t)1 << s) - 1;
+  return v > INT32_MAX ? INT32_MAX : (v < INT32_MIN ? INT32_MIN : (int32_t)v);
+}
+
 // Four results -> one little-endian dword of their low bytes.
 __device__ __forceinline__ uint32_t pack4_perm(int32_t b0, int32_t b1, int32_t b2, int32_t b3) {
   const uint32_t lo = __builtin_amdgcn_perm((uint32_t)b1, (uint32_t)b0, 0x0c0c0400u);

@@ -5,7 +5,24 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace hago {
+
+// The dynamic-LDS limit of a kernel is a per-device attribute.  `done` holds one bit per device
+// (ids modulo 64) on which it has been raised; concurrent first calls may both set it, which is
+// harmless.
+inline hipError_t raise_lds_limit(const void* kern, int lds_bytes, std::atomic<uint64_t>& done) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const uint64_t bit = 1ull << (dev & 63);
+  if (done.load(std::memory_order_acquire) & bit) return hipSuccess;
+  e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+  if (e == hipSuccess) done.fetch_or(bit, std::memory_order_release);
+  return e;
+}
+
 
 struct RequantArgs {
   const int32_t* multiplier;  // device
@@ -94,6 +111,9 @@ hipError_t launch_conv_prepack(const GemmArgs& g, const ConvGeom& cg, int32_t Cp
 // Test hooks (see hago_set_test_hook): which GEMM kernel family and tile serve the next calls.
 enum { kHookGemmPath = 0, kHookDmaTile = 1, kHookGenericTile = 2, kNumHooks = 3 };
 void set_test_hook(int key, int value);
+// 3x3 stride-1 pad-1 NCHW convolution in one launch, no scratch; false when the geometry is not
+// that kernel's (nothing is launched then).
+bool try_qconv3x3_nchw(const GemmArgs& g, const ConvGeom& cg, hipStream_t st, hipError_t* err);
 // 1x1 stride-1 unpadded NCHW convolution straight from the caller's buffers; false when the
 // geometry is not that kernel's (nothing is launched then).
 bool try_qconv_pointwise_nchw(const GemmArgs& g, const ConvGeom& cg, hipStream_t st, hipError_t* err);

@@ -593,6 +593,9 @@ hipError_t launch_qconv_gemm(const GemmArgs& a, const ConvGeom& cg, void* ws, bo
     if (cg.nhwc && cg.KH == 1 && cg.KW == 1 && cg.stride_h == 1 && cg.stride_w == 1 && cg.pad_h == 0 &&
         cg.pad_w == 0)
       return launch_qdense(a, st);
+    // 3x3 stride 1 over NCHW: one launch that transposes the tensor on its way into the LDS
+    // (faster than rewriting it through the workspace first, and it needs none)
+    if (try_qconv3x3_nchw(a, cg, st, &err)) return err;
   }
   if (ws && path != 1 && qconv_workspace_bytes(cg) >= 0) return conv_dma(a, cg, ws, weights_ready, st);
   QgemmParams p = make_qgemm_params(a, &cg);

@@ -6,7 +6,6 @@
 #include "hago_device.h"
 #include "launch.h"
 
-#include <atomic>
 #include <cstdlib>
 
 namespace hago {
@@ -82,20 +81,6 @@ inline QgemmParams make_qgemm_params(const GemmArgs& a, const ConvGeom* cg) {
   p.dbg_skip = g_stamp_skip;
 #endif
   return p;
-}
-
-// The dynamic-LDS limit of a kernel is a per-device attribute.  `done` holds one bit per device
-// (ids modulo 64) on which it has been raised; concurrent first calls may both set it, which is
-// harmless.
-inline hipError_t raise_lds_limit(const void* kern, int lds_bytes, std::atomic<uint64_t>& done) {
-  int dev = 0;
-  hipError_t e = hipGetDevice(&dev);
-  if (e != hipSuccess) return e;
-  const uint64_t bit = 1ull << (dev & 63);
-  if (done.load(std::memory_order_acquire) & bit) return hipSuccess;
-  e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-  if (e == hipSuccess) done.fetch_or(bit, std::memory_order_release);
-  return e;
 }
 
 inline bool ptr_aligned(const void* ptr, size_t n) {

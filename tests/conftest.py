@@ -33,12 +33,18 @@ def ref():
     return hago_ref
 
 
-@pytest.fixture(params=["plain", "ws"])
+@pytest.fixture(params=["plain", "ws", "ws_stream"])
 def conv_entry(request):
-    """Runs a convolution parity test once per entry point (see gpu_util.qconv2d)."""
+    """Runs a convolution parity test once per entry point (see gpu_util.qconv2d); "ws_stream" also
+    switches off the kernels specialised for 1x1 and 3x3 geometries, so that the streaming implicit
+    GEMM over the workspace copies meets every geometry."""
     import gpu_util
-    gpu_util.CONV_ENTRY["name"] = request.param
+    import paper_2103_14949_amd as hago
+    gpu_util.CONV_ENTRY["name"] = "plain" if request.param == "plain" else "ws"
+    if request.param == "ws_stream":
+        hago.set_test_hook(hago.HOOK_GEMM_PATH, 2)
     yield request.param
+    hago.set_test_hook(hago.HOOK_GEMM_PATH, 0)
     gpu_util.CONV_ENTRY["name"] = "plain"
 
 
@@ -52,8 +58,8 @@ def stream_tile():
 
 @pytest.fixture
 def gemm_path():
-    """Forces the GEMM kernel family (1: general register-staged, 2: streaming without the 1x1
-    special cases) for the rest of a test."""
+    """Forces the GEMM kernel family (1: general register-staged, 2: streaming without the kernels
+    specialised for 1x1 and 3x3 convolutions) for the rest of a test."""
     import paper_2103_14949_amd as hago
     yield lambda path: hago.set_test_hook(hago.HOOK_GEMM_PATH, path)
     hago.set_test_hook(hago.HOOK_GEMM_PATH, 0)

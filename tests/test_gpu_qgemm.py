@@ -416,6 +416,51 @@ def test_qconv2d_config3_int16_accumulation_full_size(conv_entry):
         assert e.value.code == 6
 
 
+DIRECT3X3_CASES = [
+    # B C H W O : NCHW 3x3 stride 1 pad 1 without a workspace -> the one-launch kernel
+    (1, 32, 5, 8, 7),         # one partial tile, fewer than 32 output channels
+    (2, 64, 9, 56, 64),       # tiles of two rows, the last one a single row
+    (1, 64, 56, 56, 64),      # config 2's geometry
+    (3, 128, 28, 28, 128),    # config 3's geometry: two blocks of output channels
+    (2, 96, 7, 60, 65),       # H * W not a multiple of 16: byte stores; a second block with one channel
+    (1, 32, 3, 128, 130),     # one row per tile, the widest image the kernel takes
+    (2, 32, 40, 4, 33),       # narrow images: 32 rows per tile
+    (1, 128, 16, 16, 24),
+]
+
+
+@pytest.mark.parametrize("case", DIRECT3X3_CASES)
+@pytest.mark.parametrize("adt,za", [(np.uint8, 128), (np.uint8, 3), (np.int8, -5)])
+def test_qconv2d_one_launch_3x3(case, adt, za):
+    """hago_qconv2d without scratch on the geometries its one-launch kernel takes: every output mode."""
+    B, C, H, W, O = case
+    rng = np.random.default_rng(abs(hash(case)) % 2 ** 31 + za)
+    a, w = rnd_act(rng, (B, C, H, W), adt), rnd_w(rng, (O, C, 3, 3))
+    bias = rng.integers(-10 ** 5, 10 ** 5, O).astype(np.int32)
+    a_t, w_t = act_qtype(a, za), hago.QType(hago.I8)
+    args = (hago.NCHW, (1, 1), (1, 1), 1)
+    rargs = (ref.NCHW, (1, 1), (1, 1), 1)
+    assert_same(host(hago.qconv2d(dev(a), a_t, dev(w), w_t, dev(bias), *args)), ref.qconv2d(a, za, w, bias, *rargs), f"raw {case}")
+    assert_same(host(hago.qconv2d(dev(a), a_t, dev(w), w_t, None, *args, hago.I16)), ref.qconv2d(a, za, w, None, *rargs, ref.I16),
+                f"raw int16 {case}")
+    assert_same(host(hago.qconv2d(dev(a), a_t, dev(w), w_t, dev(bias), *args, hago.I24)), ref.qconv2d(a, za, w, bias, *rargs, ref.I24),
+                f"24-bit {case}")
+    mult, shift = datagen.requant_params(rng, np.full(O, 74.0 * 73.0 * np.sqrt(9 * C)), 40.0)
+    shift[0] = 0
+    for out_u8, z_out, clip, rounding in ((False, 0, (-128, 127), 0), (True, 10, (10, 255), 1), (False, -3, (-8, 7), 0)):
+        want = ref.qconv2d(a, za, w, bias, *rargs, ref.I32, ref_requant(mult, shift, out_u8, z_out, clip, rounding))
+        got = hago.qconv2d(dev(a), a_t, dev(w), w_t, dev(bias), *args, hago.I32,
+                           gpu_requant(mult, shift, out_u8, z_out, clip, bits=4 if clip == (-8, 7) else 8, rounding=rounding))
+        assert_same(host(got), want, f"requantized {case} u8={out_u8}")
+    assert np.mean((want == -8) | (want == 7)) < 0.95
+    # unaligned output pointer: the 16-byte stores give way to single ones
+    buf = torch.empty(B * O * H * W + 1, dtype=torch.int8, device=DEV)
+    out = buf[1:].view(B, O, H, W)
+    want = ref.qconv2d(a, za, w, bias, *rargs, ref.I32, ref_requant(mult, shift))
+    hago.qconv2d(dev(a), a_t, dev(w), w_t, dev(bias), *args, hago.I32, gpu_requant(mult, shift), out=out)
+    assert_same(host(out), want, f"unaligned output {case}")
+
+
 @pytest.mark.parametrize("O", [128, 100])
 def test_qconv2d_many_pixels_128_channels(O, conv_entry):
     """3x3 convolution with 128 input channels over more than 2^15 output pixels (the 256-pixel
