@@ -76,22 +76,34 @@ __device__ __forceinline__ void transpose4(uint32_t a, uint32_t b, uint32_t c, u
 }
 
 // NW: wavefronts per workgroup; AF: 32-pixel MFMA row blocks per wavefront (tiles of 32 * NW * AF
-// pixels); NU: staging units per thread.
-template <int NW, int AF, int NU>
+// pixels); NU: staging units per thread; CK: input channels / 32.
+template <int NW, int AF, int NU, int CK>
 __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void conv3x3_nchw_kernel(C3Params p) {
   constexpr int NT = 64 * NW;
   extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
   const int t = threadIdx.x;
   const int lane = t & 63;
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
-  const int C = p.C, H = p.H, W = p.W, O = p.O;
-  const int Cp = C + 16;               // bytes per staged pixel
+  constexpr int C = 32 * CK;
+  const int H = p.H, W = p.W, O = p.O;
+  constexpr int Cp = C + 16;           // bytes per staged pixel
   const int Wp = W + 2;
-  const int wstride = 9 * C + 16;      // bytes per staged output channel
+  constexpr int wstride = 9 * C + 16;  // bytes per staged output channel
   const int HW = H * W;
-  const int blk = (int)blockIdx.x % p.nblk;           // this workgroup's block of output channels
-  const int o0 = blk * 64;
-  const int wg = (int)blockIdx.x / p.nblk, nwg = (int)gridDim.x / p.nblk;
+  // Workgroups that share a pixel tile (one per block of output channels) read the same input:
+  // consecutive workgroup ids go round the 8 XCDs, so the block index is taken from the id
+  // divided by 8 and the sharers land on one XCD, whose L2 then fetches the tile once.
+  int blk, wg;
+  const int nwg = (int)gridDim.x / p.nblk;
+  if (nwg % 8 == 0) {
+    const int xcd = (int)blockIdx.x & 7, q = (int)blockIdx.x >> 3;
+    blk = q % p.nblk;
+    wg = (q / p.nblk) * 8 + xcd;
+  } else {
+    blk = (int)blockIdx.x % p.nblk;
+    wg = (int)blockIdx.x / p.nblk;
+  }
+  const int o0 = blk * 64;                             // this workgroup's block of output channels
 
   uint8_t* s_w = smem;                                 // [64][wstride]
   uint8_t* s_in = smem + 64 * wstride;                 // [(TR + 2)][Wp][Cp]
@@ -270,19 +282,41 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void conv3x3_nchw_kernel(
       for (int tn = 0; tn < 2; ++tn)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[f][tn][r] = 0;
-    for (int tap = 0; tap < 9; ++tap) {
-      const int ky = tap / 3, kx = tap - 3 * ky;
-      const uint32_t a_tap = (uint32_t)((ky * Wp + kx) * Cp);
-      const uint32_t b_tap = b_base + (uint32_t)(tap * C);
-      for (int cg = 0; cg < C; cg += 32) {
-        const v4i b0 = *reinterpret_cast<const v4i*>(s_w + b_tap + cg);
-        const v4i b1 = *reinterpret_cast<const v4i*>(s_w + b_tap + 32 * wstride + cg);
+    // Fully unrolled, the fragments of step s + 1 are requested before the matrix instructions of
+    // step s are issued, so the LDS latency hides behind them; all offsets of the weight
+    // fragments are immediates, a tap costs one address addition per row block.
+    {
+      v4i bq[2][2], aq[2][AF];
+      uint32_t a_addr[AF];
+      auto fetch = [&](int buf, int tap, int c) {
+        bq[buf][0] = *reinterpret_cast<const v4i*>(s_w + b_base + tap * C + 32 * c);
+        bq[buf][1] = *reinterpret_cast<const v4i*>(s_w + b_base + 32 * wstride + tap * C + 32 * c);
+#pragma unroll
+        for (int f = 0; f < AF; ++f) aq[buf][f] = *reinterpret_cast<const v4i*>(s_in + a_addr[f] + 32 * c);
+      };
+#pragma unroll
+      for (int f = 0; f < AF; ++f) a_addr[f] = a_base[f];
+      fetch(0, 0, 0);
+#pragma unroll
+      for (int step = 0; step < 9 * CK; ++step) {
+        const int cur = step & 1;
+        if (step + 1 < 9 * CK) {
+          const int ntap = (step + 1) / CK, nc = (step + 1) % CK;
+          if (nc == 0) {
+            const int ky = ntap / 3, kx = ntap - 3 * ky;
+            const uint32_t a_tap = (uint32_t)((ky * Wp + kx) * Cp);
+#pragma unroll
+            for (int f = 0; f < AF; ++f) a_addr[f] = a_base[f] + a_tap;
+          }
+          fetch(cur ^ 1, ntap, nc);
+        }
+        __builtin_amdgcn_sched_barrier(0);   // keep the requests ahead of this step's matrix instructions
 #pragma unroll
         for (int f = 0; f < AF; ++f) {
-          const v4i af = *reinterpret_cast<const v4i*>(s_in + a_base[f] + a_tap + cg);
-          acc[f][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af, b0, acc[f][0], 0, 0, 0);
-          acc[f][1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af, b1, acc[f][1], 0, 0, 0);
+          acc[f][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(aq[cur][f], bq[cur][0], acc[f][0], 0, 0, 0);
+          acc[f][1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(aq[cur][f], bq[cur][1], acc[f][1], 0, 0, 0);
         }
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
 
@@ -375,13 +409,23 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void conv3x3_nchw_kernel(
   }
 }
 
+template <int NW, int AF, int NU, int CK>
+hipError_t launch_c3_ck(const C3Params& p, size_t lds, int64_t grid, hipStream_t st) {
+  static std::atomic<uint64_t> attr_set{0};
+  hipError_t e = raise_lds_limit(reinterpret_cast<const void*>(conv3x3_nchw_kernel<NW, AF, NU, CK>), (int)lds, attr_set);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((conv3x3_nchw_kernel<NW, AF, NU, CK>), dim3((unsigned)grid), dim3(64 * NW), lds, st, p);
+  return hipGetLastError();
+}
+
 template <int NW, int AF, int NU>
 hipError_t launch_c3(const C3Params& p, size_t lds, int64_t grid, hipStream_t st) {
-  static std::atomic<uint64_t> attr_set{0};
-  hipError_t e = raise_lds_limit(reinterpret_cast<const void*>(conv3x3_nchw_kernel<NW, AF, NU>), (int)lds, attr_set);
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((conv3x3_nchw_kernel<NW, AF, NU>), dim3((unsigned)grid), dim3(64 * NW), lds, st, p);
-  return hipGetLastError();
+  switch (p.C / 32) {
+    case 1: return launch_c3_ck<NW, AF, NU, 1>(p, lds, grid, st);
+    case 2: return launch_c3_ck<NW, AF, NU, 2>(p, lds, grid, st);
+    case 3: return launch_c3_ck<NW, AF, NU, 3>(p, lds, grid, st);
+    default: return launch_c3_ck<NW, AF, NU, 4>(p, lds, grid, st);
+  }
 }
 
 }  // namespace
