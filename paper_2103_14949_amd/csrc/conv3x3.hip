@@ -90,18 +90,24 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void conv3x3_nchw_kernel(
   const int Wp = W + 2;
   constexpr int wstride = 9 * C + 16;  // bytes per staged output channel
   const int HW = H * W;
-  // Workgroups that share a pixel tile (one per block of output channels) read the same input:
-  // consecutive workgroup ids go round the 8 XCDs, so the block index is taken from the id
-  // divided by 8 and the sharers land on one XCD, whose L2 then fetches the tile once.
-  int blk, wg;
+  // Workgroups that share a pixel tile (one per block of output channels) read the same input,
+  // and neighbouring tiles of an image share their halo rows.  Consecutive workgroup ids go round
+  // the 8 XCDs, each with an L2 of its own, so the block index is taken from the id divided by 8
+  // (the sharers land on one XCD) and each XCD walks a contiguous eighth of the tiles.
+  int blk, tile, tile_end, tile_step;
   const int nwg = (int)gridDim.x / p.nblk;
   if (nwg % 8 == 0) {
     const int xcd = (int)blockIdx.x & 7, q = (int)blockIdx.x >> 3;
+    const int per_xcd = (p.ntiles + 7) / 8;
     blk = q % p.nblk;
-    wg = (q / p.nblk) * 8 + xcd;
+    tile = xcd * per_xcd + q / p.nblk;
+    tile_end = (xcd + 1) * per_xcd < p.ntiles ? (xcd + 1) * per_xcd : p.ntiles;
+    tile_step = nwg / 8;
   } else {
     blk = (int)blockIdx.x % p.nblk;
-    wg = (int)blockIdx.x / p.nblk;
+    tile = (int)blockIdx.x / p.nblk;
+    tile_end = p.ntiles;
+    tile_step = nwg;
   }
   const int o0 = blk * 64;                             // this workgroup's block of output channels
 
@@ -171,8 +177,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void conv3x3_nchw_kernel(
   if (t < 64) s_sum[t] = 0;
   __syncthreads();
 
-  int tile = wg;
-  if (tile < p.ntiles) load_tile(tile);   // in flight while the weights are staged
+  if (tile < tile_end) load_tile(tile);   // in flight while the weights are staged
 
   // ---- per-lane constants: output channels o0 + j and o0 + 32 + j (their loads go out now too)
   const int j = lane & 31, h = lane >> 5;
@@ -265,14 +270,14 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void conv3x3_nchw_kernel(
   }
   const uint32_t b_base = (uint32_t)(j * wstride + 16 * h);
 
-  for (; tile < p.ntiles; tile += nwg) {
+  for (; tile < tile_end; tile += tile_step) {
     const int b = tile / p.tiles_per_img;
     const int y0 = (tile - b * p.tiles_per_img) * p.TR;          // first output row
     const int rows = (H - y0 < p.TR) ? H - y0 : p.TR;            // output rows of this tile
     __syncthreads();       // the previous tile has been consumed
     store_tile(tile);      // registers -> LDS (waits for this tile's loads)
     __syncthreads();
-    if (tile + nwg < p.ntiles) load_tile(tile + nwg);            // the next tile's loads go out now
+    if (tile + tile_step < tile_end) load_tile(tile + tile_step);   // the next tile's loads go out now
 
     // ---- implicit GEMM: 9 taps x C / 32 steps, 2 AF MFMAs (64 output channels) per step
     v16i acc[AF][2];
