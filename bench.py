@@ -49,6 +49,9 @@ def main():
     ap.add_argument("--only", default="", help="comma list of extra-op names to time (default all)")
     ap.add_argument("--gemm", default="", help="M,N,K: only time hago_qdense on this shape (uniform random "
                     "uint8 activations and int8 weights) and print its line; for counter runs")
+    ap.add_argument("--phase-stamps", action="store_true",
+                    help="development: load libhago_phase.so (python -m paper_2103_14949_amd.build "
+                         "--phase-timing) and print, per config 5 layer, where a workgroup's time goes")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run plain copies of known size (for scaling rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
@@ -62,6 +65,11 @@ def main():
 
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
+    if args.phase_stamps:
+        from paper_2103_14949_amd import binding, build as hip_build
+        if not os.path.exists(hip_build.PHASE_LIB):
+            sys.exit(f"bench.py: {hip_build.PHASE_LIB} is missing: python -m paper_2103_14949_amd.build --phase-timing")
+        binding._LIB_PATH = hip_build.PHASE_LIB
     hago.lib()  # fails loudly if the HIP library is missing
     dev = "cuda:0"
     torch.cuda.set_device(0)
@@ -146,6 +154,10 @@ def main():
     def step():
         for c in calls:
             c()
+
+    if args.phase_stamps:
+        print(json.dumps(phase_stamps(torch, hago, layers, event_times_ms)))
+        return
 
     # An idle board needs about 50 ms of load before its clocks settle (the first 200 steps after
     # idling run 8-13 % slower than the steady state): the stack runs untimed for RAMP_MS before the
@@ -264,6 +276,41 @@ def measured_ceilings(torch, hago, event_times_ms, dev):
         del srcs, dsts
     res["copy_note"] = "hago_probe_copy (128-bit nontemporal loads/stores), read + written bytes, rotating buffers"
     return res
+
+
+def phase_stamps(torch, hago, layers, event_times_ms):
+    """Per layer of the stack: back-to-back launch time, and the mean over its workgroups of the time
+    between the phase timestamps the development build's GEMM kernel writes (100 MHz wall clock)."""
+    import ctypes as C
+    L = hago.lib()
+    L.hago_debug_set_stamp_buffer.argtypes = [C.c_void_p, C.c_int]
+    L.hago_debug_set_stamp_buffer.restype = None
+    names = ["setup", "prologue_issue", "first_stage_wait", "main_loop", "drain_and_channel_terms",
+             "requantize_to_lds", "copy_out"]
+    nslots = 8192
+    out = []
+    for l in layers:
+        L.hago_debug_set_stamp_buffer(None, 0)
+        us = float(np.median(event_times_ms(l["call"], 100, 20))) * 1e3
+        buf = torch.zeros(nslots * 8, dtype=torch.int64, device=l["a"].device)
+        L.hago_debug_set_stamp_buffer(buf.data_ptr(), 0)
+        for _ in range(5):
+            l["call"]()
+        torch.cuda.synchronize()
+        L.hago_debug_set_stamp_buffer(None, 0)
+        h = buf.cpu().numpy().reshape(nslots, 8)
+        h = h[h[:, 0] != 0]
+        # slot 7: entry, slots 0..6: end of each phase
+        t = np.concatenate([h[:, 7:8], h[:, 0:7]], axis=1).astype(np.float64)
+        ph = np.diff(t, axis=1).mean(axis=0) * 0.01
+        rec = {"K": l["K"], "N": l["N"], "workgroups": int(len(h)), "us_per_launch_back_to_back": round(us, 2),
+               "first_entry_to_last_end_us": round(float(h[:, 6].max() - h[:, 7].min()) * 0.01, 2),
+               "entry_spread_us": round(float(h[:, 7].max() - h[:, 7].min()) * 0.01, 2),
+               "end_spread_us": round(float(h[:, 6].max() - h[:, 6].min()) * 0.01, 2),
+               "phase_us": {n: round(float(v), 2) for n, v in zip(names, ph)}}
+        rec["main_loop_share_of_workgroup_time"] = round(float(ph[3] / ph.sum()), 3)
+        out.append(rec)
+    return out
 
 
 def cpu_baseline(datagen, layers, torch):

@@ -59,5 +59,36 @@ def _drain(procs, verbose):
             print("\n".join(lines), flush=True)
 
 
+PHASE_LIB = os.path.join(HERE, "libhago_phase.so")
+
+
+def build_phase_timing(verbose: bool = False) -> str:
+    """Development variant of the library for `bench.py --phase-stamps`: the GEMM kernels write a
+    timestamp per workgroup at each phase boundary (first loads, main loop, channel terms,
+    requantize, copy-out).  Needs the objects of a normal build() for the other sources."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    objdir = os.path.join(HERE, "_build", "phase")
+    os.makedirs(objdir, exist_ok=True)
+    timed = ("qgemm_dma.hip", "qgemm.hip")
+    procs, objs = [], []
+    for src in sources():
+        base = os.path.basename(src)
+        if base in timed:
+            obj = os.path.join(objdir, base + ".o")
+            cmd = [hipcc, *HIPCC_FLAGS, "-DHAGO_PHASE_TIMING", "-c", src, "-o", obj]
+            procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
+        else:
+            obj = os.path.join(HERE, "_build", base + ".o")
+            if not os.path.exists(obj):
+                raise RuntimeError(f"{obj} is missing: run build() first")
+        objs.append(obj)
+    _drain(procs, verbose)
+    subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", PHASE_LIB], check=True)
+    return PHASE_LIB
+
+
 if __name__ == "__main__":
-    print(build(verbose="-v" in sys.argv))
+    if "--phase-timing" in sys.argv:
+        print(build_phase_timing(verbose="-v" in sys.argv))
+    else:
+        print(build(verbose="-v" in sys.argv))
