@@ -417,7 +417,9 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void conv3x3_nchw_kernel(
 template <int NW, int AF, int NU, int CK>
 hipError_t launch_c3_ck(const C3Params& p, size_t lds, int64_t grid, hipStream_t st) {
   static std::atomic<uint64_t> attr_set{0};
-  hipError_t e = raise_lds_limit(reinterpret_cast<const void*>(conv3x3_nchw_kernel<NW, AF, NU, CK>), (int)lds, attr_set);
+  // the LDS size depends on the geometry, not only on the template arguments: raise the kernel's
+  // limit to the CU's 160 KB once, whatever this call needs
+  hipError_t e = raise_lds_limit(reinterpret_cast<const void*>(conv3x3_nchw_kernel<NW, AF, NU, CK>), 160 * 1024, attr_set);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((conv3x3_nchw_kernel<NW, AF, NU, CK>), dim3((unsigned)grid), dim3(64 * NW), lds, st, p);
   return hipGetLastError();

@@ -461,6 +461,18 @@ def test_qconv2d_one_launch_3x3(case, adt, za):
     assert_same(host(out), want, f"unaligned output {case}")
 
 
+def test_qconv2d_one_launch_3x3_small_then_large_lds():
+    """One instantiation of the one-launch kernel serves geometries with different LDS sizes (the size depends
+    on the image width and rows per tile): a call that needs little LDS followed by calls that need more than
+    the 64 KB default limit."""
+    rng = np.random.default_rng(99)
+    for B, C, H, W, O in ((1, 64, 4, 8, 16), (1, 64, 56, 56, 64), (1, 64, 8, 120, 64), (70, 64, 8, 8, 64), (130, 64, 16, 60, 64)):
+        a, w = rnd_act(rng, (B, C, H, W), np.uint8), rnd_w(rng, (O, C, 3, 3))
+        want = ref.qconv2d(a, 128, w, None, ref.NCHW, (1, 1), (1, 1), 1)
+        got = hago.qconv2d(dev(a), act_qtype(a, 128), dev(w), hago.QType(hago.I8), None, hago.NCHW, (1, 1), (1, 1), 1)
+        assert_same(host(got), want, f"raw {(B, C, H, W, O)}")
+
+
 @pytest.mark.parametrize("O", [128, 100])
 def test_qconv2d_many_pixels_128_channels(O, conv_entry):
     """3x3 convolution with 128 input channels over more than 2^15 output pixels (the 256-pixel
