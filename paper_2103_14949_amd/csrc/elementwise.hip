@@ -33,6 +33,21 @@ inline void split_row(int64_t inner_vec, int u, int32_t* nseg, int32_t* seg_len)
   *seg_len = (int32_t)((inner_vec + n - 1) / n);
 }
 
+// Row and channel of a row kernel's job (job = row * nseg + segment).  Jobs below 2^32, the usual
+// case, take 32-bit divisions: the 64-bit ones cost a few hundred cycles per job, a visible part
+// of a job that streams a dozen kilobytes.
+__device__ __forceinline__ void job_row_channel(int64_t job, int32_t nseg, int32_t channels, int per_channel,
+                                                int64_t& row, int32_t& c) {
+  if (job <= 0xffffffffll) {
+    const uint32_t r32 = (uint32_t)job / (uint32_t)nseg;
+    row = r32;
+    c = per_channel ? (int32_t)(r32 % (uint32_t)channels) : 0;
+  } else {
+    row = job / nseg;
+    c = per_channel ? (int32_t)(row % channels) : 0;
+  }
+}
+
 // Eq. 3 with zero point and saturation, in binary32.  The clip is written as
 // compare-select so that NaN propagates and the comparison structure is the
 // same as the scalar definition.
@@ -84,14 +99,7 @@ __global__ __launch_bounds__(kThreads) void simquant_rows_kernel(
   for (int64_t job = blockIdx.x; job < rows * nseg; job += gridDim.x) {
     int64_t row;
     int32_t c;
-    if (job <= 0xffffffffll) {  // the usual case: 32-bit division
-      const uint32_t r32 = (uint32_t)job / (uint32_t)nseg;
-      row = r32;
-      c = per_channel ? (int32_t)(r32 % (uint32_t)channels) : 0;
-    } else {
-      row = job / nseg;
-      c = per_channel ? (int32_t)(row % channels) : 0;
-    }
+    job_row_channel(job, nseg, channels, per_channel, row, c);
     const int32_t seg = (int32_t)(job - row * nseg);
     const float s = scale[c];
     const float zf = (float)zp[c];
@@ -135,8 +143,9 @@ __global__ __launch_bounds__(kThreads) void simquant_batched_rows_kernel(
     CandidateClips clips) {
   const int64_t batch_stride = rows * inner_vec;  // vectors per candidate output
   for (int64_t job = blockIdx.x; job < rows * nseg; job += gridDim.x) {
-    const int64_t row = job / nseg;
-    const int32_t c = per_channel ? (int32_t)(row % channels) : 0;
+    int64_t row;
+    int32_t c;
+    job_row_channel(job, nseg, channels, per_channel, row, c);
     const int32_t seg = (int32_t)(job - row * nseg);
     const int64_t v0 = (int64_t)seg * seg_len;
     const int64_t v1 = (v0 + seg_len < inner_vec) ? v0 + seg_len : inner_vec;
@@ -219,14 +228,7 @@ __global__ __launch_bounds__(kThreads) void requant_rows_kernel(
   for (int64_t job = blockIdx.x; job < rows * nseg; job += gridDim.x) {
     int64_t row;
     int32_t c;
-    if (job <= 0xffffffffll) {  // the usual case: 32-bit division
-      const uint32_t r32 = (uint32_t)job / (uint32_t)nseg;
-      row = r32;
-      c = per_channel ? (int32_t)(r32 % (uint32_t)channels) : 0;
-    } else {
-      row = job / nseg;
-      c = per_channel ? (int32_t)(row % channels) : 0;
-    }
+    job_row_channel(job, nseg, channels, per_channel, row, c);
     const int32_t seg = (int32_t)(job - row * nseg);
     const int32_t m = POW2 ? 0 : rq_mult(mult, c);
     const int32_t sh = POW2 ? shift[c] : rq_shift(mult, shift, c);
@@ -336,8 +338,9 @@ __global__ __launch_bounds__(kThreads) void quant_rows_kernel(
     const int32_t* __restrict__ zp, int per_channel, float lo, float hi) {
   using VQ = typename QVec<Q>::T;
   for (int64_t job = blockIdx.x; job < rows * nseg; job += gridDim.x) {
-    const int64_t row = job / nseg;
-    const int32_t c = per_channel ? (int32_t)(row % channels) : 0;
+    int64_t row;
+    int32_t c;
+    job_row_channel(job, nseg, channels, per_channel, row, c);
     const int32_t seg = (int32_t)(job - row * nseg);
     const float s = scale[c];
     const float zf = (float)zp[c];
@@ -452,10 +455,20 @@ __global__ __launch_bounds__(kThreads) void absmax_rows_kernel(
   // per tensor the "row" is the whole tensor: outer == 1, channels == 1
   const int64_t jobs = (int64_t)channels * nseg * ogroups;
   for (int64_t job = blockIdx.x; job < jobs; job += gridDim.x) {
-    const int64_t cs = job % ((int64_t)channels * nseg);  // neighbouring workgroups, neighbouring rows
-    const int32_t og = (int32_t)(job / ((int64_t)channels * nseg));
-    const int32_t seg = (int32_t)(cs % nseg);
-    const int32_t c = (int32_t)(cs / nseg);
+    // job = og * (channels * nseg) + c * nseg + seg: neighbouring workgroups, neighbouring rows
+    int32_t og, seg, c;
+    const int64_t per_group = (int64_t)channels * nseg;
+    if (jobs <= 0xffffffffll) {  // the usual case: 32-bit divisions
+      og = (int32_t)((uint32_t)job / (uint32_t)per_group);
+      const uint32_t cs = (uint32_t)job - (uint32_t)og * (uint32_t)per_group;
+      c = (int32_t)(cs / (uint32_t)nseg);
+      seg = (int32_t)(cs - (uint32_t)c * (uint32_t)nseg);
+    } else {
+      og = (int32_t)(job / per_group);
+      const int64_t cs = job - og * per_group;
+      c = (int32_t)(cs / nseg);
+      seg = (int32_t)(cs - (int64_t)c * nseg);
+    }
     const int64_t v0 = (int64_t)seg * seg_len;
     const int64_t v1 = (v0 + seg_len < inner_vec) ? v0 + seg_len : inner_vec;
     float m = 0.0f;
