@@ -48,25 +48,64 @@ __device__ __forceinline__ void job_row_channel(int64_t job, int32_t nseg, int32
   }
 }
 
-// Eq. 3 with zero point and saturation, in binary32.  The clip is written as
-// compare-select so that NaN propagates and the comparison structure is the
-// same as the scalar definition.
-__device__ __forceinline__ float simquant_one(float x, float s, float zf, float lo, float hi) {
-  const float t = x / s;  // IEEE division (correctly rounded)
-  const float u = rintf(t);
+// u = rintf(x / s), the rounded quotient of Eq. 3 (correctly rounded binary32 division, then
+// round half to even), for a divisor that many elements share.  The division expands to about
+// fifteen vector instructions, which made the row kernels issue-bound; this takes five on
+// almost every element and gives the SAME value on every element:
+//   rc = RN(1 / s), computed once per row with |s| in [2^-100, 2^100] (so rc is normal and within
+//   2^-24 of 1 / s, relatively); qt = RN(x * rc) is within |x / s| * (2^-23 + 2^-48) of the
+//   exact quotient, and so is RN(x / s) within |x / s| * 2^-24: the two differ by less than
+//   |qt| * 2^-22.  With n = rintf(qt) and d = qt - n (exact: |qt| < 2^23 here), both lie strictly
+//   inside (n - 1/2, n + 1/2) whenever |d| + |qt| * 2^-22 < 1/2, and then rintf of either is n
+//   (an underflowing qt has n = 0, as the quotient has).  The test below asks for twice that margin,
+//   which also covers the rounding of the threshold itself.
+//   Anything else takes the division: quotients within about 2^-21 |qt| of a tie (one element in
+//   2^14 for |qt| near 32), |qt| >= 2^20, infinities and NaN (every comparison false), and, through
+//   rc = NaN, scales outside the range above.
+__device__ __forceinline__ float quotient_reciprocal(float s) {
+  const float a = fabsf(s);
+  return (a >= 0x1p-100f && a <= 0x1p100f) ? 1.0f / s : __builtin_nanf("");
+}
+
+// Four elements at once: one branch per 128-bit vector (the slow side redoes all four).
+__device__ __forceinline__ v4f rounded_quotient4(v4f x, float s, float rc) {
+  v4f n;
+  bool ok = true;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const float qt = x[e] * rc;
+    n[e] = rintf(qt);
+    const float d = qt - n[e];
+    const float thr = __builtin_fmaf(fabsf(qt), -0x1p-21f, 0.5f);
+    ok = ok && (fabsf(d) < thr);
+  }
+  if (__builtin_expect(!ok, 0)) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) n[e] = rintf(x[e] / s);  // IEEE division (correctly rounded)
+  }
+  return n;
+}
+
+// Eq. 3 with zero point and saturation, in binary32, from the rounded quotient u.  The clip is
+// written as compare-select so that NaN propagates and the comparison structure is the same as
+// the scalar definition.
+__device__ __forceinline__ float simquant_of(float u, float s, float zf, float lo, float hi) {
   float v = u + zf;
   v = (v < lo) ? lo : ((v > hi) ? hi : v);
   return (v - zf) * s;
 }
 
+__device__ __forceinline__ float simquant_one(float x, float s, float zf, float lo, float hi) {
+  return simquant_of(rintf(x / s), s, zf, lo, hi);
+}
+
+
 // The same with the overflow of the simulated integer type (Sec. 5.2 of the paper: the third error
 // source): the code is reduced modulo 2^wrap_bits before the clip, into the two's-complement range
 // (wrap_signed) or into 0 .. 2^wrap_bits - 1.  A code of magnitude 4e18 or more, or an infinite one,
 // reduces to 0 (every binary32 number that large is a multiple of 2^32); NaN stays NaN.
-__device__ __forceinline__ float simquant_wrap_one(float x, float s, float zf, float lo, float hi,
-                                                   int wrap_bits, int wrap_signed) {
-  const float t = x / s;
-  const float u = rintf(t);
+__device__ __forceinline__ float simquant_wrap_of(float u, float s, float zf, float lo, float hi,
+                                                  int wrap_bits, int wrap_signed) {
   float v = u + zf;
   if (v == v) {
     long long code = 0;
@@ -92,10 +131,6 @@ __global__ __launch_bounds__(kThreads) void simquant_rows_kernel(
     int64_t inner_vec, int32_t nseg, int32_t seg_len, const float* __restrict__ scale,
     const int32_t* __restrict__ zp, int per_channel, float lo, float hi, int wrap_bits = 0,
     int wrap_signed = 0) {
-  auto one = [&](float v, float s, float zf) {
-    if constexpr (WRAP) return simquant_wrap_one(v, s, zf, lo, hi, wrap_bits, wrap_signed);
-    else return simquant_one(v, s, zf, lo, hi);
-  };
   for (int64_t job = blockIdx.x; job < rows * nseg; job += gridDim.x) {
     int64_t row;
     int32_t c;
@@ -103,6 +138,11 @@ __global__ __launch_bounds__(kThreads) void simquant_rows_kernel(
     const int32_t seg = (int32_t)(job - row * nseg);
     const float s = scale[c];
     const float zf = (float)zp[c];
+    const float rc = quotient_reciprocal(s);
+    auto of = [&](float u, float s, float zf) {
+      if constexpr (WRAP) return simquant_wrap_of(u, s, zf, lo, hi, wrap_bits, wrap_signed);
+      else return simquant_of(u, s, zf, lo, hi);
+    };
     const int64_t v0 = (int64_t)seg * seg_len;
     const int64_t v1 = (v0 + seg_len < inner_vec) ? v0 + seg_len : inner_vec;
     const v4f* xr = x + row * inner_vec;
@@ -115,11 +155,8 @@ __global__ __launch_bounds__(kThreads) void simquant_rows_kernel(
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         if (vb + u * kThreads < v1) {
-          v4f r;
-          r.x = one(a[u].x, s, zf);
-          r.y = one(a[u].y, s, zf);
-          r.z = one(a[u].z, s, zf);
-          r.w = one(a[u].w, s, zf);
+          const v4f n = rounded_quotient4(a[u], s, rc);
+          const v4f r = {of(n.x, s, zf), of(n.y, s, zf), of(n.z, s, zf), of(n.w, s, zf)};
           __builtin_nontemporal_store(r, yr + vb + u * kThreads);
         }
       }
@@ -160,14 +197,13 @@ __global__ __launch_bounds__(kThreads) void simquant_batched_rows_kernel(
         const float s = scale[(int64_t)b * nparam + c];
         const float zf = (float)zp[(int64_t)b * nparam + c];
         const float lo = clips.lo[b], hi = clips.hi[b];
+        const float rc = quotient_reciprocal(s);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
           if (vb + u * kThreads < v1) {
-            v4f r;
-            r.x = simquant_one(a[u].x, s, zf, lo, hi);
-            r.y = simquant_one(a[u].y, s, zf, lo, hi);
-            r.z = simquant_one(a[u].z, s, zf, lo, hi);
-            r.w = simquant_one(a[u].w, s, zf, lo, hi);
+            const v4f n = rounded_quotient4(a[u], s, rc);
+            const v4f r = {simquant_of(n.x, s, zf, lo, hi), simquant_of(n.y, s, zf, lo, hi),
+                           simquant_of(n.z, s, zf, lo, hi), simquant_of(n.w, s, zf, lo, hi)};
             __builtin_nontemporal_store(r, yr + b * batch_stride + vb + u * kThreads);
           }
         }
@@ -199,7 +235,7 @@ __global__ __launch_bounds__(kThreads) void simquant_flat_kernel(
   const int64_t stride = (int64_t)gridDim.x * kThreads;
   for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += stride) {
     const int64_t c = per_channel ? (i / inner) % channels : 0;
-    if constexpr (WRAP) y[i] = simquant_wrap_one(x[i], scale[c], (float)zp[c], lo, hi, wrap_bits, wrap_signed);
+    if constexpr (WRAP) y[i] = simquant_wrap_of(rintf(x[i] / scale[c]), scale[c], (float)zp[c], lo, hi, wrap_bits, wrap_signed);
     else y[i] = simquant_one(x[i], scale[c], (float)zp[c], lo, hi);
   }
 }
@@ -295,11 +331,14 @@ __global__ __launch_bounds__(kThreads) void requant_flat_kernel(
 // ---- quantize / dequantize (the two halves of Eq. 3; Sec. 6.1): the code is formed exactly as in
 // simulated_quantize (binary32 division, round half to even, zero point added as a float,
 // compare-select clip), then stored in the integer container; NaN takes the code of real zero.
-__device__ __forceinline__ int32_t quantize_one(float x, float s, float zf, float lo, float hi) {
-  const float u = rintf(x / s);
+__device__ __forceinline__ int32_t quantize_of(float u, float zf, float lo, float hi) {
   float v = (u != u) ? zf : u + zf;
   v = (v < lo) ? lo : ((v > hi) ? hi : v);
   return (int32_t)v;  // integral and within +-2^24
+}
+
+__device__ __forceinline__ int32_t quantize_one(float x, float s, float zf, float lo, float hi) {
+  return quantize_of(rintf(x / s), zf, lo, hi);
 }
 
 __device__ __forceinline__ float dequantize_one(int32_t q, float s, float zf) {
@@ -344,6 +383,7 @@ __global__ __launch_bounds__(kThreads) void quant_rows_kernel(
     const int32_t seg = (int32_t)(job - row * nseg);
     const float s = scale[c];
     const float zf = (float)zp[c];
+    const float rc = OP == 1 ? 0.0f : quotient_reciprocal(s);
     const int64_t v0 = (int64_t)seg * seg_len;
     const int64_t v1 = (v0 + seg_len < inner_vec) ? v0 + seg_len : inner_vec;
     for (int64_t vb = v0 + threadIdx.x; vb < v1; vb += (int64_t)kThreads * U) {
@@ -374,12 +414,14 @@ __global__ __launch_bounds__(kThreads) void quant_rows_kernel(
 #pragma unroll
         for (int u = 0; u < U; ++u) {
           if (vb + u * kThreads < v1) {
-            const VQ r = pack_codes<Q>(quantize_one(a[u].x, s, zf, lo, hi), quantize_one(a[u].y, s, zf, lo, hi),
-                                       quantize_one(a[u].z, s, zf, lo, hi), quantize_one(a[u].w, s, zf, lo, hi));
+            const v4f n = rounded_quotient4(a[u], s, rc);
+            const float u0 = n.x, u1 = n.y, u2 = n.z, u3 = n.w;
+            const VQ r = pack_codes<Q>(quantize_of(u0, zf, lo, hi), quantize_of(u1, zf, lo, hi),
+                                       quantize_of(u2, zf, lo, hi), quantize_of(u3, zf, lo, hi));
             __builtin_nontemporal_store(r, qr + vb + u * kThreads);
             if constexpr (OP == 2) {
-              const v4f y = {simquant_one(a[u].x, s, zf, lo, hi), simquant_one(a[u].y, s, zf, lo, hi),
-                             simquant_one(a[u].z, s, zf, lo, hi), simquant_one(a[u].w, s, zf, lo, hi)};
+              const v4f y = {simquant_of(u0, s, zf, lo, hi), simquant_of(u1, s, zf, lo, hi),
+                             simquant_of(u2, s, zf, lo, hi), simquant_of(u3, s, zf, lo, hi)};
               __builtin_nontemporal_store(y, reinterpret_cast<v4f*>(out2) + row * inner_vec + vb + u * kThreads);
             }
           }

@@ -49,6 +49,65 @@ def test_simquant_special_values_and_bits():
     assert_same_bits(host(got), want, "denormal")
 
 
+def _near_tie_inputs(rng, scales, inner):
+    """[2, len(scales), inner] fp32: per scale, quotients at and a few ulps around ties (k + 1/2) * s, whole
+    multiples, special values and random magnitudes over many binades."""
+    x = np.empty((2, len(scales), inner), np.float32)
+    special = np.array([0.0, -0.0, 1e-45, -1e-45, 1e-40, 1e-38, -1e-38, 3e38, -3e38, np.inf, -np.inf, np.nan,
+                        2.0 ** 20, 2.0 ** 23, 2.0 ** 24, 2.0 ** 25, 0.49999997, 0.5, 0.50000006], np.float32)
+    for o in range(2):
+        for c, s in enumerate(scales):
+            k = rng.integers(-(1 << 9) if o == 0 else -(1 << 21), (1 << 9) if o == 0 else (1 << 21), inner).astype(np.float64)
+            with np.errstate(all="ignore"):
+                v = ((k + 0.5) * np.float64(s)).astype(np.float32)
+                ulps = rng.integers(-4, 5, inner)
+                for u in range(-4, 5):
+                    moved = v.copy()
+                    for _ in range(abs(u)):
+                        moved = np.nextafter(moved, np.float32(np.inf if u > 0 else -np.inf))
+                    v = np.where(ulps == u, moved, v)
+                q = inner // 4
+                v[:q] = (k[:q] * np.float64(s)).astype(np.float32)
+                v[q:q + len(special)] = special
+                v[q + len(special):q + 2 * len(special)] = special * np.float32(s)
+                v[2 * q:3 * q] = (rng.standard_normal(q) * 2.0 ** rng.uniform(-12, 22, q)).astype(np.float32) * np.float32(s)
+            x[o, c] = v
+    return x
+
+
+def test_rounded_quotient_near_ties_special_values_and_extreme_scales():
+    """The row kernels take rint(x / s) from a multiplication by the reciprocal wherever that provably gives the
+    same value and from the division elsewhere: quotients at and around ties, huge, tiny and non-finite ones,
+    scales at and beyond the reciprocal's range, for every operator that rounds a quotient."""
+    rng = np.random.default_rng(4242)
+    scales = np.concatenate([rng.uniform(0.001, 0.1, 6), 2.0 ** rng.uniform(-20, 20, 6),
+                             [1.0 / 3.0, 0.1, 3.0, 1.0, 2.0 ** -100, 2.0 ** 100, 2.0 ** -101, 2.0 ** 101, 1e-40, 3e38,
+                              -0.037, 255.0 / 256.0]]).astype(np.float32)
+    C = len(scales)
+    x = _near_tie_inputs(rng, scales, 4096)
+    zp = rng.integers(-5, 6, C).astype(np.int32)
+    dx, ds, dz = dev(x), dev(scales), dev(zp)
+    for q, lo, hi in ((hago.QType(hago.I8), -128, 127), (hago.QType(hago.I16), -2 ** 15, 2 ** 15 - 1),
+                      (hago.QType(hago.I32, 25, True), -2 ** 24, 2 ** 24 - 1)):
+        want = ref.simquant(x, scales, zp, lo, hi)
+        assert_same_bits(host(hago.simquant(dx, ds, dz, q, lo, hi)), want, f"simquant {lo}..{hi}")
+        codes = ref.quantize(x, scales, zp, lo, hi)
+        assert_same(host(hago.quantize(dx, ds, dz, q, lo, hi)).astype(np.int32), codes, f"quantize {lo}..{hi}")
+        y, qc = hago.simquant_codes(dx, ds, dz, q, lo, hi)
+        assert_same_bits(host(y), want, f"simquant_codes value {lo}..{hi}")
+        assert_same(host(qc).astype(np.int32), codes, f"simquant_codes codes {lo}..{hi}")
+    # batched candidates: three parameter sets over the same tensor
+    sc3 = np.stack([scales, scales * np.float32(1.7), scales[::-1]]).astype(np.float32)
+    zp3 = np.stack([zp, zp + 1, -zp]).astype(np.int32)
+    los, his = np.array([-128, -8, -2 ** 15], np.int32), np.array([127, 7, 2 ** 15 - 1], np.int32)
+    got = host(hago.simquant_batched(dx, dev(sc3), dev(zp3), hago.QType(hago.I16), los, his))
+    for b in range(3):
+        assert_same_bits(got[b], ref.simquant(x, sc3[b], zp3[b], int(los[b]), int(his[b])), f"batched candidate {b}")
+    # the overflow-simulating form
+    want = ref.simquant_wrap(x, scales, zp, 8, True, -128, 127)
+    assert_same_bits(host(hago.simquant_wrap(dx, ds, dz, hago.QType(hago.I8))), want, "simquant_wrap")
+
+
 def test_simquant_in_place_and_idempotent():
     rng = np.random.default_rng(3)
     x = rng.standard_normal((4, 8, 1024)).astype(np.float32)
