@@ -33,15 +33,33 @@ inline void split_row(int64_t inner_vec, int u, int32_t* nseg, int32_t* seg_len)
   *seg_len = (int32_t)((inner_vec + n - 1) / n);
 }
 
-// Row and channel of a row kernel's job (job = row * nseg + segment).  Jobs below 2^32, the usual
-// case, take 32-bit divisions: the 64-bit ones cost a few hundred cycles per job, a visible part
-// of a job that streams a dozen kilobytes.
+// Row and channel of a row kernel's job (job = row * nseg + segment).  A job streams a dozen
+// kilobytes, so its bookkeeping counts: jobs below 2^32, the usual case, are divided with the
+// host's reciprocals floor(2^32 / d) (a multiply-high and at most two corrections, all on
+// wavefront-uniform values, i.e. scalar instructions) instead of the 25 vector instructions of an
+// integer division each.
+struct JobDiv {
+  uint32_t inv_nseg, inv_channels;
+};
+inline uint32_t reciprocal32(int64_t d) { return d <= 1 ? 0xffffffffu : (uint32_t)((1ull << 32) / (uint64_t)d); }
+
+__device__ __forceinline__ uint32_t div32(uint32_t n, uint32_t d, uint32_t inv, uint32_t& rem) {
+  uint32_t q = __umulhi(n, inv);   // q - 2 <= this <= q
+  uint32_t r = n - q * d;
+  if (r >= d) { ++q; r -= d; }
+  if (r >= d) { ++q; r -= d; }
+  rem = r;
+  return q;
+}
+
 __device__ __forceinline__ void job_row_channel(int64_t job, int32_t nseg, int32_t channels, int per_channel,
-                                                int64_t& row, int32_t& c) {
+                                                JobDiv jd, int64_t& row, int32_t& c) {
   if (job <= 0xffffffffll) {
-    const uint32_t r32 = (uint32_t)job / (uint32_t)nseg;
+    uint32_t seg, cc;
+    const uint32_t r32 = div32((uint32_t)job, (uint32_t)nseg, jd.inv_nseg, seg);
     row = r32;
-    c = per_channel ? (int32_t)(r32 % (uint32_t)channels) : 0;
+    div32(r32, (uint32_t)channels, jd.inv_channels, cc);
+    c = per_channel ? (int32_t)cc : 0;
   } else {
     row = job / nseg;
     c = per_channel ? (int32_t)(row % channels) : 0;
@@ -129,12 +147,12 @@ template <int U, bool WRAP = false>
 __global__ __launch_bounds__(kThreads) void simquant_rows_kernel(
     const v4f* __restrict__ x, v4f* __restrict__ y, int64_t rows, int32_t channels,
     int64_t inner_vec, int32_t nseg, int32_t seg_len, const float* __restrict__ scale,
-    const int32_t* __restrict__ zp, int per_channel, float lo, float hi, int wrap_bits = 0,
+    const int32_t* __restrict__ zp, int per_channel, JobDiv jd, float lo, float hi, int wrap_bits = 0,
     int wrap_signed = 0) {
   for (int64_t job = blockIdx.x; job < rows * nseg; job += gridDim.x) {
     int64_t row;
     int32_t c;
-    job_row_channel(job, nseg, channels, per_channel, row, c);
+    job_row_channel(job, nseg, channels, per_channel, jd, row, c);
     const int32_t seg = (int32_t)(job - row * nseg);
     const float s = scale[c];
     const float zf = (float)zp[c];
@@ -176,13 +194,13 @@ template <int U>
 __global__ __launch_bounds__(kThreads) void simquant_batched_rows_kernel(
     const v4f* __restrict__ x, v4f* __restrict__ y, int64_t rows, int32_t channels,
     int64_t inner_vec, int32_t nseg, int32_t seg_len, int32_t nbatch, int32_t nparam,
-    const float* __restrict__ scale, const int32_t* __restrict__ zp, int per_channel,
+    const float* __restrict__ scale, const int32_t* __restrict__ zp, int per_channel, JobDiv jd,
     CandidateClips clips) {
   const int64_t batch_stride = rows * inner_vec;  // vectors per candidate output
   for (int64_t job = blockIdx.x; job < rows * nseg; job += gridDim.x) {
     int64_t row;
     int32_t c;
-    job_row_channel(job, nseg, channels, per_channel, row, c);
+    job_row_channel(job, nseg, channels, per_channel, jd, row, c);
     const int32_t seg = (int32_t)(job - row * nseg);
     const int64_t v0 = (int64_t)seg * seg_len;
     const int64_t v1 = (v0 + seg_len < inner_vec) ? v0 + seg_len : inner_vec;
@@ -259,12 +277,12 @@ template <typename AccT, int U, bool AWAY, bool POW2 = false>
 __global__ __launch_bounds__(kThreads) void requant_rows_kernel(
     const AccT* __restrict__ acc, uint32_t* __restrict__ out, int64_t rows, int32_t channels,
     int64_t inner_vec, int32_t nseg, int32_t seg_len, const int32_t* __restrict__ mult,
-    const int32_t* __restrict__ shift, int per_channel, RequantScalars rs) {
+    const int32_t* __restrict__ shift, int per_channel, JobDiv jd, RequantScalars rs) {
   using VecT = typename std::conditional<sizeof(AccT) == 4, v4i32, v4i16>::type;
   for (int64_t job = blockIdx.x; job < rows * nseg; job += gridDim.x) {
     int64_t row;
     int32_t c;
-    job_row_channel(job, nseg, channels, per_channel, row, c);
+    job_row_channel(job, nseg, channels, per_channel, jd, row, c);
     const int32_t seg = (int32_t)(job - row * nseg);
     const int32_t m = POW2 ? 0 : rq_mult(mult, c);
     const int32_t sh = POW2 ? shift[c] : rq_shift(mult, shift, c);
@@ -374,12 +392,12 @@ template <typename Q, int OP, int U>
 __global__ __launch_bounds__(kThreads) void quant_rows_kernel(
     const void* __restrict__ in, void* __restrict__ out, float* __restrict__ out2, int64_t rows, int32_t channels,
     int64_t inner_vec, int32_t nseg, int32_t seg_len, const float* __restrict__ scale,
-    const int32_t* __restrict__ zp, int per_channel, float lo, float hi) {
+    const int32_t* __restrict__ zp, int per_channel, JobDiv jd, float lo, float hi) {
   using VQ = typename QVec<Q>::T;
   for (int64_t job = blockIdx.x; job < rows * nseg; job += gridDim.x) {
     int64_t row;
     int32_t c;
-    job_row_channel(job, nseg, channels, per_channel, row, c);
+    job_row_channel(job, nseg, channels, per_channel, jd, row, c);
     const int32_t seg = (int32_t)(job - row * nseg);
     const float s = scale[c];
     const float zf = (float)zp[c];
@@ -573,7 +591,7 @@ hipError_t launch_simquant(const float* x, float* y, int64_t outer, int64_t chan
     hipLaunchKernelGGL((simquant_rows_kernel<kVecPerLane, false>), dim3(grid_for(rows * nseg)), dim3(kThreads), 0, st,
                        reinterpret_cast<const v4f*>(x), reinterpret_cast<v4f*>(y), rows,
                        (int32_t)(per_channel ? channels : 1), inner_vec, nseg, seg_len, scale, zp,
-                       per_channel, lo, hi, 0, 0);
+                       per_channel, JobDiv{reciprocal32(nseg), reciprocal32(per_channel ? channels : 1)}, lo, hi, 0, 0);
   } else {
     hipLaunchKernelGGL(simquant_flat_kernel<false>, dim3(grid_for((total + kThreads - 1) / kThreads)),
                        dim3(kThreads), 0, st, x, y, total, inner, channels, scale, zp, per_channel,
@@ -597,7 +615,8 @@ hipError_t launch_simquant_wrap(const float* x, float* y, int64_t outer, int64_t
     hipLaunchKernelGGL((simquant_rows_kernel<kVecPerLane, true>), dim3(grid_for(rows * nseg)), dim3(kThreads), 0, st,
                        reinterpret_cast<const v4f*>(x), reinterpret_cast<v4f*>(y), rows,
                        (int32_t)(per_channel ? channels : 1), inner_vec, nseg, seg_len, scale, zp,
-                       per_channel, lo, hi, wrap_bits, wrap_signed);
+                       per_channel, JobDiv{reciprocal32(nseg), reciprocal32(per_channel ? channels : 1)}, lo, hi,
+                       wrap_bits, wrap_signed);
   } else {
     hipLaunchKernelGGL(simquant_flat_kernel<true>, dim3(grid_for((total + kThreads - 1) / kThreads)),
                        dim3(kThreads), 0, st, x, y, total, inner, channels, scale, zp, per_channel,
@@ -629,7 +648,7 @@ hipError_t launch_simquant_batched(const float* x, float* y, int64_t outer, int6
     hipLaunchKernelGGL(simquant_batched_rows_kernel<kU>, dim3(grid_for(rows * nseg)), dim3(kThreads),
                        0, st, reinterpret_cast<const v4f*>(x), reinterpret_cast<v4f*>(y), rows,
                        nparam, inner_vec, nseg, seg_len, nbatch, nparam, scale, zp, per_channel,
-                       clips);
+                       JobDiv{reciprocal32(nseg), reciprocal32(nparam)}, clips);
   } else {
     hipLaunchKernelGGL(simquant_batched_flat_kernel, dim3(grid_for((total + kThreads - 1) / kThreads)),
                        dim3(kThreads), 0, st, x, y, total, inner, channels, nbatch, nparam, scale, zp,
@@ -653,7 +672,8 @@ static hipError_t launch_quant_t(const void* in, void* out, float* out2, int64_t
     split_row(inner_vec, kVecPerLane, &nseg, &seg_len);
     hipLaunchKernelGGL((quant_rows_kernel<Q, OP, kVecPerLane>), dim3(grid_for(rows * nseg)),
                        dim3(kThreads), 0, st, in, out, out2, rows, (int32_t)(per_channel ? channels : 1),
-                       inner_vec, nseg, seg_len, scale, zp, per_channel, lo, hi);
+                       inner_vec, nseg, seg_len, scale, zp, per_channel,
+                       JobDiv{reciprocal32(nseg), reciprocal32(per_channel ? channels : 1)}, lo, hi);
   } else {
     hipLaunchKernelGGL((quant_flat_kernel<Q, OP>), dim3(grid_for((total + kThreads - 1) / kThreads)),
                        dim3(kThreads), 0, st, in, out, out2, total, inner, channels, scale, zp, per_channel,
@@ -749,7 +769,8 @@ static hipError_t launch_requantize_t(const AccT* acc, int64_t outer, int64_t ch
                                  : requant_rows_kernel<AccT, kVecPerLane, false, true>);
     hipLaunchKernelGGL(kern, dim3(grid_for(rows * nseg)), dim3(kThreads), 0, st,
                        acc, reinterpret_cast<uint32_t*>(out), rows, (int32_t)(pc ? channels : 1),
-                       inner_vec, nseg, seg_len, rq.multiplier, rq.shift, pc, rs);
+                       inner_vec, nseg, seg_len, rq.multiplier, rq.shift, pc,
+                       JobDiv{reciprocal32(nseg), reciprocal32(pc ? channels : 1)}, rs);
   } else if (pc && inner == 1 && channels % 4 == 0 && io_aligned && rq.multiplier && aligned16(rq.multiplier) &&
              aligned16(rq.shift)) {
     const int64_t total_vec = total / 4;

@@ -78,3 +78,27 @@ def test_scales_outside_the_range_never_take_the_fast_path():
         d = qt - n
         thr = (0.5 - np.abs(qt).astype(np.float64) * 2.0 ** -21).astype(np.float32)
         assert not (np.abs(d) < thr).any()
+
+
+def test_reciprocal_division_of_job_indices():
+    """The row kernels divide 32-bit job indices by the segment and channel counts with the host's
+    floor(2^32 / d) (0xffffffff for d = 1), a multiply-high and two conditional corrections
+    (csrc/elementwise.hip, div32): exact for every 32-bit n and d >= 1."""
+    rng = np.random.default_rng(5)
+    d = np.concatenate([np.array([1, 2, 3, 5, 7, 144, 255, 256, 257, 65535, 65536, 65537, 1000003, 2 ** 31 - 1, 2 ** 31,
+                                  2 ** 32 - 2, 2 ** 32 - 1], np.uint64),
+                        (rng.integers(1, 2 ** 32, 3000, dtype=np.uint64) >> rng.integers(0, 31, 3000).astype(np.uint64)) | np.uint64(1)])
+    for dd in d:
+        dd = int(dd)
+        inv = 0xffffffff if dd <= 1 else (1 << 32) // dd
+        n = np.concatenate([rng.integers(0, 2 ** 32, 2000, dtype=np.uint64),
+                            np.uint64(2 ** 32 - 1) - rng.integers(0, 1000, 200, dtype=np.uint64),
+                            (rng.integers(0, 2 ** 32 // dd + 1, 500, dtype=np.uint64) * np.uint64(dd)
+                             + np.uint64(dd - 1)) % np.uint64(2 ** 32)])
+        q = (n * np.uint64(inv)) >> np.uint64(32)
+        r = n - q * np.uint64(dd)
+        for _ in range(2):
+            fix = r >= np.uint64(dd)
+            q = q + fix.astype(np.uint64)
+            r = r - fix.astype(np.uint64) * np.uint64(dd)
+        assert np.array_equal(q, n // np.uint64(dd)) and np.array_equal(r, n % np.uint64(dd)), dd
