@@ -27,6 +27,11 @@
  *     for the device.  The one operator that wants scratch memory, the
  *     groups == 1 convolution (it rewrites its operands before the matrix
  *     cores read them), takes it from the caller: hago_qconv2d_ws.
+ *   - A call is kernel launches on `stream` and nothing else, so it may be
+ *     recorded into a HIP graph.  The first call that reaches a kernel with a
+ *     large LDS footprint raises that kernel's limit on the current device
+ *     (hipFuncSetAttribute): make one ordinary call of the same operator and
+ *     geometry before capturing.
  *   - Tensors are dense and contiguous in the stated order.  `out` must not
  *     overlap any input.  A tensor with zero elements may be passed as NULL.
  *   - `stream` is the caller's hipStream_t (NULL = the default stream).  Calls
