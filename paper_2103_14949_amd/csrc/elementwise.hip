@@ -104,13 +104,14 @@ __device__ __forceinline__ v4f rounded_quotient4(v4f x, float s, float rc) {
   return n;
 }
 
-// Eq. 3 with zero point and saturation, in binary32, from the rounded quotient u.  The clip is
-// written as compare-select so that NaN propagates and the comparison structure is the same as
-// the scalar definition.
+// Eq. 3 with zero point and saturation, in binary32, from the rounded quotient u.  The scalar
+// definition clips with two compare-selects, (v < lo) ? lo : ((v > hi) ? hi : v), under which NaN
+// stays NaN; for every other v (lo <= hi, both finite) that is the median of the three, one
+// instruction, and v is never -0 here (a sum that is zero is +0), so no zero changes sign.
 __device__ __forceinline__ float simquant_of(float u, float s, float zf, float lo, float hi) {
-  float v = u + zf;
-  v = (v < lo) ? lo : ((v > hi) ? hi : v);
-  return (v - zf) * s;
+  const float v = u + zf;
+  const float c = (v != v) ? v : __builtin_amdgcn_fmed3f(v, lo, hi);
+  return (c - zf) * s;
 }
 
 __device__ __forceinline__ float simquant_one(float x, float s, float zf, float lo, float hi) {
@@ -350,9 +351,8 @@ __global__ __launch_bounds__(kThreads) void requant_flat_kernel(
 // simulated_quantize (binary32 division, round half to even, zero point added as a float,
 // compare-select clip), then stored in the integer container; NaN takes the code of real zero.
 __device__ __forceinline__ int32_t quantize_of(float u, float zf, float lo, float hi) {
-  float v = (u != u) ? zf : u + zf;
-  v = (v < lo) ? lo : ((v > hi) ? hi : v);
-  return (int32_t)v;  // integral and within +-2^24
+  const float v = (u != u) ? zf : u + zf;                  // never NaN from here on
+  return (int32_t)__builtin_amdgcn_fmed3f(v, lo, hi);      // the clip; integral and within +-2^24
 }
 
 __device__ __forceinline__ int32_t quantize_one(float x, float s, float zf, float lo, float hi) {
