@@ -85,9 +85,10 @@ __device__ __forceinline__ float quotient_reciprocal(float s) {
   return (a >= 0x1p-100f && a <= 0x1p100f) ? 1.0f / s : __builtin_nanf("");
 }
 
-// Four elements at once: one branch per 128-bit vector (the slow side redoes all four).
-__device__ __forceinline__ v4f rounded_quotient4(v4f x, float s, float rc) {
-  v4f n;
+// Four elements at once, so that a kernel branches once per 128-bit vector: true when all four
+// pass the test, and then n[e] = rintf(x[e] / s), all finite; otherwise the caller redoes the four
+// with the division.
+__device__ __forceinline__ bool fast_quotient4(v4f x, float rc, v4f& n) {
   bool ok = true;
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
@@ -97,11 +98,7 @@ __device__ __forceinline__ v4f rounded_quotient4(v4f x, float s, float rc) {
     const float thr = __builtin_fmaf(fabsf(qt), -0x1p-21f, 0.5f);
     ok = ok && (fabsf(d) < thr);
   }
-  if (__builtin_expect(!ok, 0)) {
-#pragma unroll
-    for (int e = 0; e < 4; ++e) n[e] = rintf(x[e] / s);  // IEEE division (correctly rounded)
-  }
-  return n;
+  return ok;
 }
 
 // Eq. 3 with zero point and saturation, in binary32, from the rounded quotient u.  The scalar
@@ -112,6 +109,11 @@ __device__ __forceinline__ float simquant_of(float u, float s, float zf, float l
   const float v = u + zf;
   const float c = (v != v) ? v : __builtin_amdgcn_fmed3f(v, lo, hi);
   return (c - zf) * s;
+}
+
+// The same for a finite u (what fast_quotient4 hands out): no NaN to keep.
+__device__ __forceinline__ float simquant_of_finite(float u, float s, float zf, float lo, float hi) {
+  return (__builtin_amdgcn_fmed3f(u + zf, lo, hi) - zf) * s;
 }
 
 __device__ __forceinline__ float simquant_one(float x, float s, float zf, float lo, float hi) {
@@ -174,8 +176,15 @@ __global__ __launch_bounds__(kThreads) void simquant_rows_kernel(
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         if (vb + u * kThreads < v1) {
-          const v4f n = rounded_quotient4(a[u], s, rc);
-          const v4f r = {of(n.x, s, zf), of(n.y, s, zf), of(n.z, s, zf), of(n.w, s, zf)};
+          v4f n, r;
+          if (__builtin_expect(fast_quotient4(a[u], rc, n), 1)) {
+            if constexpr (WRAP) r = v4f{of(n.x, s, zf), of(n.y, s, zf), of(n.z, s, zf), of(n.w, s, zf)};
+            else r = v4f{simquant_of_finite(n.x, s, zf, lo, hi), simquant_of_finite(n.y, s, zf, lo, hi),
+                         simquant_of_finite(n.z, s, zf, lo, hi), simquant_of_finite(n.w, s, zf, lo, hi)};
+          } else {  // IEEE division (correctly rounded)
+            r = v4f{of(rintf(a[u].x / s), s, zf), of(rintf(a[u].y / s), s, zf), of(rintf(a[u].z / s), s, zf),
+                    of(rintf(a[u].w / s), s, zf)};
+          }
           __builtin_nontemporal_store(r, yr + vb + u * kThreads);
         }
       }
@@ -220,9 +229,14 @@ __global__ __launch_bounds__(kThreads) void simquant_batched_rows_kernel(
 #pragma unroll
         for (int u = 0; u < U; ++u) {
           if (vb + u * kThreads < v1) {
-            const v4f n = rounded_quotient4(a[u], s, rc);
-            const v4f r = {simquant_of(n.x, s, zf, lo, hi), simquant_of(n.y, s, zf, lo, hi),
-                           simquant_of(n.z, s, zf, lo, hi), simquant_of(n.w, s, zf, lo, hi)};
+            v4f n, r;
+            if (__builtin_expect(fast_quotient4(a[u], rc, n), 1)) {
+              r = v4f{simquant_of_finite(n.x, s, zf, lo, hi), simquant_of_finite(n.y, s, zf, lo, hi),
+                      simquant_of_finite(n.z, s, zf, lo, hi), simquant_of_finite(n.w, s, zf, lo, hi)};
+            } else {
+              r = v4f{simquant_one(a[u].x, s, zf, lo, hi), simquant_one(a[u].y, s, zf, lo, hi),
+                      simquant_one(a[u].z, s, zf, lo, hi), simquant_one(a[u].w, s, zf, lo, hi)};
+            }
             __builtin_nontemporal_store(r, yr + b * batch_stride + vb + u * kThreads);
           }
         }
@@ -355,6 +369,10 @@ __device__ __forceinline__ int32_t quantize_of(float u, float zf, float lo, floa
   return (int32_t)__builtin_amdgcn_fmed3f(v, lo, hi);      // the clip; integral and within +-2^24
 }
 
+__device__ __forceinline__ int32_t quantize_of_finite(float u, float zf, float lo, float hi) {
+  return (int32_t)__builtin_amdgcn_fmed3f(u + zf, lo, hi);
+}
+
 __device__ __forceinline__ int32_t quantize_one(float x, float s, float zf, float lo, float hi) {
   return quantize_of(rintf(x / s), zf, lo, hi);
 }
@@ -432,14 +450,23 @@ __global__ __launch_bounds__(kThreads) void quant_rows_kernel(
 #pragma unroll
         for (int u = 0; u < U; ++u) {
           if (vb + u * kThreads < v1) {
-            const v4f n = rounded_quotient4(a[u], s, rc);
-            const float u0 = n.x, u1 = n.y, u2 = n.z, u3 = n.w;
-            const VQ r = pack_codes<Q>(quantize_of(u0, zf, lo, hi), quantize_of(u1, zf, lo, hi),
-                                       quantize_of(u2, zf, lo, hi), quantize_of(u3, zf, lo, hi));
+            v4f n, y;
+            VQ r;
+            if (__builtin_expect(fast_quotient4(a[u], rc, n), 1)) {   // four finite quotients
+              r = pack_codes<Q>(quantize_of_finite(n.x, zf, lo, hi), quantize_of_finite(n.y, zf, lo, hi),
+                                quantize_of_finite(n.z, zf, lo, hi), quantize_of_finite(n.w, zf, lo, hi));
+              if constexpr (OP == 2)
+                y = v4f{simquant_of_finite(n.x, s, zf, lo, hi), simquant_of_finite(n.y, s, zf, lo, hi),
+                        simquant_of_finite(n.z, s, zf, lo, hi), simquant_of_finite(n.w, s, zf, lo, hi)};
+            } else {
+              r = pack_codes<Q>(quantize_one(a[u].x, s, zf, lo, hi), quantize_one(a[u].y, s, zf, lo, hi),
+                                quantize_one(a[u].z, s, zf, lo, hi), quantize_one(a[u].w, s, zf, lo, hi));
+              if constexpr (OP == 2)
+                y = v4f{simquant_one(a[u].x, s, zf, lo, hi), simquant_one(a[u].y, s, zf, lo, hi),
+                        simquant_one(a[u].z, s, zf, lo, hi), simquant_one(a[u].w, s, zf, lo, hi)};
+            }
             __builtin_nontemporal_store(r, qr + vb + u * kThreads);
             if constexpr (OP == 2) {
-              const v4f y = {simquant_of(u0, s, zf, lo, hi), simquant_of(u1, s, zf, lo, hi),
-                             simquant_of(u2, s, zf, lo, hi), simquant_of(u3, s, zf, lo, hi)};
               __builtin_nontemporal_store(y, reinterpret_cast<v4f*>(out2) + row * inner_vec + vb + u * kThreads);
             }
           }
