@@ -550,7 +550,7 @@ def extra_ops(torch, hago, datagen, to_dev, rq_of, event_times_ms, only, ceiling
                note="u8 [M,256] x i8 [128,256]" + (" (scaled batch)" if Mrows != 64 else ""))
 
     # ---- config 2 (as specified and scaled)
-    for name, B in (("conv_c2", 1), ("conv_c2_B64", 64)):
+    for name, B in (("conv_c2", 1), ("conv_c2_B64", 64), ("conv_c2_B256", 256)):
         if not want(name):
             continue
         c = datagen.config2(B=B)
@@ -577,7 +577,7 @@ def extra_ops(torch, hago, datagen, to_dev, rq_of, event_times_ms, only, ceiling
             hago.set_test_hook(hago.HOOK_GEMM_PATH, 0)
 
     # ---- config 3 (int16 accumulation; as specified and scaled)
-    for name, B in (("conv_c3_acc16", 8), ("conv_c3_acc16_B64", 64)):
+    for name, B in (("conv_c3_acc16", 8), ("conv_c3_acc16_B64", 64), ("conv_c3_acc16_B256", 256)):
         if not want(name):
             continue
         c = datagen.config3(B=B)
